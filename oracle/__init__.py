@@ -1,0 +1,158 @@
+"""CPU oracle for the ZNN convolutional-layer hot path (arXiv 1510.06706).
+
+TEST INFRASTRUCTURE ONLY.  Only the test-suite, the smoke check and the
+``cpu_baseline`` leg of the benchmark may import this package; the GPU library
+never does, and nothing here imports the GPU library.
+
+``znn_ref.c`` holds the plain double-precision definitions (nested loops);
+this module is the ctypes binding around it plus numpy-level helpers.  All
+functions take and return float64 numpy arrays (float32 inputs are widened
+exactly).
+
+Layouts: images ``[map, z, y, x]``; kernels ``[fan_out, fan_in, kz, ky, kx]``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "znn_ref.c")
+_LIB = os.path.join(_HERE, "libznn_ref.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile znn_ref.c with gcc (-O2, OpenMP, no fast-math)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99", "-Wall", "-o", tmp, _SRC]
+        )
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        lib.znn_ref_num_threads.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().znn_ref_num_threads())
+
+
+def _i3(v):
+    a = (ctypes.c_int * 3)(*[int(t) for t in v])
+    return a
+
+
+def _d(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _f64(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.float64))
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise ValueError("oracle %s rejected its arguments (rc=%d)" % (what, rc))
+
+
+def conv3d_fwd(inp, w):
+    """out[j] = sum_i valid_conv(in[i], w[j, i])   (Section 2, Convolution)."""
+    inp, w = _f64(inp), _f64(w)
+    fo, f = w.shape[:2]
+    assert inp.ndim == 4 and w.ndim == 5 and inp.shape[0] == f
+    n, k = inp.shape[1:], w.shape[2:]
+    out = np.empty((fo,) + tuple(n[d] - k[d] + 1 for d in range(3)), dtype=np.float64)
+    _check(_load().znn_ref_conv3d_fwd(f, fo, _i3(n), _i3(k), _d(inp), _d(w), _d(out)), "fwd")
+    return out
+
+
+def conv3d_bwd(gout, w, n):
+    """gin[i] = sum_j full_conv(gout[j], reflect(w[j, i]))   (Section 3.1)."""
+    gout, w = _f64(gout), _f64(w)
+    fo, f = w.shape[:2]
+    k = w.shape[2:]
+    assert gout.shape == (fo,) + tuple(n[d] - k[d] + 1 for d in range(3))
+    gin = np.empty((f,) + tuple(n), dtype=np.float64)
+    _check(_load().znn_ref_conv3d_bwd(f, fo, _i3(n), _i3(k), _d(gout), _d(w), _d(gin)), "bwd")
+    return gin
+
+
+def conv3d_wgrad(inp, gout):
+    """gw[j, i] = valid_conv(reflect(in[i]), gout[j])   (Section 3.2)."""
+    inp, gout = _f64(inp), _f64(gout)
+    f, fo = inp.shape[0], gout.shape[0]
+    n = inp.shape[1:]
+    k = tuple(n[d] - gout.shape[1 + d] + 1 for d in range(3))
+    gw = np.empty((fo, f) + k, dtype=np.float64)
+    _check(_load().znn_ref_conv3d_wgrad(f, fo, _i3(n), _i3(k), _d(inp), _d(gout), _d(gw)), "wgrad")
+    return gw
+
+
+def _at(fn, what, f, fo, n, k, a, b, pos):
+    pos = np.ascontiguousarray(np.asarray(pos, dtype=np.int64))
+    val = np.empty(pos.shape, dtype=np.float64)
+    rc = fn(f, fo, _i3(n), _i3(k), _d(a), _d(b), ctypes.c_long(pos.size),
+            pos.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), _d(val))
+    _check(rc, what)
+    return val
+
+
+def conv3d_fwd_at(inp, w, pos):
+    """Forward outputs at flat positions ``pos`` of the [fo, n'] tensor."""
+    inp, w = _f64(inp), _f64(w)
+    fo, f = w.shape[:2]
+    return _at(_load().znn_ref_conv3d_fwd_at, "fwd_at", f, fo, inp.shape[1:], w.shape[2:], inp, w, pos)
+
+
+def conv3d_bwd_at(gout, w, n, pos):
+    """Backward outputs at flat positions ``pos`` of the [f, n] tensor."""
+    gout, w = _f64(gout), _f64(w)
+    fo, f = w.shape[:2]
+    return _at(_load().znn_ref_conv3d_bwd_at, "bwd_at", f, fo, n, w.shape[2:], gout, w, pos)
+
+
+def conv3d_wgrad_at(inp, gout, pos):
+    """Kernel-gradient entries at flat positions ``pos`` of the [fo, f, k] tensor."""
+    inp, gout = _f64(inp), _f64(gout)
+    f, fo = inp.shape[0], gout.shape[0]
+    n = inp.shape[1:]
+    k = tuple(n[d] - gout.shape[1 + d] + 1 for d in range(3))
+    return _at(_load().znn_ref_conv3d_wgrad_at, "wgrad_at", f, fo, n, k, inp, gout, pos)
+
+
+def maxfilter3d_fwd(inp, win):
+    """Sliding-window maximum and the flat input offset that supplied it."""
+    inp = _f64(inp)
+    maps, n = inp.shape[0], inp.shape[1:]
+    o = tuple(n[d] - win[d] + 1 for d in range(3))
+    out = np.empty((maps,) + o, dtype=np.float64)
+    idx = np.empty((maps,) + o, dtype=np.int32)
+    rc = _load().znn_ref_maxfilter3d_fwd(maps, _i3(n), _i3(win), _d(inp), _d(out),
+                                         idx.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
+    _check(rc, "maxfilter_fwd")
+    return out, idx
+
+
+def maxfilter3d_bwd(gout, idx, n, win):
+    """Max-filter Jacobian: scatter-add gout to the recorded argmax voxels."""
+    gout = _f64(gout)
+    idx = np.ascontiguousarray(np.asarray(idx, dtype=np.int32))
+    maps = gout.shape[0]
+    gin = np.empty((maps,) + tuple(n), dtype=np.float64)
+    rc = _load().znn_ref_maxfilter3d_bwd(maps, _i3(n), _i3(win), _d(gout),
+                                         idx.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), _d(gin))
+    _check(rc, "maxfilter_bwd")
+    return gin
