@@ -1,0 +1,175 @@
+/*
+ * znn.h -- C ABI of the MI355X (gfx950) convolutional-layer library.
+ *
+ * The library computes the per-edge 3D convolutions of a ConvNet computation
+ * graph in the sense of ZNN (arXiv 1510.06706, Section 2): a layer has f input
+ * nodes and f' output nodes joined by f*f' convolution edges, and a node sums
+ * the outputs of the edges that converge on it.  All three training passes are
+ * provided (forward, backward, kernel gradient; Sections 2, 3.1, 3.2), each by
+ * the direct method or by the FFT method (Section 4), together with the
+ * sliding-window max-filter and its Jacobian and the per-layer choice between
+ * the two methods.
+ *
+ * Conventions common to every entry point
+ *   - All tensor pointers are DEVICE pointers to dense fp32 (or int32) arrays,
+ *     row-major with x fastest:
+ *        images   [map][z][y][x]
+ *        kernels  [fan_out][fan_in][kz][ky][kx]
+ *     2D is the special case z-extent 1.  Extents may differ per axis.
+ *   - The caller owns every buffer.  Outputs are overwritten, inputs are never
+ *     modified, inputs and outputs must not overlap.  Scratch memory comes from
+ *     the caller's workspace `ws` (256-byte aligned, size from
+ *     znn_plan_workspace_bytes); the compute entry points never allocate or
+ *     free device memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Every entry point only enqueues work on `stream` and returns; it never
+ *     synchronises with the host (znn_autotune is the one exception).
+ *   - Return value: ZNN_OK or a negative error code; a description of the last
+ *     error on the calling thread is available from znn_last_error().  Nothing
+ *     throws or aborts across this boundary.  Argument validation happens on
+ *     the host before anything is launched.
+ */
+#ifndef ZNN_H
+#define ZNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ZNN_OK             0
+#define ZNN_EINVAL       (-1)  /* null pointer, extent < 1, kernel or window larger than image */
+#define ZNN_EUNSUPPORTED (-2)  /* sparsity != 1, index range beyond int32, FFT extent too large */
+#define ZNN_EWORKSPACE   (-3)  /* workspace (or spectra buffer) missing, misaligned or too small  */
+#define ZNN_EHIP         (-4)  /* the HIP runtime reported an error; see znn_last_error()          */
+
+typedef struct { int32_t z, y, x; } znn_vec3;
+
+typedef enum { ZNN_DIRECT = 0, ZNN_FFT = 1, ZNN_AUTO = 2 } znn_mode;
+typedef enum { ZNN_PASS_FWD = 0, ZNN_PASS_BWD = 1, ZNN_PASS_WGRAD = 2 } znn_pass;
+
+/* One fully connected convolutional layer (Section 2; Table 2 uses the same f, f', n, k). */
+typedef struct {
+    int32_t  fan_in;      /* f  >= 1 : number of input nodes                                */
+    int32_t  fan_out;     /* f' >= 1 : number of output nodes                               */
+    znn_vec3 image;       /* n  : extents of every input image                              */
+    znn_vec3 kernel;      /* k  : extents of every kernel, 1 <= k_d <= n_d                  */
+    znn_vec3 sparsity;    /* s  : must be {1,1,1} (sparse convolution is not built yet)     */
+    int32_t  mode;        /* znn_mode; ZNN_AUTO takes the autotuner's cached choice for this
+                             descriptor, or a cost-model guess when nothing is cached       */
+} znn_conv_desc;
+
+typedef struct znn_plan znn_plan;   /* opaque host object: method, FFT extents, resident spectra */
+
+/* Host only.  Validates the descriptor and fixes the method and the FFT extents
+ * N_d (the smallest 2^a 3^b 5^c >= n_d per axis).  *plan is set on success only. */
+int  znn_plan_create(const znn_conv_desc* desc, znn_plan** plan);
+void znn_plan_destroy(znn_plan* plan);
+
+/* Host only queries.  mode is ZNN_DIRECT or ZNN_FFT (never ZNN_AUTO). */
+int  znn_plan_mode(const znn_plan* plan, int32_t* mode);
+int  znn_plan_fft_extents(const znn_plan* plan, znn_vec3* N);
+/* Bytes of workspace the given pass (znn_pass) needs with the plan's method and
+ * its current state (resident kernel spectra make forward/backward smaller). */
+int  znn_plan_workspace_bytes(const znn_plan* plan, int32_t pass, size_t* bytes);
+/* Bytes of the kernel spectra W^[f'][f][N_z][N_y][N_x/2+1] (complex fp32). */
+int  znn_plan_spectra_bytes(const znn_plan* plan, size_t* bytes);
+
+/*
+ * FFT method only: transform all f*f' kernels once and keep their spectra in
+ * the caller's buffer `spectra` (device, 256-byte aligned, at least
+ * znn_plan_spectra_bytes).  This is the kernel half of the FFT memoization of
+ * Section 4.  Afterwards znn_conv3d_fwd / znn_conv3d_bwd on this plan ignore
+ * their `w` argument (it may be NULL) and stream the resident spectra.  The
+ * buffer stays owned by the caller and must outlive the plan or a later
+ * znn_conv_release_kernels.  `ws` needs no more than the forward workspace.
+ */
+int  znn_conv_prepare_kernels(znn_plan* plan, const float* w, void* spectra, size_t spectra_bytes,
+                              void* ws, size_t ws_bytes, void* stream);
+int  znn_conv_release_kernels(znn_plan* plan);
+
+/*
+ * Forward pass (Section 2, "Convolution", and the node sum of the computation
+ * graph): out[j] = sum_i valid_conv(in[i], w[j][i]), a true convolution (kernel
+ * index runs against the image index), output extents n' = n - k + 1.
+ *   in  [f][n]   w [f'][f][k]   ->   out [f'][n']
+ */
+int  znn_conv3d_fwd(znn_plan* plan, const float* in, const float* w, float* out,
+                    void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Backward pass (Section 3.1, "Convolution Jacobian"): full convolution of the
+ * output gradients with the kernel reflected along all three axes, summed over
+ * the outgoing edges of each input node.
+ *   gout [f'][n']   w [f'][f][k]   ->   gin [f][n]
+ */
+int  znn_conv3d_bwd(znn_plan* plan, const float* gout, const float* w, float* gin,
+                    void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Kernel gradient (Section 3.2, "Kernel update"): valid convolution of the
+ * reflected forward image at the source node with the backward image at the
+ * target node, kernel-sized.
+ *   in [f][n]   gout [f'][n']   ->   gw [f'][f][k]
+ */
+int  znn_conv3d_wgrad(znn_plan* plan, const float* in, const float* gout, float* gw,
+                      void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Max-filtering (Section 2): out[m][p] = max over the window p + [0, win) of
+ * in[m]; extents n - win + 1.  idx[m][p] is the flat offset (z*n_y + y)*n_x + x
+ * inside map m of the voxel that supplied the maximum; among equal values the
+ * smallest offset wins (+0 and -0 are equal).  Inputs must not contain NaN.
+ *   in [maps][n]  ->  out [maps][n-win+1] (fp32), idx [maps][n-win+1] (int32)
+ */
+int  znn_maxfilter3d_fwd(int32_t maps, znn_vec3 n, znn_vec3 win, const float* in,
+                         float* out, int32_t* idx, void* stream);
+
+/*
+ * Max-filtering Jacobian (Section 3.1): gin is a zero image of the filter's
+ * input extents n into which every gout[m][p] is accumulated at idx[m][p].
+ * idx must come from znn_maxfilter3d_fwd with the same maps, n and win (every
+ * recorded offset lies inside its own window); the sum for a voxel is taken in
+ * ascending window order, so results are reproducible bit for bit.
+ */
+int  znn_maxfilter3d_bwd(int32_t maps, znn_vec3 n, znn_vec3 win, const float* gout,
+                         const int32_t* idx, float* gin, void* stream);
+
+/*
+ * Transfer-function edges and the update step that a training round needs
+ * around the convolutions (Sections 2, 3.1, 3.2).  All are elementwise or
+ * per-map reductions over images [maps][voxels].
+ *   znn_transfer_fwd : y = max(x + bias[m], 0)             (half-wave rectification)
+ *   znn_transfer_bwd : gx = gy * (y > 0 ? 1 : 0)           (y = forward output)
+ *   znn_bias_grad    : gb[m] = sum of all voxels of g[m]   (fixed summation order)
+ *   znn_square_loss_grad : g = out - target                (loss 1/2 sum (out-target)^2)
+ *   znn_sgd_update   : p -= eta * g                        (Algorithm 3)
+ */
+int  znn_transfer_fwd(int32_t maps, int64_t voxels, const float* x, const float* bias, float* y, void* stream);
+int  znn_transfer_bwd(int32_t maps, int64_t voxels, const float* gy, const float* y, float* gx, void* stream);
+int  znn_bias_grad(int32_t maps, int64_t voxels, const float* g, float* gb, void* stream);
+int  znn_square_loss_grad(int64_t count, const float* out, const float* target, float* g, void* stream);
+int  znn_sgd_update(int64_t count, float eta, const float* g, float* p, void* stream);
+
+/*
+ * Layer-wise choice between the direct and the FFT method (Section 4): times
+ * forward + backward + kernel gradient in both methods on the given shape
+ * (2 warm-up rounds, 5 timed), stores the faster one in a process-wide cache
+ * keyed by the descriptor (consulted by znn_plan_create for ZNN_AUTO) and
+ * reports it.  ms[method][pass] receives the mean milliseconds.  The tensors
+ * are carved from `ws` and filled with a fixed pattern; `ws` must hold
+ * znn_autotune_workspace_bytes.  Synchronises `stream` with the host.
+ */
+int  znn_autotune_workspace_bytes(const znn_conv_desc* desc, size_t* bytes);
+int  znn_autotune(const znn_conv_desc* desc, void* ws, size_t ws_bytes, void* stream,
+                  int32_t* chosen_mode, float ms[2][3]);
+
+/* Description of the last error on the calling thread ("" if none). Never NULL. */
+const char* znn_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZNN_H */

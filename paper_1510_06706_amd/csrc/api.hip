@@ -1,0 +1,348 @@
+// Host side of the C ABI: validation, plans, dispatch, autotuner cache.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <new>
+#include <tuple>
+
+#include "znn_internal.h"
+
+namespace znn {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+int fail(int code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int check_launch(const char* what)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ZNN_EHIP, "%s: %s", what, hipGetErrorString(e));
+    return ZNN_OK;
+}
+
+int next_fft_extent(int n)
+{
+    for (int m = n;; ++m) {
+        int t = m;
+        while (t % 2 == 0) t /= 2;
+        while (t % 3 == 0) t /= 3;
+        while (t % 5 == 0) t /= 5;
+        if (t == 1) return m;
+    }
+}
+
+// ---------------------------------------------------------------- autotune cache
+using DescKey = std::tuple<int, int, int, int, int, int, int, int>;
+static std::mutex g_tune_mu;
+static std::map<DescKey, int> g_tune;
+
+static DescKey key_of(const znn_conv_desc& d)
+{
+    return DescKey(d.fan_in, d.fan_out, d.image.z, d.image.y, d.image.x, d.kernel.z, d.kernel.y, d.kernel.x);
+}
+
+// Work model of Table 2 turned into a time guess: the direct method is a dense
+// fp32 contraction, the FFT method is bound by streaming the kernel spectra.
+static int model_choice(const Geom& g)
+{
+    const double macs = (double)g.f * g.fo * (double)g.ovol() * (double)g.kvol();
+    const double t_direct = 3.0 * 2.0 * macs / 60e12;
+    const double spec = 8.0 * (double)g.svol();
+    const double per_pass = spec * g.f * g.fo * 2.0 + spec * (g.f + g.fo) * 6.0;
+    const double t_fft = (3.0 * per_pass + spec * g.f * g.fo * 4.0) / 3e12 + 60e-6;
+    return t_fft < t_direct ? ZNN_FFT : ZNN_DIRECT;
+}
+
+static int validate_desc(const znn_conv_desc* d, Geom* g)
+{
+    if (!d) return fail(ZNN_EINVAL, "descriptor is NULL");
+    if (d->fan_in < 1 || d->fan_out < 1)
+        return fail(ZNN_EINVAL, "fan_in and fan_out must be >= 1 (got %d, %d)", d->fan_in, d->fan_out);
+    const int n[3] = {d->image.z, d->image.y, d->image.x};
+    const int k[3] = {d->kernel.z, d->kernel.y, d->kernel.x};
+    const int sp[3] = {d->sparsity.z, d->sparsity.y, d->sparsity.x};
+    for (int a = 0; a < 3; ++a) {
+        if (n[a] < 1 || k[a] < 1) return fail(ZNN_EINVAL, "image and kernel extents must be >= 1");
+        if (k[a] > n[a])
+            return fail(ZNN_EINVAL, "kernel extent %d exceeds image extent %d on axis %d", k[a], n[a], a);
+    }
+    for (int a = 0; a < 3; ++a)
+        if (sp[a] != 1) return fail(ZNN_EUNSUPPORTED, "sparse convolution (sparsity != 1) is not supported");
+    if (d->mode != ZNN_DIRECT && d->mode != ZNN_FFT && d->mode != ZNN_AUTO)
+        return fail(ZNN_EINVAL, "unknown mode %d", d->mode);
+    g->f = d->fan_in; g->fo = d->fan_out;
+    g->nz = n[0]; g->ny = n[1]; g->nx = n[2];
+    g->kz = k[0]; g->ky = k[1]; g->kx = k[2];
+    g->oz = n[0] - k[0] + 1; g->oy = n[1] - k[1] + 1; g->ox = n[2] - k[2] + 1;
+    if ((double)g->nvol() >= 2147483648.0)
+        return fail(ZNN_EUNSUPPORTED, "image volume does not fit 32-bit voxel offsets");
+    g->Nz = next_fft_extent(n[0]); g->Ny = next_fft_extent(n[1]); g->Nx = next_fft_extent(n[2]);
+    g->Nxh = g->Nx / 2 + 1;
+    return ZNN_OK;
+}
+
+static bool aligned256(const void* p) { return ((uintptr_t)p & 255) == 0; }
+
+static int check_ws(const znn_plan* p, int pass, void* ws, size_t ws_bytes)
+{
+    size_t need = 0;
+    int rc = znn_plan_workspace_bytes(p, pass, &need);
+    if (rc != ZNN_OK) return rc;
+    if (need == 0) return ZNN_OK;
+    if (!ws) return fail(ZNN_EWORKSPACE, "workspace is NULL but %zu bytes are needed", need);
+    if (!aligned256(ws)) return fail(ZNN_EWORKSPACE, "workspace is not 256-byte aligned");
+    if (ws_bytes < need) return fail(ZNN_EWORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, need);
+    return ZNN_OK;
+}
+
+}  // namespace znn
+
+using namespace znn;
+
+extern "C" {
+
+const char* znn_last_error(void) { return g_err; }
+
+int znn_plan_create(const znn_conv_desc* desc, znn_plan** plan)
+{
+    if (!plan) return fail(ZNN_EINVAL, "plan output pointer is NULL");
+    Geom g;
+    int rc = validate_desc(desc, &g);
+    if (rc != ZNN_OK) return rc;
+    int mode = desc->mode;
+    if (mode == ZNN_AUTO) {
+        std::lock_guard<std::mutex> lk(g_tune_mu);
+        auto it = g_tune.find(key_of(*desc));
+        mode = (it != g_tune.end()) ? it->second : model_choice(g);
+        if (mode == ZNN_FFT && (g.Nz > kMaxFftExtent || g.Ny > kMaxFftExtent || g.Nx > kMaxFftExtent))
+            mode = ZNN_DIRECT;
+    }
+    if (mode == ZNN_FFT && (g.Nz > kMaxFftExtent || g.Ny > kMaxFftExtent || g.Nx > kMaxFftExtent))
+        return fail(ZNN_EUNSUPPORTED, "FFT extents above %d are not supported", kMaxFftExtent);
+    znn_plan* p = new (std::nothrow) znn_plan;
+    if (!p) return fail(ZNN_EINVAL, "out of host memory");
+    p->desc = *desc;
+    p->g = g;
+    p->mode = mode;
+    p->resident = nullptr;
+    *plan = p;
+    return ZNN_OK;
+}
+
+void znn_plan_destroy(znn_plan* plan) { delete plan; }
+
+int znn_plan_mode(const znn_plan* plan, int32_t* mode)
+{
+    if (!plan || !mode) return fail(ZNN_EINVAL, "NULL argument");
+    *mode = plan->mode;
+    return ZNN_OK;
+}
+
+int znn_plan_fft_extents(const znn_plan* plan, znn_vec3* N)
+{
+    if (!plan || !N) return fail(ZNN_EINVAL, "NULL argument");
+    N->z = plan->g.Nz; N->y = plan->g.Ny; N->x = plan->g.Nx;
+    return ZNN_OK;
+}
+
+int znn_plan_workspace_bytes(const znn_plan* plan, int32_t pass, size_t* bytes)
+{
+    if (!plan || !bytes) return fail(ZNN_EINVAL, "NULL argument");
+    if (pass < ZNN_PASS_FWD || pass > ZNN_PASS_WGRAD) return fail(ZNN_EINVAL, "unknown pass %d", pass);
+    if (plan->mode == ZNN_DIRECT) *bytes = direct_workspace_bytes(plan->g, pass);
+    else *bytes = fft_workspace(plan->g, pass, plan->resident != nullptr).total;
+    return ZNN_OK;
+}
+
+int znn_plan_spectra_bytes(const znn_plan* plan, size_t* bytes)
+{
+    if (!plan || !bytes) return fail(ZNN_EINVAL, "NULL argument");
+    *bytes = fft_spectra_bytes(plan->g);
+    return ZNN_OK;
+}
+
+int znn_conv_prepare_kernels(znn_plan* plan, const float* w, void* spectra, size_t spectra_bytes,
+                             void* ws, size_t ws_bytes, void* stream)
+{
+    (void)ws; (void)ws_bytes;
+    if (!plan || !w) return fail(ZNN_EINVAL, "NULL argument");
+    if (plan->mode != ZNN_FFT) return fail(ZNN_EINVAL, "kernel spectra exist only for the FFT method");
+    const size_t need = fft_spectra_bytes(plan->g);
+    if (!spectra) return fail(ZNN_EWORKSPACE, "spectra buffer is NULL");
+    if (!aligned256(spectra)) return fail(ZNN_EWORKSPACE, "spectra buffer is not 256-byte aligned");
+    if (spectra_bytes < need) return fail(ZNN_EWORKSPACE, "spectra buffer has %zu bytes, %zu needed", spectra_bytes, need);
+    int rc = fft_kernel_spectra(plan->g, w, (float2*)spectra, (hipStream_t)stream);
+    if (rc != ZNN_OK) return rc;
+    plan->resident = (const float2*)spectra;
+    return ZNN_OK;
+}
+
+int znn_conv_release_kernels(znn_plan* plan)
+{
+    if (!plan) return fail(ZNN_EINVAL, "NULL argument");
+    plan->resident = nullptr;
+    return ZNN_OK;
+}
+
+int znn_conv3d_fwd(znn_plan* plan, const float* in, const float* w, float* out,
+                   void* ws, size_t ws_bytes, void* stream)
+{
+    if (!plan || !in || !out) return fail(ZNN_EINVAL, "NULL argument");
+    if (!w && !(plan->mode == ZNN_FFT && plan->resident)) return fail(ZNN_EINVAL, "kernel pointer is NULL");
+    int rc = check_ws(plan, ZNN_PASS_FWD, ws, ws_bytes);
+    if (rc != ZNN_OK) return rc;
+    if (plan->mode == ZNN_DIRECT) return direct_fwd(plan->g, in, w, out, ws, (hipStream_t)stream);
+    return fft_fwd(plan->g, in, w, plan->resident, out, ws, (hipStream_t)stream);
+}
+
+int znn_conv3d_bwd(znn_plan* plan, const float* gout, const float* w, float* gin,
+                   void* ws, size_t ws_bytes, void* stream)
+{
+    if (!plan || !gout || !gin) return fail(ZNN_EINVAL, "NULL argument");
+    if (!w && !(plan->mode == ZNN_FFT && plan->resident)) return fail(ZNN_EINVAL, "kernel pointer is NULL");
+    int rc = check_ws(plan, ZNN_PASS_BWD, ws, ws_bytes);
+    if (rc != ZNN_OK) return rc;
+    if (plan->mode == ZNN_DIRECT) return direct_bwd(plan->g, gout, w, gin, ws, (hipStream_t)stream);
+    return fft_bwd(plan->g, gout, w, plan->resident, gin, ws, (hipStream_t)stream);
+}
+
+int znn_conv3d_wgrad(znn_plan* plan, const float* in, const float* gout, float* gw,
+                     void* ws, size_t ws_bytes, void* stream)
+{
+    if (!plan || !in || !gout || !gw) return fail(ZNN_EINVAL, "NULL argument");
+    int rc = check_ws(plan, ZNN_PASS_WGRAD, ws, ws_bytes);
+    if (rc != ZNN_OK) return rc;
+    if (plan->mode == ZNN_DIRECT) return direct_wgrad(plan->g, in, gout, gw, ws, (hipStream_t)stream);
+    return fft_wgrad(plan->g, in, gout, gw, ws, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------- autotuner
+static size_t tune_tensor_bytes(const Geom& g, size_t off[6])
+{
+    size_t o = 0;
+    off[0] = o; o += align256(sizeof(float) * g.f * g.nvol());                 // in
+    off[1] = o; o += align256(sizeof(float) * g.fo * g.f * g.kvol());          // w
+    off[2] = o; o += align256(sizeof(float) * g.fo * g.ovol());                // gout
+    off[3] = o; o += align256(sizeof(float) * g.f * g.nvol());                 // gin
+    off[4] = o; o += align256(sizeof(float) * g.fo * g.f * g.kvol());          // gw
+    off[5] = o; o += align256(sizeof(float) * g.fo * g.ovol());                // out
+    return o;
+}
+
+static size_t tune_scratch_bytes(const Geom& g, bool fft_ok)
+{
+    size_t m = 0;
+    for (int pass = 0; pass < 3; ++pass) {
+        size_t d = direct_workspace_bytes(g, pass);
+        if (d > m) m = d;
+        if (fft_ok) {
+            size_t f = fft_workspace(g, pass, false).total;
+            if (f > m) m = f;
+        }
+    }
+    return m;
+}
+
+int znn_autotune_workspace_bytes(const znn_conv_desc* desc, size_t* bytes)
+{
+    if (!bytes) return fail(ZNN_EINVAL, "NULL argument");
+    Geom g;
+    int rc = validate_desc(desc, &g);
+    if (rc != ZNN_OK) return rc;
+    const bool fft_ok = g.Nz <= kMaxFftExtent && g.Ny <= kMaxFftExtent && g.Nx <= kMaxFftExtent;
+    size_t off[6];
+    *bytes = tune_tensor_bytes(g, off) + tune_scratch_bytes(g, fft_ok);
+    return ZNN_OK;
+}
+
+int znn_autotune(const znn_conv_desc* desc, void* ws, size_t ws_bytes, void* stream,
+                 int32_t* chosen_mode, float ms[2][3])
+{
+    if (!chosen_mode || !ms) return fail(ZNN_EINVAL, "NULL argument");
+    Geom g;
+    int rc = validate_desc(desc, &g);
+    if (rc != ZNN_OK) return rc;
+    const bool fft_ok = g.Nz <= kMaxFftExtent && g.Ny <= kMaxFftExtent && g.Nx <= kMaxFftExtent;
+    size_t off[6];
+    const size_t tensors = tune_tensor_bytes(g, off);
+    const size_t scratch = tune_scratch_bytes(g, fft_ok);
+    if (!ws) return fail(ZNN_EWORKSPACE, "workspace is NULL");
+    if (!aligned256(ws)) return fail(ZNN_EWORKSPACE, "workspace is not 256-byte aligned");
+    if (ws_bytes < tensors + scratch)
+        return fail(ZNN_EWORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, tensors + scratch);
+    hipStream_t s = (hipStream_t)stream;
+    char* base = (char*)ws;
+    float* in = (float*)(base + off[0]);
+    float* w = (float*)(base + off[1]);
+    float* gout = (float*)(base + off[2]);
+    float* gin = (float*)(base + off[3]);
+    float* gw = (float*)(base + off[4]);
+    float* out = (float*)(base + off[5]);
+    void* scr = base + tensors;
+    if ((rc = fill_pattern(in, (long)g.f * g.nvol(), 1.0f, s)) != ZNN_OK) return rc;
+    if ((rc = fill_pattern(w, (long)g.fo * g.f * g.kvol(), 1.0f / std::sqrt((float)(g.f * g.kvol())), s)) != ZNN_OK) return rc;
+    if ((rc = fill_pattern(gout, (long)g.fo * g.ovol(), 1.0f, s)) != ZNN_OK) return rc;
+
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
+        return fail(ZNN_EHIP, "hipEventCreate failed");
+    const int warm = 2, timed = 5;
+    for (int m = 0; m < 2; ++m)
+        for (int p = 0; p < 3; ++p) ms[m][p] = INFINITY;
+    rc = ZNN_OK;
+    for (int mode = 0; mode < 2 && rc == ZNN_OK; ++mode) {
+        if (mode == ZNN_FFT && !fft_ok) continue;
+        for (int pass = 0; pass < 3 && rc == ZNN_OK; ++pass) {
+            for (int it = 0; it < warm + timed && rc == ZNN_OK; ++it) {
+                if (it == warm) (void)hipEventRecord(e0, s);
+                if (mode == ZNN_DIRECT) {
+                    if (pass == 0) rc = direct_fwd(g, in, w, out, scr, s);
+                    else if (pass == 1) rc = direct_bwd(g, gout, w, gin, scr, s);
+                    else rc = direct_wgrad(g, in, gout, gw, scr, s);
+                } else {
+                    if (pass == 0) rc = fft_fwd(g, in, w, nullptr, out, scr, s);
+                    else if (pass == 1) rc = fft_bwd(g, gout, w, nullptr, gin, scr, s);
+                    else rc = fft_wgrad(g, in, gout, gw, scr, s);
+                }
+            }
+            if (rc != ZNN_OK) break;
+            (void)hipEventRecord(e1, s);
+            if (hipEventSynchronize(e1) != hipSuccess) { rc = fail(ZNN_EHIP, "hipEventSynchronize failed"); break; }
+            float t = 0.f;
+            (void)hipEventElapsedTime(&t, e0, e1);
+            ms[mode][pass] = t / timed;
+        }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc != ZNN_OK) return rc;
+    const float td = ms[0][0] + ms[0][1] + ms[0][2];
+    const float tf = ms[1][0] + ms[1][1] + ms[1][2];
+    const int choice = (fft_ok && tf < td) ? ZNN_FFT : ZNN_DIRECT;
+    {
+        std::lock_guard<std::mutex> lk(g_tune_mu);
+        g_tune[key_of(*desc)] = choice;
+    }
+    *chosen_mode = choice;
+    return ZNN_OK;
+}
+
+}  // extern "C"

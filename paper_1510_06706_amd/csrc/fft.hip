@@ -1,0 +1,617 @@
+// FFT method (Section 4): batched 3D real-to-complex and inverse transforms
+// whose 1D passes run entirely in LDS, the per-frequency complex
+// multiply-accumulate that fuses the sum over convergent edges, and the pruned
+// inverse transforms of the kernel gradient.
+//
+// A 3D transform is three launches, one per axis.  Every launch stages a batch
+// of W pencils in LDS as data[element][pencil] (pencil fastest, row length Wp
+// odd so that the transposing loads and stores spread over the banks), runs a
+// Stockham autosort FFT with radices 4/2/3/5 between two LDS buffers, and
+// writes the result back.  Input rows known to be zero (padding) are never
+// read and output rows nobody needs (outside the crop) are never written, so
+// the transforms of the small kernels and the cropped inverses are pruned for
+// free.
+//
+// Spectra are stored as [map][N_z][N_y][N_x/2+1] complex fp32.
+//
+// Fourier-domain identities used (G_s = output gradient embedded at offset k-1
+// in the N-volume; any N >= n is free of wrap-around):
+//   forward   out = crop_{[k-1, n-1]} IFFT( sum_i W^[j][i] I^[i] )
+//   backward  gin = crop_{[0, n)}     IFFT( sum_j conj(W^[j][i]) G_s^[j] )
+//   gradient  gw  = crop_{[0, k)}     IFFT( G_s^[j] conj(I^[i]) )
+#include "znn_internal.h"
+
+namespace znn {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kLdsBudget = 64 * 1024;
+
+struct Radices { int n; int r[12]; };
+
+Radices factorize(int N)
+{
+    Radices R; R.n = 0;
+    while (N % 4 == 0) { R.r[R.n++] = 4; N /= 4; }
+    while (N % 2 == 0) { R.r[R.n++] = 2; N /= 2; }
+    while (N % 3 == 0) { R.r[R.n++] = 3; N /= 3; }
+    while (N % 5 == 0) { R.r[R.n++] = 5; N /= 5; }
+    return R;
+}
+
+// Largest odd pencil-row length such that two N x Wp buffers plus N twiddles fit.
+int max_row_len(int N)
+{
+    int lim = (kLdsBudget / 8 - N) / (2 * N);
+    if (lim < 1) lim = 1;
+    if ((lim & 1) == 0) --lim;
+    return lim;
+}
+
+size_t lds_bytes(int N, int Wp) { return (size_t)(2 * N * Wp + N) * sizeof(float2); }
+
+__device__ __forceinline__ float2 cadd(float2 a, float2 b) { return make_float2(a.x + b.x, a.y + b.y); }
+__device__ __forceinline__ float2 csub(float2 a, float2 b) { return make_float2(a.x - b.x, a.y - b.y); }
+__device__ __forceinline__ float2 cmul(float2 a, float2 b)
+{
+    return make_float2(a.x * b.x - a.y * b.y, a.x * b.y + a.y * b.x);
+}
+// multiply by  DIR * i
+template <int DIR> __device__ __forceinline__ float2 mul_di(float2 a)
+{
+    return DIR > 0 ? make_float2(-a.y, a.x) : make_float2(a.y, -a.x);
+}
+
+__device__ __forceinline__ void make_twiddles(float2* tw, int N, int dir)
+{
+    for (int t = threadIdx.x; t < N; t += kThreads) {
+        float s, c;
+        sincospif(2.0f * (float)t / (float)N, &s, &c);
+        tw[t] = make_float2(c, dir > 0 ? s : -s);
+    }
+}
+
+// Stockham autosort FFT of W pencils of length N held as src[e * Wp + p].
+// DIR = -1: forward kernel exp(-2 pi i jk/N); DIR = +1: unnormalised inverse.
+// Returns the buffer that holds the result (natural order).
+template <int DIR>
+__device__ float2* lds_fft(float2* src, float2* dst, const float2* tw, int N, int W, int Wp,
+                           const Radices& R)
+{
+    int s = 1, n = N;
+    for (int ri = 0; ri < R.n; ++ri) {
+        const int r = R.r[ri];
+        const int m = n / r;
+        const int units = m * s * W;
+        const int xs = s * m * Wp;   // distance between the r inputs of a butterfly
+        const int ys = s * Wp;       // distance between its r outputs
+        for (int u = threadIdx.x; u < units; u += kThreads) {
+            const int p = u % W;
+            const int t = u / W;
+            const int q = t % s;
+            const int pp = t / s;
+            const float2* x = src + (q + s * pp) * Wp + p;
+            float2* y = dst + (q + s * r * pp) * Wp + p;
+            const int ti = pp * s;   // twiddle index for output 1: exp(DIR 2 pi i pp / n)
+            if (r == 4) {
+                const float2 a0 = x[0], a1 = x[xs], a2 = x[2 * xs], a3 = x[3 * xs];
+                const float2 s02 = cadd(a0, a2), d02 = csub(a0, a2);
+                const float2 s13 = cadd(a1, a3), d13 = mul_di<DIR>(csub(a1, a3));
+                y[0] = cadd(s02, s13);
+                y[ys] = cmul(cadd(d02, d13), tw[ti]);
+                y[2 * ys] = cmul(csub(s02, s13), tw[2 * ti]);
+                y[3 * ys] = cmul(csub(d02, d13), tw[3 * ti]);
+            } else if (r == 2) {
+                const float2 a0 = x[0], a1 = x[xs];
+                y[0] = cadd(a0, a1);
+                y[ys] = cmul(csub(a0, a1), tw[ti]);
+            } else if (r == 3) {
+                const float2 a0 = x[0], a1 = x[xs], a2 = x[2 * xs];
+                const float2 t1 = cadd(a1, a2);
+                const float2 t2 = make_float2(a0.x - 0.5f * t1.x, a0.y - 0.5f * t1.y);
+                float2 t3 = csub(a1, a2);
+                t3 = mul_di<DIR>(make_float2(0.8660254037844386f * t3.x, 0.8660254037844386f * t3.y));
+                y[0] = cadd(a0, t1);
+                y[ys] = cmul(cadd(t2, t3), tw[ti]);
+                y[2 * ys] = cmul(csub(t2, t3), tw[2 * ti]);
+            } else {   // r == 5
+                const float c1 = 0.30901699437494745f, c2 = -0.8090169943749475f;
+                const float s1 = 0.9510565162951535f, s2 = 0.5877852522924731f;
+                const float2 a0 = x[0], a1 = x[xs], a2 = x[2 * xs], a3 = x[3 * xs], a4 = x[4 * xs];
+                const float2 t1 = cadd(a1, a4), t2 = cadd(a2, a3), t3 = csub(a1, a4), t4 = csub(a2, a3);
+                const float2 m1 = make_float2(a0.x + c1 * t1.x + c2 * t2.x, a0.y + c1 * t1.y + c2 * t2.y);
+                const float2 m2 = make_float2(a0.x + c2 * t1.x + c1 * t2.x, a0.y + c2 * t1.y + c1 * t2.y);
+                const float2 n1 = mul_di<DIR>(make_float2(s1 * t3.x + s2 * t4.x, s1 * t3.y + s2 * t4.y));
+                const float2 n2 = mul_di<DIR>(make_float2(s2 * t3.x - s1 * t4.x, s2 * t3.y - s1 * t4.y));
+                y[0] = cadd(a0, cadd(t1, t2));
+                y[ys] = cmul(cadd(m1, n1), tw[ti]);
+                y[2 * ys] = cmul(cadd(m2, n2), tw[2 * ti]);
+                y[3 * ys] = cmul(csub(m2, n2), tw[3 * ti]);
+                y[4 * ys] = cmul(csub(m1, n1), tw[4 * ti]);
+            }
+        }
+        __syncthreads();
+        float2* tmp = src; src = dst; dst = tmp;
+        n = m;
+        s *= r;
+    }
+    return src;
+}
+
+// ---------------------------------------------------------------- x axis, real -> complex
+// Source rows are the x-lines of real images [maps][sz][sy][sx]; row (map,z,y)
+// lands at spectrum row (map, z+oz, y+oy) with its samples at x+ox of an
+// N_x-long zero line.  Two real rows share one complex transform.
+struct R2CParams {
+    const float* src; float2* dst;
+    long rows;
+    int sz, sy, sx;
+    int Nz, Ny, Nx, Nxh;
+    int oz, oy, ox;
+    int W, Wp;
+    Radices rad;
+};
+
+__global__ void __launch_bounds__(kThreads) k_fft_r2c_x(R2CParams P)
+{
+    extern __shared__ float2 lds[];
+    const int N = P.Nx, Wp = P.Wp;
+    float2* a = lds;
+    float2* b = lds + N * Wp;
+    float2* tw = lds + 2 * N * Wp;
+    make_twiddles(tw, N, -1);
+    for (int t = threadIdx.x; t < N * Wp; t += kThreads) a[t] = make_float2(0.f, 0.f);
+    __syncthreads();
+    const long row0 = (long)blockIdx.x * (2 * P.W);
+    const int nrows = (int)min((long)(2 * P.W), P.rows - row0);
+    float* af = reinterpret_cast<float*>(a);
+    for (int t = threadIdx.x; t < nrows * P.sx; t += kThreads) {
+        const int r = t / P.sx, x = t % P.sx;
+        af[2 * ((x + P.ox) * Wp + (r >> 1)) + (r & 1)] = P.src[(row0 + r) * P.sx + x];
+    }
+    __syncthreads();
+    const int npen = (nrows + 1) >> 1;
+    const float2* res = lds_fft<-1>(a, b, tw, N, npen, Wp, P.rad);
+    // split the packed transform: A = (Z[k] + conj Z[N-k]) / 2,  B = (Z[k] - conj Z[N-k]) / (2i)
+    for (int t = threadIdx.x; t < nrows * P.Nxh; t += kThreads) {
+        const int r = t / P.Nxh, k = t % P.Nxh;
+        const long row = row0 + r;
+        const int y = (int)(row % P.sy);
+        const int z = (int)((row / P.sy) % P.sz);
+        const long map = row / ((long)P.sy * P.sz);
+        const float2 z1 = res[k * Wp + (r >> 1)];
+        const float2 z2 = res[(k == 0 ? 0 : N - k) * Wp + (r >> 1)];
+        float2 v;
+        if ((r & 1) == 0) v = make_float2(0.5f * (z1.x + z2.x), 0.5f * (z1.y - z2.y));
+        else              v = make_float2(0.5f * (z1.y + z2.y), 0.5f * (z2.x - z1.x));
+        P.dst[((map * P.Nz + z + P.oz) * P.Ny + (y + P.oy)) * P.Nxh + k] = v;
+    }
+}
+
+// ---------------------------------------------------------------- x axis, complex -> real
+// Rows (map, z+cz, y+cy) of a Hermitian half-spectrum become real lines; only
+// samples x in [cx, cx+dx) are written, scaled.  Two rows share one transform.
+struct C2RParams {
+    const float2* src; float* dst;
+    long rows;                  // maps * dz * dy
+    int cz, cy, cx;
+    int dz, dy, dx;
+    int Nz, Ny, Nx, Nxh;
+    float scale;
+    int W, Wp;
+    Radices rad;
+};
+
+__global__ void __launch_bounds__(kThreads) k_fft_c2r_x(C2RParams P)
+{
+    extern __shared__ float2 lds[];
+    const int N = P.Nx, Wp = P.Wp;
+    float2* a = lds;
+    float2* b = lds + N * Wp;
+    float2* tw = lds + 2 * N * Wp;
+    make_twiddles(tw, N, +1);
+    const long row0 = (long)blockIdx.x * (2 * P.W);
+    const int nrows = (int)min((long)(2 * P.W), P.rows - row0);
+    const int npen = (nrows + 1) >> 1;
+    for (int t = threadIdx.x; t < npen * P.Nxh; t += kThreads) {
+        const int p = t / P.Nxh, k = t % P.Nxh;
+        float2 A, B = make_float2(0.f, 0.f);
+        {
+            const long row = row0 + 2 * p;
+            const int y = (int)(row % P.dy);
+            const int z = (int)((row / P.dy) % P.dz);
+            const long map = row / ((long)P.dy * P.dz);
+            A = P.src[((map * P.Nz + z + P.cz) * P.Ny + (y + P.cy)) * P.Nxh + k];
+        }
+        if (2 * p + 1 < nrows) {
+            const long row = row0 + 2 * p + 1;
+            const int y = (int)(row % P.dy);
+            const int z = (int)((row / P.dy) % P.dz);
+            const long map = row / ((long)P.dy * P.dz);
+            B = P.src[((map * P.Nz + z + P.cz) * P.Ny + (y + P.cy)) * P.Nxh + k];
+        }
+        // Z = A + iB on the stored half, Hermitian extension on the rest; the
+        // imaginary parts of the DC and Nyquist bins of a real line are zero.
+        if (k == 0 || 2 * k == N) {
+            a[k * Wp + p] = make_float2(A.x, B.x);
+        } else {
+            a[k * Wp + p] = make_float2(A.x - B.y, A.y + B.x);
+            a[(N - k) * Wp + p] = make_float2(A.x + B.y, B.x - A.y);
+        }
+    }
+    __syncthreads();
+    const float2* res = lds_fft<+1>(a, b, tw, N, npen, Wp, P.rad);
+    const float* rf = reinterpret_cast<const float*>(res);
+    for (int t = threadIdx.x; t < nrows * P.dx; t += kThreads) {
+        const int r = t / P.dx, x = t % P.dx;
+        P.dst[(row0 + r) * P.dx + x] = P.scale * rf[2 * ((x + P.cx) * Wp + (r >> 1)) + (r & 1)];
+    }
+}
+
+// ---------------------------------------------------------------- strided axis, complex -> complex
+// Pencils run along an axis with element stride `in_stride`; L neighbouring
+// pencils are contiguous in memory and are cut into chunks of W.  Three outer
+// indices (counts Oa, Ob, Oc) enumerate the remaining dimensions.  Only input
+// elements [i0, i0+ni) are read (the rest are zero) and only output elements
+// [o0, o0+no) are written, at out + e * out_stride.  With `in2` set the input
+// is the product in[...] * conj(in2[...]) (kernel gradient).
+struct AxisParams {
+    const float2* in; const float2* in2; float2* out;
+    int N, i0, ni, o0, no;
+    long in_stride, out_stride;
+    int L, W, Wp, chunks;
+    int Oa, Ob, Oc;
+    long in_sa, in_sb, in_sc;
+    long in2_sa, in2_sb, in2_sc;
+    long out_sa, out_sb, out_sc;
+    Radices rad;
+};
+
+template <int DIR, bool PRODUCT>
+__global__ void __launch_bounds__(kThreads) k_fft_axis(AxisParams P)
+{
+    extern __shared__ float2 lds[];
+    const int N = P.N, Wp = P.Wp;
+    float2* a = lds;
+    float2* b = lds + N * Wp;
+    float2* tw = lds + 2 * N * Wp;
+    make_twiddles(tw, N, DIR);
+    const long blk = blockIdx.x;
+    const int chunk = (int)(blk % P.chunks);
+    long o = blk / P.chunks;
+    const int oc = (int)(o % P.Oc); o /= P.Oc;
+    const int ob = (int)(o % P.Ob);
+    const int oa = (int)(o / P.Ob);
+    const int p0 = chunk * P.W;
+    const int w = min(P.W, P.L - p0);
+    if (P.ni < N) {
+        for (int t = threadIdx.x; t < N * Wp; t += kThreads) a[t] = make_float2(0.f, 0.f);
+        __syncthreads();
+    }
+    const float2* in = P.in + (oa * P.in_sa + ob * P.in_sb + oc * P.in_sc) + p0;
+    const float2* in2 = PRODUCT ? P.in2 + (oa * P.in2_sa + ob * P.in2_sb + oc * P.in2_sc) + p0 : nullptr;
+    for (int t = threadIdx.x; t < P.ni * w; t += kThreads) {
+        const int e = t / w + P.i0, p = t % w;
+        float2 v = in[e * P.in_stride + p];
+        if (PRODUCT) {
+            const float2 c = in2[e * P.in_stride + p];
+            v = make_float2(v.x * c.x + v.y * c.y, v.y * c.x - v.x * c.y);   // v * conj(c)
+        }
+        a[e * Wp + p] = v;
+    }
+    __syncthreads();
+    const float2* res = lds_fft<DIR>(a, b, tw, N, w, Wp, P.rad);
+    float2* out = P.out + (oa * P.out_sa + ob * P.out_sb + oc * P.out_sc) + p0;
+    for (int t = threadIdx.x; t < P.no * w; t += kThreads) {
+        const int e = t / w + P.o0, p = t % w;
+        out[e * P.out_stride + p] = res[e * Wp + p];
+    }
+}
+
+// ---------------------------------------------------------------- per-frequency multiply-accumulate
+// Forward: O^[j][w] = sum_i W^[j][i][w] I^[i][w].  A thread owns one frequency
+// and G output nodes; the kernel spectra are streamed exactly once.
+constexpr int kMacGroup = 8;
+
+__global__ void __launch_bounds__(kThreads)
+k_mac_fwd(int f, int fo, long svol, const float2* __restrict__ What, const float2* __restrict__ Ihat,
+          float2* __restrict__ Ohat)
+{
+    const long wv = (long)blockIdx.x * kThreads + threadIdx.x;
+    if (wv >= svol) return;
+    const int j0 = blockIdx.y * kMacGroup;
+    float2 acc[kMacGroup];
+#pragma unroll
+    for (int g = 0; g < kMacGroup; ++g) acc[g] = make_float2(0.f, 0.f);
+    for (int i = 0; i < f; ++i) {
+        const float2 x = Ihat[i * svol + wv];
+#pragma unroll
+        for (int g = 0; g < kMacGroup; ++g) {
+            if (j0 + g < fo) {
+                const float2 k = What[((long)(j0 + g) * f + i) * svol + wv];
+                acc[g].x = fmaf(k.x, x.x, fmaf(-k.y, x.y, acc[g].x));
+                acc[g].y = fmaf(k.x, x.y, fmaf(k.y, x.x, acc[g].y));
+            }
+        }
+    }
+#pragma unroll
+    for (int g = 0; g < kMacGroup; ++g)
+        if (j0 + g < fo) Ohat[(long)(j0 + g) * svol + wv] = acc[g];
+}
+
+// Backward: Gin^[i][w] = sum_j conj(W^[j][i][w]) G^[j][w].
+__global__ void __launch_bounds__(kThreads)
+k_mac_bwd(int f, int fo, long svol, const float2* __restrict__ What, const float2* __restrict__ Ghat,
+          float2* __restrict__ Ginhat)
+{
+    const long wv = (long)blockIdx.x * kThreads + threadIdx.x;
+    if (wv >= svol) return;
+    const int i0 = blockIdx.y * kMacGroup;
+    float2 acc[kMacGroup];
+#pragma unroll
+    for (int g = 0; g < kMacGroup; ++g) acc[g] = make_float2(0.f, 0.f);
+    for (int j = 0; j < fo; ++j) {
+        const float2 x = Ghat[j * svol + wv];
+#pragma unroll
+        for (int g = 0; g < kMacGroup; ++g) {
+            if (i0 + g < f) {
+                const float2 k = What[((long)j * f + (i0 + g)) * svol + wv];
+                acc[g].x = fmaf(k.x, x.x, fmaf(k.y, x.y, acc[g].x));
+                acc[g].y = fmaf(k.x, x.y, fmaf(-k.y, x.x, acc[g].y));
+            }
+        }
+    }
+#pragma unroll
+    for (int g = 0; g < kMacGroup; ++g)
+        if (i0 + g < f) Ginhat[(long)(i0 + g) * svol + wv] = acc[g];
+}
+
+// ---------------------------------------------------------------- launch helpers
+int launch_r2c(const float* src, float2* dst, long maps, int sz, int sy, int sx,
+               int Nz, int Ny, int Nx, int oz, int oy, int ox, hipStream_t s)
+{
+    R2CParams P;
+    P.src = src; P.dst = dst;
+    P.rows = maps * sz * sy;
+    P.sz = sz; P.sy = sy; P.sx = sx;
+    P.Nz = Nz; P.Ny = Ny; P.Nx = Nx; P.Nxh = Nx / 2 + 1;
+    P.oz = oz; P.oy = oy; P.ox = ox;
+    int wp = max_row_len(Nx);
+    if (wp > 33) wp = 33;
+    P.W = wp; P.Wp = wp;
+    P.rad = factorize(Nx);
+    const long blocks = (P.rows + 2 * P.W - 1) / (2 * P.W);
+    if (blocks >= 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many rows for one launch");
+    hipLaunchKernelGGL(k_fft_r2c_x, dim3((unsigned)blocks), dim3(kThreads), lds_bytes(Nx, P.Wp), s, P);
+    return check_launch("r2c x pass");
+}
+
+int launch_c2r(const float2* src, float* dst, long maps, int Nz, int Ny, int Nx,
+               int cz, int cy, int cx, int dz, int dy, int dx, float scale, hipStream_t s)
+{
+    C2RParams P;
+    P.src = src; P.dst = dst;
+    P.rows = maps * dz * dy;
+    P.cz = cz; P.cy = cy; P.cx = cx;
+    P.dz = dz; P.dy = dy; P.dx = dx;
+    P.Nz = Nz; P.Ny = Ny; P.Nx = Nx; P.Nxh = Nx / 2 + 1;
+    P.scale = scale;
+    int wp = max_row_len(Nx);
+    if (wp > 33) wp = 33;
+    P.W = wp; P.Wp = wp;
+    P.rad = factorize(Nx);
+    const long blocks = (P.rows + 2 * P.W - 1) / (2 * P.W);
+    if (blocks >= 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many rows for one launch");
+    hipLaunchKernelGGL(k_fft_c2r_x, dim3((unsigned)blocks), dim3(kThreads), lds_bytes(Nx, P.Wp), s, P);
+    return check_launch("c2r x pass");
+}
+
+// Fills the chunking fields and launches.  `P` arrives with everything else set.
+int launch_axis(AxisParams P, int dir, hipStream_t s)
+{
+    if (P.N == 1 && !P.in2 && P.in == P.out && P.in_stride == P.out_stride &&
+        P.in_sa == P.out_sa && P.in_sb == P.out_sb && P.in_sc == P.out_sc)
+        return ZNN_OK;   // length-1 transform in place: nothing to do
+    const int wmax = max_row_len(P.N) > 63 ? 63 : max_row_len(P.N);
+    const int chunks = (P.L + wmax - 1) / wmax;
+    P.chunks = chunks;
+    P.W = (P.L + chunks - 1) / chunks;
+    P.Wp = P.W | 1;
+    P.rad = factorize(P.N);
+    const long blocks = (long)P.Oa * P.Ob * P.Oc * chunks;
+    if (blocks >= 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many pencils for one launch");
+    const size_t lds = lds_bytes(P.N, P.Wp);
+    const dim3 grid((unsigned)blocks), block(kThreads);
+    if (P.in2) {
+        if (dir > 0) hipLaunchKernelGGL((k_fft_axis<+1, true>), grid, block, lds, s, P);
+        else         hipLaunchKernelGGL((k_fft_axis<-1, true>), grid, block, lds, s, P);
+    } else {
+        if (dir > 0) hipLaunchKernelGGL((k_fft_axis<+1, false>), grid, block, lds, s, P);
+        else         hipLaunchKernelGGL((k_fft_axis<-1, false>), grid, block, lds, s, P);
+    }
+    return check_launch("strided FFT pass");
+}
+
+// Forward 3D transform of `maps` real volumes of extents (sz,sy,sx) embedded at
+// offset (oz,oy,ox) of the (Nz,Ny,Nx) volume.
+int forward3d(const Geom& g, const float* src, float2* spec, long maps, int sz, int sy, int sx,
+              int oz, int oy, int ox, hipStream_t s)
+{
+    int rc = launch_r2c(src, spec, maps, sz, sy, sx, g.Nz, g.Ny, g.Nx, oz, oy, ox, s);
+    if (rc != ZNN_OK) return rc;
+    const long plane = (long)g.Ny * g.Nxh, vol = g.svol();
+    if (maps > 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many maps");
+    AxisParams P = {};
+    // y: only the sz planes that hold data, rows [oy, oy+sy) are non-zero
+    P.in = spec + oz * plane; P.in2 = nullptr; P.out = spec + oz * plane;
+    P.N = g.Ny; P.i0 = oy; P.ni = sy; P.o0 = 0; P.no = g.Ny;
+    P.in_stride = P.out_stride = g.Nxh;
+    P.L = g.Nxh;
+    P.Oa = (int)maps; P.Ob = sz; P.Oc = 1;
+    P.in_sa = P.out_sa = vol; P.in_sb = P.out_sb = plane; P.in_sc = P.out_sc = 0;
+    if (!(g.Ny == 1)) { rc = launch_axis(P, -1, s); if (rc != ZNN_OK) return rc; }
+    // z: planes [oz, oz+sz) are non-zero
+    P.in = spec; P.out = spec;
+    P.N = g.Nz; P.i0 = oz; P.ni = sz; P.o0 = 0; P.no = g.Nz;
+    P.in_stride = P.out_stride = plane;
+    P.L = (int)plane;
+    P.Oa = (int)maps; P.Ob = 1; P.Oc = 1;
+    P.in_sb = P.out_sb = 0;
+    if (!(g.Nz == 1)) { rc = launch_axis(P, -1, s); if (rc != ZNN_OK) return rc; }
+    return ZNN_OK;
+}
+
+// Inverse 3D transform of `maps` spectra (destroyed) to real volumes cropped to
+// [c, c+d) per axis and scaled by 1/(Nz Ny Nx).
+int inverse3d(const Geom& g, float2* spec, float* dst, long maps, int cz, int cy, int cx,
+              int dz, int dy, int dx, hipStream_t s)
+{
+    const long plane = (long)g.Ny * g.Nxh, vol = g.svol();
+    if (maps > 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many maps");
+    int rc;
+    AxisParams P = {};
+    P.in = spec; P.in2 = nullptr; P.out = spec;
+    P.N = g.Nz; P.i0 = 0; P.ni = g.Nz; P.o0 = cz; P.no = dz;
+    P.in_stride = P.out_stride = plane;
+    P.L = (int)plane;
+    P.Oa = (int)maps; P.Ob = 1; P.Oc = 1;
+    P.in_sa = P.out_sa = vol;
+    if (g.Nz != 1) { rc = launch_axis(P, +1, s); if (rc != ZNN_OK) return rc; }
+    P.in = spec + cz * plane; P.out = spec + cz * plane;
+    P.N = g.Ny; P.i0 = 0; P.ni = g.Ny; P.o0 = cy; P.no = dy;
+    P.in_stride = P.out_stride = g.Nxh;
+    P.L = g.Nxh;
+    P.Oa = (int)maps; P.Ob = dz; P.Oc = 1;
+    P.in_sb = P.out_sb = plane;
+    if (g.Ny != 1) { rc = launch_axis(P, +1, s); if (rc != ZNN_OK) return rc; }
+    const float scale = (float)(1.0 / ((double)g.Nz * g.Ny * g.Nx));
+    return launch_c2r(spec, dst, maps, g.Nz, g.Ny, g.Nx, cz, cy, cx, dz, dy, dx, scale, s);
+}
+
+int launch_mac(bool backward, const Geom& g, const float2* What, const float2* a, float2* b, hipStream_t s)
+{
+    const long svol = g.svol();
+    const int outs = backward ? g.f : g.fo;
+    dim3 grid((unsigned)((svol + kThreads - 1) / kThreads), (unsigned)((outs + kMacGroup - 1) / kMacGroup));
+    if (backward) hipLaunchKernelGGL(k_mac_bwd, grid, dim3(kThreads), 0, s, g.f, g.fo, svol, What, a, b);
+    else          hipLaunchKernelGGL(k_mac_fwd, grid, dim3(kThreads), 0, s, g.f, g.fo, svol, What, a, b);
+    return check_launch("spectral multiply-accumulate");
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------- public (library-internal) entry points
+size_t fft_spectra_bytes(const Geom& g)
+{
+    return align256(sizeof(float2) * (size_t)g.f * g.fo * g.svol());
+}
+
+FftWorkspace fft_workspace(const Geom& g, int pass, bool resident)
+{
+    FftWorkspace w = {};
+    size_t o = 0;
+    const size_t spec = sizeof(float2) * (size_t)g.svol();
+    if (pass == ZNN_PASS_FWD || pass == ZNN_PASS_BWD) {
+        const int na = pass == ZNN_PASS_FWD ? g.f : g.fo;
+        const int nb = pass == ZNN_PASS_FWD ? g.fo : g.f;
+        w.off_a = o; o += align256(spec * na);
+        w.off_b = o; o += align256(spec * nb);
+        w.off_w = o;
+        if (!resident) o += fft_spectra_bytes(g);
+    } else {
+        const size_t pairs = (size_t)g.f * g.fo;
+        w.off_a = o; o += align256(spec * g.f);
+        w.off_b = o; o += align256(spec * g.fo);
+        w.off_t1 = o; o += align256(sizeof(float2) * pairs * g.kz * g.Ny * g.Nxh);
+        w.off_t2 = o; o += align256(sizeof(float2) * pairs * g.kz * g.ky * g.Nxh);
+    }
+    w.total = o;
+    return w;
+}
+
+int fft_kernel_spectra(const Geom& g, const float* w, float2* What, hipStream_t s)
+{
+    return forward3d(g, w, What, (long)g.f * g.fo, g.kz, g.ky, g.kx, 0, 0, 0, s);
+}
+
+int fft_fwd(const Geom& g, const float* in, const float* w, const float2* resident, float* out,
+            void* ws, hipStream_t s)
+{
+    const FftWorkspace L = fft_workspace(g, ZNN_PASS_FWD, resident != nullptr);
+    float2* Ihat = (float2*)((char*)ws + L.off_a);
+    float2* Ohat = (float2*)((char*)ws + L.off_b);
+    const float2* What = resident;
+    int rc = forward3d(g, in, Ihat, g.f, g.nz, g.ny, g.nx, 0, 0, 0, s);
+    if (rc != ZNN_OK) return rc;
+    if (!What) {
+        float2* wbuf = (float2*)((char*)ws + L.off_w);
+        rc = fft_kernel_spectra(g, w, wbuf, s);
+        if (rc != ZNN_OK) return rc;
+        What = wbuf;
+    }
+    rc = launch_mac(false, g, What, Ihat, Ohat, s);
+    if (rc != ZNN_OK) return rc;
+    return inverse3d(g, Ohat, out, g.fo, g.kz - 1, g.ky - 1, g.kx - 1, g.oz, g.oy, g.ox, s);
+}
+
+int fft_bwd(const Geom& g, const float* gout, const float* w, const float2* resident, float* gin,
+            void* ws, hipStream_t s)
+{
+    const FftWorkspace L = fft_workspace(g, ZNN_PASS_BWD, resident != nullptr);
+    float2* Ghat = (float2*)((char*)ws + L.off_a);
+    float2* Ginhat = (float2*)((char*)ws + L.off_b);
+    const float2* What = resident;
+    int rc = forward3d(g, gout, Ghat, g.fo, g.oz, g.oy, g.ox, g.kz - 1, g.ky - 1, g.kx - 1, s);
+    if (rc != ZNN_OK) return rc;
+    if (!What) {
+        float2* wbuf = (float2*)((char*)ws + L.off_w);
+        rc = fft_kernel_spectra(g, w, wbuf, s);
+        if (rc != ZNN_OK) return rc;
+        What = wbuf;
+    }
+    rc = launch_mac(true, g, What, Ghat, Ginhat, s);
+    if (rc != ZNN_OK) return rc;
+    return inverse3d(g, Ginhat, gin, g.f, 0, 0, 0, g.nz, g.ny, g.nx, s);
+}
+
+int fft_wgrad(const Geom& g, const float* in, const float* gout, float* gw, void* ws, hipStream_t s)
+{
+    const FftWorkspace L = fft_workspace(g, ZNN_PASS_WGRAD, false);
+    float2* Ihat = (float2*)((char*)ws + L.off_a);
+    float2* Ghat = (float2*)((char*)ws + L.off_b);
+    float2* T1 = (float2*)((char*)ws + L.off_t1);
+    float2* T2 = (float2*)((char*)ws + L.off_t2);
+    int rc = forward3d(g, in, Ihat, g.f, g.nz, g.ny, g.nx, 0, 0, 0, s);
+    if (rc != ZNN_OK) return rc;
+    rc = forward3d(g, gout, Ghat, g.fo, g.oz, g.oy, g.ox, g.kz - 1, g.ky - 1, g.kx - 1, s);
+    if (rc != ZNN_OK) return rc;
+    const long plane = (long)g.Ny * g.Nxh, vol = g.svol();
+    // z: product G^[j] conj(I^[i]) formed while loading; only z in [0, kz) is kept
+    AxisParams P = {};
+    P.in = Ghat; P.in2 = Ihat; P.out = T1;
+    P.N = g.Nz; P.i0 = 0; P.ni = g.Nz; P.o0 = 0; P.no = g.kz;
+    P.in_stride = plane; P.out_stride = plane;
+    P.L = (int)plane;
+    P.Oa = g.fo; P.Ob = g.f; P.Oc = 1;
+    P.in_sa = vol; P.in_sb = 0;
+    P.in2_sa = 0; P.in2_sb = vol;
+    P.out_sa = (long)g.f * g.kz * plane; P.out_sb = (long)g.kz * plane;
+    rc = launch_axis(P, +1, s);
+    if (rc != ZNN_OK) return rc;
+    // y: only y in [0, ky) is kept, written compactly
+    P = AxisParams{};
+    P.in = T1; P.in2 = nullptr; P.out = T2;
+    P.N = g.Ny; P.i0 = 0; P.ni = g.Ny; P.o0 = 0; P.no = g.ky;
+    P.in_stride = g.Nxh; P.out_stride = g.Nxh;
+    P.L = g.Nxh;
+    P.Oa = g.fo * g.f; P.Ob = g.kz; P.Oc = 1;
+    P.in_sa = (long)g.kz * plane; P.in_sb = plane;
+    P.out_sa = (long)g.kz * g.ky * g.Nxh; P.out_sb = (long)g.ky * g.Nxh;
+    rc = launch_axis(P, +1, s);
+    if (rc != ZNN_OK) return rc;
+    const float scale = (float)(1.0 / ((double)g.Nz * g.Ny * g.Nx));
+    return launch_c2r(T2, gw, (long)g.f * g.fo, g.kz, g.ky, g.Nx, 0, 0, 0, g.kz, g.ky, g.kx, scale, s);
+}
+
+}  // namespace znn

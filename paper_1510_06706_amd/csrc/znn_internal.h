@@ -1,0 +1,71 @@
+// Internal declarations shared by the host-side API and the kernel launchers.
+// Nothing in here is part of the public boundary (that is include/znn.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "znn.h"
+
+namespace znn {
+
+// ---------------------------------------------------------------- errors
+void set_error(const char* fmt, ...);
+int  fail(int code, const char* fmt, ...);
+// Checks hipGetLastError() after a launch; returns ZNN_OK or ZNN_EHIP.
+int  check_launch(const char* what);
+
+// ---------------------------------------------------------------- geometry
+struct Geom {
+    int f, fo;            // fan-in, fan-out
+    int nz, ny, nx;       // image extents n
+    int kz, ky, kx;       // kernel extents k
+    int oz, oy, ox;       // n' = n - k + 1
+    int Nz, Ny, Nx, Nxh;  // FFT extents and N_x/2+1
+    __host__ __device__ long nvol() const { return (long)nz * ny * nx; }
+    __host__ __device__ long kvol() const { return (long)kz * ky * kx; }
+    __host__ __device__ long ovol() const { return (long)oz * oy * ox; }
+    __host__ __device__ long svol() const { return (long)Nz * Ny * Nxh; }   // complex elements per spectrum
+};
+
+inline size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+// Smallest 2^a 3^b 5^c >= n.
+int  next_fft_extent(int n);
+// Largest FFT extent the LDS-resident passes accept.
+constexpr int kMaxFftExtent = 1024;
+
+// ---------------------------------------------------------------- direct method
+int direct_fwd(const Geom& g, const float* in, const float* w, float* out, void* ws, hipStream_t s);
+int direct_bwd(const Geom& g, const float* gout, const float* w, float* gin, void* ws, hipStream_t s);
+int direct_wgrad(const Geom& g, const float* in, const float* gout, float* gw, void* ws, hipStream_t s);
+size_t direct_workspace_bytes(const Geom& g, int pass);
+
+// ---------------------------------------------------------------- FFT method
+struct FftWorkspace {
+    size_t total;
+    size_t off_a, off_b;        // spectra of the two node sets of the pass
+    size_t off_w;               // kernel spectra (when not resident)
+    size_t off_t1, off_t2;      // partially inverted pair volumes (kernel gradient)
+};
+FftWorkspace fft_workspace(const Geom& g, int pass, bool resident);
+size_t fft_spectra_bytes(const Geom& g);
+int fft_kernel_spectra(const Geom& g, const float* w, float2* What, hipStream_t s);
+int fft_fwd(const Geom& g, const float* in, const float* w, const float2* resident, float* out,
+            void* ws, hipStream_t s);
+int fft_bwd(const Geom& g, const float* gout, const float* w, const float2* resident, float* gin,
+            void* ws, hipStream_t s);
+int fft_wgrad(const Geom& g, const float* in, const float* gout, float* gw, void* ws, hipStream_t s);
+
+// ---------------------------------------------------------------- fill (autotuner)
+int fill_pattern(float* p, long count, float scale, hipStream_t s);
+
+}  // namespace znn
+
+struct znn_plan {
+    znn_conv_desc desc;
+    znn::Geom g;
+    int mode;                    // ZNN_DIRECT or ZNN_FFT
+    const float2* resident;      // kernel spectra held by the caller, or nullptr
+};

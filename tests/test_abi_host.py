@@ -1,0 +1,112 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol include/znn.h declares, and validates its arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_1510_06706_amd import binding as znn
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "znn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(znn_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = znn.lib()
+    names = declared_symbols()
+    assert len(names) >= 20
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(znn.EXPORTS) == names
+
+
+def plan_rc(**kw):
+    d = dict(fan_in=2, fan_out=3, image=(4, 5, 6), kernel=(2, 2, 3), mode="direct", sparsity=(1, 1, 1))
+    d.update(kw)
+    desc = znn.make_desc(d["fan_in"], d["fan_out"], d["image"], d["kernel"], d["mode"], d["sparsity"])
+    h = ctypes.c_void_p(0)
+    rc = znn.lib().znn_plan_create(ctypes.byref(desc), ctypes.byref(h))
+    if rc == 0:
+        znn.lib().znn_plan_destroy(h)
+    return rc
+
+
+def test_descriptor_validation():
+    assert plan_rc() == znn.ZNN_OK
+    assert plan_rc(fan_in=0) == znn.ZNN_EINVAL
+    assert plan_rc(fan_out=-1) == znn.ZNN_EINVAL
+    assert plan_rc(kernel=(5, 2, 3)) == znn.ZNN_EINVAL
+    assert "exceeds" in znn.last_error()
+    assert plan_rc(image=(0, 5, 6)) == znn.ZNN_EINVAL
+    assert plan_rc(kernel=(1, 0, 1)) == znn.ZNN_EINVAL
+    assert plan_rc(sparsity=(2, 2, 2)) == znn.ZNN_EUNSUPPORTED
+    assert plan_rc(mode=7) == znn.ZNN_EINVAL
+    assert plan_rc(mode="fft", image=(1, 4, 2000), kernel=(1, 1, 1)) == znn.ZNN_EUNSUPPORTED
+    assert znn.lib().znn_plan_create(None, ctypes.byref(ctypes.c_void_p(0))) == znn.ZNN_EINVAL
+
+
+@pytest.mark.parametrize("n,N", [((16, 16, 16), (16, 16, 16)), ((26, 22, 17), (27, 24, 18)),
+                                 ((1, 256, 246), (1, 256, 250)), ((96, 90, 7), (96, 90, 8))])
+def test_fft_extents_are_the_next_5_smooth_numbers(n, N):
+    p = znn.Plan(1, 1, n, (1, 1, 1), "fft")
+    assert p.fft_extents == N
+    assert p.mode == znn.ZNN_FFT
+    p.close()
+
+
+def test_workspace_and_spectra_sizes():
+    p = znn.Plan(40, 40, (64, 64, 64), (5, 5, 5), "fft")
+    spec = 64 * 64 * 33 * 8
+    assert p.spectra_bytes() == 40 * 40 * spec
+    assert p.workspace_bytes(znn.ZNN_PASS_FWD) == 80 * spec + 1600 * spec
+    assert p.workspace_bytes(znn.ZNN_PASS_BWD) == 80 * spec + 1600 * spec
+    assert p.workspace_bytes(znn.ZNN_PASS_WGRAD) >= 80 * spec
+    b = ctypes.c_size_t(0)
+    assert znn.lib().znn_plan_workspace_bytes(p._h, 5, ctypes.byref(b)) == znn.ZNN_EINVAL
+    p.close()
+    d = znn.Plan(40, 40, (64, 64, 64), (5, 5, 5), "direct")
+    assert d.mode == znn.ZNN_DIRECT
+    d.close()
+
+
+def test_compute_entry_points_reject_null_and_short_workspace_without_launching():
+    L = znn.lib()
+    p = znn.Plan(2, 2, (8, 8, 8), (3, 3, 3), "fft")
+    null = ctypes.c_void_p(0)
+    fake = ctypes.c_void_p(0x1000)     # never dereferenced: validation fails first
+    assert L.znn_conv3d_fwd(p._h, null, fake, fake, fake, 1 << 30, null) == znn.ZNN_EINVAL
+    assert L.znn_conv3d_fwd(p._h, fake, fake, fake, null, 0, null) == znn.ZNN_EWORKSPACE
+    assert L.znn_conv3d_bwd(p._h, fake, fake, fake, fake, 16, null) == znn.ZNN_EWORKSPACE
+    assert L.znn_conv3d_wgrad(p._h, fake, fake, fake, ctypes.c_void_p(0x1001), 1 << 30, null) == znn.ZNN_EWORKSPACE
+    assert "aligned" in znn.last_error()
+    assert L.znn_conv_prepare_kernels(p._h, fake, null, 0, null, 0, null) == znn.ZNN_EWORKSPACE
+    p.close()
+    d = znn.Plan(2, 2, (8, 8, 8), (3, 3, 3), "direct")
+    assert L.znn_conv_prepare_kernels(d._h, fake, fake, 1 << 30, null, 0, null) == znn.ZNN_EINVAL
+    d.close()
+
+
+def test_filter_and_pointwise_validation():
+    L = znn.lib()
+    fake, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
+    v = znn.Vec3
+    assert L.znn_maxfilter3d_fwd(1, v(4, 4, 4), v(5, 1, 1), fake, fake, fake, null) == znn.ZNN_EINVAL
+    assert L.znn_maxfilter3d_fwd(0, v(4, 4, 4), v(2, 2, 2), fake, fake, fake, null) == znn.ZNN_EINVAL
+    assert L.znn_maxfilter3d_fwd(1, v(4, 4, 4), v(2, 2, 2), null, fake, fake, null) == znn.ZNN_EINVAL
+    assert L.znn_maxfilter3d_bwd(1, v(4, 4, 4), v(2, 0, 2), fake, fake, fake, null) == znn.ZNN_EINVAL
+    assert L.znn_maxfilter3d_fwd(1, v(2048, 2048, 1024), v(2, 2, 2), fake, fake, fake, null) == znn.ZNN_EUNSUPPORTED
+    assert L.znn_transfer_fwd(0, 10, fake, fake, fake, null) == znn.ZNN_EINVAL
+    assert L.znn_bias_grad(2, 10, null, fake, null) == znn.ZNN_EINVAL
+    assert L.znn_sgd_update(0, 0.1, fake, fake, null) == znn.ZNN_EINVAL
+
+
+def test_auto_mode_resolves_to_a_concrete_method():
+    p = znn.Plan(120, 120, (96, 96, 96), (7, 7, 7), "auto")
+    assert p.mode in (znn.ZNN_DIRECT, znn.ZNN_FFT)
+    p.close()

@@ -1,0 +1,141 @@
+"""Parity of the HIP library with the CPU oracle, element by element, through the C ABI.
+
+Tolerances are the ones the task fixes: max|gpu - ref| / max|ref| <= 1e-4 for the
+direct method and <= 1e-3 for the FFT method; max-filter values and indices are exact.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1510_06706_amd import binding as znn
+from paper_1510_06706_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"direct": 1e-4, "fft": 1e-3}
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def host(t):
+    import torch
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def rel_err(got, ref):
+    return float(np.max(np.abs(got.astype(np.float64) - ref)) / max(np.max(np.abs(ref)), 1e-300))
+
+
+SMALL = [
+    # f, fo, n, k      (several tiles, ragged tails, anisotropic, 2D, k = n, k = 1)
+    (1, 4, (16, 16, 16), (3, 3, 3)),
+    (3, 5, (9, 10, 11), (2, 3, 4)),
+    (5, 3, (1, 20, 23), (1, 5, 4)),
+    (40, 40, (12, 12, 14), (3, 3, 3)),
+    (2, 2, (4, 4, 4), (4, 4, 4)),
+    (3, 2, (6, 7, 8), (1, 1, 1)),
+    (7, 9, (17, 13, 20), (5, 3, 2)),
+    (4, 6, (7, 25, 15), (3, 1, 5)),
+    (17, 33, (8, 9, 35), (2, 2, 3)),
+]
+
+
+@pytest.mark.parametrize("mode", ["direct", "fft"])
+@pytest.mark.parametrize("f,fo,n,k", SMALL)
+def test_three_passes_match_the_oracle(f, fo, n, k, mode):
+    print("case", f, fo, n, k, mode, flush=True)
+    cfg = synth.LayerShape("t", f, fo, n, k, 1.0, 77 + f + fo)
+    inp, w, gout = synth.layer_tensors(cfg)
+    p = znn.Plan(f, fo, n, k, mode)
+    d_in, d_w, d_g = dev(inp), dev(w), dev(gout)
+    out = host(p.fwd(d_in, d_w))
+    gin = host(p.bwd(d_g, d_w))
+    gw = host(p.wgrad(d_in, d_g))
+    tol = TOL[mode]
+    assert rel_err(out, oracle.conv3d_fwd(inp, w)) <= tol
+    assert rel_err(gin, oracle.conv3d_bwd(gout, w, n)) <= tol
+    assert rel_err(gw, oracle.conv3d_wgrad(inp, gout)) <= tol
+    # run-to-run reproducibility: no atomics, fixed summation order
+    assert np.array_equal(out, host(p.fwd(d_in, d_w)))
+    assert np.array_equal(gin, host(p.bwd(d_g, d_w)))
+    assert np.array_equal(gw, host(p.wgrad(d_in, d_g)))
+    p.close()
+
+
+def test_resident_kernel_spectra_give_the_same_result():
+    f, fo, n, k = 6, 5, (10, 12, 9), (3, 4, 2)
+    cfg = synth.LayerShape("t", f, fo, n, k, 1.0, 91)
+    inp, w, gout = synth.layer_tensors(cfg)
+    p = znn.Plan(f, fo, n, k, "fft")
+    d_in, d_w, d_g = dev(inp), dev(w), dev(gout)
+    out0, gin0 = host(p.fwd(d_in, d_w)), host(p.bwd(d_g, d_w))
+    big = p.workspace_bytes(znn.ZNN_PASS_FWD)
+    p.prepare_kernels(d_w)
+    assert p.workspace_bytes(znn.ZNN_PASS_FWD) < big
+    out1, gin1 = host(p.fwd(d_in, None)), host(p.bwd(d_g, None))
+    assert np.array_equal(out0, out1) and np.array_equal(gin0, gin1)
+    assert rel_err(out1, oracle.conv3d_fwd(inp, w)) <= TOL["fft"]
+    p.release_kernels()
+    assert p.workspace_bytes(znn.ZNN_PASS_FWD) == big
+    p.close()
+
+
+FILTERS = [((5, 6, 7), (2, 2, 2)), ((22, 22, 22), (2, 2, 2)), ((1, 30, 17), (1, 2, 2)),
+           ((6, 5, 9), (3, 1, 4)), ((3, 3, 3), (3, 3, 3)), ((4, 5, 6), (1, 1, 1))]
+
+
+@pytest.mark.parametrize("kind", ["random", "ties", "zeros"])
+@pytest.mark.parametrize("n,win", FILTERS)
+def test_maxfilter_is_exact_and_its_jacobian_matches(n, win, kind):
+    print("case", n, win, kind, flush=True)
+    maps = 5
+    if kind == "random":
+        x = synth.uniform_pm1(5, 0, (maps,) + n)
+    elif kind == "ties":       # what a rectified image looks like: many exact zeros and repeats
+        x = np.maximum(np.round(synth.uniform_pm1(6, 0, (maps,) + n) * 2), 0).astype(np.float32)
+        x[0].flat[::3] = -0.0
+    else:
+        x = np.zeros((maps,) + n, dtype=np.float32)
+    ref_out, ref_idx = oracle.maxfilter3d_fwd(x, win)
+    out, idx = znn.maxfilter3d_fwd(dev(x), win)
+    out, idx_h = host(out), host(idx)
+    assert np.array_equal(out.astype(np.float64), ref_out)
+    assert np.array_equal(idx_h, ref_idx)
+    g = synth.uniform_pm1(7, 2, ref_out.shape)
+    gin = host(znn.maxfilter3d_bwd(dev(g), idx, n, win))
+    ref_gin = oracle.maxfilter3d_bwd(g, ref_idx, n, win)
+    assert rel_err(gin, ref_gin) <= 1e-6
+
+
+def test_pointwise_steps_of_a_training_round():
+    maps, vox = 7, 1000
+    x = synth.uniform_pm1(8, 0, (maps, 10, 10, 10))
+    b = synth.uniform_pm1(8, 4, (maps,), 0.1)
+    y = host(znn.transfer_fwd(dev(x), dev(b)))
+    want = np.maximum(x + b[:, None, None, None], 0)
+    assert np.array_equal(y, want)
+    gy = synth.uniform_pm1(8, 2, x.shape)
+    gx = host(znn.transfer_bwd(dev(gy), dev(y)))
+    assert np.array_equal(gx, np.where(want > 0, gy, 0).astype(np.float32))
+    gb = host(znn.bias_grad(dev(gy)))
+    assert rel_err(gb, gy.astype(np.float64).reshape(maps, -1).sum(1)) <= 1e-5
+    t = synth.uniform_01(8, 3, x.shape)
+    assert np.array_equal(host(znn.square_loss_grad(dev(x), dev(t))), x - t)
+    p = dev(x.copy())
+    znn.sgd_update(p, dev(gy), 0.01)
+    assert np.allclose(host(p), x - np.float32(0.01) * gy, rtol=0, atol=1e-7)
+
+
+def test_autotuner_times_both_methods_and_caches_its_choice():
+    f, fo, n, k = 8, 8, (20, 20, 20), (3, 3, 3)
+    chosen, ms = znn.autotune(f, fo, n, k)
+    assert chosen in (znn.ZNN_DIRECT, znn.ZNN_FFT)
+    assert all(np.isfinite(v) and v > 0 for row in ms for v in row)
+    assert chosen == (znn.ZNN_FFT if sum(ms[1]) < sum(ms[0]) else znn.ZNN_DIRECT)
+    p = znn.Plan(f, fo, n, k, "auto")
+    assert p.mode == chosen
+    p.close()
