@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Benchmark of the convolutional-layer hot path on one MI355X.
+
+Workload: the wide 3D layer (fan-in 40 -> fan-out 40, 64^3 images, 5^3 kernels,
+fp32, synthetic values).  One step trains the layer once with each method:
+
+    direct : forward + backward + kernel gradient
+    fft    : kernel spectra once, then forward + backward (streaming the resident
+             spectra) + kernel gradient
+    plus the sliding max-filter forward/backward on a 40 x 22^3 node set.
+
+`value` is output voxels per second: every step produces the layer's f'*n'^3
+output voxels twice (once per method).  Per-method and per-pass times, the
+roofline of the dominant kernel and the CPU oracle timed on a bounded sample
+are reported in the same JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(cfg, inp, w, gout, budget_s=18.0):
+    """The oracle as it stands, timed on sampled outputs of each pass, extrapolated to the layer."""
+    import oracle
+    rs = np.random.RandomState(1)
+    fo_vox = cfg.out_voxels
+    in_vox = cfg.fan_in * int(np.prod(cfg.image))
+    gw_n = cfg.fan_in * cfg.fan_out * int(np.prod(cfg.kernel))
+    macs_full = cfg.macs
+    per = {"fwd": (fo_vox, lambda p: oracle.conv3d_fwd_at(inp, w, p)),
+           "bwd": (in_vox, lambda p: oracle.conv3d_bwd_at(gout, w, cfg.image, p)),
+           "wgrad": (gw_n, lambda p: oracle.conv3d_wgrad_at(inp, gout, p))}
+    inp64, w64, g64 = (a.astype(np.float64) for a in (inp, w, gout))
+    inp, w, gout = inp64, w64, g64
+    est = {}
+    samples = {}
+    for name, (total, fn) in per.items():
+        macs_each = macs_full / total
+        n0 = max(16, int(2e8 / macs_each))
+        pos = rs.randint(0, total, size=n0)
+        t0 = time.perf_counter(); fn(pos); t1 = time.perf_counter()
+        rate = n0 / max(t1 - t0, 1e-6)
+        n1 = int(min(total, max(n0, rate * budget_s / 3.0)))
+        pos = rs.randint(0, total, size=n1)
+        t0 = time.perf_counter(); fn(pos); t1 = time.perf_counter()
+        est[name] = (t1 - t0) * total / n1
+        samples[name] = n1
+    t_layer = est["fwd"] + est["bwd"] + est["wgrad"]
+    return {"value": fo_vox / t_layer, "unit": "output voxels/s", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": "fp64 nested-loop oracle on %d fwd voxels, %d bwd voxels, %d kernel-gradient entries "
+                      "drawn uniformly from the same layer, each a full-depth sum; layer time extrapolated "
+                      "(fwd %.1f s, bwd %.1f s, wgrad %.1f s)" % (samples["fwd"], samples["bwd"], samples["wgrad"],
+                                                                   est["fwd"], est["bwd"], est["wgrad"]),
+            "gflops": 3 * 2 * macs_full / t_layer / 1e9}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "run it with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1510_06706_amd import binding as znn
+    from paper_1510_06706_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    cfg = synth.CONFIG2
+    inp, w, gout = synth.layer_tensors(cfg)
+    d_in, d_w, d_g = (torch.from_numpy(a).to(dev) for a in (inp, w, gout))
+    out = torch.empty((cfg.fan_out,) + cfg.out, dtype=torch.float32, device=dev)
+    gin = torch.empty_like(d_in)
+    gw = torch.empty_like(d_w)
+    mf_n, mf_win = (22, 22, 22), (2, 2, 2)
+    d_mf = torch.from_numpy(np.maximum(synth.uniform_pm1(1003, 0, (40,) + mf_n), 0)).to(dev)
+    d_mfg = torch.from_numpy(synth.uniform_pm1(1003, 2, (40, 21, 21, 21))).to(dev)
+
+    plans = {"direct": znn.Plan(cfg.fan_in, cfg.fan_out, cfg.image, cfg.kernel, "direct"),
+             "fft": znn.Plan(cfg.fan_in, cfg.fan_out, cfg.image, cfg.kernel, "fft")}
+
+    def run_mode(mode):
+        p = plans[mode]
+        if mode == "fft":
+            p.prepare_kernels(d_w)
+            p.fwd(d_in, None, out)
+            p.bwd(d_g, None, gin)
+        else:
+            p.fwd(d_in, d_w, out)
+            p.bwd(d_g, d_w, gin)
+        p.wgrad(d_in, d_g, gw)
+
+    def step():
+        run_mode("direct")
+        run_mode("fft")
+        _, idx = znn.maxfilter3d_fwd(d_mf, mf_win)
+        znn.maxfilter3d_bwd(d_mfg, idx, mf_n, mf_win)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # per-pass times with events on the stream the kernels run on (torch's current stream)
+    def timed(fn, reps=10):
+        fn(); fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    pd, pf = plans["direct"], plans["fft"]
+    per = {"direct": {"fwd": timed(lambda: pd.fwd(d_in, d_w, out)),
+                      "bwd": timed(lambda: pd.bwd(d_g, d_w, gin)),
+                      "wgrad": timed(lambda: pd.wgrad(d_in, d_g, gw))}}
+    t_ker = timed(lambda: pf.prepare_kernels(d_w))
+    per["fft"] = {"kernel_spectra": t_ker,
+                  "fwd": timed(lambda: pf.fwd(d_in, None, out)),
+                  "bwd": timed(lambda: pf.bwd(d_g, None, gin)),
+                  "wgrad": timed(lambda: pf.wgrad(d_in, d_g, gw))}
+    flop_pass = 2.0 * cfg.macs
+    summary = {}
+    for mode, t in per.items():
+        tot = sum(t.values())
+        summary[mode] = {"ms": {k: round(v, 4) for k, v in t.items()}, "layer_ms": round(tot, 4),
+                         "voxels_per_s": cfg.out_voxels / (tot * 1e-3),
+                         "effective_tflops": 3 * flop_pass / (tot * 1e-3) / 1e12}
+
+    # roofline of the dominant kernel of the step
+    from paper_1510_06706_amd import roofline as rl
+    roof = rl.dominant(cfg, per, plans, d_in, d_w, d_g, out, gin, gw)
+
+    result = {
+        "metric": "conv-layer fwd+bwd+wgrad output voxels/s (direct and FFT method, each once per step)",
+        "value": 2 * cfg.out_voxels / (ms_per_step * 1e-3),
+        "unit": "output voxels/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "wide 3D layer f=40 -> f'=40, n=64^3, k=5^3 (config 2), direct + FFT, "
+                               "plus 2^3 max-filter on 40x22^3", "global_batch": 1},
+        "effective_tflops_per_step": 2 * 3 * flop_pass / (ms_per_step * 1e-3) / 1e12,
+        "per_mode": summary,
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, inp, w, gout)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

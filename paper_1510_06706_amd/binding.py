@@ -53,6 +53,9 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError("libznn.so is not built: run `python -m paper_1510_06706_amd.build` "
                                "(or __graft_entry__.build()) first")
+        # torch ships its own HIP runtime; load it first so that this library binds to
+        # the same runtime instance (one process, one runtime) instead of a second copy.
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, sz, i32, i64 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int64
         L.znn_last_error.restype = ctypes.c_char_p
