@@ -1,0 +1,337 @@
+// Direct method on the fp32 matrix cores: forward and backward pass as an
+// implicit GEMM whose reduction runs over (fan-in x kernel volume), i.e. the
+// sum over the edges converging on a node is part of the GEMM's K loop.
+//
+//   D[m][n] += A[m][k] * B[k][n]      v_mfma_f32_16x16x4_f32
+//     m : 16 output maps            (A = packed kernel weights, one coalesced load)
+//     n : 16 output voxels          (B = input voxels read from an LDS halo tile)
+//     k : 4 input maps at one kernel tap
+//
+// A workgroup of four waves owns a box of output voxels for up to 128 output
+// maps; per chunk of four input maps it stages the input halo box in LDS once
+// and walks all taps over it.  The backward pass is the same contraction with
+// the roles of the two node sets swapped, the kernel reflected and the output
+// gradient zero-extended by k-1 on every side (Section 3.1), which the halo
+// loader and the weight packer provide; no separate kernel is needed.
+#include "znn_internal.h"
+
+namespace znn {
+
+namespace {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+constexpr int kMaxTaps = 4096;
+
+struct ConvTile {
+    const float* src;   // K-side images [fK][sz][sy][sx]
+    const float* wp;    // packed weights [jgroup][chunk][tap][NJ][64]
+    float* dst;         // M-side images [fM][dz][dy][dx]
+    int fK, fM;
+    int sz, sy, sx;     // source extents
+    int pz, py, px;     // zeros virtually in front of the source on each axis
+    int dz, dy, dx;     // output extents
+    int kz, ky, kx;
+    int Tz, Ty, Tx;     // output voxels per workgroup
+    int HZ, HY, HX, MS; // halo box and LDS stride between the four staged maps
+    int cz, cy, cx;     // workgroups per axis
+    int nchunk;         // ceil(fK / 4)
+};
+
+// Packs w[f'][f][k] so that lane l of a wave finds its A element of tile jt at
+// [..][jt][l]: output map jt*16 + l%16, input map chunk*4 + l/16.  For the
+// backward pass the two map indices trade places and the tap is reflected.
+__global__ void __launch_bounds__(256)
+k_pack_weights(const float* __restrict__ w, float* __restrict__ wp, int f, int fo, int kz, int ky, int kx,
+               int backward, int NJ, int jgroups, int nchunk)
+{
+    const int taps = kz * ky * kx;
+    const long total = (long)jgroups * nchunk * taps * NJ * 64;
+    const long t = (long)blockIdx.x * 256 + threadIdx.x;
+    if (t >= total) return;
+    const int lane = (int)(t % 64);
+    long r = t / 64;
+    const int jt = (int)(r % NJ); r /= NJ;
+    const int tap = (int)(r % taps); r /= taps;
+    const int ic = (int)(r % nchunk);
+    const int jg = (int)(r / nchunk);
+    const int m = (jg * NJ + jt) * 16 + (lane & 15);   // M-side map
+    const int k = ic * 4 + (lane >> 4);                // K-side map
+    const int fM = backward ? f : fo, fK = backward ? fo : f;
+    float v = 0.f;
+    if (m < fM && k < fK) {
+        if (!backward) {
+            v = w[((long)m * f + k) * taps + tap];
+        } else {
+            const int c = tap % kx, b = (tap / kx) % ky, a = tap / (kx * ky);
+            const int rt = ((kz - 1 - a) * ky + (ky - 1 - b)) * kx + (kx - 1 - c);
+            v = w[((long)k * f + m) * taps + rt];
+        }
+    }
+    wp[t] = v;
+}
+
+template <int NJ, int NV>
+__global__ void __launch_bounds__(256, 2) k_conv_mfma(ConvTile P)
+{
+    extern __shared__ float lds[];
+    const int taps = P.kz * P.ky * P.kx;
+    int* tapoff = reinterpret_cast<int*>(lds);      // [taps]
+    float* halo = lds + ((taps + 63) & ~63);        // [4][MS]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = lane & 15, grp = lane >> 4;
+
+    int b = blockIdx.x;
+    const int bxi = b % P.cx; b /= P.cx;
+    const int byi = b % P.cy;
+    const int bzi = b / P.cy;
+    const int jg = blockIdx.y;
+    const int z0 = bzi * P.Tz, y0 = byi * P.Ty, x0 = bxi * P.Tx;
+    const int Ttot = P.Tz * P.Ty * P.Tx;
+
+    for (int t = threadIdx.x; t < taps; t += 256) {
+        const int c = t % P.kx, bb = (t / P.kx) % P.ky, a = t / (P.kx * P.ky);
+        tapoff[t] = ((P.kz - 1 - a) * P.HY + (P.ky - 1 - bb)) * P.HX + (P.kx - 1 - c);
+    }
+
+    int voff[NV];
+#pragma unroll
+    for (int nv = 0; nv < NV; ++nv) {
+        int t = (wave * NV + nv) * 16 + col;
+        if (t >= Ttot) t = 0;
+        const int tx = t % P.Tx, ty = (t / P.Tx) % P.Ty, tz = t / (P.Tx * P.Ty);
+        voff[nv] = grp * P.MS + (tz * P.HY + ty) * P.HX + tx;
+    }
+
+    floatx4 acc[NJ][NV];
+#pragma unroll
+    for (int jt = 0; jt < NJ; ++jt)
+#pragma unroll
+        for (int nv = 0; nv < NV; ++nv) acc[jt][nv] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    const int hvol = P.HZ * P.HY * P.HX;
+    const long splane = (long)P.sy * P.sx;
+    const float* wq = P.wp + (long)jg * P.nchunk * taps * NJ * 64 + lane;
+
+    for (int ic = 0; ic < P.nchunk; ++ic) {
+        __syncthreads();   // everyone is done reading the previous chunk
+        for (int t = threadIdx.x; t < 4 * hvol; t += 256) {
+            const int hx = t % P.HX;
+            int r = t / P.HX;
+            const int hy = r % P.HY; r /= P.HY;
+            const int hz = r % P.HZ;
+            const int m = r / P.HZ;
+            const int gz = z0 + hz - P.pz, gy = y0 + hy - P.py, gx = x0 + hx - P.px;
+            const int i = ic * 4 + m;
+            float v = 0.f;
+            if (i < P.fK && gz >= 0 && gz < P.sz && gy >= 0 && gy < P.sy && gx >= 0 && gx < P.sx)
+                v = P.src[(long)i * P.sz * splane + gz * splane + (long)gy * P.sx + gx];
+            halo[m * P.MS + (hz * P.HY + hy) * P.HX + hx] = v;
+        }
+        __syncthreads();
+
+        float an[NJ], bn[NV];
+#pragma unroll
+        for (int jt = 0; jt < NJ; ++jt) an[jt] = wq[jt * 64];
+        {
+            const int o = tapoff[0];
+#pragma unroll
+            for (int nv = 0; nv < NV; ++nv) bn[nv] = halo[voff[nv] + o];
+        }
+        for (int t = 0; t < taps; ++t) {
+            float av[NJ], bv[NV];
+#pragma unroll
+            for (int jt = 0; jt < NJ; ++jt) av[jt] = an[jt];
+#pragma unroll
+            for (int nv = 0; nv < NV; ++nv) bv[nv] = bn[nv];
+            // operands of the next tap are fetched while this tap's MFMAs run
+            const int tn = t + 1 < taps ? t + 1 : t;
+            const float* wn = wq + (long)tn * NJ * 64;
+#pragma unroll
+            for (int jt = 0; jt < NJ; ++jt) an[jt] = wn[jt * 64];
+            const int o = tapoff[tn];
+#pragma unroll
+            for (int nv = 0; nv < NV; ++nv) bn[nv] = halo[voff[nv] + o];
+#pragma unroll
+            for (int jt = 0; jt < NJ; ++jt)
+#pragma unroll
+                for (int nv = 0; nv < NV; ++nv)
+                    acc[jt][nv] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[jt], bv[nv], acc[jt][nv], 0, 0, 0);
+        }
+        wq += (long)taps * NJ * 64;
+    }
+
+    // D[m][n]: lane holds rows m = 4*(lane/16) + r, column n = lane%16
+    const long dplane = (long)P.dy * P.dx;
+#pragma unroll
+    for (int nv = 0; nv < NV; ++nv) {
+        const int t = (wave * NV + nv) * 16 + col;
+        if (t >= Ttot) continue;
+        const int tx = t % P.Tx, ty = (t / P.Tx) % P.Ty, tz = t / (P.Tx * P.Ty);
+        const int z = z0 + tz, y = y0 + ty, x = x0 + tx;
+        if (z >= P.dz || y >= P.dy || x >= P.dx) continue;
+        const long vox = z * dplane + (long)y * P.dx + x;
+#pragma unroll
+        for (int jt = 0; jt < NJ; ++jt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int j = (jg * NJ + jt) * 16 + grp * 4 + r;
+                if (j < P.fM) P.dst[(long)j * P.dz * dplane + vox] = acc[jt][nv][r];
+            }
+    }
+}
+
+using ConvFn = void (*)(ConvTile);
+
+template <int NJ> ConvFn pick_nv(int nv)
+{
+    switch (nv) {
+        case 2: return k_conv_mfma<NJ, 2>;
+        case 4: return k_conv_mfma<NJ, 4>;
+        case 5: if (NJ * 5 <= 40) return k_conv_mfma<NJ, (NJ * 5 <= 40 ? 5 : 2)>; break;
+        case 6: if (NJ * 6 <= 40) return k_conv_mfma<NJ, (NJ * 6 <= 40 ? 6 : 2)>; break;
+        case 7: if (NJ * 7 <= 40) return k_conv_mfma<NJ, (NJ * 7 <= 40 ? 7 : 2)>; break;
+        case 8: if (NJ * 8 <= 40) return k_conv_mfma<NJ, (NJ * 8 <= 40 ? 8 : 2)>; break;
+    }
+    return nullptr;
+}
+
+ConvFn pick_kernel(int nj, int nv)
+{
+    switch (nj) {
+        case 1: return pick_nv<1>(nv);
+        case 2: return pick_nv<2>(nv);
+        case 3: return pick_nv<3>(nv);
+        case 4: return pick_nv<4>(nv);
+        case 5: return pick_nv<5>(nv);
+        case 6: return pick_nv<6>(nv);
+        case 7: return pick_nv<7>(nv);
+        case 8: return pick_nv<8>(nv);
+    }
+    return nullptr;
+}
+
+struct TileChoice {
+    bool ok;
+    int NJ, jgroups, NV;
+    int Tz, Ty, Tx, HZ, HY, HX, MS;
+    int cz, cy, cx;
+    size_t lds;
+};
+
+constexpr int kCUs = 256;
+constexpr size_t kConvLdsMax = 64 * 1024;
+
+// Picks the tile box and the per-wave tile count so that the launch fills the
+// 256 compute units in as few, as full rounds as possible.
+TileChoice choose_tile(int fM, int dz, int dy, int dx, int kz, int ky, int kx)
+{
+    TileChoice best = {};
+    best.ok = false;
+    const int taps = kz * ky * kx;
+    if (taps > kMaxTaps) return best;
+    const int tiles = (fM + 15) / 16;
+    const int jgroups = (tiles + 7) / 8;
+    const int NJ = (tiles + jgroups - 1) / jgroups;
+    double best_cost = 1e300;
+    const int nvs[6] = {2, 4, 5, 6, 7, 8};
+    for (int ni = 0; ni < 6; ++ni) {
+        const int NV = nvs[ni];
+        if (NJ * NV > 40 || !pick_kernel(NJ, NV)) continue;
+        const int cap = 64 * NV;
+        for (int Tx = 1; Tx <= dx && Tx <= cap; ++Tx) {
+            for (int Ty = 1; Ty <= dy && Tx * Ty <= cap; ++Ty) {
+                int Tz = cap / (Tx * Ty);
+                if (Tz > dz) Tz = dz;
+                if (Tz < 1) continue;
+                const int HZ = Tz + kz - 1, HY = Ty + ky - 1, HX = Tx + kx - 1;
+                long hvol = (long)HZ * HY * HX;
+                long MS = hvol;
+                while (MS % 32 != 16) ++MS;
+                const size_t lds = (size_t)(((taps + 63) & ~63) + 4 * MS) * 4;
+                if (lds > kConvLdsMax) continue;
+                const int cz = (dz + Tz - 1) / Tz, cy = (dy + Ty - 1) / Ty, cx = (dx + Tx - 1) / Tx;
+                const long blocks = (long)cz * cy * cx * jgroups;
+                const long rounds = (blocks + kCUs - 1) / kCUs;
+                // time ~ rounds x (MFMA work of a workgroup + halo staging)
+                const double mfma = (double)taps * NJ * NV * 32.0;
+                const double stage = (double)hvol * 4.0 / 256.0 * 12.0;
+                const double cost = (double)rounds * (mfma + stage);
+                if (cost < best_cost) {
+                    best_cost = cost;
+                    best.ok = true;
+                    best.NJ = NJ; best.jgroups = jgroups; best.NV = NV;
+                    best.Tz = Tz; best.Ty = Ty; best.Tx = Tx;
+                    best.HZ = HZ; best.HY = HY; best.HX = HX; best.MS = (int)MS;
+                    best.cz = cz; best.cy = cy; best.cx = cx;
+                    best.lds = lds;
+                }
+            }
+        }
+    }
+    return best;
+}
+
+size_t packed_bytes(const TileChoice& c, int fK, int taps)
+{
+    return align256((size_t)c.jgroups * ((fK + 3) / 4) * taps * c.NJ * 64 * sizeof(float));
+}
+
+}  // namespace
+
+// The tiled path takes every shape whose halo box fits LDS; otherwise the caller falls back.
+bool mfma_conv_supported(const Geom& g, bool backward)
+{
+    const TileChoice c = backward ? choose_tile(g.f, g.nz, g.ny, g.nx, g.kz, g.ky, g.kx)
+                                  : choose_tile(g.fo, g.oz, g.oy, g.ox, g.kz, g.ky, g.kx);
+    return c.ok;
+}
+
+size_t mfma_conv_workspace(const Geom& g, bool backward)
+{
+    const TileChoice c = backward ? choose_tile(g.f, g.nz, g.ny, g.nx, g.kz, g.ky, g.kx)
+                                  : choose_tile(g.fo, g.oz, g.oy, g.ox, g.kz, g.ky, g.kx);
+    if (!c.ok) return 0;
+    return packed_bytes(c, backward ? g.fo : g.f, (int)g.kvol());
+}
+
+int mfma_conv(const Geom& g, bool backward, const float* src, const float* w, float* dst, void* ws,
+              hipStream_t s)
+{
+    ConvTile P = {};
+    P.src = src; P.dst = dst;
+    P.kz = g.kz; P.ky = g.ky; P.kx = g.kx;
+    if (!backward) {
+        P.fK = g.f; P.fM = g.fo;
+        P.sz = g.nz; P.sy = g.ny; P.sx = g.nx;
+        P.pz = P.py = P.px = 0;
+        P.dz = g.oz; P.dy = g.oy; P.dx = g.ox;
+    } else {
+        P.fK = g.fo; P.fM = g.f;
+        P.sz = g.oz; P.sy = g.oy; P.sx = g.ox;
+        P.pz = g.kz - 1; P.py = g.ky - 1; P.px = g.kx - 1;
+        P.dz = g.nz; P.dy = g.ny; P.dx = g.nx;
+    }
+    const TileChoice c = choose_tile(P.fM, P.dz, P.dy, P.dx, g.kz, g.ky, g.kx);
+    if (!c.ok) return fail(ZNN_EUNSUPPORTED, "no tile configuration fits this shape");
+    P.Tz = c.Tz; P.Ty = c.Ty; P.Tx = c.Tx;
+    P.HZ = c.HZ; P.HY = c.HY; P.HX = c.HX; P.MS = c.MS;
+    P.cz = c.cz; P.cy = c.cy; P.cx = c.cx;
+    P.nchunk = (P.fK + 3) / 4;
+    const int taps = (int)g.kvol();
+    float* wp = (float*)ws;
+    P.wp = wp;
+    const long total = (long)c.jgroups * P.nchunk * taps * c.NJ * 64;
+    hipLaunchKernelGGL(k_pack_weights, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                       w, wp, g.f, g.fo, g.kz, g.ky, g.kx, backward ? 1 : 0, c.NJ, c.jgroups, P.nchunk);
+    int rc = check_launch("weight packing");
+    if (rc != ZNN_OK) return rc;
+    ConvFn fn = pick_kernel(c.NJ, c.NV);
+    if (!fn) return fail(ZNN_EUNSUPPORTED, "no kernel instance for tile %dx%d", c.NJ, c.NV);
+    const long blocks = (long)c.cz * c.cy * c.cx;
+    if (blocks >= 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many tiles for one launch");
+    hipLaunchKernelGGL(fn, dim3((unsigned)blocks, (unsigned)c.jgroups), dim3(256), c.lds, s, P);
+    return check_launch(backward ? "direct backward (MFMA)" : "direct forward (MFMA)");
+}
+
+}  // namespace znn

@@ -41,6 +41,8 @@ SMALL = [
     (7, 9, (17, 13, 20), (5, 3, 2)),
     (4, 6, (7, 25, 15), (3, 1, 5)),
     (17, 33, (8, 9, 35), (2, 2, 3)),
+    (9, 130, (6, 7, 8), (2, 2, 2)),       # more than 128 output maps: several map groups
+    (131, 5, (5, 6, 9), (2, 1, 3)),
 ]
 
 
