@@ -2,6 +2,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <mutex>
@@ -36,6 +37,12 @@ int check_launch(const char* what)
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(ZNN_EHIP, "%s: %s", what, hipGetErrorString(e));
     return ZNN_OK;
+}
+
+bool log_enabled()
+{
+    static const bool on = [] { const char* e = getenv("ZNN_LOG"); return e && *e && *e != '0'; }();
+    return on;
 }
 
 int next_fft_extent(int n)

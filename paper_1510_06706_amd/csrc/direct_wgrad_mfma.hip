@@ -15,6 +15,9 @@
 // through LDS and written as one partial matrix per workgroup.  A second
 // kernel adds the partial matrices in ascending split order, so the result is
 // bit-reproducible (no atomics).
+#include <cstdio>
+#include <cstdlib>
+
 #include "znn_internal.h"
 
 namespace znn {
@@ -22,6 +25,8 @@ namespace znn {
 namespace {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+constexpr int kBatch = 8;
 
 struct WgradTile {
     const float* in; const float* gout; float* partial;
@@ -35,10 +40,11 @@ struct WgradTile {
     int G;              // column groups
     int tiles, tps;     // voxel tiles in total and per split
     int AB;             // kz * ky
+    FastDiv dRT, dTX, dRTH, dTXH, dOY;   // R*TX, TX, R*TXH, TXH, oy
 };
 
 template <int NJ, int NT>
-__global__ void __launch_bounds__(256) k_wgrad_mfma(WgradTile P)
+__global__ void __launch_bounds__(256, (NJ * NT <= 24 ? 2 : 1)) k_wgrad_mfma(WgradTile P)
 {
     extern __shared__ float lds[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -87,35 +93,64 @@ __global__ void __launch_bounds__(256) k_wgrad_mfma(WgradTile P)
         const int xt = tile % P.XT, rt = tile / P.XT;
         const int rho0 = rt * P.R, xs0 = xt * P.TX;
         __syncthreads();
-        for (int t = threadIdx.x; t < NJ * 16 * P.R * P.TX; t += 256) {
-            const int x = t % P.TX;
-            const int r = (t / P.TX) % P.R;
-            const int m = t / (P.TX * P.R);
-            const int j = jg * NJ * 16 + m, rho = rho0 + r, gx = xs0 + x;
-            float v = 0.f;
-            if (j < P.fo && rho < rows && gx < P.ox) v = P.gout[j * oplane + (long)rho * P.ox + gx];
-            gt[m * P.GS + r * P.TX + x] = v;
-        }
-        const int xin0 = xs0 + (P.kx - 1 - cmax);
-        for (int t = threadIdx.x; t < nmaps * P.R * TXH; t += 256) {
-            const int x = t % TXH;
-            const int r = (t / TXH) % P.R;
-            const int m = t / (TXH * P.R);
-            const int rho = rho0 + r, ix = xin0 + x;
-            float v = 0.f;
-            if (rho < rows && ix < P.nx) {
-                const int z = rho / P.oy, y = rho % P.oy;
-                v = P.in[((long)(imin + m) * P.nz + (z + P.kz - 1 - a)) * iplane +
-                         (long)(y + P.ky - 1 - b) * P.nx + ix];
+        // both tiles are fetched in batches of kBatch independent loads per thread
+        {
+            const unsigned total = (unsigned)(NJ * 16 * P.R * P.TX);
+            const unsigned RT = (unsigned)(P.R * P.TX);
+            for (unsigned base = threadIdx.x; base < total; base += 256 * kBatch) {
+                float v[kBatch];
+                int lo[kBatch];
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    const unsigned idx = base + u * 256;
+                    v[u] = 0.f; lo[u] = -1;
+                    if (idx < total) {
+                        const unsigned m = fdiv(idx, P.dRT), e = idx - m * RT;
+                        const unsigned r = fdiv(e, P.dTX), x = e - r * P.TX;
+                        const int j = jg * NJ * 16 + (int)m, rho = rho0 + (int)r, gx = xs0 + (int)x;
+                        lo[u] = (int)(m * P.GS + e);
+                        if (j < P.fo && rho < rows && gx < P.ox) v[u] = P.gout[j * oplane + (long)rho * P.ox + gx];
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u)
+                    if (lo[u] >= 0) gt[lo[u]] = v[u];
             }
-            it[m * P.IS + r * TXH + x] = v;
+        }
+        {
+            const int xin0 = xs0 + (P.kx - 1 - cmax);
+            const unsigned RTH = (unsigned)(P.R * TXH);
+            const unsigned total = (unsigned)nmaps * RTH;
+            for (unsigned base = threadIdx.x; base < total; base += 256 * kBatch) {
+                float v[kBatch];
+                int lo[kBatch];
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    const unsigned idx = base + u * 256;
+                    v[u] = 0.f; lo[u] = -1;
+                    if (idx < total) {
+                        const unsigned m = fdiv(idx, P.dRTH), e = idx - m * RTH;
+                        const unsigned r = fdiv(e, P.dTXH), x = e - r * TXH;
+                        const int rho = rho0 + (int)r, ix = xin0 + (int)x;
+                        lo[u] = (int)(m * P.IS + e);
+                        if (rho < rows && ix < P.nx) {
+                            const int z = (int)fdiv((unsigned)rho, P.dOY), y = rho - z * P.oy;
+                            v[u] = P.in[((long)(imin + (int)m) * P.nz + (z + P.kz - 1 - a)) * iplane +
+                                        (long)(y + P.ky - 1 - b) * P.nx + ix];
+                        }
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u)
+                    if (lo[u] >= 0) it[lo[u]] = v[u];
+            }
         }
         __syncthreads();
 
         float an[NJ], bn[NT];
         {
             const int q = 4 * min(wave, nks - 1);
-            const int r = q / P.TX, tx = q % P.TX;
+            const int r = (int)fdiv((unsigned)q, P.dTX), tx = q - r * P.TX;
             const int ao = r * P.TX + tx, bo = r * TXH + tx;
 #pragma unroll
             for (int jt = 0; jt < NJ; ++jt) an[jt] = gt[aoff[jt] + ao];
@@ -130,7 +165,7 @@ __global__ void __launch_bounds__(256) k_wgrad_mfma(WgradTile P)
             for (int nt = 0; nt < NT; ++nt) bv[nt] = bn[nt];
             const int kn = ks + 4 < nks ? ks + 4 : ks;
             const int q = 4 * kn;
-            const int r = q / P.TX, tx = q % P.TX;
+            const int r = (int)fdiv((unsigned)q, P.dTX), tx = q - r * P.TX;
             const int ao = r * P.TX + tx, bo = r * TXH + tx;
 #pragma unroll
             for (int jt = 0; jt < NJ; ++jt) an[jt] = gt[aoff[jt] + ao];
@@ -199,16 +234,28 @@ k_wgrad_reduce(const float* __restrict__ partial, float* __restrict__ gw, int f,
 
 using WgradFn = void (*)(WgradTile);
 
+constexpr int kMaxTiles = 40;   // accumulator tiles per wave (4 registers each)
+
+template <int NJ, int NT> WgradFn inst()
+{
+    if constexpr (NJ * NT <= kMaxTiles) return k_wgrad_mfma<NJ, NT>;
+    else return nullptr;
+}
+
 template <int NJ> WgradFn pick_nt(int nt)
 {
     switch (nt) {
-        case 1: return k_wgrad_mfma<NJ, 1>;
-        case 2: return k_wgrad_mfma<NJ, 2>;
-        case 4: return k_wgrad_mfma<NJ, 4>;
-        case 8: if (NJ * 8 <= 40) return k_wgrad_mfma<NJ, (NJ * 8 <= 40 ? 8 : 1)>; break;
-        case 10: if (NJ * 10 <= 40) return k_wgrad_mfma<NJ, (NJ * 10 <= 40 ? 10 : 1)>; break;
-        case 13: if (NJ * 13 <= 40) return k_wgrad_mfma<NJ, (NJ * 13 <= 40 ? 13 : 1)>; break;
-        case 16: if (NJ * 16 <= 40) return k_wgrad_mfma<NJ, (NJ * 16 <= 40 ? 16 : 1)>; break;
+        case 1: return inst<NJ, 1>();
+        case 2: return inst<NJ, 2>();
+        case 3: return inst<NJ, 3>();
+        case 4: return inst<NJ, 4>();
+        case 5: return inst<NJ, 5>();
+        case 6: return inst<NJ, 6>();
+        case 7: return inst<NJ, 7>();
+        case 8: return inst<NJ, 8>();
+        case 10: return inst<NJ, 10>();
+        case 13: return inst<NJ, 13>();
+        case 16: return inst<NJ, 16>();
     }
     return nullptr;
 }
@@ -237,7 +284,6 @@ struct WgradChoice {
     size_t lds;
 };
 
-constexpr size_t kWgradLdsMax = 64 * 1024;
 
 int pad_stride(int n)   // smallest value >= n that is 4 modulo 32 (bank spread of 16 maps x 4 voxels)
 {
@@ -245,8 +291,16 @@ int pad_stride(int n)   // smallest value >= n that is 4 modulo 32 (bank spread 
     return n;
 }
 
+int wgrad_occupancy()
+{
+    static const int occ = [] { const char* e = getenv("ZNN_WGRAD_OCC"); return e ? atoi(e) : 2; }();
+    return occ;
+}
+
 WgradChoice choose_wgrad(const Geom& g)
 {
+    const int occ = wgrad_occupancy();
+    const size_t lds_max = occ >= 2 ? 64 * 1024 : 128 * 1024;
     WgradChoice c = {};
     c.ok = false;
     const int mt = (g.fo + 15) / 16;
@@ -254,15 +308,18 @@ WgradChoice choose_wgrad(const Geom& g)
     c.NJ = (mt + c.JG - 1) / c.JG;
     const int ncols = g.f * g.kx;
     const int nt_tot = (ncols + 15) / 16;
-    const int allowed[7] = {1, 2, 4, 8, 10, 13, 16};
+    // occupancy 2 (two waves per SIMD, tiles overlap each other's staging) needs <= 24
+    // accumulator tiles per wave; occupancy 1 allows 40 and fewer column groups.
+    const int budget = occ >= 2 ? 24 : kMaxTiles;
+    const int allowed[11] = {1, 2, 3, 4, 5, 6, 7, 8, 10, 13, 16};
     int nt_max = 1;
-    for (int k = 0; k < 7; ++k)
-        if (c.NJ * allowed[k] <= 40) nt_max = allowed[k];
+    for (int k = 0; k < 11; ++k)
+        if (c.NJ * allowed[k] <= budget) nt_max = allowed[k];
     c.G = (nt_tot + nt_max - 1) / nt_max;
     const int want = (nt_tot + c.G - 1) / c.G;
     c.NT = nt_max;
-    for (int k = 6; k >= 0; --k)
-        if (allowed[k] >= want && c.NJ * allowed[k] <= 40) c.NT = allowed[k];
+    for (int k = 10; k >= 0; --k)
+        if (allowed[k] >= want && c.NJ * allowed[k] <= budget) c.NT = allowed[k];
     c.G = (nt_tot + c.NT - 1) / c.NT;
     if (!pick_wgrad(c.NJ, c.NT)) return c;
     c.Mpad = c.JG * c.NJ * 16;
@@ -285,17 +342,17 @@ WgradChoice choose_wgrad(const Geom& g)
         const int TX = (seg + 3) & ~3;
         const int TXH = TX + cspan;
         int bestR = 0;
-        for (int R = 1; R <= 8 && R <= rows; ++R) {
+        for (int R = 1; R <= 16 && R <= rows && R * (TX + cspan) * nmaps < 60000; ++R) {
             const int GS = pad_stride(R * TX), IS = pad_stride(R * TXH);
             const size_t bytes = ((size_t)c.NJ * 16 * GS + (size_t)nmaps * IS) * 4;
-            if (bytes <= kWgradLdsMax) bestR = R;
+            if (bytes <= lds_max) bestR = R;
         }
         if (bestR == 0) continue;
         c.XT = XT; c.TX = TX; c.TXH = TXH; c.R = bestR;
         c.GS = pad_stride(bestR * TX); c.IS = pad_stride(bestR * TXH);
         size_t bytes = ((size_t)c.NJ * 16 * c.GS + (size_t)nmaps * c.IS) * 4;
         if (bytes < red) bytes = red;
-        if (bytes > kWgradLdsMax) continue;
+        if (bytes > lds_max) continue;
         c.lds = bytes;
         c.ok = true;
         break;
@@ -339,8 +396,16 @@ int mfma_wgrad(const Geom& g, const float* in, const float* gout, float* gw, voi
     P.G = c.G;
     P.tiles = c.tiles; P.tps = c.tps;
     P.AB = g.kz * g.ky;
+    P.dRT = make_fastdiv(c.R * c.TX); P.dTX = make_fastdiv(c.TX);
+    P.dRTH = make_fastdiv(c.R * c.TXH); P.dTXH = make_fastdiv(c.TXH); P.dOY = make_fastdiv(g.oy);
+    if (log_enabled())
+        fprintf(stderr, "[znn] wgrad mfma: NJ=%d JG=%d NT=%d G=%d TX=%d XT=%d R=%d lds=%zu ksplit=%d tiles=%d\n",
+                c.NJ, c.JG, c.NT, c.G, c.TX, c.XT, c.R, c.lds, c.ksplit, c.tiles);
     WgradFn fn = pick_wgrad(c.NJ, c.NT);
     if (!fn) return fail(ZNN_EUNSUPPORTED, "no kernel instance for tile %dx%d", c.NJ, c.NT);
+    if (c.lds > 64 * 1024 &&
+        hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c.lds) != hipSuccess)
+        return fail(ZNN_EHIP, "cannot reserve %zu bytes of LDS", c.lds);
     hipLaunchKernelGGL(fn, dim3((unsigned)c.ksplit, (unsigned)P.AB, (unsigned)(c.G * c.JG)), dim3(256), c.lds, s, P);
     int rc = check_launch("direct kernel gradient (MFMA)");
     if (rc != ZNN_OK) return rc;

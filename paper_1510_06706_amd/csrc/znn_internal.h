@@ -36,6 +36,26 @@ int  next_fft_extent(int n);
 // Largest FFT extent the LDS-resident passes accept.
 constexpr int kMaxFftExtent = 1024;
 
+// Division of small unsigned numbers by a launch constant without a hardware divide:
+// q = (n * M) >> 32 with M = floor(2^32 / d) + 1 is exact while n * d < 2^32.
+struct FastDiv {
+    unsigned d, M;
+};
+inline FastDiv make_fastdiv(unsigned d)
+{
+    FastDiv f;
+    f.d = d;
+    f.M = d <= 1 ? 0u : (unsigned)(((1ull << 32) / d) + 1ull);
+    return f;
+}
+__device__ __forceinline__ unsigned fdiv(unsigned n, FastDiv f)
+{
+    return f.d <= 1 ? n : __umulhi(n, f.M);
+}
+
+// True when ZNN_LOG is set in the environment: launch configurations are printed to stderr.
+bool log_enabled();
+
 // ---------------------------------------------------------------- direct method
 int direct_fwd(const Geom& g, const float* in, const float* w, float* out, void* ws, hipStream_t s);
 int direct_bwd(const Geom& g, const float* gout, const float* w, float* gin, void* ws, hipStream_t s);

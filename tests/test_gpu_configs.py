@@ -1,0 +1,172 @@
+"""Parity at the benchmark's full sizes: configs 2, 4, 5 on outputs sampled one by one
+from the oracle, config 3 (a whole training round) layer by layer and end to end."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import net as onet
+from paper_1510_06706_amd import binding as znn
+from paper_1510_06706_amd import net as znet
+from paper_1510_06706_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"direct": 1e-4, "fft": 1e-3}
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def host(t):
+    import torch
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def rel_err(got, ref):
+    return float(np.max(np.abs(np.asarray(got, dtype=np.float64) - ref)) / max(np.max(np.abs(ref)), 1e-300))
+
+
+def sampled_layer_check(cfg, mode, resident, n_fwd, n_bwd, n_gw):
+    inp, w, gout = synth.layer_tensors(cfg)
+    p = znn.Plan(cfg.fan_in, cfg.fan_out, cfg.image, cfg.kernel, mode)
+    d_in, d_w, d_g = dev(inp), dev(w), dev(gout)
+    if resident:
+        p.prepare_kernels(d_w)
+    wk = None if resident else d_w
+    rs = np.random.RandomState(cfg.seed)
+    out = host(p.fwd(d_in, wk)).ravel()
+    pos = rs.randint(0, out.size, size=n_fwd)
+    pos[:2] = (0, out.size - 1)
+    e_fwd = rel_err(out[pos], oracle.conv3d_fwd_at(inp, w, pos))
+    del out
+    gin = host(p.bwd(d_g, wk)).ravel()
+    pos = rs.randint(0, gin.size, size=n_bwd)
+    pos[:2] = (0, gin.size - 1)
+    e_bwd = rel_err(gin[pos], oracle.conv3d_bwd_at(gout, w, cfg.image, pos))
+    del gin
+    gw = host(p.wgrad(d_in, d_g)).ravel()
+    pos = rs.randint(0, gw.size, size=n_gw)
+    pos[:2] = (0, gw.size - 1)
+    e_gw = rel_err(gw[pos], oracle.conv3d_wgrad_at(inp, gout, pos))
+    print("%s %s: rel-err fwd %.2e bwd %.2e wgrad %.2e" % (cfg.name, mode, e_fwd, e_bwd, e_gw), flush=True)
+    p.close()
+    tol = TOL[mode]
+    assert e_fwd <= tol and e_bwd <= tol and e_gw <= tol
+
+
+@pytest.mark.parametrize("mode", ["direct", "fft"])
+def test_config2_wide_3d_layer(mode):
+    sampled_layer_check(synth.CONFIG2, mode, False, 4096, 4096, 1024)
+
+
+@pytest.mark.parametrize("mode", ["direct", "fft"])
+def test_config4_two_dimensional_large_kernel(mode):
+    sampled_layer_check(synth.CONFIG4, mode, False, 4096, 4096, 1024)
+
+
+@pytest.mark.timeout(600)
+def test_config5_large_layer_with_resident_kernel_spectra():
+    sampled_layer_check(synth.CONFIG5, "fft", True, 4096, 4096, 1024)
+
+
+@pytest.mark.parametrize("mode", ["direct", "fft", "auto"])
+def test_config3_training_round(mode):
+    import torch
+    layers = znet.CONFIG3_LAYERS
+    x, target, params = znet.config3_tensors()
+    if mode == "auto":      # let the autotuner measure every convolutional layer first
+        sh = znet.shapes(layers, znet.CONFIG3_INPUT)
+        for l, spec in enumerate(layers):
+            if spec[0] == "conv":
+                chosen, ms = znn.autotune(spec[1], spec[2], sh[l][1:], spec[3])
+                print("  autotune layer %d: %s  direct %.3f ms, fft %.3f ms"
+                      % (l, "fft" if chosen == znn.ZNN_FFT else "direct", sum(ms[0]), sum(ms[1])), flush=True)
+    net = znet.Net(layers, znet.CONFIG3_INPUT, params, mode)
+    record = []
+    acts, aux, gout, grads = net.train_round(dev(x), dev(target), znet.CONFIG3_ETA, record)
+    torch.cuda.synchronize()
+    plan_modes = net.modes()
+    arriving = dict(record)
+
+    def tol_of(l):
+        return TOL["fft" if plan_modes[l] == znn.ZNN_FFT else "direct"]
+
+    # layer by layer: every oracle op is fed the GPU's own input to that layer
+    for l, spec in enumerate(layers):
+        a = host(acts[l]).astype(np.float64)
+        y = host(acts[l + 1])
+        g_out = host(arriving[l]).astype(np.float64)
+        if spec[0] == "conv":
+            w = params[l]["w"]
+            assert rel_err(y, oracle.conv3d_fwd(a, w)) <= tol_of(l), ("fwd", l)
+            assert rel_err(host(grads[l]["w"]), oracle.conv3d_wgrad(a, g_out)) <= tol_of(l), ("wgrad", l)
+        elif spec[0] == "transfer":
+            want = np.maximum(a + params[l]["b"].astype(np.float64)[:, None, None, None], 0.0)
+            assert rel_err(y, want) <= 1e-6, ("transfer", l)
+            assert np.array_equal(y > 0, want > 0) or np.mean((y > 0) != (want > 0)) < 1e-5
+            g_in = g_out * (y > 0)
+            assert rel_err(host(grads[l]["b"]), g_in.reshape(g_in.shape[0], -1).sum(1)) <= 1e-5, ("bias", l)
+        else:
+            r_out, r_idx = oracle.maxfilter3d_fwd(a, spec[1])
+            assert np.array_equal(y.astype(np.float64), r_out), ("maxfilter", l)
+            assert np.array_equal(host(aux[l]), r_idx), ("maxfilter idx", l)
+    # backward images: conv Jacobian and max-filter Jacobian, fed the GPU's incoming gradient
+    for l, spec in enumerate(layers):
+        if l == 0:
+            continue
+        g_out = host(arriving[l]).astype(np.float64)
+        g_in = host(arriving[l - 1]).astype(np.float64)
+        if spec[0] == "conv":
+            want = oracle.conv3d_bwd(g_out, params[l]["w"], net.shapes[l][1:])
+            assert rel_err(g_in, want) <= tol_of(l), ("bwd", l)
+        elif spec[0] == "maxfilter":
+            want = oracle.maxfilter3d_bwd(g_out, host(aux[l]), net.shapes[l][1:], spec[1])
+            assert rel_err(g_in, want) <= 1e-6, ("maxfilter bwd", l)
+
+    # end to end against the float64 round started from the same fp32 inputs
+    p64 = [None if p is None else {k: v.astype(np.float64) for k, v in p.items()} for p in params]
+    loss, r_acts, r_aux, r_grads, r_new = onet.train_round(layers, p64, x, target, znet.CONFIG3_ETA)
+    e2e = max(TOL["fft" if m == znn.ZNN_FFT else "direct"] for m in plan_modes if m is not None)
+    out = host(acts[-1])
+    assert rel_err(out, r_acts[-1]) <= e2e
+    gpu_loss = 0.5 * float(np.sum((out.astype(np.float64) - target) ** 2))
+    assert abs(gpu_loss - loss) <= e2e * abs(loss)
+    # Several winners are correct where two voxels of a window agree to rounding: an fp32
+    # difference upstream may pick the other one.  Such flips must be near-ties in the
+    # oracle's own images; the oracle's backward pass then takes the GPU's (valid) choice,
+    # so that the gradients compared below are those of the same selection.
+    r_aux_sel = list(r_aux)
+    for l, spec in enumerate(layers):
+        if spec[0] != "maxfilter":
+            continue
+        g_idx = host(aux[l])
+        bad = np.argwhere(g_idx != r_aux[l])
+        a = r_acts[l]
+        for m, z, y, xx in bad:
+            q = int(g_idx[m, z, y, xx])
+            qz, qy, qx = np.unravel_index(q, a.shape[1:])
+            assert z <= qz < z + spec[1][0] and y <= qy < y + spec[1][1] and xx <= qx < xx + spec[1][2]
+            assert abs(a[m].ravel()[q] - r_acts[l + 1][m, z, y, xx]) <= 1e-5 * np.max(np.abs(a))
+        r_aux_sel[l] = g_idx
+    r_grads = onet.backward(layers, p64, r_acts, r_aux_sel, r_acts[-1] - target.astype(np.float64))
+    r_new = [None if p is None else {k: v - znet.CONFIG3_ETA * r_grads[l][k] for k, v in p.items()}
+             for l, p in enumerate(p64)]
+    worst_g, worst_p = 0.0, 0.0
+    for l, g in enumerate(r_grads):
+        if g is None:
+            continue
+        for k in g:
+            eg = rel_err(host(grads[l][k]), g[k])
+            ep = rel_err(host(net.params[l][k]), r_new[l][k])
+            print("  layer %2d %s: gradient rel-err %.2e, updated parameter rel-err %.2e" % (l, k, eg, ep), flush=True)
+            worst_g, worst_p = max(worst_g, eg), max(worst_p, ep)
+    flips = sum(int(np.sum(host(aux[l]) != r_aux[l])) for l in range(len(layers)) if r_aux[l] is not None)
+    relu_flips = sum(int(np.sum((host(acts[l + 1]) > 0) != (r_acts[l + 1] > 0)))
+                     for l, spec in enumerate(layers) if spec[0] == "transfer")
+    print("config 3 %s: modes %s loss %.6f (ref %.6f) worst gradient rel-err %.2e, worst parameter rel-err %.2e, "
+          "argmax flips %d, rectifier flips %d" % (mode, [m for m in plan_modes if m is not None], gpu_loss, loss,
+                                                   worst_g, worst_p, flips, relu_flips), flush=True)
+    assert worst_g <= e2e and worst_p <= e2e
