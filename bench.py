@@ -152,9 +152,18 @@ def main():
                          "voxels_per_s": cfg.out_voxels / (tot * 1e-3),
                          "effective_tflops": 3 * flop_pass / (tot * 1e-3) / 1e12}
 
-    # roofline of the dominant kernel of the step
+    # per-kernel durations from HIP events recorded by the library around every launch,
+    # on the stream the kernels run on; roofline of the kernel that dominates the step
     from paper_1510_06706_amd import roofline as rl
-    roof = rl.dominant(cfg, per, plans, d_in, d_w, d_g, out, gin, gw)
+    trace_steps = 3
+    torch.cuda.synchronize()
+    znn.trace_enable(True)
+    for _ in range(trace_steps):
+        step()
+    torch.cuda.synchronize()
+    records = znn.trace_collect(65536)
+    znn.trace_enable(False)
+    roof, kernels = rl.report(cfg, plans["fft"].fft_extents, records, trace_steps)
 
     result = {
         "metric": "conv-layer fwd+bwd+wgrad output voxels/s (direct and FFT method, each once per step)",
@@ -169,6 +178,7 @@ def main():
         "effective_tflops_per_step": 2 * 3 * flop_pass / (ms_per_step * 1e-3) / 1e12,
         "per_mode": summary,
         "roofline": roof,
+        "kernels": kernels,
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, inp, w, gout)

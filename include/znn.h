@@ -166,6 +166,17 @@ int  znn_autotune_workspace_bytes(const znn_conv_desc* desc, size_t* bytes);
 int  znn_autotune(const znn_conv_desc* desc, void* ws, size_t ws_bytes, void* stream,
                   int32_t* chosen_mode, float ms[2][3]);
 
+/*
+ * Kernel-level timing for benchmarks and roofline reports.  While enabled, every
+ * kernel the library launches is bracketed by two HIP events on its stream.
+ * znn_trace_collect waits for the recorded launches, returns them in launch
+ * order (name of the kernel's role, milliseconds) and forgets them; *count is
+ * the number recorded even when it exceeds `capacity`.  Process-wide; off by default.
+ */
+typedef struct { char name[56]; float ms; } znn_trace_record;
+int  znn_trace_enable(int32_t on);
+int  znn_trace_collect(znn_trace_record* records, int32_t capacity, int32_t* count);
+
 /* Description of the last error on the calling thread ("" if none). Never NULL. */
 const char* znn_last_error(void);
 

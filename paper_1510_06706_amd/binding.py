@@ -24,7 +24,7 @@ EXPORTS = [
     "znn_conv_release_kernels", "znn_conv3d_fwd", "znn_conv3d_bwd", "znn_conv3d_wgrad",
     "znn_maxfilter3d_fwd", "znn_maxfilter3d_bwd", "znn_transfer_fwd", "znn_transfer_bwd",
     "znn_bias_grad", "znn_square_loss_grad", "znn_sgd_update", "znn_autotune_workspace_bytes",
-    "znn_autotune", "znn_last_error",
+    "znn_autotune", "znn_last_error", "znn_trace_enable", "znn_trace_collect",
 ]
 
 
@@ -35,6 +35,10 @@ class Vec3(ctypes.Structure):
 class ConvDesc(ctypes.Structure):
     _fields_ = [("fan_in", ctypes.c_int32), ("fan_out", ctypes.c_int32), ("image", Vec3),
                 ("kernel", Vec3), ("sparsity", Vec3), ("mode", ctypes.c_int32)]
+
+
+class TraceRecord(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char * 56), ("ms", ctypes.c_float)]
 
 
 class ZnnError(RuntimeError):
@@ -80,6 +84,8 @@ def lib():
         L.znn_autotune_workspace_bytes.argtypes = [ctypes.POINTER(ConvDesc), ctypes.POINTER(sz)]
         L.znn_autotune.argtypes = [ctypes.POINTER(ConvDesc), vp, sz, vp, ctypes.POINTER(i32),
                                    ctypes.POINTER(ctypes.c_float * 3 * 2)]
+        L.znn_trace_enable.argtypes = [i32]
+        L.znn_trace_collect.argtypes = [ctypes.POINTER(TraceRecord), i32, ctypes.POINTER(i32)]
         for name in EXPORTS:
             if name not in ("znn_last_error", "znn_plan_destroy"):
                 getattr(L, name).restype = ctypes.c_int
@@ -319,3 +325,15 @@ def autotune(fan_in, fan_out, image, kernel, device="cuda:0", stream=None):
     _check(lib().znn_autotune(ctypes.byref(desc), ctypes.c_void_p(aligned), need, _stream_ptr(stream),
                               ctypes.byref(chosen), ctypes.byref(ms)))
     return chosen.value, [[ms[m][p] for p in range(3)] for m in range(2)]
+
+
+def trace_enable(on: bool):
+    _check(lib().znn_trace_enable(1 if on else 0))
+
+
+def trace_collect(capacity: int = 4096):
+    """[(kernel role, ms)] of every launch recorded since the last call, in launch order."""
+    buf = (TraceRecord * capacity)()
+    n = ctypes.c_int32(0)
+    _check(lib().znn_trace_collect(buf, capacity, ctypes.byref(n)))
+    return [(buf[i].name.decode(), float(buf[i].ms)) for i in range(min(n.value, capacity))]

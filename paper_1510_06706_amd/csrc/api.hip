@@ -8,6 +8,7 @@
 #include <mutex>
 #include <new>
 #include <tuple>
+#include <vector>
 
 #include "znn_internal.h"
 
@@ -37,6 +38,32 @@ int check_launch(const char* what)
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(ZNN_EHIP, "%s: %s", what, hipGetErrorString(e));
     return ZNN_OK;
+}
+
+// ---------------------------------------------------------------- tracing
+struct TraceEntry { const char* name; hipEvent_t e0, e1; };
+static std::mutex g_trace_mu;
+static bool g_trace_on = false;
+static std::vector<TraceEntry> g_trace;
+
+TraceScope::TraceScope(const char* name, hipStream_t s) : slot(-1), stream(s)
+{
+    if (!g_trace_on) return;
+    std::lock_guard<std::mutex> lk(g_trace_mu);
+    TraceEntry e;
+    e.name = name;
+    if (hipEventCreate(&e.e0) != hipSuccess) return;
+    if (hipEventCreate(&e.e1) != hipSuccess) { (void)hipEventDestroy(e.e0); return; }
+    (void)hipEventRecord(e.e0, s);
+    g_trace.push_back(e);
+    slot = (int)g_trace.size() - 1;
+}
+
+TraceScope::~TraceScope()
+{
+    if (slot < 0) return;
+    std::lock_guard<std::mutex> lk(g_trace_mu);
+    if (slot < (int)g_trace.size()) (void)hipEventRecord(g_trace[slot].e1, stream);
 }
 
 bool log_enabled()
@@ -127,6 +154,35 @@ using namespace znn;
 extern "C" {
 
 const char* znn_last_error(void) { return g_err; }
+
+int znn_trace_enable(int32_t on)
+{
+    std::lock_guard<std::mutex> lk(g_trace_mu);
+    g_trace_on = on != 0;
+    return ZNN_OK;
+}
+
+int znn_trace_collect(znn_trace_record* records, int32_t capacity, int32_t* count)
+{
+    if (!count || capacity < 0 || (capacity > 0 && !records)) return fail(ZNN_EINVAL, "bad trace buffer");
+    std::lock_guard<std::mutex> lk(g_trace_mu);
+    int n = 0, rc = ZNN_OK;
+    for (TraceEntry& e : g_trace) {
+        float ms = 0.f;
+        if (hipEventSynchronize(e.e1) != hipSuccess || hipEventElapsedTime(&ms, e.e0, e.e1) != hipSuccess)
+            rc = fail(ZNN_EHIP, "cannot read the events of '%s'", e.name);
+        if (n < capacity) {
+            snprintf(records[n].name, sizeof(records[n].name), "%s", e.name);
+            records[n].ms = ms;
+        }
+        ++n;
+        (void)hipEventDestroy(e.e0);
+        (void)hipEventDestroy(e.e1);
+    }
+    g_trace.clear();
+    *count = n;
+    return rc;
+}
 
 int znn_plan_create(const znn_conv_desc* desc, znn_plan** plan)
 {

@@ -102,14 +102,14 @@ k_direct_wgrad_generic(Geom g, const float* __restrict__ in, const float* __rest
 int direct_fwd_generic(const Geom& g, const float* in, const float* w, float* out, hipStream_t s)
 {
     dim3 grid((unsigned)((g.ovol() + 255) / 256), (unsigned)g.fo);
-    hipLaunchKernelGGL(k_direct_fwd_generic, grid, dim3(256), 0, s, g, in, w, out);
+    ZNN_LAUNCH("direct forward (generic)", s, k_direct_fwd_generic, grid, dim3(256), 0, g, in, w, out);
     return check_launch("direct forward (generic)");
 }
 
 int direct_bwd_generic(const Geom& g, const float* gout, const float* w, float* gin, hipStream_t s)
 {
     dim3 grid((unsigned)((g.nvol() + 255) / 256), (unsigned)g.f);
-    hipLaunchKernelGGL(k_direct_bwd_generic, grid, dim3(256), 0, s, g, gout, w, gin);
+    ZNN_LAUNCH("direct backward (generic)", s, k_direct_bwd_generic, grid, dim3(256), 0, g, gout, w, gin);
     return check_launch("direct backward (generic)");
 }
 
@@ -117,7 +117,7 @@ int direct_wgrad_generic(const Geom& g, const float* in, const float* gout, floa
 {
     const long blocks = (long)g.f * g.fo * g.kvol();
     if (blocks >= 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many kernel taps for one launch");
-    hipLaunchKernelGGL(k_direct_wgrad_generic, dim3((unsigned)blocks), dim3(256), 0, s, g, in, gout, gw);
+    ZNN_LAUNCH("direct kernel gradient (generic)", s, k_direct_wgrad_generic, dim3((unsigned)blocks), dim3(256), 0, g, in, gout, gw);
     return check_launch("direct kernel gradient (generic)");
 }
 

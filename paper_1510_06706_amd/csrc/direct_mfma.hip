@@ -358,7 +358,7 @@ int mfma_conv(const Geom& g, bool backward, const float* src, const float* w, fl
     float* wp = (float*)ws;
     P.wp = wp;
     const long total = (long)c.jgroups * P.nchunk * taps * c.NJ * 64;
-    hipLaunchKernelGGL(k_pack_weights, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+    ZNN_LAUNCH("weight packing", s, k_pack_weights, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
                        w, wp, g.f, g.fo, g.kz, g.ky, g.kx, backward ? 1 : 0, c.NJ, c.jgroups, P.nchunk);
     int rc = check_launch("weight packing");
     if (rc != ZNN_OK) return rc;
@@ -366,7 +366,7 @@ int mfma_conv(const Geom& g, bool backward, const float* src, const float* w, fl
     if (!fn) return fail(ZNN_EUNSUPPORTED, "no kernel instance for tile %dx%d", c.NJ, c.NV);
     const long blocks = (long)c.cz * c.cy * c.cx;
     if (blocks >= 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many tiles for one launch");
-    hipLaunchKernelGGL(fn, dim3((unsigned)blocks, (unsigned)c.jgroups), dim3(256), c.lds, s, P);
+    ZNN_LAUNCH(backward ? "direct backward (MFMA)" : "direct forward (MFMA)", s, fn, dim3((unsigned)blocks, (unsigned)c.jgroups), dim3(256), c.lds, P);
     return check_launch(backward ? "direct backward (MFMA)" : "direct forward (MFMA)");
 }
 

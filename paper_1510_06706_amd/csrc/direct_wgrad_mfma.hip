@@ -406,11 +406,11 @@ int mfma_wgrad(const Geom& g, const float* in, const float* gout, float* gw, voi
     if (c.lds > 64 * 1024 &&
         hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c.lds) != hipSuccess)
         return fail(ZNN_EHIP, "cannot reserve %zu bytes of LDS", c.lds);
-    hipLaunchKernelGGL(fn, dim3((unsigned)c.ksplit, (unsigned)P.AB, (unsigned)(c.G * c.JG)), dim3(256), c.lds, s, P);
+    ZNN_LAUNCH("direct kernel gradient (MFMA)", s, fn, dim3((unsigned)c.ksplit, (unsigned)P.AB, (unsigned)(c.G * c.JG)), dim3(256), c.lds, P);
     int rc = check_launch("direct kernel gradient (MFMA)");
     if (rc != ZNN_OK) return rc;
     const long total = (long)g.fo * g.f * g.kvol();
-    hipLaunchKernelGGL(k_wgrad_reduce, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+    ZNN_LAUNCH("kernel gradient reduction", s, k_wgrad_reduce, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
                        (const float*)ws, gw, g.f, g.fo, g.kz, g.ky, g.kx, c.ksplit, c.Mpad, c.Npad);
     return check_launch("kernel gradient reduction");
 }

@@ -383,7 +383,7 @@ int launch_r2c(const float* src, float2* dst, long maps, int sz, int sy, int sx,
     P.rad = factorize(Nx);
     const long blocks = (P.rows + 2 * P.W - 1) / (2 * P.W);
     if (blocks >= 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many rows for one launch");
-    hipLaunchKernelGGL(k_fft_r2c_x, dim3((unsigned)blocks), dim3(kThreads), lds_bytes(Nx, P.Wp), s, P);
+    ZNN_LAUNCH("fft r2c x", s, k_fft_r2c_x, dim3((unsigned)blocks), dim3(kThreads), lds_bytes(Nx, P.Wp), P);
     return check_launch("r2c x pass");
 }
 
@@ -403,7 +403,7 @@ int launch_c2r(const float2* src, float* dst, long maps, int Nz, int Ny, int Nx,
     P.rad = factorize(Nx);
     const long blocks = (P.rows + 2 * P.W - 1) / (2 * P.W);
     if (blocks >= 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many rows for one launch");
-    hipLaunchKernelGGL(k_fft_c2r_x, dim3((unsigned)blocks), dim3(kThreads), lds_bytes(Nx, P.Wp), s, P);
+    ZNN_LAUNCH("fft c2r x", s, k_fft_c2r_x, dim3((unsigned)blocks), dim3(kThreads), lds_bytes(Nx, P.Wp), P);
     return check_launch("c2r x pass");
 }
 
@@ -424,11 +424,11 @@ int launch_axis(AxisParams P, int dir, hipStream_t s)
     const size_t lds = lds_bytes(P.N, P.Wp);
     const dim3 grid((unsigned)blocks), block(kThreads);
     if (P.in2) {
-        if (dir > 0) hipLaunchKernelGGL((k_fft_axis<+1, true>), grid, block, lds, s, P);
-        else         hipLaunchKernelGGL((k_fft_axis<-1, true>), grid, block, lds, s, P);
+        if (dir > 0) ZNN_LAUNCH("fft axis inverse of product", s, (k_fft_axis<+1, true>), grid, block, lds, P);
+        else         ZNN_LAUNCH("fft axis forward of product", s, (k_fft_axis<-1, true>), grid, block, lds, P);
     } else {
-        if (dir > 0) hipLaunchKernelGGL((k_fft_axis<+1, false>), grid, block, lds, s, P);
-        else         hipLaunchKernelGGL((k_fft_axis<-1, false>), grid, block, lds, s, P);
+        if (dir > 0) ZNN_LAUNCH("fft axis inverse", s, (k_fft_axis<+1, false>), grid, block, lds, P);
+        else         ZNN_LAUNCH("fft axis forward", s, (k_fft_axis<-1, false>), grid, block, lds, P);
     }
     return check_launch("strided FFT pass");
 }
@@ -494,8 +494,8 @@ int launch_mac(bool backward, const Geom& g, const float2* What, const float2* a
     const long svol = g.svol();
     const int outs = backward ? g.f : g.fo;
     dim3 grid((unsigned)((svol + kThreads - 1) / kThreads), (unsigned)((outs + kMacGroup - 1) / kMacGroup));
-    if (backward) hipLaunchKernelGGL(k_mac_bwd, grid, dim3(kThreads), 0, s, g.f, g.fo, svol, What, a, b);
-    else          hipLaunchKernelGGL(k_mac_fwd, grid, dim3(kThreads), 0, s, g.f, g.fo, svol, What, a, b);
+    if (backward) ZNN_LAUNCH("spectral mac backward", s, k_mac_bwd, grid, dim3(kThreads), 0, g.f, g.fo, svol, What, a, b);
+    else          ZNN_LAUNCH("spectral mac forward", s, k_mac_fwd, grid, dim3(kThreads), 0, g.f, g.fo, svol, What, a, b);
     return check_launch("spectral multiply-accumulate");
 }
 

@@ -124,7 +124,7 @@ k_fill_pattern(long total, float scale, float* __restrict__ p)
 int fill_pattern(float* p, long count, float scale, hipStream_t s)
 {
     if (count <= 0) return ZNN_OK;
-    hipLaunchKernelGGL(k_fill_pattern, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, count, scale, p);
+    ZNN_LAUNCH("fill", s, k_fill_pattern, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, count, scale, p);
     return check_launch("fill");
 }
 
@@ -156,7 +156,7 @@ int znn_maxfilter3d_fwd(int32_t maps, znn_vec3 n, znn_vec3 win, const float* in,
     if (rc != ZNN_OK) return rc;
     if (!in || !out || !idx) return fail(ZNN_EINVAL, "NULL argument");
     const long total = (long)maps * (n.z - win.z + 1) * (n.y - win.y + 1) * (n.x - win.x + 1);
-    hipLaunchKernelGGL(k_maxfilter_fwd, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+    ZNN_LAUNCH("max-filter forward", (hipStream_t)stream, k_maxfilter_fwd, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
                        maps, n.z, n.y, n.x, win.z, win.y, win.x, in, out, idx);
     return check_launch("max-filter forward");
 }
@@ -168,7 +168,7 @@ int znn_maxfilter3d_bwd(int32_t maps, znn_vec3 n, znn_vec3 win, const float* gou
     if (rc != ZNN_OK) return rc;
     if (!gout || !idx || !gin) return fail(ZNN_EINVAL, "NULL argument");
     const long total = (long)maps * n.z * n.y * n.x;
-    hipLaunchKernelGGL(k_maxfilter_bwd, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+    ZNN_LAUNCH("max-filter backward", (hipStream_t)stream, k_maxfilter_bwd, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
                        maps, n.z, n.y, n.x, win.z, win.y, win.x, gout, idx, gin);
     return check_launch("max-filter backward");
 }
@@ -187,7 +187,7 @@ int znn_transfer_fwd(int32_t maps, int64_t voxels, const float* x, const float* 
     const long total = (long)maps * voxels;
     int rc = check_count(total);
     if (rc != ZNN_OK) return rc;
-    hipLaunchKernelGGL(k_transfer_fwd, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+    ZNN_LAUNCH("transfer forward", (hipStream_t)stream, k_transfer_fwd, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
                        total, (long)voxels, x, bias, y);
     return check_launch("transfer forward");
 }
@@ -199,7 +199,7 @@ int znn_transfer_bwd(int32_t maps, int64_t voxels, const float* gy, const float*
     const long total = (long)maps * voxels;
     int rc = check_count(total);
     if (rc != ZNN_OK) return rc;
-    hipLaunchKernelGGL(k_transfer_bwd, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+    ZNN_LAUNCH("transfer backward", (hipStream_t)stream, k_transfer_bwd, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
                        total, gy, y, gx);
     return check_launch("transfer backward");
 }
@@ -208,7 +208,7 @@ int znn_bias_grad(int32_t maps, int64_t voxels, const float* g, float* gb, void*
 {
     if (maps < 1 || voxels < 1) return fail(ZNN_EINVAL, "maps and voxels must be >= 1");
     if (!g || !gb) return fail(ZNN_EINVAL, "NULL argument");
-    hipLaunchKernelGGL(k_bias_grad, dim3((unsigned)maps), dim3(256), 0, (hipStream_t)stream, (long)voxels, g, gb);
+    ZNN_LAUNCH("bias gradient", (hipStream_t)stream, k_bias_grad, dim3((unsigned)maps), dim3(256), 0, (long)voxels, g, gb);
     return check_launch("bias gradient");
 }
 
@@ -217,7 +217,7 @@ int znn_square_loss_grad(int64_t count, const float* out, const float* target, f
     int rc = check_count(count);
     if (rc != ZNN_OK) return rc;
     if (!out || !target || !g) return fail(ZNN_EINVAL, "NULL argument");
-    hipLaunchKernelGGL(k_sub, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+    ZNN_LAUNCH("loss gradient", (hipStream_t)stream, k_sub, dim3((unsigned)((count + 255) / 256)), dim3(256), 0,
                        (long)count, out, target, g);
     return check_launch("loss gradient");
 }
@@ -227,7 +227,7 @@ int znn_sgd_update(int64_t count, float eta, const float* g, float* p, void* str
     int rc = check_count(count);
     if (rc != ZNN_OK) return rc;
     if (!g || !p) return fail(ZNN_EINVAL, "NULL argument");
-    hipLaunchKernelGGL(k_sgd, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+    ZNN_LAUNCH("SGD update", (hipStream_t)stream, k_sgd, dim3((unsigned)((count + 255) / 256)), dim3(256), 0,
                        (long)count, eta, g, p);
     return check_launch("SGD update");
 }

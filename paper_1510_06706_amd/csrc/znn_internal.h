@@ -16,6 +16,20 @@ int  fail(int code, const char* fmt, ...);
 // Checks hipGetLastError() after a launch; returns ZNN_OK or ZNN_EHIP.
 int  check_launch(const char* what);
 
+// ---------------------------------------------------------------- kernel-level tracing
+// While tracing is on, every launch is bracketed by two HIP events on its stream.
+struct TraceScope {
+    TraceScope(const char* name, hipStream_t s);
+    ~TraceScope();
+    int slot;
+    hipStream_t stream;
+};
+#define ZNN_LAUNCH(name, stream, kern, grid, block, lds, ...)                 \
+    do {                                                                      \
+        znn::TraceScope _ts(name, stream);                                    \
+        hipLaunchKernelGGL(kern, grid, block, lds, stream, __VA_ARGS__);      \
+    } while (0)
+
 // ---------------------------------------------------------------- geometry
 struct Geom {
     int f, fo;            // fan-in, fan-out

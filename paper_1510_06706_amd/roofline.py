@@ -1,24 +1,67 @@
-"""Roofline bookkeeping for the benchmark: algorithmic work of each pass and the
+"""Roofline bookkeeping for the benchmark: algorithmic work of each kernel role and the
 published MI355X peaks it is priced against.  No compute happens here."""
 from __future__ import annotations
+
+from collections import OrderedDict
 
 PEAK_FP32_MFMA_TFLOPS = 157.3   # dense fp32 matrix-core peak
 PEAK_HBM_GBS = 8000.0           # HBM3E
 
 
-def direct_pass_flops(cfg) -> float:
-    """2 FLOP per multiply-add of the direct method, f * f' * n'^3 * k^3 of them (Table 2)."""
-    return 2.0 * cfg.macs
+def spectrum_elems(N) -> int:
+    return N[0] * N[1] * (N[2] // 2 + 1)
 
 
-def dominant(cfg, per, plans, *tensors):
-    """Roofline entry of the kernel that takes the largest share of a step.
+def work_model(cfg, N):
+    """Algorithmic work per launch of the kernels that can dominate a step.
 
-    Each direct pass is one kernel launch, so its event-timed duration is the kernel's.
+    direct passes: 2 FLOP per multiply-add, f f' n'^3 k^3 of them (Table 2, "Direct").
+    spectral multiply-accumulate: every kernel-spectrum element is read once (8 B) and used
+    in one complex multiply-add (8 FLOP); the node spectra are read / written once.
     """
-    name, ms = max(per["direct"].items(), key=lambda kv: kv[1])
-    flops = direct_pass_flops(cfg)
-    achieved = flops / (ms * 1e-3) / 1e12
-    return {"kernel": "direct %s" % name, "bound": "mfma", "achieved": achieved,
-            "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
-            "traffic": None, "ms": ms}
+    sv = spectrum_elems(N)
+    mac_bytes = 8.0 * sv * (cfg.fan_in * cfg.fan_out + cfg.fan_in + cfg.fan_out)
+    flops = 2.0 * cfg.macs
+    return {
+        "direct forward (MFMA)": ("mfma", flops),
+        "direct backward (MFMA)": ("mfma", flops),
+        "direct kernel gradient (MFMA)": ("mfma", flops),
+        "spectral mac forward": ("hbm", mac_bytes),
+        "spectral mac backward": ("hbm", mac_bytes),
+    }
+
+
+def summarize(records, steps):
+    """records: [(name, ms)] over `steps` traced steps -> {name: (launches per step, ms per launch)}."""
+    agg = OrderedDict()
+    for name, ms in records:
+        n, t = agg.get(name, (0, 0.0))
+        agg[name] = (n + 1, t + ms)
+    return OrderedDict((k, (n / steps, t / n)) for k, (n, t) in agg.items())
+
+
+def entry(name, ms, model):
+    bound, work = model[name]
+    if bound == "mfma":
+        achieved, peak, unit = work / (ms * 1e-3) / 1e12, PEAK_FP32_MFMA_TFLOPS, "TFLOP/s"
+    else:
+        achieved, peak, unit = work / (ms * 1e-3) / 1e9, PEAK_HBM_GBS, "GB/s"
+    return {"kernel": name, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
+            "frac": achieved / peak, "traffic": None, "ms": ms}
+
+
+def report(cfg, N, records, steps):
+    """(roofline of the dominant modelled kernel, per-kernel table)."""
+    model = work_model(cfg, N)
+    table = summarize(records, steps)
+    kernels = []
+    best = None
+    for name, (per_step, ms) in table.items():
+        row = {"kernel": name, "launches_per_step": per_step, "ms_per_launch": ms, "ms_per_step": per_step * ms}
+        if name in model:
+            e = entry(name, ms, model)
+            row.update({"bound": e["bound"], "achieved": e["achieved"], "unit": e["unit"], "frac": e["frac"]})
+            if best is None or per_step * ms > best[0]:
+                best = (per_step * ms, e)
+        kernels.append(row)
+    return (best[1] if best else None), kernels
