@@ -10,11 +10,13 @@
 //     k : 4 consecutive output voxels of one x-row
 //
 // A workgroup owns one (a, b) tap plane, a group of columns n = c*f + i and a
-// share of the voxel rows (split-K).  Its four waves take alternate 4-voxel
-// steps of every staged tile; their accumulators are added in a fixed order
-// through LDS and written as one partial matrix per workgroup.  A second
-// kernel adds the partial matrices in ascending split order, so the result is
-// bit-reproducible (no atomics).
+// share of the voxel rows (split-K).  Tiles of R voxel rows travel from global
+// memory straight into LDS (global_load_lds, no registers in between) into one
+// of two buffers, so the next tile is in flight while the four waves run the
+// MFMAs of the current one.  The waves take alternate 4-voxel steps of a tile;
+// their accumulators are added in a fixed order through LDS and written as one
+// partial matrix per workgroup.  A second kernel adds the partial matrices in
+// ascending split order, so the result is bit-reproducible (no atomics).
 #include <cstdio>
 #include <cstdlib>
 
@@ -25,8 +27,13 @@ namespace znn {
 namespace {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(1))) const void* global_cptr;
+typedef __attribute__((address_space(3))) void* lds_ptr;
 
-constexpr int kBatch = 8;
+// Two tile buffers as separate LDS objects: the compiler then knows that loads
+// landing in one buffer do not alias reads of the other and lets them overlap.
+constexpr int kBufFloats = 18432;                 // 72 KiB each
+__device__ float g_zero_words[64];                // source of tile elements outside the images
 
 struct WgradTile {
     const float* in; const float* gout; float* partial;
@@ -40,13 +47,21 @@ struct WgradTile {
     int G;              // column groups
     int tiles, tps;     // voxel tiles in total and per split
     int AB;             // kz * ky
-    FastDiv dRT, dTX, dRTH, dTXH, dOY;   // R*TX, TX, R*TXH, TXH, oy
+    FastDiv dTX, dTXH, dOY;
 };
 
 template <int NJ, int NT>
-__global__ void __launch_bounds__(256, (NJ * NT <= 24 ? 2 : 1)) k_wgrad_mfma(WgradTile P)
+__global__ void __launch_bounds__(256) k_wgrad_mfma(WgradTile P)
 {
-    extern __shared__ float lds[];
+    __shared__ __attribute__((aligned(16))) float bufA[kBufFloats];
+    __shared__ __attribute__((aligned(16))) float bufB[kBufFloats];
+    // The tile buffers are filled by global_load_lds only, which the optimizer does not
+    // count as a store to them; this never-taken ordinary store keeps their contents
+    // "unknown" instead of "never written".
+    if (P.tiles < 0) {
+        bufA[threadIdx.x] = P.in[threadIdx.x];
+        bufB[threadIdx.x] = P.gout[threadIdx.x];
+    }
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & 15, grp = lane >> 4;
     const int s = blockIdx.x, ab = blockIdx.y;
@@ -60,8 +75,7 @@ __global__ void __launch_bounds__(256, (NJ * NT <= 24 ? 2 : 1)) k_wgrad_mfma(Wgr
     if (cmin == cmax) { imin = n0 % P.f; imax = (n1 - 1) % P.f; }
     const int nmaps = imax - imin + 1;
     const int TXH = P.TXH;
-    float* gt = lds;                        // [NJ*16][GS]
-    float* it = lds + NJ * 16 * P.GS;       // [nmaps][IS]
+    const int itoff = NJ * 16 * P.GS;       // the in tile follows the gout tile in a buffer
 
     int aoff[NJ], boff[NT];
 #pragma unroll
@@ -74,7 +88,7 @@ __global__ void __launch_bounds__(256, (NJ * NT <= 24 ? 2 : 1)) k_wgrad_mfma(Wgr
             const int c = n / P.f, i = n % P.f;
             o = (i - imin) * P.IS + (cmax - c) + grp;
         }
-        boff[nt] = o;
+        boff[nt] = itoff + o;
     }
 
     floatx4 acc[NJ][NT];
@@ -86,76 +100,56 @@ __global__ void __launch_bounds__(256, (NJ * NT <= 24 ? 2 : 1)) k_wgrad_mfma(Wgr
     const int rows = P.oz * P.oy;
     const long oplane = (long)rows * P.ox;
     const long iplane = (long)P.ny * P.nx;
+    const long ivol = (long)P.nz * iplane;
     const int t_end = min((s + 1) * P.tps, P.tiles);
-    const int nks = P.R * P.TX / 4;
+    const int RT = P.R * P.TX, RTH = P.R * TXH;
+    const int nks = RT / 4;
+    const int nsegG = (RT + 63) >> 6, nsegI = (RTH + 63) >> 6;
+    const float* zero = g_zero_words + lane;
 
-    for (int tile = s * P.tps; tile < t_end; ++tile) {
+    // Queue the global->LDS loads of one tile.  A wave-load moves 64 consecutive tile
+    // elements of one map; elements outside the images come from a zero word.
+    auto issue_tile = [&](int tile, float* buf) {
         const int xt = tile % P.XT, rt = tile / P.XT;
         const int rho0 = rt * P.R, xs0 = xt * P.TX;
-        __syncthreads();
-        // both tiles are fetched in batches of kBatch independent loads per thread
-        {
-            const unsigned total = (unsigned)(NJ * 16 * P.R * P.TX);
-            const unsigned RT = (unsigned)(P.R * P.TX);
-            for (unsigned base = threadIdx.x; base < total; base += 256 * kBatch) {
-                float v[kBatch];
-                int lo[kBatch];
-#pragma unroll
-                for (int u = 0; u < kBatch; ++u) {
-                    const unsigned idx = base + u * 256;
-                    v[u] = 0.f; lo[u] = -1;
-                    if (idx < total) {
-                        const unsigned m = fdiv(idx, P.dRT), e = idx - m * RT;
-                        const unsigned r = fdiv(e, P.dTX), x = e - r * P.TX;
-                        const int j = jg * NJ * 16 + (int)m, rho = rho0 + (int)r, gx = xs0 + (int)x;
-                        lo[u] = (int)(m * P.GS + e);
-                        if (j < P.fo && rho < rows && gx < P.ox) v[u] = P.gout[j * oplane + (long)rho * P.ox + gx];
-                    }
-                }
-#pragma unroll
-                for (int u = 0; u < kBatch; ++u)
-                    if (lo[u] >= 0) gt[lo[u]] = v[u];
+        for (int k = 0; k < nsegG; ++k) {
+            const int e = k * 64 + lane;
+            const int r = (int)fdiv((unsigned)e, P.dTX), x = e - r * P.TX;
+            const int rho = rho0 + r, gx = xs0 + x;
+            const bool ok = e < RT && rho < rows && gx < P.ox;
+            const long off = (long)rho * P.ox + gx;
+            for (int m = wave; m < NJ * 16; m += 4) {
+                const int j = jg * NJ * 16 + m;
+                const float* src = (ok && j < P.fo) ? P.gout + j * oplane + off : zero;
+                __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(buf + m * P.GS + k * 64), 4, 0, 0);
             }
         }
-        {
-            const int xin0 = xs0 + (P.kx - 1 - cmax);
-            const unsigned RTH = (unsigned)(P.R * TXH);
-            const unsigned total = (unsigned)nmaps * RTH;
-            for (unsigned base = threadIdx.x; base < total; base += 256 * kBatch) {
-                float v[kBatch];
-                int lo[kBatch];
-#pragma unroll
-                for (int u = 0; u < kBatch; ++u) {
-                    const unsigned idx = base + u * 256;
-                    v[u] = 0.f; lo[u] = -1;
-                    if (idx < total) {
-                        const unsigned m = fdiv(idx, P.dRTH), e = idx - m * RTH;
-                        const unsigned r = fdiv(e, P.dTXH), x = e - r * TXH;
-                        const int rho = rho0 + (int)r, ix = xin0 + (int)x;
-                        lo[u] = (int)(m * P.IS + e);
-                        if (rho < rows && ix < P.nx) {
-                            const int z = (int)fdiv((unsigned)rho, P.dOY), y = rho - z * P.oy;
-                            v[u] = P.in[((long)(imin + (int)m) * P.nz + (z + P.kz - 1 - a)) * iplane +
-                                        (long)(y + P.ky - 1 - b) * P.nx + ix];
-                        }
-                    }
-                }
-#pragma unroll
-                for (int u = 0; u < kBatch; ++u)
-                    if (lo[u] >= 0) it[lo[u]] = v[u];
+        const int xin0 = xs0 + (P.kx - 1 - cmax);
+        for (int k = 0; k < nsegI; ++k) {
+            const int e = k * 64 + lane;
+            const int r = (int)fdiv((unsigned)e, P.dTXH), x = e - r * TXH;
+            const int rho = rho0 + r, ix = xin0 + x;
+            const bool ok = e < RTH && rho < rows && ix < P.nx;
+            const int z = (int)fdiv((unsigned)rho, P.dOY), y = rho - z * P.oy;
+            const long off = (long)(z + P.kz - 1 - a) * iplane + (long)(y + P.ky - 1 - b) * P.nx + ix;
+            for (int m = wave; m < nmaps; m += 4) {
+                const float* src = ok ? P.in + (imin + m) * ivol + off : zero;
+                __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(buf + itoff + m * P.IS + k * 64), 4, 0, 0);
             }
         }
-        __syncthreads();
+    };
 
+    // All MFMAs of one staged tile; this wave takes the 4-voxel steps wave, wave+4, ...
+    auto compute_tile = [&](const float* buf) {
         float an[NJ], bn[NT];
         {
             const int q = 4 * min(wave, nks - 1);
             const int r = (int)fdiv((unsigned)q, P.dTX), tx = q - r * P.TX;
             const int ao = r * P.TX + tx, bo = r * TXH + tx;
 #pragma unroll
-            for (int jt = 0; jt < NJ; ++jt) an[jt] = gt[aoff[jt] + ao];
+            for (int jt = 0; jt < NJ; ++jt) an[jt] = buf[aoff[jt] + ao];
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) bn[nt] = it[boff[nt] + bo];
+            for (int nt = 0; nt < NT; ++nt) bn[nt] = buf[boff[nt] + bo];
         }
         for (int ks = wave; ks < nks; ks += 4) {
             float av[NJ], bv[NT];
@@ -168,19 +162,38 @@ __global__ void __launch_bounds__(256, (NJ * NT <= 24 ? 2 : 1)) k_wgrad_mfma(Wgr
             const int r = (int)fdiv((unsigned)q, P.dTX), tx = q - r * P.TX;
             const int ao = r * P.TX + tx, bo = r * TXH + tx;
 #pragma unroll
-            for (int jt = 0; jt < NJ; ++jt) an[jt] = gt[aoff[jt] + ao];
+            for (int jt = 0; jt < NJ; ++jt) an[jt] = buf[aoff[jt] + ao];
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) bn[nt] = it[boff[nt] + bo];
+            for (int nt = 0; nt < NT; ++nt) bn[nt] = buf[boff[nt] + bo];
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int jt = 0; jt < NJ; ++jt)
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
                     acc[jt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[jt], bv[nt], acc[jt][nt], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
+    };
+
+    // Two tiles per trip so that each copy of the code names its buffers statically.
+    int tile = s * P.tps;
+    if (tile < t_end) issue_tile(tile, bufA);
+    while (tile < t_end) {
+        __builtin_amdgcn_s_waitcnt(0);     // this wave's loads have landed
+        __syncthreads();                   // everyone's have, and nobody still reads bufB
+        if (tile + 1 < t_end) issue_tile(tile + 1, bufB);
+        compute_tile(bufA);
+        ++tile;
+        if (tile >= t_end) break;
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        if (tile + 1 < t_end) issue_tile(tile + 1, bufA);
+        compute_tile(bufB);
+        ++tile;
     }
 
     // add the four waves' accumulators in the order 0 + 1 + 2 + 3
-    floatx4* red = reinterpret_cast<floatx4*>(lds);
+    floatx4* red = reinterpret_cast<floatx4*>(bufA);
     for (int w = 1; w < 4; ++w) {
         __syncthreads();
         if (wave == w) {
@@ -285,22 +298,16 @@ struct WgradChoice {
 };
 
 
-int pad_stride(int n)   // smallest value >= n that is 4 modulo 32 (bank spread of 16 maps x 4 voxels)
+// Map stride in LDS: room for whole 64-element wave-loads, and 4 modulo 32 so that the
+// 16 maps x 4 voxels of an MFMA operand fall into distinct banks.
+int pad_stride(int n)
 {
-    while (n % 32 != 4) ++n;
-    return n;
-}
-
-int wgrad_occupancy()
-{
-    static const int occ = [] { const char* e = getenv("ZNN_WGRAD_OCC"); return e ? atoi(e) : 2; }();
-    return occ;
+    n = (n + 63) & ~63;
+    return n + 4;
 }
 
 WgradChoice choose_wgrad(const Geom& g)
 {
-    const int occ = wgrad_occupancy();
-    const size_t lds_max = occ >= 2 ? 64 * 1024 : 128 * 1024;
     WgradChoice c = {};
     c.ok = false;
     const int mt = (g.fo + 15) / 16;
@@ -308,18 +315,15 @@ WgradChoice choose_wgrad(const Geom& g)
     c.NJ = (mt + c.JG - 1) / c.JG;
     const int ncols = g.f * g.kx;
     const int nt_tot = (ncols + 15) / 16;
-    // occupancy 2 (two waves per SIMD, tiles overlap each other's staging) needs <= 24
-    // accumulator tiles per wave; occupancy 1 allows 40 and fewer column groups.
-    const int budget = occ >= 2 ? 24 : kMaxTiles;
     const int allowed[11] = {1, 2, 3, 4, 5, 6, 7, 8, 10, 13, 16};
     int nt_max = 1;
     for (int k = 0; k < 11; ++k)
-        if (c.NJ * allowed[k] <= budget) nt_max = allowed[k];
+        if (c.NJ * allowed[k] <= kMaxTiles) nt_max = allowed[k];
     c.G = (nt_tot + nt_max - 1) / nt_max;
     const int want = (nt_tot + c.G - 1) / c.G;
     c.NT = nt_max;
     for (int k = 10; k >= 0; --k)
-        if (allowed[k] >= want && c.NJ * allowed[k] <= budget) c.NT = allowed[k];
+        if (allowed[k] >= want && c.NJ * allowed[k] <= kMaxTiles) c.NT = allowed[k];
     c.G = (nt_tot + c.NT - 1) / c.NT;
     if (!pick_wgrad(c.NJ, c.NT)) return c;
     c.Mpad = c.JG * c.NJ * 16;
@@ -335,32 +339,30 @@ WgradChoice choose_wgrad(const Geom& g)
         if (span > cspan) cspan = span;
         if (maps > nmaps) nmaps = maps;
     }
-    const size_t red = (size_t)c.NJ * c.NT * 64 * sizeof(floatx4);
+    if ((size_t)c.NJ * c.NT * 64 * 4 > (size_t)kBufFloats) return c;   // cross-wave reduction needs this
     const int rows = g.oz * g.oy;
+    // fewest x-segments whose tile fits a buffer, then as many rows as fit
     for (int XT = 1; XT <= g.ox; ++XT) {
         const int seg = (g.ox + XT - 1) / XT;
         const int TX = (seg + 3) & ~3;
         const int TXH = TX + cspan;
         int bestR = 0;
-        for (int R = 1; R <= 16 && R <= rows && R * (TX + cspan) * nmaps < 60000; ++R) {
-            const int GS = pad_stride(R * TX), IS = pad_stride(R * TXH);
-            const size_t bytes = ((size_t)c.NJ * 16 * GS + (size_t)nmaps * IS) * 4;
-            if (bytes <= lds_max) bestR = R;
+        for (int R = 1; R <= 32 && R <= rows; ++R) {
+            const long floats = (long)c.NJ * 16 * pad_stride(R * TX) + (long)nmaps * pad_stride(R * TXH);
+            if (floats <= kBufFloats) bestR = R;
         }
         if (bestR == 0) continue;
         c.XT = XT; c.TX = TX; c.TXH = TXH; c.R = bestR;
         c.GS = pad_stride(bestR * TX); c.IS = pad_stride(bestR * TXH);
-        size_t bytes = ((size_t)c.NJ * 16 * c.GS + (size_t)nmaps * c.IS) * 4;
-        if (bytes < red) bytes = red;
-        if (bytes > lds_max) continue;
-        c.lds = bytes;
+        c.lds = 2 * (size_t)kBufFloats * 4;
         c.ok = true;
         break;
     }
     if (!c.ok) return c;
     c.tiles = ((rows + c.R - 1) / c.R) * c.XT;
+    // one workgroup per compute unit: split the voxel range until the grid reaches 256
     const long other = (long)g.kz * g.ky * c.G * c.JG;
-    long ks = (512 + other - 1) / other;
+    long ks = 256 / other;
     if (ks < 1) ks = 1;
     if (ks > c.tiles) ks = c.tiles;
     c.tps = (int)((c.tiles + ks - 1) / ks);
@@ -396,17 +398,13 @@ int mfma_wgrad(const Geom& g, const float* in, const float* gout, float* gw, voi
     P.G = c.G;
     P.tiles = c.tiles; P.tps = c.tps;
     P.AB = g.kz * g.ky;
-    P.dRT = make_fastdiv(c.R * c.TX); P.dTX = make_fastdiv(c.TX);
-    P.dRTH = make_fastdiv(c.R * c.TXH); P.dTXH = make_fastdiv(c.TXH); P.dOY = make_fastdiv(g.oy);
+    P.dTX = make_fastdiv(c.TX); P.dTXH = make_fastdiv(c.TXH); P.dOY = make_fastdiv(g.oy);
     if (log_enabled())
         fprintf(stderr, "[znn] wgrad mfma: NJ=%d JG=%d NT=%d G=%d TX=%d XT=%d R=%d lds=%zu ksplit=%d tiles=%d\n",
                 c.NJ, c.JG, c.NT, c.G, c.TX, c.XT, c.R, c.lds, c.ksplit, c.tiles);
     WgradFn fn = pick_wgrad(c.NJ, c.NT);
     if (!fn) return fail(ZNN_EUNSUPPORTED, "no kernel instance for tile %dx%d", c.NJ, c.NT);
-    if (c.lds > 64 * 1024 &&
-        hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c.lds) != hipSuccess)
-        return fail(ZNN_EHIP, "cannot reserve %zu bytes of LDS", c.lds);
-    ZNN_LAUNCH("direct kernel gradient (MFMA)", s, fn, dim3((unsigned)c.ksplit, (unsigned)P.AB, (unsigned)(c.G * c.JG)), dim3(256), c.lds, P);
+    ZNN_LAUNCH("direct kernel gradient (MFMA)", s, fn, dim3((unsigned)c.ksplit, (unsigned)P.AB, (unsigned)(c.G * c.JG)), dim3(256), 0, P);
     int rc = check_launch("direct kernel gradient (MFMA)");
     if (rc != ZNN_OK) return rc;
     const long total = (long)g.fo * g.f * g.kvol();
