@@ -25,7 +25,6 @@ namespace {
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMaxTaps = 4096;
-constexpr int kBatch = 6;      // independent global loads in flight per thread while staging a halo
 
 struct ConvTile {
     const float* src;   // K-side images [fK][sz][sy][sx]
@@ -40,7 +39,6 @@ struct ConvTile {
     int HZ, HY, HX, MS; // halo box and LDS stride between the four staged maps
     int cz, cy, cx;     // workgroups per axis
     int nchunk;         // ceil(fK / 4)
-    FastDiv dHvol, dHyx, dHx;   // HZ*HY*HX, HY*HX, HX
 };
 
 // Packs w[f'][f][k] so that lane l of a wave finds its A element of tile jt at
@@ -81,7 +79,8 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma(ConvTile P)
 {
     extern __shared__ float lds[];
     const int taps = P.kz * P.ky * P.kx;
-    float* halo = lds;                              // [4][MS]
+    int* tapoff = reinterpret_cast<int*>(lds);      // [taps]
+    float* halo = lds + ((taps + 63) & ~63);        // [4][MS]
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & 15, grp = lane >> 4;
 
@@ -92,6 +91,11 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma(ConvTile P)
     const int jg = blockIdx.y;
     const int z0 = bzi * P.Tz, y0 = byi * P.Ty, x0 = bxi * P.Tx;
     const int Ttot = P.Tz * P.Ty * P.Tx;
+
+    for (int t = threadIdx.x; t < taps; t += 256) {
+        const int c = t % P.kx, bb = (t / P.kx) % P.ky, a = t / (P.kx * P.ky);
+        tapoff[t] = ((P.kz - 1 - a) * P.HY + (P.ky - 1 - bb)) * P.HX + (P.kx - 1 - c);
+    }
 
     int voff[NV];
 #pragma unroll
@@ -112,49 +116,31 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma(ConvTile P)
     const long splane = (long)P.sy * P.sx;
     const float* wq = P.wp + (long)jg * P.nchunk * taps * NJ * 64 + lane;
 
-    // Halo element `idx` of a chunk: LDS slot and source address (or "zero").
-    const unsigned htotal = 4u * (unsigned)hvol;
-    const unsigned hyx = (unsigned)(P.HY * P.HX);
-    auto fetch = [&](unsigned idx, int ic, int& lo) -> float {
-        const unsigned m = fdiv(idx, P.dHvol), h = idx - m * (unsigned)hvol;
-        const unsigned hz = fdiv(h, P.dHyx), r = h - hz * hyx;
-        const unsigned hy = fdiv(r, P.dHx), hx = r - hy * (unsigned)P.HX;
-        lo = (int)(m * (unsigned)P.MS + h);
-        const int gz = z0 + (int)hz - P.pz, gy = y0 + (int)hy - P.py, gx = x0 + (int)hx - P.px;
-        const int i = ic * 4 + (int)m;
-        if (i < P.fK && gz >= 0 && gz < P.sz && gy >= 0 && gy < P.sy && gx >= 0 && gx < P.sx)
-            return P.src[(long)i * P.sz * splane + gz * splane + (long)gy * P.sx + gx];
-        return 0.f;
-    };
-
     for (int ic = 0; ic < P.nchunk; ++ic) {
         __syncthreads();   // everyone is done reading the previous chunk
-        for (unsigned base = threadIdx.x; base < htotal; base += 256u * kBatch) {
-            float v[kBatch];
-            int lo[kBatch];
-#pragma unroll
-            for (int u = 0; u < kBatch; ++u) {
-                const unsigned idx = base + u * 256u;
-                lo[u] = -1; v[u] = 0.f;
-                if (idx < htotal) v[u] = fetch(idx, ic, lo[u]);
-            }
-#pragma unroll
-            for (int u = 0; u < kBatch; ++u)
-                if (lo[u] >= 0) halo[lo[u]] = v[u];
+        for (int t = threadIdx.x; t < 4 * hvol; t += 256) {
+            const int hx = t % P.HX;
+            int r = t / P.HX;
+            const int hy = r % P.HY; r /= P.HY;
+            const int hz = r % P.HZ;
+            const int m = r / P.HZ;
+            const int gz = z0 + hz - P.pz, gy = y0 + hy - P.py, gx = x0 + hx - P.px;
+            const int i = ic * 4 + m;
+            float v = 0.f;
+            if (i < P.fK && gz >= 0 && gz < P.sz && gy >= 0 && gy < P.sy && gx >= 0 && gx < P.sx)
+                v = P.src[(long)i * P.sz * splane + gz * splane + (long)gy * P.sx + gx];
+            halo[m * P.MS + (hz * P.HY + hy) * P.HX + hx] = v;
         }
         __syncthreads();
-        // Tap offsets into the halo box are wave-uniform and advance with scalar
-        // counters: o(a,b,c) = ((kz-1-a)*HY + (ky-1-b))*HX + (kx-1-c).
-        const int o_first = ((P.kz - 1) * P.HY + (P.ky - 1)) * P.HX + (P.kx - 1);
-        const int step_b = P.kx - P.HX;                     // c wraps: next b (one halo row down)
-        const int step_a = step_b + (P.ky - P.HY) * P.HX;   // b wraps too: next a (one halo plane down)
+
         float an[NJ], bn[NV];
 #pragma unroll
         for (int jt = 0; jt < NJ; ++jt) an[jt] = wq[jt * 64];
+        {
+            const int o = tapoff[0];
 #pragma unroll
-        for (int nv = 0; nv < NV; ++nv) bn[nv] = halo[voff[nv] + o_first];
-        int o = o_first, cc = 0, bb = 0;
-        const float* wn = wq;
+            for (int nv = 0; nv < NV; ++nv) bn[nv] = halo[voff[nv] + o];
+        }
         for (int t = 0; t < taps; ++t) {
             float av[NJ], bv[NV];
 #pragma unroll
@@ -162,17 +148,11 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma(ConvTile P)
 #pragma unroll
             for (int nv = 0; nv < NV; ++nv) bv[nv] = bn[nv];
             // operands of the next tap are fetched while this tap's MFMAs run
-            if (t + 1 < taps) {
-                wn += NJ * 64;
-                o -= 1;
-                if (++cc == P.kx) {
-                    cc = 0;
-                    if (++bb == P.ky) { bb = 0; o += step_a; }
-                    else o += step_b;
-                }
-            }
+            const int tn = t + 1 < taps ? t + 1 : t;
+            const float* wn = wq + (long)tn * NJ * 64;
 #pragma unroll
             for (int jt = 0; jt < NJ; ++jt) an[jt] = wn[jt * 64];
+            const int o = tapoff[tn];
 #pragma unroll
             for (int nv = 0; nv < NV; ++nv) bn[nv] = halo[voff[nv] + o];
 #pragma unroll
@@ -279,7 +259,7 @@ TileChoice choose_tile(int fM, int dz, int dy, int dx, int kz, int ky, int kx)
                 long hvol = (long)HZ * HY * HX;
                 long MS = hvol;
                 while (MS % 32 != 16) ++MS;
-                const size_t lds = (size_t)(4 * MS) * 4;
+                const size_t lds = (size_t)(((taps + 63) & ~63) + 4 * MS) * 4;
                 if (lds > kConvLdsMax) continue;
                 const int cz = (dz + Tz - 1) / Tz, cy = (dy + Ty - 1) / Ty, cx = (dx + Tx - 1) / Tx;
                 const long blocks = (long)cz * cy * cx * jgroups;
@@ -349,7 +329,6 @@ int mfma_conv(const Geom& g, bool backward, const float* src, const float* w, fl
     P.HZ = c.HZ; P.HY = c.HY; P.HX = c.HX; P.MS = c.MS;
     P.cz = c.cz; P.cy = c.cy; P.cx = c.cx;
     P.nchunk = (P.fK + 3) / 4;
-    P.dHvol = make_fastdiv(c.HZ * c.HY * c.HX); P.dHyx = make_fastdiv(c.HY * c.HX); P.dHx = make_fastdiv(c.HX);
     if (log_enabled())
         fprintf(stderr, "[znn] conv mfma (%s): NJ=%d jgroups=%d NV=%d tile=%dx%dx%d halo=%dx%dx%d blocks=%d lds=%zu\n",
                 backward ? "bwd" : "fwd", c.NJ, c.jgroups, c.NV, c.Tz, c.Ty, c.Tx, c.HZ, c.HY, c.HX,
@@ -359,14 +338,15 @@ int mfma_conv(const Geom& g, bool backward, const float* src, const float* w, fl
     P.wp = wp;
     const long total = (long)c.jgroups * P.nchunk * taps * c.NJ * 64;
     ZNN_LAUNCH("weight packing", s, k_pack_weights, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
-                       w, wp, g.f, g.fo, g.kz, g.ky, g.kx, backward ? 1 : 0, c.NJ, c.jgroups, P.nchunk);
+               w, wp, g.f, g.fo, g.kz, g.ky, g.kx, backward ? 1 : 0, c.NJ, c.jgroups, P.nchunk);
     int rc = check_launch("weight packing");
     if (rc != ZNN_OK) return rc;
     ConvFn fn = pick_kernel(c.NJ, c.NV);
     if (!fn) return fail(ZNN_EUNSUPPORTED, "no kernel instance for tile %dx%d", c.NJ, c.NV);
     const long blocks = (long)c.cz * c.cy * c.cx;
     if (blocks >= 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many tiles for one launch");
-    ZNN_LAUNCH(backward ? "direct backward (MFMA)" : "direct forward (MFMA)", s, fn, dim3((unsigned)blocks, (unsigned)c.jgroups), dim3(256), c.lds, P);
+    ZNN_LAUNCH(backward ? "direct backward (MFMA)" : "direct forward (MFMA)", s, fn,
+               dim3((unsigned)blocks, (unsigned)c.jgroups), dim3(256), c.lds, P);
     return check_launch(backward ? "direct backward (MFMA)" : "direct forward (MFMA)");
 }
 

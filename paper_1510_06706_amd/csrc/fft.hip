@@ -367,6 +367,167 @@ k_mac_bwd(int f, int fo, long svol, const float2* __restrict__ What, const float
         if (i0 + g < f) Ginhat[(long)(i0 + g) * svol + wv] = acc[g];
 }
 
+// ---------------------------------------------------------------- pruned DFTs along z
+// When only KZ <= 8 of the N_z input planes are non-zero (kernels) or only KZ output
+// planes are wanted (kernel gradient), the z transform is KZ complex multiply-adds per
+// element: cheaper than an LDS round trip.  One thread owns a (y, x-frequency) pencil,
+// neighbouring threads own neighbouring pencils (coalesced), twiddles are wave-uniform.
+constexpr int kMaxPruned = 8;
+
+template <int KZ>
+__global__ void __launch_bounds__(kThreads)
+k_zdft_expand(float2* __restrict__ spec, int N, int oz, long plane, long vol, int cpm)
+{
+    __shared__ float2 tw[kMaxFftExtent];
+    make_twiddles(tw, N, -1);
+    __syncthreads();
+    const long map = blockIdx.x / cpm;
+    const long p = (long)(blockIdx.x % cpm) * kThreads + threadIdx.x;
+    if (p >= plane) return;
+    float2* base = spec + map * vol + p;
+    float2 v[KZ];
+    int idx[KZ], step[KZ];
+#pragma unroll
+    for (int a = 0; a < KZ; ++a) {
+        v[a] = base[(long)(oz + a) * plane];
+        idx[a] = 0;
+        step[a] = (oz + a) % N;
+    }
+    for (int wz = 0; wz < N; ++wz) {
+        float2 o = make_float2(0.f, 0.f);
+#pragma unroll
+        for (int a = 0; a < KZ; ++a) {
+            const float2 t = tw[idx[a]];
+            o.x = fmaf(v[a].x, t.x, fmaf(-v[a].y, t.y, o.x));
+            o.y = fmaf(v[a].x, t.y, fmaf(v[a].y, t.x, o.y));
+            idx[a] += step[a];
+            if (idx[a] >= N) idx[a] -= N;
+        }
+        base[(long)wz * plane] = o;
+    }
+}
+
+// T1[j][i][a][p] = sum_z G[j][z][p] conj(I[i][z][p]) exp(+2 pi i a z / N),  a < KZ.
+// A thread keeps the sums of a 2 x 4 block of (j, i) pairs, so every spectrum element
+// it loads is used in several products.
+constexpr int kPairJ = 2, kPairI = 4;
+
+template <int KZ>
+__global__ void __launch_bounds__(kThreads)
+k_wgrad_zdft(const float2* __restrict__ G, const float2* __restrict__ I, float2* __restrict__ T1,
+             int f, int fo, int N, long plane, long vol)
+{
+    __shared__ float2 tw[kMaxFftExtent];
+    make_twiddles(tw, N, +1);
+    __syncthreads();
+    const long p = (long)blockIdx.x * kThreads + threadIdx.x;
+    if (p >= plane) return;
+    const int j0 = blockIdx.y * kPairJ, i0 = blockIdx.z * kPairI;
+    const float2* gp[kPairJ];
+    const float2* ip[kPairI];
+#pragma unroll
+    for (int jb = 0; jb < kPairJ; ++jb) gp[jb] = G + (long)min(j0 + jb, fo - 1) * vol + p;
+#pragma unroll
+    for (int ib = 0; ib < kPairI; ++ib) ip[ib] = I + (long)min(i0 + ib, f - 1) * vol + p;
+    float2 acc[kPairJ][kPairI][KZ];
+#pragma unroll
+    for (int jb = 0; jb < kPairJ; ++jb)
+#pragma unroll
+        for (int ib = 0; ib < kPairI; ++ib)
+#pragma unroll
+            for (int a = 0; a < KZ; ++a) acc[jb][ib][a] = make_float2(0.f, 0.f);
+    int idx[KZ];
+#pragma unroll
+    for (int a = 0; a < KZ; ++a) idx[a] = 0;
+#pragma unroll 2
+    for (int z = 0; z < N; ++z) {
+        float2 gv[kPairJ], xv[kPairI], t[KZ];
+#pragma unroll
+        for (int jb = 0; jb < kPairJ; ++jb) gv[jb] = gp[jb][(long)z * plane];
+#pragma unroll
+        for (int ib = 0; ib < kPairI; ++ib) xv[ib] = ip[ib][(long)z * plane];
+#pragma unroll
+        for (int a = 0; a < KZ; ++a) {
+            t[a] = tw[idx[a]];
+            idx[a] += a;
+            if (idx[a] >= N) idx[a] -= N;
+        }
+#pragma unroll
+        for (int jb = 0; jb < kPairJ; ++jb)
+#pragma unroll
+            for (int ib = 0; ib < kPairI; ++ib) {
+                // g * conj(x)
+                const float pr = fmaf(gv[jb].x, xv[ib].x, gv[jb].y * xv[ib].y);
+                const float pi = fmaf(gv[jb].y, xv[ib].x, -gv[jb].x * xv[ib].y);
+#pragma unroll
+                for (int a = 0; a < KZ; ++a) {
+                    acc[jb][ib][a].x = fmaf(pr, t[a].x, fmaf(-pi, t[a].y, acc[jb][ib][a].x));
+                    acc[jb][ib][a].y = fmaf(pr, t[a].y, fmaf(pi, t[a].x, acc[jb][ib][a].y));
+                }
+            }
+    }
+#pragma unroll
+    for (int jb = 0; jb < kPairJ; ++jb)
+#pragma unroll
+        for (int ib = 0; ib < kPairI; ++ib) {
+            const int j = j0 + jb, i = i0 + ib;
+            if (j < fo && i < f) {
+#pragma unroll
+                for (int a = 0; a < KZ; ++a) T1[(((long)j * f + i) * KZ + a) * plane + p] = acc[jb][ib][a];
+            }
+        }
+}
+
+template <int KZ>
+int launch_expand_kz(float2* spec, long maps, int N, int oz, long plane, long vol, hipStream_t s)
+{
+    const int cpm = (int)((plane + kThreads - 1) / kThreads);
+    const long blocks = maps * cpm;
+    if (blocks >= 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many pencils for one launch");
+    ZNN_LAUNCH("pruned z DFT of kernels", s, k_zdft_expand<KZ>, dim3((unsigned)blocks), dim3(kThreads), 0,
+               spec, N, oz, plane, vol, cpm);
+    return check_launch("pruned z DFT of kernels");
+}
+
+int launch_expand(int kz, float2* spec, long maps, int N, int oz, long plane, long vol, hipStream_t s)
+{
+    switch (kz) {
+        case 1: return launch_expand_kz<1>(spec, maps, N, oz, plane, vol, s);
+        case 2: return launch_expand_kz<2>(spec, maps, N, oz, plane, vol, s);
+        case 3: return launch_expand_kz<3>(spec, maps, N, oz, plane, vol, s);
+        case 4: return launch_expand_kz<4>(spec, maps, N, oz, plane, vol, s);
+        case 5: return launch_expand_kz<5>(spec, maps, N, oz, plane, vol, s);
+        case 6: return launch_expand_kz<6>(spec, maps, N, oz, plane, vol, s);
+        case 7: return launch_expand_kz<7>(spec, maps, N, oz, plane, vol, s);
+        default: return launch_expand_kz<8>(spec, maps, N, oz, plane, vol, s);
+    }
+}
+
+template <int KZ>
+int launch_wgrad_zdft_kz(const Geom& g, const float2* G, const float2* I, float2* T1, hipStream_t s)
+{
+    const long plane = (long)g.Ny * g.Nxh;
+    const dim3 grid((unsigned)((plane + kThreads - 1) / kThreads), (unsigned)((g.fo + kPairJ - 1) / kPairJ),
+                    (unsigned)((g.f + kPairI - 1) / kPairI));
+    ZNN_LAUNCH("pruned z DFT of spectral products", s, k_wgrad_zdft<KZ>, grid, dim3(kThreads), 0,
+               G, I, T1, g.f, g.fo, g.Nz, plane, g.svol());
+    return check_launch("pruned z DFT of spectral products");
+}
+
+int launch_wgrad_zdft(const Geom& g, const float2* G, const float2* I, float2* T1, hipStream_t s)
+{
+    switch (g.kz) {
+        case 1: return launch_wgrad_zdft_kz<1>(g, G, I, T1, s);
+        case 2: return launch_wgrad_zdft_kz<2>(g, G, I, T1, s);
+        case 3: return launch_wgrad_zdft_kz<3>(g, G, I, T1, s);
+        case 4: return launch_wgrad_zdft_kz<4>(g, G, I, T1, s);
+        case 5: return launch_wgrad_zdft_kz<5>(g, G, I, T1, s);
+        case 6: return launch_wgrad_zdft_kz<6>(g, G, I, T1, s);
+        case 7: return launch_wgrad_zdft_kz<7>(g, G, I, T1, s);
+        default: return launch_wgrad_zdft_kz<8>(g, G, I, T1, s);
+    }
+}
+
 // ---------------------------------------------------------------- launch helpers
 int launch_r2c(const float* src, float2* dst, long maps, int sz, int sy, int sx,
                int Nz, int Ny, int Nx, int oz, int oy, int ox, hipStream_t s)
@@ -413,10 +574,13 @@ int launch_axis(AxisParams P, int dir, hipStream_t s)
     if (P.N == 1 && !P.in2 && P.in == P.out && P.in_stride == P.out_stride &&
         P.in_sa == P.out_sa && P.in_sb == P.out_sb && P.in_sc == P.out_sc)
         return ZNN_OK;   // length-1 transform in place: nothing to do
-    const int wmax = max_row_len(P.N) > 63 ? 63 : max_row_len(P.N);
+    // chunk width: a whole line when it fits, else a multiple of 16 pencils (128 bytes) so
+    // that every chunk starts on a cache-line boundary
+    int wmax = max_row_len(P.N) > 63 ? 63 : max_row_len(P.N);
+    if (P.L > wmax && wmax >= 16) wmax = wmax >= 48 ? 32 : (wmax / 16) * 16;
     const int chunks = (P.L + wmax - 1) / wmax;
     P.chunks = chunks;
-    P.W = (P.L + chunks - 1) / chunks;
+    P.W = P.L > wmax ? wmax : P.L;
     P.Wp = P.W | 1;
     P.rad = factorize(P.N);
     const long blocks = (long)P.Oa * P.Ob * P.Oc * chunks;
@@ -458,8 +622,9 @@ int forward3d(const Geom& g, const float* src, float2* spec, long maps, int sz, 
     P.L = (int)plane;
     P.Oa = (int)maps; P.Ob = 1; P.Oc = 1;
     P.in_sb = P.out_sb = 0;
-    if (!(g.Nz == 1)) { rc = launch_axis(P, -1, s); if (rc != ZNN_OK) return rc; }
-    return ZNN_OK;
+    if (g.Nz == 1) return ZNN_OK;
+    if (sz <= kMaxPruned && sz < g.Nz) return launch_expand(sz, spec, maps, g.Nz, oz, plane, vol, s);
+    return launch_axis(P, -1, s);
 }
 
 // Inverse 3D transform of `maps` spectra (destroyed) to real volumes cropped to
@@ -597,7 +762,10 @@ int fft_wgrad(const Geom& g, const float* in, const float* gout, float* gw, void
     P.in_sa = vol; P.in_sb = 0;
     P.in2_sa = 0; P.in2_sb = vol;
     P.out_sa = (long)g.f * g.kz * plane; P.out_sb = (long)g.kz * plane;
-    rc = launch_axis(P, +1, s);
+    if (g.kz <= kMaxPruned && (g.fo + kPairJ - 1) / kPairJ <= 65535 && (g.f + kPairI - 1) / kPairI <= 65535)
+        rc = launch_wgrad_zdft(g, Ghat, Ihat, T1, s);
+    else
+        rc = launch_axis(P, +1, s);
     if (rc != ZNN_OK) return rc;
     // y: only y in [0, ky) is kept, written compactly
     P = AxisParams{};
