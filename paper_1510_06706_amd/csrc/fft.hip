@@ -310,61 +310,63 @@ __global__ void __launch_bounds__(kThreads) k_fft_axis(AxisParams P)
 }
 
 // ---------------------------------------------------------------- per-frequency multiply-accumulate
-// Forward: O^[j][w] = sum_i W^[j][i][w] I^[i][w].  A thread owns one frequency
-// and G output nodes; the kernel spectra are streamed exactly once.
+// Forward:  O^[j][w]  = sum_i W^[j][i][w] I^[i][w]
+// Backward: Gin^[i][w] = sum_j conj(W^[j][i][w]) G^[j][w]
+// This is the sum over the edges converging on a node, done in the frequency domain.
+// A thread owns V neighbouring frequencies and kMacGroup result nodes; it walks the
+// reduction index, so the kernel spectra are streamed from HBM exactly once (they are
+// not reused: non-temporal loads) while the node spectra stay cache resident.
 constexpr int kMacGroup = 8;
 
-__global__ void __launch_bounds__(kThreads)
-k_mac_fwd(int f, int fo, long svol, const float2* __restrict__ What, const float2* __restrict__ Ihat,
-          float2* __restrict__ Ohat)
-{
-    const long wv = (long)blockIdx.x * kThreads + threadIdx.x;
-    if (wv >= svol) return;
-    const int j0 = blockIdx.y * kMacGroup;
-    float2 acc[kMacGroup];
-#pragma unroll
-    for (int g = 0; g < kMacGroup; ++g) acc[g] = make_float2(0.f, 0.f);
-    for (int i = 0; i < f; ++i) {
-        const float2 x = Ihat[i * svol + wv];
-#pragma unroll
-        for (int g = 0; g < kMacGroup; ++g) {
-            if (j0 + g < fo) {
-                const float2 k = What[((long)(j0 + g) * f + i) * svol + wv];
-                acc[g].x = fmaf(k.x, x.x, fmaf(-k.y, x.y, acc[g].x));
-                acc[g].y = fmaf(k.x, x.y, fmaf(k.y, x.x, acc[g].y));
-            }
-        }
-    }
-#pragma unroll
-    for (int g = 0; g < kMacGroup; ++g)
-        if (j0 + g < fo) Ohat[(long)(j0 + g) * svol + wv] = acc[g];
-}
+typedef float native2 __attribute__((ext_vector_type(2)));
+typedef float native4 __attribute__((ext_vector_type(4)));
+template <int V> struct CVec;
+template <> struct CVec<1> { typedef native2 type; };
+template <> struct CVec<2> { typedef native4 type; };
 
-// Backward: Gin^[i][w] = sum_j conj(W^[j][i][w]) G^[j][w].
+template <bool BWD, int V>
 __global__ void __launch_bounds__(kThreads)
-k_mac_bwd(int f, int fo, long svol, const float2* __restrict__ What, const float2* __restrict__ Ghat,
-          float2* __restrict__ Ginhat)
+k_mac(int f, int fo, long svol, const float2* __restrict__ What, const float2* __restrict__ X,
+      float2* __restrict__ Y)
 {
-    const long wv = (long)blockIdx.x * kThreads + threadIdx.x;
+    typedef typename CVec<V>::type vec_t;
+    const long wv = ((long)blockIdx.x * kThreads + threadIdx.x) * V;
     if (wv >= svol) return;
-    const int i0 = blockIdx.y * kMacGroup;
-    float2 acc[kMacGroup];
+    const int o0 = blockIdx.y * kMacGroup;
+    const int nred = BWD ? fo : f, nout = BWD ? f : fo;
+    float acc[kMacGroup][2 * V];
 #pragma unroll
-    for (int g = 0; g < kMacGroup; ++g) acc[g] = make_float2(0.f, 0.f);
-    for (int j = 0; j < fo; ++j) {
-        const float2 x = Ghat[j * svol + wv];
+    for (int g = 0; g < kMacGroup; ++g)
+#pragma unroll
+        for (int c = 0; c < 2 * V; ++c) acc[g][c] = 0.f;
+#pragma unroll 2
+    for (int r = 0; r < nred; ++r) {
+        const vec_t xv = *reinterpret_cast<const vec_t*>(X + r * svol + wv);
+        const float* x = reinterpret_cast<const float*>(&xv);
 #pragma unroll
         for (int g = 0; g < kMacGroup; ++g) {
-            if (i0 + g < f) {
-                const float2 k = What[((long)j * f + (i0 + g)) * svol + wv];
-                acc[g].x = fmaf(k.x, x.x, fmaf(k.y, x.y, acc[g].x));
-                acc[g].y = fmaf(k.x, x.y, fmaf(-k.y, x.x, acc[g].y));
+            if (o0 + g < nout) {
+                const long e = BWD ? ((long)r * f + (o0 + g)) : ((long)(o0 + g) * f + r);
+                const vec_t kv = __builtin_nontemporal_load(reinterpret_cast<const vec_t*>(What + e * svol + wv));
+                const float* k = reinterpret_cast<const float*>(&kv);
+#pragma unroll
+                for (int c = 0; c < V; ++c) {
+                    const float kr = k[2 * c], ki = BWD ? -k[2 * c + 1] : k[2 * c + 1];
+                    acc[g][2 * c] = fmaf(kr, x[2 * c], fmaf(-ki, x[2 * c + 1], acc[g][2 * c]));
+                    acc[g][2 * c + 1] = fmaf(kr, x[2 * c + 1], fmaf(ki, x[2 * c], acc[g][2 * c + 1]));
+                }
             }
         }
     }
 #pragma unroll
     for (int g = 0; g < kMacGroup; ++g)
-        if (i0 + g < f) Ginhat[(long)(i0 + g) * svol + wv] = acc[g];
+        if (o0 + g < nout) {
+            vec_t o;
+            float* op = reinterpret_cast<float*>(&o);
+#pragma unroll
+            for (int c = 0; c < 2 * V; ++c) op[c] = acc[g][c];
+            *reinterpret_cast<vec_t*>(Y + (long)(o0 + g) * svol + wv) = o;
+        }
 }
 
 // ---------------------------------------------------------------- pruned DFTs along z
@@ -658,9 +660,16 @@ int launch_mac(bool backward, const Geom& g, const float2* What, const float2* a
 {
     const long svol = g.svol();
     const int outs = backward ? g.f : g.fo;
-    dim3 grid((unsigned)((svol + kThreads - 1) / kThreads), (unsigned)((outs + kMacGroup - 1) / kMacGroup));
-    if (backward) ZNN_LAUNCH("spectral mac backward", s, k_mac_bwd, grid, dim3(kThreads), 0, g.f, g.fo, svol, What, a, b);
-    else          ZNN_LAUNCH("spectral mac forward", s, k_mac_fwd, grid, dim3(kThreads), 0, g.f, g.fo, svol, What, a, b);
+    const int V = (svol % 2 == 0) ? 2 : 1;
+    const long threads = (svol + V - 1) / V;
+    dim3 grid((unsigned)((threads + kThreads - 1) / kThreads), (unsigned)((outs + kMacGroup - 1) / kMacGroup));
+    if (backward) {
+        if (V == 2) ZNN_LAUNCH("spectral mac backward", s, (k_mac<true, 2>), grid, dim3(kThreads), 0, g.f, g.fo, svol, What, a, b);
+        else        ZNN_LAUNCH("spectral mac backward", s, (k_mac<true, 1>), grid, dim3(kThreads), 0, g.f, g.fo, svol, What, a, b);
+    } else {
+        if (V == 2) ZNN_LAUNCH("spectral mac forward", s, (k_mac<false, 2>), grid, dim3(kThreads), 0, g.f, g.fo, svol, What, a, b);
+        else        ZNN_LAUNCH("spectral mac forward", s, (k_mac<false, 1>), grid, dim3(kThreads), 0, g.f, g.fo, svol, What, a, b);
+    }
     return check_launch("spectral multiply-accumulate");
 }
 
