@@ -72,6 +72,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="for `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE`: run two steps and a plain 1 GiB device "
+                         "copy whose known size calibrates the counters, then exit")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -113,6 +116,15 @@ def main():
         run_mode("fft")
         _, idx = znn.maxfilter3d_fwd(d_mf, mf_win)
         znn.maxfilter3d_bwd(d_mfg, idx, mf_n, mf_win)
+
+    if args.traffic_probe:
+        step(); step()
+        a = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+        b = torch.empty_like(a)
+        b.copy_(a)          # plain copy kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        print(json.dumps({"traffic_probe": "done", "copy_bytes_each_way": a.numel() * 4}))
+        return
 
     for _ in range(args.warmup):
         step()

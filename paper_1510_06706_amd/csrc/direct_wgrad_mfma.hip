@@ -48,6 +48,7 @@ struct WgradTile {
     int tiles, tps;     // voxel tiles in total and per split
     int AB;             // kz * ky
     FastDiv dTX, dTXH, dOY;
+    int vec4;           // 16-byte global->LDS loads are legal for this shape
 };
 
 template <int NJ, int NT>
@@ -79,14 +80,14 @@ __global__ void __launch_bounds__(256) k_wgrad_mfma(WgradTile P)
 
     int aoff[NJ], boff[NT];
 #pragma unroll
-    for (int jt = 0; jt < NJ; ++jt) aoff[jt] = (jt * 16 + col) * P.GS + grp;
+    for (int jt = 0; jt < NJ; ++jt) aoff[jt] = (jt * 16 + col) * P.GS;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         const int n = n0 + nt * 16 + col;
-        int o = grp;
+        int o = 0;
         if (n < n1) {
             const int c = n / P.f, i = n % P.f;
-            o = (i - imin) * P.IS + (cmax - c) + grp;
+            o = (i - imin) * P.IS + (cmax - c);
         }
         boff[nt] = itoff + o;
     }
@@ -103,74 +104,119 @@ __global__ void __launch_bounds__(256) k_wgrad_mfma(WgradTile P)
     const long ivol = (long)P.nz * iplane;
     const int t_end = min((s + 1) * P.tps, P.tiles);
     const int RT = P.R * P.TX, RTH = P.R * TXH;
-    const int nks = RT / 4;
+    const int nkp = RT / 8;     // 8-voxel steps per tile (R * TX is a multiple of 8)
     const int nsegG = (RT + 63) >> 6, nsegI = (RTH + 63) >> 6;
     const float* zero = g_zero_words + lane;
+    const float* zero4 = g_zero_words;
 
-    // Queue the global->LDS loads of one tile.  A wave-load moves 64 consecutive tile
-    // elements of one map; elements outside the images come from a zero word.
+    // Queue the global->LDS loads of one tile.  A wave-load moves 64 (or, with 16-byte
+    // loads, 256) consecutive tile elements of one map; elements outside the images come
+    // from a zero word.  The 16-byte form needs every group of four x-neighbours to be
+    // entirely inside or outside the image (P.vec4, decided on the host).
     auto issue_tile = [&](int tile, float* buf) {
         const int xt = tile % P.XT, rt = tile / P.XT;
         const int rho0 = rt * P.R, xs0 = xt * P.TX;
+        const int xin0 = xs0 + (P.kx - 1 - cmax);
+        if (P.vec4) {
+            for (int k = 0; k * 256 < RT; ++k) {
+                const int e = k * 256 + lane * 4;
+                const int r = (int)fdiv((unsigned)e, P.dTX), x = e - r * P.TX;
+                const int rho = rho0 + r, gx = xs0 + x;
+                const bool ok = rho < rows && gx < P.ox;
+                const long off = (long)rho * P.ox + gx;
+                if (e < RT) {
+                    for (int m = wave; m < NJ * 16; m += 4) {
+                        const int j = jg * NJ * 16 + m;
+                        const float* src = (ok && j < P.fo) ? P.gout + j * oplane + off : zero4;
+                        __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(buf + m * P.GS + k * 256), 16, 0, 0);
+                    }
+                }
+            }
+            for (int k = 0; k * 256 < RTH; ++k) {
+                const int e = k * 256 + lane * 4;
+                const int r = (int)fdiv((unsigned)e, P.dTXH), x = e - r * TXH;
+                const int rho = rho0 + r, ix = xin0 + x;
+                const bool ok = rho < rows && ix < P.nx;
+                const int z = (int)fdiv((unsigned)rho, P.dOY), y = rho - z * P.oy;
+                const long off = (long)(z + P.kz - 1 - a) * iplane + (long)(y + P.ky - 1 - b) * P.nx + ix;
+                if (e < RTH) {
+                    for (int m = wave; m < nmaps; m += 4) {
+                        const float* src = ok ? P.in + (imin + m) * ivol + off : zero4;
+                        __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(buf + itoff + m * P.IS + k * 256), 16, 0, 0);
+                    }
+                }
+            }
+            return;
+        }
         for (int k = 0; k < nsegG; ++k) {
             const int e = k * 64 + lane;
             const int r = (int)fdiv((unsigned)e, P.dTX), x = e - r * P.TX;
             const int rho = rho0 + r, gx = xs0 + x;
-            const bool ok = e < RT && rho < rows && gx < P.ox;
+            const bool ok = rho < rows && gx < P.ox;
             const long off = (long)rho * P.ox + gx;
-            for (int m = wave; m < NJ * 16; m += 4) {
-                const int j = jg * NJ * 16 + m;
-                const float* src = (ok && j < P.fo) ? P.gout + j * oplane + off : zero;
-                __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(buf + m * P.GS + k * 64), 4, 0, 0);
+            if (e < RT) {
+                for (int m = wave; m < NJ * 16; m += 4) {
+                    const int j = jg * NJ * 16 + m;
+                    const float* src = (ok && j < P.fo) ? P.gout + j * oplane + off : zero;
+                    __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(buf + m * P.GS + k * 64), 4, 0, 0);
+                }
             }
         }
-        const int xin0 = xs0 + (P.kx - 1 - cmax);
         for (int k = 0; k < nsegI; ++k) {
             const int e = k * 64 + lane;
             const int r = (int)fdiv((unsigned)e, P.dTXH), x = e - r * TXH;
             const int rho = rho0 + r, ix = xin0 + x;
-            const bool ok = e < RTH && rho < rows && ix < P.nx;
+            const bool ok = rho < rows && ix < P.nx;
             const int z = (int)fdiv((unsigned)rho, P.dOY), y = rho - z * P.oy;
             const long off = (long)(z + P.kz - 1 - a) * iplane + (long)(y + P.ky - 1 - b) * P.nx + ix;
-            for (int m = wave; m < nmaps; m += 4) {
-                const float* src = ok ? P.in + (imin + m) * ivol + off : zero;
-                __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(buf + itoff + m * P.IS + k * 64), 4, 0, 0);
+            if (e < RTH) {
+                for (int m = wave; m < nmaps; m += 4) {
+                    const float* src = ok ? P.in + (imin + m) * ivol + off : zero;
+                    __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(buf + itoff + m * P.IS + k * 64), 4, 0, 0);
+                }
             }
         }
     };
 
-    // All MFMAs of one staged tile; this wave takes the 4-voxel steps wave, wave+4, ...
+    // All MFMAs of one staged tile.  A step covers 8 consecutive voxels: lane group g
+    // (= lane/16) reads the voxel pair (2g, 2g+1) of every operand with one two-dword
+    // LDS read and feeds two MFMAs from it.  This wave takes steps wave, wave+4, ...
     auto compute_tile = [&](const float* buf) {
-        float an[NJ], bn[NT];
+        auto offsets = [&](int kp, int& ao, int& bo) {
+            const int e = 8 * kp + 2 * grp;
+            const int r = (int)fdiv((unsigned)e, P.dTX), x = e - r * P.TX;
+            ao = e;
+            bo = r * TXH + x;
+        };
+        float2 an[NJ], bn[NT];
         {
-            const int q = 4 * min(wave, nks - 1);
-            const int r = (int)fdiv((unsigned)q, P.dTX), tx = q - r * P.TX;
-            const int ao = r * P.TX + tx, bo = r * TXH + tx;
+            int ao, bo;
+            offsets(min(wave, nkp - 1), ao, bo);
 #pragma unroll
-            for (int jt = 0; jt < NJ; ++jt) an[jt] = buf[aoff[jt] + ao];
+            for (int jt = 0; jt < NJ; ++jt) an[jt] = make_float2(buf[aoff[jt] + ao], buf[aoff[jt] + ao + 1]);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) bn[nt] = buf[boff[nt] + bo];
+            for (int nt = 0; nt < NT; ++nt) bn[nt] = make_float2(buf[boff[nt] + bo], buf[boff[nt] + bo + 1]);
         }
-        for (int ks = wave; ks < nks; ks += 4) {
-            float av[NJ], bv[NT];
+        for (int kp = wave; kp < nkp; kp += 4) {
+            float2 av[NJ], bv[NT];
 #pragma unroll
             for (int jt = 0; jt < NJ; ++jt) av[jt] = an[jt];
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) bv[nt] = bn[nt];
-            const int kn = ks + 4 < nks ? ks + 4 : ks;
-            const int q = 4 * kn;
-            const int r = (int)fdiv((unsigned)q, P.dTX), tx = q - r * P.TX;
-            const int ao = r * P.TX + tx, bo = r * TXH + tx;
+            int ao, bo;
+            offsets(kp + 4 < nkp ? kp + 4 : kp, ao, bo);
 #pragma unroll
-            for (int jt = 0; jt < NJ; ++jt) an[jt] = buf[aoff[jt] + ao];
+            for (int jt = 0; jt < NJ; ++jt) an[jt] = make_float2(buf[aoff[jt] + ao], buf[aoff[jt] + ao + 1]);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) bn[nt] = buf[boff[nt] + bo];
+            for (int nt = 0; nt < NT; ++nt) bn[nt] = make_float2(buf[boff[nt] + bo], buf[boff[nt] + bo + 1]);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int jt = 0; jt < NJ; ++jt)
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
-                    acc[jt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[jt], bv[nt], acc[jt][nt], 0, 0, 0);
+                for (int nt = 0; nt < NT; ++nt) {
+                    acc[jt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[jt].x, bv[nt].x, acc[jt][nt], 0, 0, 0);
+                    acc[jt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[jt].y, bv[nt].y, acc[jt][nt], 0, 0, 0);
+                }
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -294,16 +340,18 @@ struct WgradChoice {
     int TX, XT, R, GS, IS, TXH;
     int Mpad, Npad;
     int tiles, tps, ksplit;
+    int vec4;
     size_t lds;
 };
 
 
-// Map stride in LDS: room for whole 64-element wave-loads, and 4 modulo 32 so that the
-// 16 maps x 4 voxels of an MFMA operand fall into distinct banks.
+// Map stride in LDS: a multiple of 4 floats (16-byte loads land on 16-byte boundaries)
+// whose residue modulo 32 spreads the 16 maps of an MFMA operand over the banks.
 int pad_stride(int n)
 {
-    n = (n + 63) & ~63;
-    return n + 4;
+    static const int res = [] { const char* e = getenv("ZNN_WGRAD_STRIDE_MOD"); return e ? atoi(e) : 4; }();
+    while (n % 32 != res) ++n;
+    return n;
 }
 
 WgradChoice choose_wgrad(const Geom& g)
@@ -344,10 +392,12 @@ WgradChoice choose_wgrad(const Geom& g)
     // fewest x-segments whose tile fits a buffer, then as many rows as fit
     for (int XT = 1; XT <= g.ox; ++XT) {
         const int seg = (g.ox + XT - 1) / XT;
-        const int TX = (seg + 3) & ~3;
-        const int TXH = TX + cspan;
+        int TX = (seg + 3) & ~3;
+        if (TX % 8 != 0 && rows < 2) TX += 4;          // a single row must hold whole 8-voxel steps
+        const int TXH = (TX + cspan + 3) & ~3;
         int bestR = 0;
         for (int R = 1; R <= 32 && R <= rows; ++R) {
+            if ((R * TX) % 8 != 0) continue;    // the MFMA loop walks 8 voxels per step
             const long floats = (long)c.NJ * 16 * pad_stride(R * TX) + (long)nmaps * pad_stride(R * TXH);
             if (floats <= kBufFloats) bestR = R;
         }
@@ -355,6 +405,9 @@ WgradChoice choose_wgrad(const Geom& g)
         c.XT = XT; c.TX = TX; c.TXH = TXH; c.R = bestR;
         c.GS = pad_stride(bestR * TX); c.IS = pad_stride(bestR * TXH);
         c.lds = 2 * (size_t)kBufFloats * 4;
+        // 16-byte loads: groups of four x-neighbours must be wholly inside or outside the
+        // images and start on multiples of four in both tensors
+        c.vec4 = (g.ox % 4 == 0 && g.nx % 4 == 0 && c.G == 1) ? 1 : 0;
         c.ok = true;
         break;
     }
@@ -398,6 +451,7 @@ int mfma_wgrad(const Geom& g, const float* in, const float* gout, float* gw, voi
     P.G = c.G;
     P.tiles = c.tiles; P.tps = c.tps;
     P.AB = g.kz * g.ky;
+    P.vec4 = c.vec4;
     P.dTX = make_fastdiv(c.TX); P.dTXH = make_fastdiv(c.TXH); P.dOY = make_fastdiv(g.oy);
     if (log_enabled())
         fprintf(stderr, "[znn] wgrad mfma: NJ=%d JG=%d NT=%d G=%d TX=%d XT=%d R=%d lds=%zu ksplit=%d tiles=%d\n",

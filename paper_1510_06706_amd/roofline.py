@@ -8,6 +8,20 @@ PEAK_FP32_MFMA_TFLOPS = 157.3   # dense fp32 matrix-core peak
 PEAK_HBM_GBS = 8000.0           # HBM3E
 
 
+# HBM bytes per launch (read, write) on the config-2 layer, from the rocprofv3 FETCH_SIZE /
+# WRITE_SIZE runs summarised in profiles/config2_hbm_traffic_pmc.txt (counters scaled by a
+# plain 1 GiB copy: x2.000 for FETCH_SIZE, x1.000 for WRITE_SIZE).  Static record of a
+# separate profiler run, not measured by the benchmark itself.
+MIB = 1024.0 * 1024.0
+MEASURED_TRAFFIC_CONFIG2 = {
+    "direct forward (MFMA)": (310.9 * MIB, 70.1 * MIB),
+    "direct backward (MFMA)": (179.7 * MIB, 40.0 * MIB),
+    "direct kernel gradient (MFMA)": (848.4 * MIB, 9.5 * MIB),
+    "spectral mac forward": (1691.4 * MIB, 41.2 * MIB),
+    "spectral mac backward": (1691.3 * MIB, 41.2 * MIB),
+}
+
+
 def spectrum_elems(N) -> int:
     return N[0] * N[1] * (N[2] // 2 + 1)
 
@@ -40,26 +54,28 @@ def summarize(records, steps):
     return OrderedDict((k, (n / steps, t / n)) for k, (n, t) in agg.items())
 
 
-def entry(name, ms, model):
+def entry(name, ms, model, traffic=None):
     bound, work = model[name]
     if bound == "mfma":
         achieved, peak, unit = work / (ms * 1e-3) / 1e12, PEAK_FP32_MFMA_TFLOPS, "TFLOP/s"
     else:
         achieved, peak, unit = work / (ms * 1e-3) / 1e9, PEAK_HBM_GBS, "GB/s"
     return {"kernel": name, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
-            "frac": achieved / peak, "traffic": None, "ms": ms}
+            "frac": achieved / peak, "traffic": traffic, "ms": ms}
 
 
 def report(cfg, N, records, steps):
     """(roofline of the dominant modelled kernel, per-kernel table)."""
     model = work_model(cfg, N)
+    measured = MEASURED_TRAFFIC_CONFIG2 if cfg.name.startswith("c2_") else {}
     table = summarize(records, steps)
     kernels = []
     best = None
     for name, (per_step, ms) in table.items():
         row = {"kernel": name, "launches_per_step": per_step, "ms_per_launch": ms, "ms_per_step": per_step * ms}
         if name in model:
-            e = entry(name, ms, model)
+            t = measured.get(name)
+            e = entry(name, ms, model, None if t is None else t[0] + t[1])
             row.update({"bound": e["bound"], "achieved": e["achieved"], "unit": e["unit"], "frac": e["frac"]})
             if best is None or per_step * ms > best[0]:
                 best = (per_step * ms, e)
