@@ -66,6 +66,67 @@ def cpu_baseline(cfg, inp, w, gout, budget_s=18.0):
             "gflops": 3 * 2 * macs_full / t_layer / 1e9}
 
 
+def report_all_configs(path):
+    """Per-pass times of every benchmark configuration (not part of the timed step): configs 1, 2, 4 in
+    both methods, config 5 with resident kernel spectra, config 3 as a whole training round."""
+    import torch
+    from paper_1510_06706_amd import binding as znn
+    from paper_1510_06706_amd import net as znet
+    from paper_1510_06706_amd import synth
+
+    def timed(fn, reps):
+        fn(); fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    rows = []
+    for cfg, modes in ((synth.CONFIG1, ("direct", "fft")), (synth.CONFIG2, ("direct", "fft")),
+                       (synth.CONFIG4, ("direct", "fft")), (synth.CONFIG5, ("fft",))):
+        inp, w, gout = synth.layer_tensors(cfg)
+        d_in, d_w, d_g = (torch.from_numpy(a).to("cuda:0") for a in (inp, w, gout))
+        del inp, w, gout
+        for mode in modes:
+            p = znn.Plan(cfg.fan_in, cfg.fan_out, cfg.image, cfg.kernel, mode)
+            reps = 3 if cfg is synth.CONFIG5 else 10
+            t = {}
+            wk = d_w
+            if mode == "fft":
+                t["kernel_spectra"] = timed(lambda: p.prepare_kernels(d_w), reps)
+                wk = None
+            out = p.fwd(d_in, wk); gin = p.bwd(d_g, wk); gw = p.wgrad(d_in, d_g)
+            t["fwd"] = timed(lambda: p.fwd(d_in, wk, out), reps)
+            t["bwd"] = timed(lambda: p.bwd(d_g, wk, gin), reps)
+            t["wgrad"] = timed(lambda: p.wgrad(d_in, d_g, gw), reps)
+            tot = sum(t.values())
+            rows.append({"config": cfg.name, "mode": mode, "ms": t, "layer_ms": tot,
+                         "voxels_per_s": cfg.out_voxels / (tot * 1e-3),
+                         "effective_tflops": 3 * 2.0 * cfg.macs / (tot * 1e-3) / 1e12})
+            print("%-24s %-6s %s  layer %.3f ms  %.3g voxels/s  %.1f eff. TFLOP/s" %
+                  (cfg.name, mode, " ".join("%s %.3f" % kv for kv in t.items()), tot, rows[-1]["voxels_per_s"],
+                   rows[-1]["effective_tflops"]), file=sys.stderr, flush=True)
+            p.close()
+            del out, gin, gw
+        del d_in, d_w, d_g
+        torch.cuda.empty_cache()
+    x, target, params = znet.config3_tensors()
+    d_x, d_t = torch.from_numpy(x).to("cuda:0"), torch.from_numpy(target).to("cuda:0")
+    for mode in ("direct", "fft"):
+        net = znet.Net(znet.CONFIG3_LAYERS, znet.CONFIG3_INPUT, params, mode)
+        ms = timed(lambda: net.train_round(d_x, d_t, znet.CONFIG3_ETA), 10)
+        rows.append({"config": "c3_training_round", "mode": mode, "layer_ms": ms, "voxels_per_s": 3 * 12 ** 3 / (ms * 1e-3)})
+        print("%-24s %-6s round %.3f ms  %.3g output voxels/s" % ("c3_training_round", mode, ms, rows[-1]["voxels_per_s"]),
+              file=sys.stderr, flush=True)
+    os.makedirs(os.path.dirname(path) or ".", exist_ok=True)
+    with open(path, "w") as fh:
+        json.dump(rows, fh, indent=1)
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -75,6 +136,8 @@ def main():
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE`: run two steps and a plain 1 GiB device "
                          "copy whose known size calibrates the counters, then exit")
+    ap.add_argument("--report-all", metavar="JSON", default=None,
+                    help="also time every configuration pass by pass, print the table to stderr and write it here")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -194,6 +257,12 @@ def main():
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, inp, w, gout)
+    if args.report_all:
+        del d_in, d_w, d_g, out, gin, gw
+        for p in plans.values():
+            p.close()
+        torch.cuda.empty_cache()
+        report_all_configs(args.report_all)
     print(json.dumps(result))
 
 

@@ -93,15 +93,18 @@ static DescKey key_of(const znn_conv_desc& d)
     return DescKey(d.fan_in, d.fan_out, d.image.z, d.image.y, d.image.x, d.kernel.z, d.kernel.y, d.kernel.x);
 }
 
-// Work model of Table 2 turned into a time guess: the direct method is a dense
-// fp32 contraction, the FFT method is bound by streaming the kernel spectra.
+// Work model of Table 2 turned into a time guess with rates measured on MI355X: the direct
+// method is a dense fp32 contraction (about 75 effective TFLOP/s over a layer), the FFT
+// method is bound by writing the kernel spectra once, streaming them twice, and by the
+// node transforms; both pay a few microseconds per launch.
 static int model_choice(const Geom& g)
 {
     const double macs = (double)g.f * g.fo * (double)g.ovol() * (double)g.kvol();
-    const double t_direct = 3.0 * 2.0 * macs / 60e12;
+    const double t_direct = 3.0 * 2.0 * macs / 75e12 + 4 * 6e-6;
     const double spec = 8.0 * (double)g.svol();
-    const double per_pass = spec * g.f * g.fo * 2.0 + spec * (g.f + g.fo) * 6.0;
-    const double t_fft = (3.0 * per_pass + spec * g.f * g.fo * 4.0) / 3e12 + 60e-6;
+    const double S = spec * g.f * g.fo;
+    const double nodes = spec * (g.f + g.fo);
+    const double t_fft = S / 4.5e12 + 2.0 * S / 5.5e12 + 0.3 * S / 5e12 + 12.0 * nodes / 3e12 + 25 * 6e-6;
     return t_fft < t_direct ? ZNN_FFT : ZNN_DIRECT;
 }
 

@@ -374,7 +374,7 @@ k_mac(int f, int fo, long svol, const float2* __restrict__ What, const float2* _
 // planes are wanted (kernel gradient), the z transform is KZ complex multiply-adds per
 // element: cheaper than an LDS round trip.  One thread owns a (y, x-frequency) pencil,
 // neighbouring threads own neighbouring pencils (coalesced), twiddles are wave-uniform.
-constexpr int kMaxPruned = 8;
+constexpr int kMaxPruned = 16;
 
 template <int KZ>
 __global__ void __launch_bounds__(kThreads)
@@ -409,33 +409,33 @@ k_zdft_expand(float2* __restrict__ spec, int N, int oz, long plane, long vol, in
     }
 }
 
-// T1[j][i][a][p] = sum_z G[j][z][p] conj(I[i][z][p]) exp(+2 pi i a z / N),  a < KZ.
-// A thread keeps the sums of a 2 x 4 block of (j, i) pairs, so every spectrum element
-// it loads is used in several products.
-constexpr int kPairJ = 2, kPairI = 4;
-
-template <int KZ>
+// T1[j][i][a][p] = sum_z G[j][z][p] conj(I[i][z][p]) exp(+2 pi i a z / N),  a < KZ,
+// along the axis whose elements are `plane` apart (z in 3D; y when N_z = 1).
+// A thread keeps the sums of a JB x IB block of (j, i) pairs, so every spectrum element
+// it loads is used in several products.  Workgroups that share a pencil chunk are
+// neighbours in the grid (pair blocks vary fastest), so they find the chunk in cache.
+template <int KZ, int JB, int IB>
 __global__ void __launch_bounds__(kThreads)
 k_wgrad_zdft(const float2* __restrict__ G, const float2* __restrict__ I, float2* __restrict__ T1,
-             int f, int fo, int N, long plane, long vol)
+             int f, int fo, int N, long plane, long vol, int iblocks)
 {
     __shared__ float2 tw[kMaxFftExtent];
     make_twiddles(tw, N, +1);
     __syncthreads();
-    const long p = (long)blockIdx.x * kThreads + threadIdx.x;
+    const long p = (long)blockIdx.y * kThreads + threadIdx.x;
     if (p >= plane) return;
-    const int j0 = blockIdx.y * kPairJ, i0 = blockIdx.z * kPairI;
-    const float2* gp[kPairJ];
-    const float2* ip[kPairI];
+    const int j0 = (blockIdx.x / iblocks) * JB, i0 = (blockIdx.x % iblocks) * IB;
+    const float2* gp[JB];
+    const float2* ip[IB];
 #pragma unroll
-    for (int jb = 0; jb < kPairJ; ++jb) gp[jb] = G + (long)min(j0 + jb, fo - 1) * vol + p;
+    for (int jb = 0; jb < JB; ++jb) gp[jb] = G + (long)min(j0 + jb, fo - 1) * vol + p;
 #pragma unroll
-    for (int ib = 0; ib < kPairI; ++ib) ip[ib] = I + (long)min(i0 + ib, f - 1) * vol + p;
-    float2 acc[kPairJ][kPairI][KZ];
+    for (int ib = 0; ib < IB; ++ib) ip[ib] = I + (long)min(i0 + ib, f - 1) * vol + p;
+    float2 acc[JB][IB][KZ];
 #pragma unroll
-    for (int jb = 0; jb < kPairJ; ++jb)
+    for (int jb = 0; jb < JB; ++jb)
 #pragma unroll
-        for (int ib = 0; ib < kPairI; ++ib)
+        for (int ib = 0; ib < IB; ++ib)
 #pragma unroll
             for (int a = 0; a < KZ; ++a) acc[jb][ib][a] = make_float2(0.f, 0.f);
     int idx[KZ];
@@ -443,11 +443,11 @@ k_wgrad_zdft(const float2* __restrict__ G, const float2* __restrict__ I, float2*
     for (int a = 0; a < KZ; ++a) idx[a] = 0;
 #pragma unroll 2
     for (int z = 0; z < N; ++z) {
-        float2 gv[kPairJ], xv[kPairI], t[KZ];
+        float2 gv[JB], xv[IB], t[KZ];
 #pragma unroll
-        for (int jb = 0; jb < kPairJ; ++jb) gv[jb] = gp[jb][(long)z * plane];
+        for (int jb = 0; jb < JB; ++jb) gv[jb] = gp[jb][(long)z * plane];
 #pragma unroll
-        for (int ib = 0; ib < kPairI; ++ib) xv[ib] = ip[ib][(long)z * plane];
+        for (int ib = 0; ib < IB; ++ib) xv[ib] = ip[ib][(long)z * plane];
 #pragma unroll
         for (int a = 0; a < KZ; ++a) {
             t[a] = tw[idx[a]];
@@ -455,9 +455,9 @@ k_wgrad_zdft(const float2* __restrict__ G, const float2* __restrict__ I, float2*
             if (idx[a] >= N) idx[a] -= N;
         }
 #pragma unroll
-        for (int jb = 0; jb < kPairJ; ++jb)
+        for (int jb = 0; jb < JB; ++jb)
 #pragma unroll
-            for (int ib = 0; ib < kPairI; ++ib) {
+            for (int ib = 0; ib < IB; ++ib) {
                 // g * conj(x)
                 const float pr = fmaf(gv[jb].x, xv[ib].x, gv[jb].y * xv[ib].y);
                 const float pi = fmaf(gv[jb].y, xv[ib].x, -gv[jb].x * xv[ib].y);
@@ -469,9 +469,9 @@ k_wgrad_zdft(const float2* __restrict__ G, const float2* __restrict__ I, float2*
             }
     }
 #pragma unroll
-    for (int jb = 0; jb < kPairJ; ++jb)
+    for (int jb = 0; jb < JB; ++jb)
 #pragma unroll
-        for (int ib = 0; ib < kPairI; ++ib) {
+        for (int ib = 0; ib < IB; ++ib) {
             const int j = j0 + jb, i = i0 + ib;
             if (j < fo && i < f) {
 #pragma unroll
@@ -501,32 +501,54 @@ int launch_expand(int kz, float2* spec, long maps, int N, int oz, long plane, lo
         case 5: return launch_expand_kz<5>(spec, maps, N, oz, plane, vol, s);
         case 6: return launch_expand_kz<6>(spec, maps, N, oz, plane, vol, s);
         case 7: return launch_expand_kz<7>(spec, maps, N, oz, plane, vol, s);
-        default: return launch_expand_kz<8>(spec, maps, N, oz, plane, vol, s);
+        case 8: return launch_expand_kz<8>(spec, maps, N, oz, plane, vol, s);
+        case 9: return launch_expand_kz<9>(spec, maps, N, oz, plane, vol, s);
+        case 10: return launch_expand_kz<10>(spec, maps, N, oz, plane, vol, s);
+        case 11: return launch_expand_kz<11>(spec, maps, N, oz, plane, vol, s);
+        case 12: return launch_expand_kz<12>(spec, maps, N, oz, plane, vol, s);
+        case 13: return launch_expand_kz<13>(spec, maps, N, oz, plane, vol, s);
+        case 14: return launch_expand_kz<14>(spec, maps, N, oz, plane, vol, s);
+        case 15: return launch_expand_kz<15>(spec, maps, N, oz, plane, vol, s);
+        default: return launch_expand_kz<16>(spec, maps, N, oz, plane, vol, s);
     }
 }
 
+// Pruned inverse DFT of the spectral products along the axis with element stride `plane`.
 template <int KZ>
-int launch_wgrad_zdft_kz(const Geom& g, const float2* G, const float2* I, float2* T1, hipStream_t s)
+int launch_wgrad_dft_k(int f, int fo, int N, long plane, long vol, const float2* G, const float2* I, float2* T,
+                       hipStream_t s)
 {
-    const long plane = (long)g.Ny * g.Nxh;
-    const dim3 grid((unsigned)((plane + kThreads - 1) / kThreads), (unsigned)((g.fo + kPairJ - 1) / kPairJ),
-                    (unsigned)((g.f + kPairI - 1) / kPairI));
-    ZNN_LAUNCH("pruned z DFT of spectral products", s, k_wgrad_zdft<KZ>, grid, dim3(kThreads), 0,
-               G, I, T1, g.f, g.fo, g.Nz, plane, g.svol());
-    return check_launch("pruned z DFT of spectral products");
+    constexpr int JB = 2, IB = KZ <= 8 ? 4 : 2;
+    const int jblocks = (fo + JB - 1) / JB, iblocks = (f + IB - 1) / IB;
+    const long pchunks = (plane + kThreads - 1) / kThreads;
+    if ((long)jblocks * iblocks >= 2147483647L || pchunks > 65535)
+        return fail(ZNN_EUNSUPPORTED, "too many edges or pencils for one launch");
+    const dim3 grid((unsigned)(jblocks * iblocks), (unsigned)pchunks);
+    ZNN_LAUNCH("pruned DFT of spectral products", s, (k_wgrad_zdft<KZ, JB, IB>), grid, dim3(kThreads), 0,
+               G, I, T, f, fo, N, plane, vol, iblocks);
+    return check_launch("pruned DFT of spectral products");
 }
 
-int launch_wgrad_zdft(const Geom& g, const float2* G, const float2* I, float2* T1, hipStream_t s)
+int launch_wgrad_dft(int k, int f, int fo, int N, long plane, long vol, const float2* G, const float2* I, float2* T,
+                     hipStream_t s)
 {
-    switch (g.kz) {
-        case 1: return launch_wgrad_zdft_kz<1>(g, G, I, T1, s);
-        case 2: return launch_wgrad_zdft_kz<2>(g, G, I, T1, s);
-        case 3: return launch_wgrad_zdft_kz<3>(g, G, I, T1, s);
-        case 4: return launch_wgrad_zdft_kz<4>(g, G, I, T1, s);
-        case 5: return launch_wgrad_zdft_kz<5>(g, G, I, T1, s);
-        case 6: return launch_wgrad_zdft_kz<6>(g, G, I, T1, s);
-        case 7: return launch_wgrad_zdft_kz<7>(g, G, I, T1, s);
-        default: return launch_wgrad_zdft_kz<8>(g, G, I, T1, s);
+    switch (k) {
+        case 1: return launch_wgrad_dft_k<1>(f, fo, N, plane, vol, G, I, T, s);
+        case 2: return launch_wgrad_dft_k<2>(f, fo, N, plane, vol, G, I, T, s);
+        case 3: return launch_wgrad_dft_k<3>(f, fo, N, plane, vol, G, I, T, s);
+        case 4: return launch_wgrad_dft_k<4>(f, fo, N, plane, vol, G, I, T, s);
+        case 5: return launch_wgrad_dft_k<5>(f, fo, N, plane, vol, G, I, T, s);
+        case 6: return launch_wgrad_dft_k<6>(f, fo, N, plane, vol, G, I, T, s);
+        case 7: return launch_wgrad_dft_k<7>(f, fo, N, plane, vol, G, I, T, s);
+        case 8: return launch_wgrad_dft_k<8>(f, fo, N, plane, vol, G, I, T, s);
+        case 9: return launch_wgrad_dft_k<9>(f, fo, N, plane, vol, G, I, T, s);
+        case 10: return launch_wgrad_dft_k<10>(f, fo, N, plane, vol, G, I, T, s);
+        case 11: return launch_wgrad_dft_k<11>(f, fo, N, plane, vol, G, I, T, s);
+        case 12: return launch_wgrad_dft_k<12>(f, fo, N, plane, vol, G, I, T, s);
+        case 13: return launch_wgrad_dft_k<13>(f, fo, N, plane, vol, G, I, T, s);
+        case 14: return launch_wgrad_dft_k<14>(f, fo, N, plane, vol, G, I, T, s);
+        case 15: return launch_wgrad_dft_k<15>(f, fo, N, plane, vol, G, I, T, s);
+        default: return launch_wgrad_dft_k<16>(f, fo, N, plane, vol, G, I, T, s);
     }
 }
 
@@ -616,7 +638,12 @@ int forward3d(const Geom& g, const float* src, float2* spec, long maps, int sz, 
     P.L = g.Nxh;
     P.Oa = (int)maps; P.Ob = sz; P.Oc = 1;
     P.in_sa = P.out_sa = vol; P.in_sb = P.out_sb = plane; P.in_sc = P.out_sc = 0;
-    if (!(g.Ny == 1)) { rc = launch_axis(P, -1, s); if (rc != ZNN_OK) return rc; }
+    if (g.Ny != 1) {
+        // 2D volumes with few non-zero rows (kernels): the y transform is a pruned DFT
+        if (g.Nz == 1 && sy <= kMaxPruned && sy < g.Ny) rc = launch_expand(sy, spec, maps, g.Ny, oy, g.Nxh, vol, s);
+        else rc = launch_axis(P, -1, s);
+        if (rc != ZNN_OK) return rc;
+    }
     // z: planes [oz, oz+sz) are non-zero
     P.in = spec; P.out = spec;
     P.N = g.Nz; P.i0 = oz; P.ni = sz; P.o0 = 0; P.no = g.Nz;
@@ -761,32 +788,36 @@ int fft_wgrad(const Geom& g, const float* in, const float* gout, float* gw, void
     rc = forward3d(g, gout, Ghat, g.fo, g.oz, g.oy, g.ox, g.kz - 1, g.ky - 1, g.kx - 1, s);
     if (rc != ZNN_OK) return rc;
     const long plane = (long)g.Ny * g.Nxh, vol = g.svol();
-    // z: product G^[j] conj(I^[i]) formed while loading; only z in [0, kz) is kept
-    AxisParams P = {};
-    P.in = Ghat; P.in2 = Ihat; P.out = T1;
-    P.N = g.Nz; P.i0 = 0; P.ni = g.Nz; P.o0 = 0; P.no = g.kz;
-    P.in_stride = plane; P.out_stride = plane;
-    P.L = (int)plane;
-    P.Oa = g.fo; P.Ob = g.f; P.Oc = 1;
-    P.in_sa = vol; P.in_sb = 0;
-    P.in2_sa = 0; P.in2_sb = vol;
-    P.out_sa = (long)g.f * g.kz * plane; P.out_sb = (long)g.kz * plane;
-    if (g.kz <= kMaxPruned && (g.fo + kPairJ - 1) / kPairJ <= 65535 && (g.f + kPairI - 1) / kPairI <= 65535)
-        rc = launch_wgrad_zdft(g, Ghat, Ihat, T1, s);
-    else
+    if (g.Nz == 1 && g.Ny > 1 && g.ky <= kMaxPruned) {
+        // 2D: the y axis is the first one contracted; its ky outputs land directly in T2
+        rc = launch_wgrad_dft(g.ky, g.f, g.fo, g.Ny, g.Nxh, vol, Ghat, Ihat, T2, s);
+        if (rc != ZNN_OK) return rc;
+    } else {
+        // z: product G^[j] conj(I^[i]); only z in [0, kz) is kept
+        AxisParams P = {};
+        P.in = Ghat; P.in2 = Ihat; P.out = T1;
+        P.N = g.Nz; P.i0 = 0; P.ni = g.Nz; P.o0 = 0; P.no = g.kz;
+        P.in_stride = plane; P.out_stride = plane;
+        P.L = (int)plane;
+        P.Oa = g.fo; P.Ob = g.f; P.Oc = 1;
+        P.in_sa = vol; P.in_sb = 0;
+        P.in2_sa = 0; P.in2_sb = vol;
+        P.out_sa = (long)g.f * g.kz * plane; P.out_sb = (long)g.kz * plane;
+        if (g.kz <= kMaxPruned) rc = launch_wgrad_dft(g.kz, g.f, g.fo, g.Nz, plane, vol, Ghat, Ihat, T1, s);
+        else rc = launch_axis(P, +1, s);
+        if (rc != ZNN_OK) return rc;
+        // y: only y in [0, ky) is kept, written compactly
+        P = AxisParams{};
+        P.in = T1; P.in2 = nullptr; P.out = T2;
+        P.N = g.Ny; P.i0 = 0; P.ni = g.Ny; P.o0 = 0; P.no = g.ky;
+        P.in_stride = g.Nxh; P.out_stride = g.Nxh;
+        P.L = g.Nxh;
+        P.Oa = g.fo * g.f; P.Ob = g.kz; P.Oc = 1;
+        P.in_sa = (long)g.kz * plane; P.in_sb = plane;
+        P.out_sa = (long)g.kz * g.ky * g.Nxh; P.out_sb = (long)g.ky * g.Nxh;
         rc = launch_axis(P, +1, s);
-    if (rc != ZNN_OK) return rc;
-    // y: only y in [0, ky) is kept, written compactly
-    P = AxisParams{};
-    P.in = T1; P.in2 = nullptr; P.out = T2;
-    P.N = g.Ny; P.i0 = 0; P.ni = g.Ny; P.o0 = 0; P.no = g.ky;
-    P.in_stride = g.Nxh; P.out_stride = g.Nxh;
-    P.L = g.Nxh;
-    P.Oa = g.fo * g.f; P.Ob = g.kz; P.Oc = 1;
-    P.in_sa = (long)g.kz * plane; P.in_sb = plane;
-    P.out_sa = (long)g.kz * g.ky * g.Nxh; P.out_sb = (long)g.ky * g.Nxh;
-    rc = launch_axis(P, +1, s);
-    if (rc != ZNN_OK) return rc;
+        if (rc != ZNN_OK) return rc;
+    }
     const float scale = (float)(1.0 / ((double)g.Nz * g.Ny * g.Nx));
     return launch_c2r(T2, gw, (long)g.f * g.fo, g.kz, g.ky, g.Nx, 0, 0, 0, g.kz, g.ky, g.kx, scale, s);
 }
