@@ -91,6 +91,21 @@ int  znn_conv_prepare_kernels(znn_plan* plan, const float* w, void* spectra, siz
 int  znn_conv_release_kernels(znn_plan* plan);
 
 /*
+ * FFT method only: memoization of the node spectra (Section 4; Table 2, column
+ * "FFT-based (Memoized)").  While a caller-owned buffer `memo` (device, 256-byte
+ * aligned, at least znn_plan_memo_bytes) is attached, znn_conv3d_fwd leaves the
+ * spectra of its input images there and znn_conv3d_bwd the spectra of its output
+ * gradients; znn_conv3d_wgrad_memo then computes the kernel gradient of exactly
+ * those two tensors without transforming them again (only the f*f' pruned inverse
+ * transforms remain).  It fails with ZNN_EINVAL unless both passes have run on this
+ * plan since the buffer was attached; each later forward / backward call replaces
+ * its half.  memo = NULL detaches.  Results are bit-identical to znn_conv3d_wgrad.
+ */
+int  znn_plan_memo_bytes(const znn_plan* plan, size_t* bytes);
+int  znn_conv_set_memo(znn_plan* plan, void* memo, size_t memo_bytes);
+int  znn_conv3d_wgrad_memo(znn_plan* plan, float* gw, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Forward pass (Section 2, "Convolution", and the node sum of the computation
  * graph): out[j] = sum_i valid_conv(in[i], w[j][i]), a true convolution (kernel
  * index runs against the image index), output extents n' = n - k + 1.

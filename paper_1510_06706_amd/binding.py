@@ -25,6 +25,7 @@ EXPORTS = [
     "znn_maxfilter3d_fwd", "znn_maxfilter3d_bwd", "znn_transfer_fwd", "znn_transfer_bwd",
     "znn_bias_grad", "znn_square_loss_grad", "znn_sgd_update", "znn_autotune_workspace_bytes",
     "znn_autotune", "znn_last_error", "znn_trace_enable", "znn_trace_collect",
+    "znn_plan_memo_bytes", "znn_conv_set_memo", "znn_conv3d_wgrad_memo",
 ]
 
 
@@ -84,6 +85,9 @@ def lib():
         L.znn_autotune_workspace_bytes.argtypes = [ctypes.POINTER(ConvDesc), ctypes.POINTER(sz)]
         L.znn_autotune.argtypes = [ctypes.POINTER(ConvDesc), vp, sz, vp, ctypes.POINTER(i32),
                                    ctypes.POINTER(ctypes.c_float * 3 * 2)]
+        L.znn_plan_memo_bytes.argtypes = [vp, ctypes.POINTER(sz)]
+        L.znn_conv_set_memo.argtypes = [vp, vp, sz]
+        L.znn_conv3d_wgrad_memo.argtypes = [vp, vp, vp, sz, vp]
         L.znn_trace_enable.argtypes = [i32]
         L.znn_trace_collect.argtypes = [ctypes.POINTER(TraceRecord), i32, ctypes.POINTER(i32)]
         for name in EXPORTS:
@@ -200,6 +204,33 @@ class Plan:
         _check(lib().znn_conv_prepare_kernels(self._h, _ptr(w, torch.float32), ctypes.c_void_p(aligned), need,
                                               ws, wsb, _stream_ptr(stream)))
         self._spectra = buf
+
+    def memo_bytes(self) -> int:
+        b = ctypes.c_size_t(0)
+        _check(lib().znn_plan_memo_bytes(self._h, ctypes.byref(b)))
+        return b.value
+
+    def enable_memo(self, device="cuda:0"):
+        """Attaches a buffer (owned by this object) in which fwd / bwd leave their node spectra."""
+        import torch
+        need = self.memo_bytes()
+        self._memo = torch.empty(need + 256, dtype=torch.uint8, device=device)
+        aligned = (self._memo.data_ptr() + 255) & ~255
+        _check(lib().znn_conv_set_memo(self._h, ctypes.c_void_p(aligned), need))
+
+    def disable_memo(self):
+        _check(lib().znn_conv_set_memo(self._h, ctypes.c_void_p(0), 0))
+        self._memo = None
+
+    def wgrad_memo(self, gw=None, device="cuda:0", stream=None):
+        """Kernel gradient of the tensors given to the last fwd and bwd, from their memoized spectra."""
+        import torch
+        if gw is None:
+            gw = torch.empty((self.fo, self.f) + self.k, dtype=torch.float32, device=device)
+        assert tuple(gw.shape) == (self.fo, self.f) + self.k
+        ws, wsb = self._workspace(ZNN_PASS_WGRAD, gw.device)
+        _check(lib().znn_conv3d_wgrad_memo(self._h, _ptr(gw, torch.float32), ws, wsb, _stream_ptr(stream)))
+        return gw
 
     def release_kernels(self):
         _check(lib().znn_conv_release_kernels(self._h))

@@ -209,6 +209,8 @@ int znn_plan_create(const znn_conv_desc* desc, znn_plan** plan)
     p->g = g;
     p->mode = mode;
     p->resident = nullptr;
+    p->memo = nullptr;
+    p->memo_has_in = p->memo_has_gout = false;
     *plan = p;
     return ZNN_OK;
 }
@@ -261,6 +263,41 @@ int znn_conv_prepare_kernels(znn_plan* plan, const float* w, void* spectra, size
     return ZNN_OK;
 }
 
+int znn_plan_memo_bytes(const znn_plan* plan, size_t* bytes)
+{
+    if (!plan || !bytes) return fail(ZNN_EINVAL, "NULL argument");
+    *bytes = align256(sizeof(float2) * (size_t)(plan->g.f + plan->g.fo) * plan->g.svol());
+    return ZNN_OK;
+}
+
+int znn_conv_set_memo(znn_plan* plan, void* memo, size_t memo_bytes)
+{
+    if (!plan) return fail(ZNN_EINVAL, "NULL argument");
+    plan->memo = nullptr;
+    plan->memo_has_in = plan->memo_has_gout = false;
+    if (!memo) return ZNN_OK;
+    if (plan->mode != ZNN_FFT) return fail(ZNN_EINVAL, "spectra are memoized only by the FFT method");
+    size_t need = 0;
+    znn_plan_memo_bytes(plan, &need);
+    if (!aligned256(memo)) return fail(ZNN_EWORKSPACE, "memo buffer is not 256-byte aligned");
+    if (memo_bytes < need) return fail(ZNN_EWORKSPACE, "memo buffer has %zu bytes, %zu needed", memo_bytes, need);
+    plan->memo = (float2*)memo;
+    return ZNN_OK;
+}
+
+int znn_conv3d_wgrad_memo(znn_plan* plan, float* gw, void* ws, size_t ws_bytes, void* stream)
+{
+    if (!plan || !gw) return fail(ZNN_EINVAL, "NULL argument");
+    if (plan->mode != ZNN_FFT || !plan->memo) return fail(ZNN_EINVAL, "no memo buffer is attached to this plan");
+    if (!plan->memo_has_in || !plan->memo_has_gout)
+        return fail(ZNN_EINVAL, "the forward and the backward pass must run on this plan first");
+    int rc = check_ws(plan, ZNN_PASS_WGRAD, ws, ws_bytes);
+    if (rc != ZNN_OK) return rc;
+    const float2* Ihat = plan->memo;
+    const float2* Ghat = plan->memo + (size_t)plan->g.f * plan->g.svol();
+    return fft_wgrad_from_spectra(plan->g, Ihat, Ghat, gw, ws, (hipStream_t)stream);
+}
+
 int znn_conv_release_kernels(znn_plan* plan)
 {
     if (!plan) return fail(ZNN_EINVAL, "NULL argument");
@@ -276,7 +313,9 @@ int znn_conv3d_fwd(znn_plan* plan, const float* in, const float* w, float* out,
     int rc = check_ws(plan, ZNN_PASS_FWD, ws, ws_bytes);
     if (rc != ZNN_OK) return rc;
     if (plan->mode == ZNN_DIRECT) return direct_fwd(plan->g, in, w, out, ws, (hipStream_t)stream);
-    return fft_fwd(plan->g, in, w, plan->resident, out, ws, (hipStream_t)stream);
+    rc = fft_fwd(plan->g, in, w, plan->resident, out, ws, plan->memo, (hipStream_t)stream);
+    if (plan->memo) plan->memo_has_in = rc == ZNN_OK;
+    return rc;
 }
 
 int znn_conv3d_bwd(znn_plan* plan, const float* gout, const float* w, float* gin,
@@ -287,7 +326,10 @@ int znn_conv3d_bwd(znn_plan* plan, const float* gout, const float* w, float* gin
     int rc = check_ws(plan, ZNN_PASS_BWD, ws, ws_bytes);
     if (rc != ZNN_OK) return rc;
     if (plan->mode == ZNN_DIRECT) return direct_bwd(plan->g, gout, w, gin, ws, (hipStream_t)stream);
-    return fft_bwd(plan->g, gout, w, plan->resident, gin, ws, (hipStream_t)stream);
+    rc = fft_bwd(plan->g, gout, w, plan->resident, gin, ws,
+                 plan->memo ? plan->memo + (size_t)plan->g.f * plan->g.svol() : nullptr, (hipStream_t)stream);
+    if (plan->memo) plan->memo_has_gout = rc == ZNN_OK;
+    return rc;
 }
 
 int znn_conv3d_wgrad(znn_plan* plan, const float* in, const float* gout, float* gw,
@@ -384,8 +426,8 @@ int znn_autotune(const znn_conv_desc* desc, void* ws, size_t ws_bytes, void* str
                     else if (pass == 1) rc = direct_bwd(g, gout, w, gin, scr, s);
                     else rc = direct_wgrad(g, in, gout, gw, scr, s);
                 } else {
-                    if (pass == 0) rc = fft_fwd(g, in, w, nullptr, out, scr, s);
-                    else if (pass == 1) rc = fft_bwd(g, gout, w, nullptr, gin, scr, s);
+                    if (pass == 0) rc = fft_fwd(g, in, w, nullptr, out, scr, nullptr, s);
+                    else if (pass == 1) rc = fft_bwd(g, gout, w, nullptr, gin, scr, nullptr, s);
                     else rc = fft_wgrad(g, in, gout, gw, scr, s);
                 }
             }

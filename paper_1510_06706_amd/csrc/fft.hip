@@ -737,10 +737,10 @@ int fft_kernel_spectra(const Geom& g, const float* w, float2* What, hipStream_t 
 }
 
 int fft_fwd(const Geom& g, const float* in, const float* w, const float2* resident, float* out,
-            void* ws, hipStream_t s)
+            void* ws, float2* memo_in, hipStream_t s)
 {
     const FftWorkspace L = fft_workspace(g, ZNN_PASS_FWD, resident != nullptr);
-    float2* Ihat = (float2*)((char*)ws + L.off_a);
+    float2* Ihat = memo_in ? memo_in : (float2*)((char*)ws + L.off_a);
     float2* Ohat = (float2*)((char*)ws + L.off_b);
     const float2* What = resident;
     int rc = forward3d(g, in, Ihat, g.f, g.nz, g.ny, g.nx, 0, 0, 0, s);
@@ -757,10 +757,10 @@ int fft_fwd(const Geom& g, const float* in, const float* w, const float2* reside
 }
 
 int fft_bwd(const Geom& g, const float* gout, const float* w, const float2* resident, float* gin,
-            void* ws, hipStream_t s)
+            void* ws, float2* memo_gout, hipStream_t s)
 {
     const FftWorkspace L = fft_workspace(g, ZNN_PASS_BWD, resident != nullptr);
-    float2* Ghat = (float2*)((char*)ws + L.off_a);
+    float2* Ghat = memo_gout ? memo_gout : (float2*)((char*)ws + L.off_a);
     float2* Ginhat = (float2*)((char*)ws + L.off_b);
     const float2* What = resident;
     int rc = forward3d(g, gout, Ghat, g.fo, g.oz, g.oy, g.ox, g.kz - 1, g.ky - 1, g.kx - 1, s);
@@ -781,12 +781,22 @@ int fft_wgrad(const Geom& g, const float* in, const float* gout, float* gw, void
     const FftWorkspace L = fft_workspace(g, ZNN_PASS_WGRAD, false);
     float2* Ihat = (float2*)((char*)ws + L.off_a);
     float2* Ghat = (float2*)((char*)ws + L.off_b);
-    float2* T1 = (float2*)((char*)ws + L.off_t1);
-    float2* T2 = (float2*)((char*)ws + L.off_t2);
     int rc = forward3d(g, in, Ihat, g.f, g.nz, g.ny, g.nx, 0, 0, 0, s);
     if (rc != ZNN_OK) return rc;
     rc = forward3d(g, gout, Ghat, g.fo, g.oz, g.oy, g.ox, g.kz - 1, g.ky - 1, g.kx - 1, s);
     if (rc != ZNN_OK) return rc;
+    return fft_wgrad_from_spectra(g, Ihat, Ghat, gw, ws, s);
+}
+
+// Kernel gradient from node spectra that already exist (memoized by the forward and
+// backward pass, or just computed): gw = crop[0,k) IFFT( G_s^[j] conj(I^[i]) ).
+int fft_wgrad_from_spectra(const Geom& g, const float2* Ihat, const float2* Ghat, float* gw, void* ws,
+                           hipStream_t s)
+{
+    const FftWorkspace L = fft_workspace(g, ZNN_PASS_WGRAD, false);
+    float2* T1 = (float2*)((char*)ws + L.off_t1);
+    float2* T2 = (float2*)((char*)ws + L.off_t2);
+    int rc = ZNN_OK;
     const long plane = (long)g.Ny * g.Nxh, vol = g.svol();
     if (g.Nz == 1 && g.Ny > 1 && g.ky <= kMaxPruned) {
         // 2D: the y axis is the first one contracted; its ky outputs land directly in T2

@@ -87,10 +87,12 @@ FftWorkspace fft_workspace(const Geom& g, int pass, bool resident);
 size_t fft_spectra_bytes(const Geom& g);
 int fft_kernel_spectra(const Geom& g, const float* w, float2* What, hipStream_t s);
 int fft_fwd(const Geom& g, const float* in, const float* w, const float2* resident, float* out,
-            void* ws, hipStream_t s);
+            void* ws, float2* memo_in, hipStream_t s);
 int fft_bwd(const Geom& g, const float* gout, const float* w, const float2* resident, float* gin,
-            void* ws, hipStream_t s);
+            void* ws, float2* memo_gout, hipStream_t s);
 int fft_wgrad(const Geom& g, const float* in, const float* gout, float* gw, void* ws, hipStream_t s);
+int fft_wgrad_from_spectra(const Geom& g, const float2* Ihat, const float2* Ghat, float* gw, void* ws,
+                           hipStream_t s);
 
 // ---------------------------------------------------------------- fill (autotuner)
 int fill_pattern(float* p, long count, float scale, hipStream_t s);
@@ -102,4 +104,6 @@ struct znn_plan {
     znn::Geom g;
     int mode;                    // ZNN_DIRECT or ZNN_FFT
     const float2* resident;      // kernel spectra held by the caller, or nullptr
+    float2* memo;                // caller's buffer for memoized node spectra, or nullptr
+    bool memo_has_in, memo_has_gout;
 };

@@ -110,3 +110,21 @@ def test_auto_mode_resolves_to_a_concrete_method():
     p = znn.Plan(120, 120, (96, 96, 96), (7, 7, 7), "auto")
     assert p.mode in (znn.ZNN_DIRECT, znn.ZNN_FFT)
     p.close()
+
+
+def test_memo_entry_points_validate_their_state():
+    L = znn.lib()
+    fake, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
+    d = znn.Plan(2, 2, (8, 8, 8), (3, 3, 3), "direct")
+    assert L.znn_conv_set_memo(d._h, fake, 1 << 30) == znn.ZNN_EINVAL
+    d.close()
+    p = znn.Plan(2, 3, (8, 8, 8), (3, 3, 3), "fft")
+    assert p.memo_bytes() == 5 * 8 * 8 * 5 * 8
+    assert L.znn_conv3d_wgrad_memo(p._h, fake, fake, 1 << 30, null) == znn.ZNN_EINVAL     # nothing attached
+    assert L.znn_conv_set_memo(p._h, fake, 16) == znn.ZNN_EWORKSPACE
+    assert L.znn_conv_set_memo(p._h, ctypes.c_void_p(0x1001), 1 << 30) == znn.ZNN_EWORKSPACE
+    assert L.znn_conv_set_memo(p._h, fake, 1 << 30) == znn.ZNN_OK
+    assert L.znn_conv3d_wgrad_memo(p._h, fake, fake, 1 << 30, null) == znn.ZNN_EINVAL     # passes have not run
+    assert "forward and the backward" in znn.last_error()
+    assert L.znn_conv_set_memo(p._h, null, 0) == znn.ZNN_OK
+    p.close()

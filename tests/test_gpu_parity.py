@@ -86,6 +86,32 @@ def test_resident_kernel_spectra_give_the_same_result():
     p.close()
 
 
+def test_memoized_node_spectra_give_the_same_kernel_gradient():
+    f, fo, n, k = 5, 7, (11, 9, 12), (3, 2, 4)
+    cfg = synth.LayerShape("t", f, fo, n, k, 1.0, 93)
+    inp, w, gout = synth.layer_tensors(cfg)
+    p = znn.Plan(f, fo, n, k, "fft")
+    d_in, d_w, d_g = dev(inp), dev(w), dev(gout)
+    gw0 = host(p.wgrad(d_in, d_g))
+    p.enable_memo()
+    with pytest.raises(znn.ZnnError):
+        p.wgrad_memo()                      # forward and backward have not run yet
+    out, gin = host(p.fwd(d_in, d_w)), host(p.bwd(d_g, d_w))
+    gw1 = host(p.wgrad_memo())
+    assert np.array_equal(gw0, gw1)
+    assert rel_err(gw1, oracle.conv3d_wgrad(inp, gout)) <= TOL["fft"]
+    assert rel_err(out, oracle.conv3d_fwd(inp, w)) <= TOL["fft"]
+    assert rel_err(gin, oracle.conv3d_bwd(gout, w, n)) <= TOL["fft"]
+    # a later forward pass replaces its half of the memo
+    inp2 = synth.uniform_pm1(94, 0, inp.shape)
+    p.fwd(dev(inp2), d_w)
+    assert rel_err(host(p.wgrad_memo()), oracle.conv3d_wgrad(inp2, gout)) <= TOL["fft"]
+    p.disable_memo()
+    with pytest.raises(znn.ZnnError):
+        p.wgrad_memo()
+    p.close()
+
+
 FILTERS = [((5, 6, 7), (2, 2, 2)), ((22, 22, 22), (2, 2, 2)), ((1, 30, 17), (1, 2, 2)),
            ((6, 5, 9), (3, 1, 4)), ((3, 3, 3), (3, 3, 3)), ((4, 5, 6), (1, 1, 1))]
 
