@@ -68,69 +68,86 @@ def _check(rc, what):
         raise ValueError("oracle %s rejected its arguments (rc=%d)" % (what, rc))
 
 
-def conv3d_fwd(inp, w):
-    """out[j] = sum_i valid_conv(in[i], w[j, i])   (Section 2, Convolution)."""
+def out_extents(n, k, sparsity=(1, 1, 1)):
+    """n' = n - s (k - 1) per axis (Section 2; s = 1 gives n - k + 1)."""
+    return tuple(int(n[d]) - int(sparsity[d]) * (int(k[d]) - 1) for d in range(3))
+
+
+def conv3d_fwd(inp, w, sparsity=(1, 1, 1)):
+    """out[j] = sum_i valid_conv(in[i], w[j, i])   (Section 2, Convolution; optionally sparse)."""
     inp, w = _f64(inp), _f64(w)
     fo, f = w.shape[:2]
     assert inp.ndim == 4 and w.ndim == 5 and inp.shape[0] == f
     n, k = inp.shape[1:], w.shape[2:]
-    out = np.empty((fo,) + tuple(n[d] - k[d] + 1 for d in range(3)), dtype=np.float64)
-    _check(_load().znn_ref_conv3d_fwd(f, fo, _i3(n), _i3(k), _d(inp), _d(w), _d(out)), "fwd")
+    o = out_extents(n, k, sparsity)
+    if min(o) < 1:
+        raise ValueError("oracle fwd rejected its arguments (kernel span exceeds the image)")
+    out = np.empty((fo,) + o, dtype=np.float64)
+    _check(_load().znn_ref_conv3d_fwd(f, fo, _i3(n), _i3(k), _i3(sparsity), _d(inp), _d(w), _d(out)), "fwd")
     return out
 
 
-def conv3d_bwd(gout, w, n):
+def conv3d_bwd(gout, w, n, sparsity=(1, 1, 1)):
     """gin[i] = sum_j full_conv(gout[j], reflect(w[j, i]))   (Section 3.1)."""
     gout, w = _f64(gout), _f64(w)
     fo, f = w.shape[:2]
     k = w.shape[2:]
-    assert gout.shape == (fo,) + tuple(n[d] - k[d] + 1 for d in range(3))
+    assert gout.shape == (fo,) + out_extents(n, k, sparsity)
     gin = np.empty((f,) + tuple(n), dtype=np.float64)
-    _check(_load().znn_ref_conv3d_bwd(f, fo, _i3(n), _i3(k), _d(gout), _d(w), _d(gin)), "bwd")
+    _check(_load().znn_ref_conv3d_bwd(f, fo, _i3(n), _i3(k), _i3(sparsity), _d(gout), _d(w), _d(gin)), "bwd")
     return gin
 
 
-def conv3d_wgrad(inp, gout):
+def _kernel_extents(n, o, sparsity):
+    k = []
+    for d in range(3):
+        span = int(n[d]) - int(o[d])
+        assert span % int(sparsity[d]) == 0, "extents do not match the sparsity"
+        k.append(span // int(sparsity[d]) + 1)
+    return tuple(k)
+
+
+def conv3d_wgrad(inp, gout, sparsity=(1, 1, 1)):
     """gw[j, i] = valid_conv(reflect(in[i]), gout[j])   (Section 3.2)."""
     inp, gout = _f64(inp), _f64(gout)
     f, fo = inp.shape[0], gout.shape[0]
     n = inp.shape[1:]
-    k = tuple(n[d] - gout.shape[1 + d] + 1 for d in range(3))
+    k = _kernel_extents(n, gout.shape[1:], sparsity)
     gw = np.empty((fo, f) + k, dtype=np.float64)
-    _check(_load().znn_ref_conv3d_wgrad(f, fo, _i3(n), _i3(k), _d(inp), _d(gout), _d(gw)), "wgrad")
+    _check(_load().znn_ref_conv3d_wgrad(f, fo, _i3(n), _i3(k), _i3(sparsity), _d(inp), _d(gout), _d(gw)), "wgrad")
     return gw
 
 
-def _at(fn, what, f, fo, n, k, a, b, pos):
+def _at(fn, what, f, fo, n, k, a, b, pos, sparsity=(1, 1, 1)):
     pos = np.ascontiguousarray(np.asarray(pos, dtype=np.int64))
     val = np.empty(pos.shape, dtype=np.float64)
-    rc = fn(f, fo, _i3(n), _i3(k), _d(a), _d(b), ctypes.c_long(pos.size),
+    rc = fn(f, fo, _i3(n), _i3(k), _i3(sparsity), _d(a), _d(b), ctypes.c_long(pos.size),
             pos.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), _d(val))
     _check(rc, what)
     return val
 
 
-def conv3d_fwd_at(inp, w, pos):
+def conv3d_fwd_at(inp, w, pos, sparsity=(1, 1, 1)):
     """Forward outputs at flat positions ``pos`` of the [fo, n'] tensor."""
     inp, w = _f64(inp), _f64(w)
     fo, f = w.shape[:2]
-    return _at(_load().znn_ref_conv3d_fwd_at, "fwd_at", f, fo, inp.shape[1:], w.shape[2:], inp, w, pos)
+    return _at(_load().znn_ref_conv3d_fwd_at, "fwd_at", f, fo, inp.shape[1:], w.shape[2:], inp, w, pos, sparsity)
 
 
-def conv3d_bwd_at(gout, w, n, pos):
+def conv3d_bwd_at(gout, w, n, pos, sparsity=(1, 1, 1)):
     """Backward outputs at flat positions ``pos`` of the [f, n] tensor."""
     gout, w = _f64(gout), _f64(w)
     fo, f = w.shape[:2]
-    return _at(_load().znn_ref_conv3d_bwd_at, "bwd_at", f, fo, n, w.shape[2:], gout, w, pos)
+    return _at(_load().znn_ref_conv3d_bwd_at, "bwd_at", f, fo, n, w.shape[2:], gout, w, pos, sparsity)
 
 
-def conv3d_wgrad_at(inp, gout, pos):
+def conv3d_wgrad_at(inp, gout, pos, sparsity=(1, 1, 1)):
     """Kernel-gradient entries at flat positions ``pos`` of the [fo, f, k] tensor."""
     inp, gout = _f64(inp), _f64(gout)
     f, fo = inp.shape[0], gout.shape[0]
     n = inp.shape[1:]
-    k = tuple(n[d] - gout.shape[1 + d] + 1 for d in range(3))
-    return _at(_load().znn_ref_conv3d_wgrad_at, "wgrad_at", f, fo, n, k, inp, gout, pos)
+    k = _kernel_extents(n, gout.shape[1:], sparsity)
+    return _at(_load().znn_ref_conv3d_wgrad_at, "wgrad_at", f, fo, n, k, inp, gout, pos, sparsity)
 
 
 def maxfilter3d_fwd(inp, win):

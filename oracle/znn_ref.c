@@ -40,11 +40,13 @@ int znn_ref_num_threads(void)
 #endif
 }
 
-static int bad_conv(int f, int fo, const int n[3], const int k[3])
+/* Sparse convolution (Section 2): only every s-th voxel of the window enters the sum, so a
+ * kernel of k taps spans s*(k-1)+1 voxels and the output extent is n - s*(k-1). */
+static int bad_conv(int f, int fo, const int n[3], const int k[3], const int s[3])
 {
     if (f < 1 || fo < 1) return 1;
     for (int d = 0; d < 3; ++d)
-        if (n[d] < 1 || k[d] < 1 || k[d] > n[d]) return 1;
+        if (n[d] < 1 || k[d] < 1 || s[d] < 1 || (long)s[d] * (k[d] - 1) + 1 > n[d]) return 1;
     return 0;
 }
 
@@ -55,15 +57,18 @@ static int bad_conv(int f, int fo, const int n[3], const int k[3])
  * image index.
  *
  *   out[j][z][y][x] = sum_i sum_{a,b,c} w[j][i][a][b][c]
- *                       * in[i][z + kz-1-a][y + ky-1-b][x + kx-1-c]
+ *                       * in[i][z + sz(kz-1-a)][y + sy(ky-1-b)][x + sx(kx-1-c)]
+ *
+ * (s = sparsity; s = 1 is the dense convolution.)
  */
-int znn_ref_conv3d_fwd(int f, int fo, const int n[3], const int k[3],
+int znn_ref_conv3d_fwd(int f, int fo, const int n[3], const int k[3], const int s[3],
                        const double *in, const double *w, double *out)
 {
-    if (bad_conv(f, fo, n, k) || !in || !w || !out) return ZNN_REF_EINVAL;
+    if (bad_conv(f, fo, n, k, s) || !in || !w || !out) return ZNN_REF_EINVAL;
     const int nz = n[0], ny = n[1], nx = n[2];
     const int kz = k[0], ky = k[1], kx = k[2];
-    const int oz = nz - kz + 1, oy = ny - ky + 1, ox = nx - kx + 1;
+    const int sz = s[0], sy = s[1], sx = s[2];
+    const int oz = nz - sz * (kz - 1), oy = ny - sy * (ky - 1), ox = nx - sx * (kx - 1);
     const size_t nvol = (size_t)nz * ny * nx, kvol = (size_t)kz * ky * kx;
     const size_t ovol = (size_t)oz * oy * ox;
 #pragma omp parallel for schedule(dynamic, 1)
@@ -79,8 +84,8 @@ int znn_ref_conv3d_fwd(int f, int fo, const int n[3], const int k[3],
                 for (int b = 0; b < ky; ++b)
                 for (int c = 0; c < kx; ++c)
                     acc += ker[((size_t)a * ky + b) * kx + c] *
-                           img[((size_t)(z + kz - 1 - a) * ny + (y + ky - 1 - b)) * nx +
-                               (x + kx - 1 - c)];
+                           img[((size_t)(z + sz * (kz - 1 - a)) * ny + (y + sy * (ky - 1 - b))) * nx +
+                               (x + sx * (kx - 1 - c))];
             }
             out[(size_t)j * ovol + ((size_t)z * oy + y) * ox + x] = acc;
         }
@@ -95,17 +100,18 @@ int znn_ref_conv3d_fwd(int f, int fo, const int n[3], const int k[3],
  * Reflecting the kernel of a true convolution leaves a correlation:
  *
  *   gin[i][z][y][x] = sum_j sum_{a,b,c} w[j][i][a][b][c]
- *                       * gout[j][z-(kz-1)+a][y-(ky-1)+b][x-(kx-1)+c]
+ *                       * gout[j][z - sz(kz-1-a)][y - sy(ky-1-b)][x - sx(kx-1-c)]
  *
  * where terms whose gout index leaves the image are zero.
  */
-int znn_ref_conv3d_bwd(int f, int fo, const int n[3], const int k[3],
+int znn_ref_conv3d_bwd(int f, int fo, const int n[3], const int k[3], const int s[3],
                        const double *gout, const double *w, double *gin)
 {
-    if (bad_conv(f, fo, n, k) || !gout || !w || !gin) return ZNN_REF_EINVAL;
+    if (bad_conv(f, fo, n, k, s) || !gout || !w || !gin) return ZNN_REF_EINVAL;
     const int nz = n[0], ny = n[1], nx = n[2];
     const int kz = k[0], ky = k[1], kx = k[2];
-    const int oz = nz - kz + 1, oy = ny - ky + 1, ox = nx - kx + 1;
+    const int sz = s[0], sy = s[1], sx = s[2];
+    const int oz = nz - sz * (kz - 1), oy = ny - sy * (ky - 1), ox = nx - sx * (kx - 1);
     const size_t nvol = (size_t)nz * ny * nx, kvol = (size_t)kz * ky * kx;
     const size_t ovol = (size_t)oz * oy * ox;
 #pragma omp parallel for schedule(dynamic, 1)
@@ -118,13 +124,13 @@ int znn_ref_conv3d_bwd(int f, int fo, const int n[3], const int k[3],
                 const double *g = gout + (size_t)j * ovol;
                 const double *ker = w + ((size_t)j * f + i) * kvol;
                 for (int a = 0; a < kz; ++a) {
-                    const int gz = z - (kz - 1) + a;
+                    const int gz = z - sz * (kz - 1 - a);
                     if (gz < 0 || gz >= oz) continue;
                     for (int b = 0; b < ky; ++b) {
-                        const int gy = y - (ky - 1) + b;
+                        const int gy = y - sy * (ky - 1 - b);
                         if (gy < 0 || gy >= oy) continue;
                         for (int c = 0; c < kx; ++c) {
-                            const int gx = x - (kx - 1) + c;
+                            const int gx = x - sx * (kx - 1 - c);
                             if (gx < 0 || gx >= ox) continue;
                             acc += ker[((size_t)a * ky + b) * kx + c] *
                                    g[((size_t)gz * oy + gy) * ox + gx];
@@ -144,15 +150,16 @@ int znn_ref_conv3d_bwd(int f, int fo, const int n[3], const int k[3],
  * (Section 3.2, "Kernel update").
  *
  *   gw[j][i][a][b][c] = sum_{z,y,x} gout[j][z][y][x]
- *                         * in[i][z + kz-1-a][y + ky-1-b][x + kx-1-c]
+ *                         * in[i][z + sz(kz-1-a)][y + sy(ky-1-b)][x + sx(kx-1-c)]
  */
-int znn_ref_conv3d_wgrad(int f, int fo, const int n[3], const int k[3],
+int znn_ref_conv3d_wgrad(int f, int fo, const int n[3], const int k[3], const int s[3],
                          const double *in, const double *gout, double *gw)
 {
-    if (bad_conv(f, fo, n, k) || !in || !gout || !gw) return ZNN_REF_EINVAL;
+    if (bad_conv(f, fo, n, k, s) || !in || !gout || !gw) return ZNN_REF_EINVAL;
     const int nz = n[0], ny = n[1], nx = n[2];
     const int kz = k[0], ky = k[1], kx = k[2];
-    const int oz = nz - kz + 1, oy = ny - ky + 1, ox = nx - kx + 1;
+    const int sz = s[0], sy = s[1], sx = s[2];
+    const int oz = nz - sz * (kz - 1), oy = ny - sy * (ky - 1), ox = nx - sx * (kx - 1);
     const size_t nvol = (size_t)nz * ny * nx, kvol = (size_t)kz * ky * kx;
     const size_t ovol = (size_t)oz * oy * ox;
     const long pairs = (long)f * fo;
@@ -169,8 +176,8 @@ int znn_ref_conv3d_wgrad(int f, int fo, const int n[3], const int k[3],
             for (int y = 0; y < oy; ++y)
             for (int x = 0; x < ox; ++x)
                 acc += g[((size_t)z * oy + y) * ox + x] *
-                       img[((size_t)(z + kz - 1 - a) * ny + (y + ky - 1 - b)) * nx +
-                           (x + kx - 1 - c)];
+                       img[((size_t)(z + sz * (kz - 1 - a)) * ny + (y + sy * (ky - 1 - b))) * nx +
+                           (x + sx * (kx - 1 - c))];
             gw[(size_t)e * kvol + ((size_t)a * ky + b) * kx + c] = acc;
         }
     }
@@ -182,14 +189,15 @@ int znn_ref_conv3d_wgrad(int f, int fo, const int n[3], const int k[3],
  * layer too large for a full CPU pass can still be checked element by element.
  * pos[s] is the flat index into the full output tensor of that pass.
  */
-int znn_ref_conv3d_fwd_at(int f, int fo, const int n[3], const int k[3],
+int znn_ref_conv3d_fwd_at(int f, int fo, const int n[3], const int k[3], const int s[3],
                           const double *in, const double *w,
                           long count, const int64_t *pos, double *val)
 {
-    if (bad_conv(f, fo, n, k) || !in || !w || !pos || !val || count < 0) return ZNN_REF_EINVAL;
+    if (bad_conv(f, fo, n, k, s) || !in || !w || !pos || !val || count < 0) return ZNN_REF_EINVAL;
     const int nz = n[0], ny = n[1], nx = n[2];
     const int kz = k[0], ky = k[1], kx = k[2];
-    const int oz = nz - kz + 1, oy = ny - ky + 1, ox = nx - kx + 1;
+    const int sz = s[0], sy = s[1], sx = s[2];
+    const int oz = nz - sz * (kz - 1), oy = ny - sy * (ky - 1), ox = nx - sx * (kx - 1);
     const size_t nvol = (size_t)nz * ny * nx, kvol = (size_t)kz * ky * kx;
     const size_t ovol = (size_t)oz * oy * ox;
     for (long s = 0; s < count; ++s)
@@ -208,22 +216,23 @@ int znn_ref_conv3d_fwd_at(int f, int fo, const int n[3], const int k[3],
             for (int b = 0; b < ky; ++b)
             for (int c = 0; c < kx; ++c)
                 acc += ker[((size_t)a * ky + b) * kx + c] *
-                       img[((size_t)(z + kz - 1 - a) * ny + (y + ky - 1 - b)) * nx +
-                           (x + kx - 1 - c)];
+                       img[((size_t)(z + sz * (kz - 1 - a)) * ny + (y + sy * (ky - 1 - b))) * nx +
+                           (x + sx * (kx - 1 - c))];
         }
         val[s] = acc;
     }
     return ZNN_REF_OK;
 }
 
-int znn_ref_conv3d_bwd_at(int f, int fo, const int n[3], const int k[3],
+int znn_ref_conv3d_bwd_at(int f, int fo, const int n[3], const int k[3], const int s[3],
                           const double *gout, const double *w,
                           long count, const int64_t *pos, double *val)
 {
-    if (bad_conv(f, fo, n, k) || !gout || !w || !pos || !val || count < 0) return ZNN_REF_EINVAL;
+    if (bad_conv(f, fo, n, k, s) || !gout || !w || !pos || !val || count < 0) return ZNN_REF_EINVAL;
     const int nz = n[0], ny = n[1], nx = n[2];
     const int kz = k[0], ky = k[1], kx = k[2];
-    const int oz = nz - kz + 1, oy = ny - ky + 1, ox = nx - kx + 1;
+    const int sz = s[0], sy = s[1], sx = s[2];
+    const int oz = nz - sz * (kz - 1), oy = ny - sy * (ky - 1), ox = nx - sx * (kx - 1);
     const size_t nvol = (size_t)nz * ny * nx, kvol = (size_t)kz * ky * kx;
     const size_t ovol = (size_t)oz * oy * ox;
     for (long s = 0; s < count; ++s)
@@ -239,13 +248,13 @@ int znn_ref_conv3d_bwd_at(int f, int fo, const int n[3], const int k[3],
             const double *g = gout + (size_t)j * ovol;
             const double *ker = w + ((size_t)j * f + i) * kvol;
             for (int a = 0; a < kz; ++a) {
-                const int gz = z - (kz - 1) + a;
+                const int gz = z - sz * (kz - 1 - a);
                 if (gz < 0 || gz >= oz) continue;
                 for (int b = 0; b < ky; ++b) {
-                    const int gy = y - (ky - 1) + b;
+                    const int gy = y - sy * (ky - 1 - b);
                     if (gy < 0 || gy >= oy) continue;
                     for (int c = 0; c < kx; ++c) {
-                        const int gx = x - (kx - 1) + c;
+                        const int gx = x - sx * (kx - 1 - c);
                         if (gx < 0 || gx >= ox) continue;
                         acc += ker[((size_t)a * ky + b) * kx + c] *
                                g[((size_t)gz * oy + gy) * ox + gx];
@@ -258,14 +267,15 @@ int znn_ref_conv3d_bwd_at(int f, int fo, const int n[3], const int k[3],
     return ZNN_REF_OK;
 }
 
-int znn_ref_conv3d_wgrad_at(int f, int fo, const int n[3], const int k[3],
+int znn_ref_conv3d_wgrad_at(int f, int fo, const int n[3], const int k[3], const int s[3],
                             const double *in, const double *gout,
                             long count, const int64_t *pos, double *val)
 {
-    if (bad_conv(f, fo, n, k) || !in || !gout || !pos || !val || count < 0) return ZNN_REF_EINVAL;
+    if (bad_conv(f, fo, n, k, s) || !in || !gout || !pos || !val || count < 0) return ZNN_REF_EINVAL;
     const int nz = n[0], ny = n[1], nx = n[2];
     const int kz = k[0], ky = k[1], kx = k[2];
-    const int oz = nz - kz + 1, oy = ny - ky + 1, ox = nx - kx + 1;
+    const int sz = s[0], sy = s[1], sx = s[2];
+    const int oz = nz - sz * (kz - 1), oy = ny - sy * (ky - 1), ox = nx - sx * (kx - 1);
     const size_t nvol = (size_t)nz * ny * nx, kvol = (size_t)kz * ky * kx;
     const size_t ovol = (size_t)oz * oy * ox;
     for (long s = 0; s < count; ++s)
@@ -284,8 +294,8 @@ int znn_ref_conv3d_wgrad_at(int f, int fo, const int n[3], const int k[3],
         for (int y = 0; y < oy; ++y)
         for (int x = 0; x < ox; ++x)
             acc += g[((size_t)z * oy + y) * ox + x] *
-                   img[((size_t)(z + kz - 1 - a) * ny + (y + ky - 1 - b)) * nx +
-                       (x + kx - 1 - c)];
+                   img[((size_t)(z + sz * (kz - 1 - a)) * ny + (y + sy * (ky - 1 - b))) * nx +
+                       (x + sx * (kx - 1 - c))];
         val[s] = acc;
     }
     return ZNN_REF_OK;

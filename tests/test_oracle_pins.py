@@ -241,6 +241,72 @@ def test_rejects_bad_extents():
         oracle.maxfilter3d_fwd(np.zeros((1, 2, 2, 2)), (1, 3, 1))
 
 
+# ---------------------------------------------------------------- sparse convolution
+def stuff(w, s):
+    """Kernel with s-1 zeros between neighbouring taps along every axis."""
+    k = w.shape[2:]
+    span = tuple(s[d] * (k[d] - 1) + 1 for d in range(3))
+    out = np.zeros(w.shape[:2] + span)
+    out[:, :, ::s[0], ::s[1], ::s[2]] = w
+    return out
+
+
+SPARSE = [(2, 2, (7, 8, 9), (2, 3, 2), (2, 2, 3)), (1, 3, (9, 5, 6), (3, 2, 1), (3, 1, 2)),
+          (3, 1, (1, 11, 10), (1, 3, 4), (1, 4, 2)), (2, 2, (6, 6, 6), (2, 2, 2), (1, 1, 1))]
+
+
+@pytest.mark.parametrize("f,fo,n,k,s", SPARSE)
+def test_sparse_convolution_equals_dense_convolution_with_a_zero_stuffed_kernel(f, fo, n, k, s):
+    """Only every s-th voxel of the window enters the sum (Section 2): that is a dense
+    convolution whose kernel has s-1 zeros between its taps."""
+    inp, w = rnd(61, 0, (f,) + n), rnd(61, 1, (fo, f) + k)
+    o = oracle.out_extents(n, k, s)
+    assert o == tuple(n[d] - s[d] * (k[d] - 1) for d in range(3))
+    g = rnd(61, 2, (fo,) + o)
+    ws = stuff(w, s)
+    fwd = oracle.conv3d_fwd(inp, w, s)
+    assert fwd.shape == (fo,) + o
+    np.testing.assert_allclose(fwd, oracle.conv3d_fwd(inp, ws), atol=1e-13)
+    for j in range(fo):
+        want = sum(scipy.signal.convolve(inp[i], ws[j, i], mode="valid", method="direct") for i in range(f))
+        np.testing.assert_allclose(fwd[j], want, atol=1e-13)
+    np.testing.assert_allclose(oracle.conv3d_bwd(g, w, n, s), oracle.conv3d_bwd(g, ws, n), atol=1e-13)
+    gws = oracle.conv3d_wgrad(inp, g)                   # dense gradient of the stuffed kernel ...
+    gw = oracle.conv3d_wgrad(inp, g, s)
+    assert gw.shape == w.shape
+    np.testing.assert_allclose(gw, gws[:, :, ::s[0], ::s[1], ::s[2]], atol=1e-12)   # ... at the real taps
+
+
+@pytest.mark.parametrize("f,fo,n,k,s", SPARSE)
+def test_sparse_adjoint_identities_and_sampled_entry_points(f, fo, n, k, s):
+    inp, w = rnd(62, 0, (f,) + n), rnd(62, 1, (fo, f) + k)
+    y = rnd(62, 2, (fo,) + oracle.out_extents(n, k, s))
+    fwd, bwd, gw = oracle.conv3d_fwd(inp, w, s), oracle.conv3d_bwd(y, w, n, s), oracle.conv3d_wgrad(inp, y, s)
+    a = np.sum(fwd * y)
+    assert abs(a - np.sum(inp * bwd)) <= 1e-12 * max(1.0, abs(a))
+    assert abs(a - np.sum(w * gw)) <= 1e-12 * max(1.0, abs(a))
+    rs = np.random.RandomState(8)
+    for full, fn in ((fwd, lambda p: oracle.conv3d_fwd_at(inp, w, p, s)),
+                     (bwd, lambda p: oracle.conv3d_bwd_at(y, w, n, p, s)),
+                     (gw, lambda p: oracle.conv3d_wgrad_at(inp, y, p, s))):
+        pos = rs.randint(0, full.size, size=40)
+        assert np.array_equal(fn(pos), full.ravel()[pos])
+
+
+def test_sparse_delta_kernel_shifts_by_the_sparsity():
+    n, k, s = (9, 8, 7), (3, 2, 2), (2, 3, 2)
+    inp = rnd(63, 0, (1,) + n)
+    tap = (0, 1, 0)
+    w = np.zeros((1, 1) + k)
+    w[(0, 0) + tap] = 1.0
+    out = oracle.conv3d_fwd(inp, w, s)
+    o = out.shape[1:]
+    sh = tuple(s[d] * (k[d] - 1 - tap[d]) for d in range(3))     # out[x] = in[x + s (k-1-tap)]
+    assert np.array_equal(out[0], inp[0, sh[0]:sh[0] + o[0], sh[1]:sh[1] + o[1], sh[2]:sh[2] + o[2]])
+    with pytest.raises(ValueError):
+        oracle.conv3d_fwd(inp, np.zeros((1, 1, 3, 2, 2)), (5, 1, 1))     # span 11 > 9
+
+
 # ---------------------------------------------------------------- Fourier identities
 @pytest.mark.parametrize("pad", [(0, 0, 0), (1, 0, 3), (2, 5, 1)])
 @pytest.mark.parametrize("f,fo,n,k", SHAPES[:4])
