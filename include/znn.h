@@ -41,7 +41,7 @@ extern "C" {
 
 #define ZNN_OK             0
 #define ZNN_EINVAL       (-1)  /* null pointer, extent < 1, kernel or window larger than image */
-#define ZNN_EUNSUPPORTED (-2)  /* sparsity != 1, index range beyond int32, FFT extent too large */
+#define ZNN_EUNSUPPORTED (-2)  /* index range beyond int32, FFT extent too large               */
 #define ZNN_EWORKSPACE   (-3)  /* workspace (or spectra buffer) missing, misaligned or too small  */
 #define ZNN_EHIP         (-4)  /* the HIP runtime reported an error; see znn_last_error()          */
 
@@ -55,8 +55,10 @@ typedef struct {
     int32_t  fan_in;      /* f  >= 1 : number of input nodes                                */
     int32_t  fan_out;     /* f' >= 1 : number of output nodes                               */
     znn_vec3 image;       /* n  : extents of every input image                              */
-    znn_vec3 kernel;      /* k  : extents of every kernel, 1 <= k_d <= n_d                  */
-    znn_vec3 sparsity;    /* s  : must be {1,1,1} (sparse convolution is not built yet)     */
+    znn_vec3 kernel;      /* k  : extents of every kernel, k_d >= 1, s_d (k_d - 1) + 1 <= n_d */
+    znn_vec3 sparsity;    /* s  : s_d >= 1; neighbouring taps are s_d voxels apart (Section 2,
+                             sparse convolution), outputs have extents n - s (k - 1);
+                             {1,1,1} is the ordinary dense convolution                      */
     int32_t  mode;        /* znn_mode; ZNN_AUTO takes the autotuner's cached choice for this
                              descriptor, or a cost-model guess when nothing is cached       */
 } znn_conv_desc;
@@ -108,7 +110,9 @@ int  znn_conv3d_wgrad_memo(znn_plan* plan, float* gw, void* ws, size_t ws_bytes,
 /*
  * Forward pass (Section 2, "Convolution", and the node sum of the computation
  * graph): out[j] = sum_i valid_conv(in[i], w[j][i]), a true convolution (kernel
- * index runs against the image index), output extents n' = n - k + 1.
+ * index runs against the image index), output extents n' = n - s (k - 1):
+ *   out[j][x] = sum_i sum_a w[j][i][a] in[i][x + s (k - 1 - a)]   (per axis)
+ * With sparsity s > 1 only every s-th voxel of the window enters the sum.
  *   in  [f][n]   w [f'][f][k]   ->   out [f'][n']
  */
 int  znn_conv3d_fwd(znn_plan* plan, const float* in, const float* w, float* out,

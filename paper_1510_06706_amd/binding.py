@@ -142,7 +142,8 @@ class Plan:
         self.desc = make_desc(fan_in, fan_out, image, kernel, mode, sparsity)
         self.f, self.fo = int(fan_in), int(fan_out)
         self.n, self.k = tuple(int(v) for v in image), tuple(int(v) for v in kernel)
-        self.o = tuple(n - k + 1 for n, k in zip(self.n, self.k))
+        self.s = tuple(int(v) for v in sparsity)
+        self.o = tuple(n - s * (k - 1) for n, k, s in zip(self.n, self.k, self.s))
         self._h = ctypes.c_void_p(0)
         self._ws = None
         self._spectra = None

@@ -84,13 +84,14 @@ int next_fft_extent(int n)
 }
 
 // ---------------------------------------------------------------- autotune cache
-using DescKey = std::tuple<int, int, int, int, int, int, int, int>;
+using DescKey = std::tuple<int, int, int, int, int, int, int, int, int, int, int>;
 static std::mutex g_tune_mu;
 static std::map<DescKey, int> g_tune;
 
 static DescKey key_of(const znn_conv_desc& d)
 {
-    return DescKey(d.fan_in, d.fan_out, d.image.z, d.image.y, d.image.x, d.kernel.z, d.kernel.y, d.kernel.x);
+    return DescKey(d.fan_in, d.fan_out, d.image.z, d.image.y, d.image.x, d.kernel.z, d.kernel.y, d.kernel.x,
+                   d.sparsity.z, d.sparsity.y, d.sparsity.x);
 }
 
 // Work model of Table 2 turned into a time guess with rates measured on MI355X: the direct
@@ -118,17 +119,18 @@ static int validate_desc(const znn_conv_desc* d, Geom* g)
     const int sp[3] = {d->sparsity.z, d->sparsity.y, d->sparsity.x};
     for (int a = 0; a < 3; ++a) {
         if (n[a] < 1 || k[a] < 1) return fail(ZNN_EINVAL, "image and kernel extents must be >= 1");
-        if (k[a] > n[a])
-            return fail(ZNN_EINVAL, "kernel extent %d exceeds image extent %d on axis %d", k[a], n[a], a);
+        if (sp[a] < 1) return fail(ZNN_EINVAL, "sparsity must be >= 1");
+        if ((long)sp[a] * (k[a] - 1) + 1 > n[a])
+            return fail(ZNN_EINVAL, "kernel extent %d (sparsity %d) exceeds image extent %d on axis %d",
+                        k[a], sp[a], n[a], a);
     }
-    for (int a = 0; a < 3; ++a)
-        if (sp[a] != 1) return fail(ZNN_EUNSUPPORTED, "sparse convolution (sparsity != 1) is not supported");
     if (d->mode != ZNN_DIRECT && d->mode != ZNN_FFT && d->mode != ZNN_AUTO)
         return fail(ZNN_EINVAL, "unknown mode %d", d->mode);
     g->f = d->fan_in; g->fo = d->fan_out;
     g->nz = n[0]; g->ny = n[1]; g->nx = n[2];
     g->kz = k[0]; g->ky = k[1]; g->kx = k[2];
-    g->oz = n[0] - k[0] + 1; g->oy = n[1] - k[1] + 1; g->ox = n[2] - k[2] + 1;
+    g->spz = sp[0]; g->spy = sp[1]; g->spx = sp[2];
+    g->oz = n[0] - sp[0] * (k[0] - 1); g->oy = n[1] - sp[1] * (k[1] - 1); g->ox = n[2] - sp[2] * (k[2] - 1);
     if ((double)g->nvol() >= 2147483648.0)
         return fail(ZNN_EUNSUPPORTED, "image volume does not fit 32-bit voxel offsets");
     g->Nz = next_fft_extent(n[0]); g->Ny = next_fft_extent(n[1]); g->Nx = next_fft_extent(n[2]);

@@ -5,7 +5,7 @@
 
 namespace znn {
 
-// Forward pass (Section 2): out[j][p] = sum_i sum_a w[j][i][a] * in[i][p + k-1-a].
+// Forward pass (Section 2): out[j][p] = sum_i sum_a w[j][i][a] * in[i][p + s(k-1-a)].
 __global__ void __launch_bounds__(256)
 k_direct_fwd_generic(Geom g, const float* __restrict__ in, const float* __restrict__ w,
                      float* __restrict__ out)
@@ -24,15 +24,16 @@ k_direct_fwd_generic(Geom g, const float* __restrict__ in, const float* __restri
         const float* ker = w + ((long)j * g.f + i) * kvol;
         for (int a = 0; a < g.kz; ++a)
             for (int b = 0; b < g.ky; ++b) {
-                const float* row = img + ((long)(z + g.kz - 1 - a) * g.ny + (y + g.ky - 1 - b)) * g.nx + x + g.kx - 1;
+                const float* row = img + ((long)(z + g.spz * (g.kz - 1 - a)) * g.ny + (y + g.spy * (g.ky - 1 - b))) * g.nx +
+                                   x + g.spx * (g.kx - 1);
                 const float* kr = ker + ((long)a * g.ky + b) * g.kx;
-                for (int c = 0; c < g.kx; ++c) acc = fmaf(kr[c], row[-c], acc);
+                for (int c = 0; c < g.kx; ++c) acc = fmaf(kr[c], row[-c * g.spx], acc);
             }
     }
     out[(long)j * ovol + p] = acc;
 }
 
-// Backward pass (Section 3.1): gin[i][q] = sum_j sum_a w[j][i][a] * gout[j][q - (k-1) + a].
+// Backward pass (Section 3.1): gin[i][q] = sum_j sum_a w[j][i][a] * gout[j][q - s(k-1-a)].
 __global__ void __launch_bounds__(256)
 k_direct_bwd_generic(Geom g, const float* __restrict__ gout, const float* __restrict__ w,
                      float* __restrict__ gin)
@@ -50,15 +51,15 @@ k_direct_bwd_generic(Geom g, const float* __restrict__ gout, const float* __rest
         const float* gimg = gout + j * ovol;
         const float* ker = w + ((long)j * g.f + i) * kvol;
         for (int a = 0; a < g.kz; ++a) {
-            const int gz = z - (g.kz - 1) + a;
+            const int gz = z - g.spz * (g.kz - 1 - a);
             if (gz < 0 || gz >= g.oz) continue;
             for (int b = 0; b < g.ky; ++b) {
-                const int gy = y - (g.ky - 1) + b;
+                const int gy = y - g.spy * (g.ky - 1 - b);
                 if (gy < 0 || gy >= g.oy) continue;
                 const float* kr = ker + ((long)a * g.ky + b) * g.kx;
                 const float* row = gimg + ((long)gz * g.oy + gy) * g.ox;
                 for (int c = 0; c < g.kx; ++c) {
-                    const int gx = x - (g.kx - 1) + c;
+                    const int gx = x - g.spx * (g.kx - 1 - c);
                     if (gx >= 0 && gx < g.ox) acc = fmaf(kr[c], row[gx], acc);
                 }
             }
@@ -67,7 +68,7 @@ k_direct_bwd_generic(Geom g, const float* __restrict__ gout, const float* __rest
     gin[(long)i * nvol + q] = acc;
 }
 
-// Kernel gradient (Section 3.2): gw[j][i][a] = sum_p gout[j][p] * in[i][p + k-1-a].
+// Kernel gradient (Section 3.2): gw[j][i][a] = sum_p gout[j][p] * in[i][p + s(k-1-a)].
 // One block per (edge, tap); fixed-shape tree reduction, so the result does not
 // depend on timing.
 __global__ void __launch_bounds__(256)
@@ -82,7 +83,7 @@ k_direct_wgrad_generic(Geom g, const float* __restrict__ in, const float* __rest
     const int c = tap % g.kx, b = (tap / g.kx) % g.ky, a = tap / (g.kx * g.ky);
     const float* img = in + i * nvol;
     const float* gimg = gout + j * ovol;
-    const long shift = ((long)(g.kz - 1 - a) * g.ny + (g.ky - 1 - b)) * g.nx + (g.kx - 1 - c);
+    const long shift = ((long)g.spz * (g.kz - 1 - a) * g.ny + g.spy * (g.ky - 1 - b)) * g.nx + g.spx * (g.kx - 1 - c);
     float acc = 0.f;
     for (long p = threadIdx.x; p < ovol; p += 256) {
         const int x = (int)(p % g.ox);

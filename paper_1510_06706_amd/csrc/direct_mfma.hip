@@ -35,6 +35,7 @@ struct ConvTile {
     int pz, py, px;     // zeros virtually in front of the source on each axis
     int dz, dy, dx;     // output extents
     int kz, ky, kx;
+    int spz, spy, spx;  // sparsity: taps are this many voxels apart
     int Tz, Ty, Tx;     // output voxels per workgroup
     int HZ, HY, HX, MS; // halo box and LDS stride between the four staged maps
     int cz, cy, cx;     // workgroups per axis
@@ -94,7 +95,7 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma(ConvTile P)
 
     for (int t = threadIdx.x; t < taps; t += 256) {
         const int c = t % P.kx, bb = (t / P.kx) % P.ky, a = t / (P.kx * P.ky);
-        tapoff[t] = ((P.kz - 1 - a) * P.HY + (P.ky - 1 - bb)) * P.HX + (P.kx - 1 - c);
+        tapoff[t] = ((P.kz - 1 - a) * P.spz * P.HY + (P.ky - 1 - bb) * P.spy) * P.HX + (P.kx - 1 - c) * P.spx;
     }
 
     int voff[NV];
@@ -227,7 +228,7 @@ constexpr size_t kConvLdsMax = 64 * 1024;
 
 // Picks the tile box and the per-wave tile count so that the launch fills the
 // 256 compute units in as few, as full rounds as possible.
-TileChoice choose_tile(int fM, int dz, int dy, int dx, int kz, int ky, int kx)
+TileChoice choose_tile(int fM, int dz, int dy, int dx, int kz, int ky, int kx, int spz, int spy, int spx)
 {
     TileChoice best = {};
     best.ok = false;
@@ -255,7 +256,7 @@ TileChoice choose_tile(int fM, int dz, int dy, int dx, int kz, int ky, int kx)
                     if (Tx != pin[3] || Ty != pin[2] || pin[1] * Ty * Tx > cap) continue;
                     Tz = pin[1];
                 }
-                const int HZ = Tz + kz - 1, HY = Ty + ky - 1, HX = Tx + kx - 1;
+                const int HZ = Tz + spz * (kz - 1), HY = Ty + spy * (ky - 1), HX = Tx + spx * (kx - 1);
                 long hvol = (long)HZ * HY * HX;
                 long MS = hvol;
                 while (MS % 32 != 16) ++MS;
@@ -293,15 +294,15 @@ size_t packed_bytes(const TileChoice& c, int fK, int taps)
 // The tiled path takes every shape whose halo box fits LDS; otherwise the caller falls back.
 bool mfma_conv_supported(const Geom& g, bool backward)
 {
-    const TileChoice c = backward ? choose_tile(g.f, g.nz, g.ny, g.nx, g.kz, g.ky, g.kx)
-                                  : choose_tile(g.fo, g.oz, g.oy, g.ox, g.kz, g.ky, g.kx);
+    const TileChoice c = backward ? choose_tile(g.f, g.nz, g.ny, g.nx, g.kz, g.ky, g.kx, g.spz, g.spy, g.spx)
+                                  : choose_tile(g.fo, g.oz, g.oy, g.ox, g.kz, g.ky, g.kx, g.spz, g.spy, g.spx);
     return c.ok;
 }
 
 size_t mfma_conv_workspace(const Geom& g, bool backward)
 {
-    const TileChoice c = backward ? choose_tile(g.f, g.nz, g.ny, g.nx, g.kz, g.ky, g.kx)
-                                  : choose_tile(g.fo, g.oz, g.oy, g.ox, g.kz, g.ky, g.kx);
+    const TileChoice c = backward ? choose_tile(g.f, g.nz, g.ny, g.nx, g.kz, g.ky, g.kx, g.spz, g.spy, g.spx)
+                                  : choose_tile(g.fo, g.oz, g.oy, g.ox, g.kz, g.ky, g.kx, g.spz, g.spy, g.spx);
     if (!c.ok) return 0;
     return packed_bytes(c, backward ? g.fo : g.f, (int)g.kvol());
 }
@@ -312,6 +313,7 @@ int mfma_conv(const Geom& g, bool backward, const float* src, const float* w, fl
     ConvTile P = {};
     P.src = src; P.dst = dst;
     P.kz = g.kz; P.ky = g.ky; P.kx = g.kx;
+    P.spz = g.spz; P.spy = g.spy; P.spx = g.spx;
     if (!backward) {
         P.fK = g.f; P.fM = g.fo;
         P.sz = g.nz; P.sy = g.ny; P.sx = g.nx;
@@ -320,10 +322,10 @@ int mfma_conv(const Geom& g, bool backward, const float* src, const float* w, fl
     } else {
         P.fK = g.fo; P.fM = g.f;
         P.sz = g.oz; P.sy = g.oy; P.sx = g.ox;
-        P.pz = g.kz - 1; P.py = g.ky - 1; P.px = g.kx - 1;
+        P.pz = g.spz * (g.kz - 1); P.py = g.spy * (g.ky - 1); P.px = g.spx * (g.kx - 1);
         P.dz = g.nz; P.dy = g.ny; P.dx = g.nx;
     }
-    const TileChoice c = choose_tile(P.fM, P.dz, P.dy, P.dx, g.kz, g.ky, g.kx);
+    const TileChoice c = choose_tile(P.fM, P.dz, P.dy, P.dx, g.kz, g.ky, g.kx, g.spz, g.spy, g.spx);
     if (!c.ok) return fail(ZNN_EUNSUPPORTED, "no tile configuration fits this shape");
     P.Tz = c.Tz; P.Ty = c.Ty; P.Tx = c.Tx;
     P.HZ = c.HZ; P.HY = c.HY; P.HX = c.HX; P.MS = c.MS;

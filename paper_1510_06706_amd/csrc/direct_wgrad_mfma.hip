@@ -41,6 +41,7 @@ struct WgradTile {
     int nz, ny, nx;
     int oz, oy, ox;
     int kz, ky, kx;
+    int spz, spy, spx;  // sparsity: taps are this many voxels apart
     int TX, XT, R;      // x-segment width (multiple of 4), segments per row, rows per tile
     int GS, IS, TXH;    // LDS strides: gout map, in map, in row
     int Mpad, Npad;     // padded partial-matrix extents
@@ -87,7 +88,7 @@ __global__ void __launch_bounds__(256) k_wgrad_mfma(WgradTile P)
         int o = 0;
         if (n < n1) {
             const int c = n / P.f, i = n % P.f;
-            o = (i - imin) * P.IS + (cmax - c);
+            o = (i - imin) * P.IS + (cmax - c) * P.spx;
         }
         boff[nt] = itoff + o;
     }
@@ -116,7 +117,7 @@ __global__ void __launch_bounds__(256) k_wgrad_mfma(WgradTile P)
     auto issue_tile = [&](int tile, float* buf) {
         const int xt = tile % P.XT, rt = tile / P.XT;
         const int rho0 = rt * P.R, xs0 = xt * P.TX;
-        const int xin0 = xs0 + (P.kx - 1 - cmax);
+        const int xin0 = xs0 + (P.kx - 1 - cmax) * P.spx;
         if (P.vec4) {
             for (int k = 0; k * 256 < RT; ++k) {
                 const int e = k * 256 + lane * 4;
@@ -138,7 +139,7 @@ __global__ void __launch_bounds__(256) k_wgrad_mfma(WgradTile P)
                 const int rho = rho0 + r, ix = xin0 + x;
                 const bool ok = rho < rows && ix < P.nx;
                 const int z = (int)fdiv((unsigned)rho, P.dOY), y = rho - z * P.oy;
-                const long off = (long)(z + P.kz - 1 - a) * iplane + (long)(y + P.ky - 1 - b) * P.nx + ix;
+                const long off = (long)(z + (P.kz - 1 - a) * P.spz) * iplane + (long)(y + (P.ky - 1 - b) * P.spy) * P.nx + ix;
                 if (e < RTH) {
                     for (int m = wave; m < nmaps; m += 4) {
                         const float* src = ok ? P.in + (imin + m) * ivol + off : zero4;
@@ -168,7 +169,7 @@ __global__ void __launch_bounds__(256) k_wgrad_mfma(WgradTile P)
             const int rho = rho0 + r, ix = xin0 + x;
             const bool ok = rho < rows && ix < P.nx;
             const int z = (int)fdiv((unsigned)rho, P.dOY), y = rho - z * P.oy;
-            const long off = (long)(z + P.kz - 1 - a) * iplane + (long)(y + P.ky - 1 - b) * P.nx + ix;
+            const long off = (long)(z + (P.kz - 1 - a) * P.spz) * iplane + (long)(y + (P.ky - 1 - b) * P.spy) * P.nx + ix;
             if (e < RTH) {
                 for (int m = wave; m < nmaps; m += 4) {
                     const float* src = ok ? P.in + (imin + m) * ivol + off : zero;
@@ -394,7 +395,7 @@ WgradChoice choose_wgrad(const Geom& g)
         const int seg = (g.ox + XT - 1) / XT;
         int TX = (seg + 3) & ~3;
         if (TX % 8 != 0 && rows < 2) TX += 4;          // a single row must hold whole 8-voxel steps
-        const int TXH = (TX + cspan + 3) & ~3;
+        const int TXH = (TX + cspan * g.spx + 3) & ~3;
         int bestR = 0;
         for (int R = 1; R <= 32 && R <= rows; ++R) {
             if ((R * TX) % 8 != 0) continue;    // the MFMA loop walks 8 voxels per step
@@ -445,6 +446,7 @@ int mfma_wgrad(const Geom& g, const float* in, const float* gout, float* gw, voi
     P.nz = g.nz; P.ny = g.ny; P.nx = g.nx;
     P.oz = g.oz; P.oy = g.oy; P.ox = g.ox;
     P.kz = g.kz; P.ky = g.ky; P.kx = g.kx;
+    P.spz = g.spz; P.spy = g.spy; P.spx = g.spx;
     P.TX = c.TX; P.XT = c.XT; P.R = c.R;
     P.GS = c.GS; P.IS = c.IS; P.TXH = c.TXH;
     P.Mpad = c.Mpad; P.Npad = c.Npad;

@@ -149,6 +149,7 @@ struct R2CParams {
     int sz, sy, sx;
     int Nz, Ny, Nx, Nxh;
     int oz, oy, ox;
+    int tz, ty, tx;     // spacing of the source samples inside the volume (1 except for sparse kernels)
     int W, Wp;
     Radices rad;
 };
@@ -168,7 +169,7 @@ __global__ void __launch_bounds__(kThreads) k_fft_r2c_x(R2CParams P)
     float* af = reinterpret_cast<float*>(a);
     for (int t = threadIdx.x; t < nrows * P.sx; t += kThreads) {
         const int r = t / P.sx, x = t % P.sx;
-        af[2 * ((x + P.ox) * Wp + (r >> 1)) + (r & 1)] = P.src[(row0 + r) * P.sx + x];
+        af[2 * ((x * P.tx + P.ox) * Wp + (r >> 1)) + (r & 1)] = P.src[(row0 + r) * P.sx + x];
     }
     __syncthreads();
     const int npen = (nrows + 1) >> 1;
@@ -185,7 +186,7 @@ __global__ void __launch_bounds__(kThreads) k_fft_r2c_x(R2CParams P)
         float2 v;
         if ((r & 1) == 0) v = make_float2(0.5f * (z1.x + z2.x), 0.5f * (z1.y - z2.y));
         else              v = make_float2(0.5f * (z1.y + z2.y), 0.5f * (z2.x - z1.x));
-        P.dst[((map * P.Nz + z + P.oz) * P.Ny + (y + P.oy)) * P.Nxh + k] = v;
+        P.dst[((map * P.Nz + z * P.tz + P.oz) * P.Ny + (y * P.ty + P.oy)) * P.Nxh + k] = v;
     }
 }
 
@@ -199,6 +200,7 @@ struct C2RParams {
     int dz, dy, dx;
     int Nz, Ny, Nx, Nxh;
     float scale;
+    int tx;             // spacing of the wanted samples along x (1 except for sparse kernel gradients)
     int W, Wp;
     Radices rad;
 };
@@ -245,7 +247,7 @@ __global__ void __launch_bounds__(kThreads) k_fft_c2r_x(C2RParams P)
     const float* rf = reinterpret_cast<const float*>(res);
     for (int t = threadIdx.x; t < nrows * P.dx; t += kThreads) {
         const int r = t / P.dx, x = t % P.dx;
-        P.dst[(row0 + r) * P.dx + x] = P.scale * rf[2 * ((x + P.cx) * Wp + (r >> 1)) + (r & 1)];
+        P.dst[(row0 + r) * P.dx + x] = P.scale * rf[2 * ((x * P.tx + P.cx) * Wp + (r >> 1)) + (r & 1)];
     }
 }
 
@@ -259,6 +261,7 @@ __global__ void __launch_bounds__(kThreads) k_fft_c2r_x(C2RParams P)
 struct AxisParams {
     const float2* in; const float2* in2; float2* out;
     int N, i0, ni, o0, no;
+    int istep, ostep;   // element e of the input sits at i0 + e*istep; output e is element o0 + e*ostep
     long in_stride, out_stride;
     int L, W, Wp, chunks;
     int Oa, Ob, Oc;
@@ -285,14 +288,14 @@ __global__ void __launch_bounds__(kThreads) k_fft_axis(AxisParams P)
     const int oa = (int)(o / P.Ob);
     const int p0 = chunk * P.W;
     const int w = min(P.W, P.L - p0);
-    if (P.ni < N) {
+    if (P.ni < N || P.istep > 1) {
         for (int t = threadIdx.x; t < N * Wp; t += kThreads) a[t] = make_float2(0.f, 0.f);
         __syncthreads();
     }
     const float2* in = P.in + (oa * P.in_sa + ob * P.in_sb + oc * P.in_sc) + p0;
     const float2* in2 = PRODUCT ? P.in2 + (oa * P.in2_sa + ob * P.in2_sb + oc * P.in2_sc) + p0 : nullptr;
     for (int t = threadIdx.x; t < P.ni * w; t += kThreads) {
-        const int e = t / w + P.i0, p = t % w;
+        const int e = (t / w) * P.istep + P.i0, p = t % w;
         float2 v = in[e * P.in_stride + p];
         if (PRODUCT) {
             const float2 c = in2[e * P.in_stride + p];
@@ -304,8 +307,8 @@ __global__ void __launch_bounds__(kThreads) k_fft_axis(AxisParams P)
     const float2* res = lds_fft<DIR>(a, b, tw, N, w, Wp, P.rad);
     float2* out = P.out + (oa * P.out_sa + ob * P.out_sb + oc * P.out_sc) + p0;
     for (int t = threadIdx.x; t < P.no * w; t += kThreads) {
-        const int e = t / w + P.o0, p = t % w;
-        out[e * P.out_stride + p] = res[e * Wp + p];
+        const int q = t / w, p = t % w;
+        out[(q + P.o0) * P.out_stride + p] = res[(q * P.ostep + P.o0) * Wp + p];
     }
 }
 
@@ -378,7 +381,7 @@ constexpr int kMaxPruned = 16;
 
 template <int KZ>
 __global__ void __launch_bounds__(kThreads)
-k_zdft_expand(float2* __restrict__ spec, int N, int oz, long plane, long vol, int cpm)
+k_zdft_expand(float2* __restrict__ spec, int N, int oz, int tz, long plane, long vol, int cpm)
 {
     __shared__ float2 tw[kMaxFftExtent];
     make_twiddles(tw, N, -1);
@@ -391,9 +394,9 @@ k_zdft_expand(float2* __restrict__ spec, int N, int oz, long plane, long vol, in
     int idx[KZ], step[KZ];
 #pragma unroll
     for (int a = 0; a < KZ; ++a) {
-        v[a] = base[(long)(oz + a) * plane];
+        v[a] = base[(long)(oz + a * tz) * plane];
         idx[a] = 0;
-        step[a] = (oz + a) % N;
+        step[a] = (oz + a * tz) % N;
     }
     for (int wz = 0; wz < N; ++wz) {
         float2 o = make_float2(0.f, 0.f);
@@ -417,7 +420,7 @@ k_zdft_expand(float2* __restrict__ spec, int N, int oz, long plane, long vol, in
 template <int KZ, int JB, int IB>
 __global__ void __launch_bounds__(kThreads)
 k_wgrad_zdft(const float2* __restrict__ G, const float2* __restrict__ I, float2* __restrict__ T1,
-             int f, int fo, int N, long plane, long vol, int iblocks)
+             int f, int fo, int N, int tz, long plane, long vol, int iblocks)
 {
     __shared__ float2 tw[kMaxFftExtent];
     make_twiddles(tw, N, +1);
@@ -451,7 +454,7 @@ k_wgrad_zdft(const float2* __restrict__ G, const float2* __restrict__ I, float2*
 #pragma unroll
         for (int a = 0; a < KZ; ++a) {
             t[a] = tw[idx[a]];
-            idx[a] += a;
+            idx[a] += a * tz;               // lag a*tz < N
             if (idx[a] >= N) idx[a] -= N;
         }
 #pragma unroll
@@ -481,41 +484,41 @@ k_wgrad_zdft(const float2* __restrict__ G, const float2* __restrict__ I, float2*
 }
 
 template <int KZ>
-int launch_expand_kz(float2* spec, long maps, int N, int oz, long plane, long vol, hipStream_t s)
+int launch_expand_kz(float2* spec, long maps, int N, int oz, int tz, long plane, long vol, hipStream_t s)
 {
     const int cpm = (int)((plane + kThreads - 1) / kThreads);
     const long blocks = maps * cpm;
     if (blocks >= 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many pencils for one launch");
     ZNN_LAUNCH("pruned z DFT of kernels", s, k_zdft_expand<KZ>, dim3((unsigned)blocks), dim3(kThreads), 0,
-               spec, N, oz, plane, vol, cpm);
+               spec, N, oz, tz, plane, vol, cpm);
     return check_launch("pruned z DFT of kernels");
 }
 
-int launch_expand(int kz, float2* spec, long maps, int N, int oz, long plane, long vol, hipStream_t s)
+int launch_expand(int kz, float2* spec, long maps, int N, int oz, int tz, long plane, long vol, hipStream_t s)
 {
     switch (kz) {
-        case 1: return launch_expand_kz<1>(spec, maps, N, oz, plane, vol, s);
-        case 2: return launch_expand_kz<2>(spec, maps, N, oz, plane, vol, s);
-        case 3: return launch_expand_kz<3>(spec, maps, N, oz, plane, vol, s);
-        case 4: return launch_expand_kz<4>(spec, maps, N, oz, plane, vol, s);
-        case 5: return launch_expand_kz<5>(spec, maps, N, oz, plane, vol, s);
-        case 6: return launch_expand_kz<6>(spec, maps, N, oz, plane, vol, s);
-        case 7: return launch_expand_kz<7>(spec, maps, N, oz, plane, vol, s);
-        case 8: return launch_expand_kz<8>(spec, maps, N, oz, plane, vol, s);
-        case 9: return launch_expand_kz<9>(spec, maps, N, oz, plane, vol, s);
-        case 10: return launch_expand_kz<10>(spec, maps, N, oz, plane, vol, s);
-        case 11: return launch_expand_kz<11>(spec, maps, N, oz, plane, vol, s);
-        case 12: return launch_expand_kz<12>(spec, maps, N, oz, plane, vol, s);
-        case 13: return launch_expand_kz<13>(spec, maps, N, oz, plane, vol, s);
-        case 14: return launch_expand_kz<14>(spec, maps, N, oz, plane, vol, s);
-        case 15: return launch_expand_kz<15>(spec, maps, N, oz, plane, vol, s);
-        default: return launch_expand_kz<16>(spec, maps, N, oz, plane, vol, s);
+        case 1: return launch_expand_kz<1>(spec, maps, N, oz, tz, plane, vol, s);
+        case 2: return launch_expand_kz<2>(spec, maps, N, oz, tz, plane, vol, s);
+        case 3: return launch_expand_kz<3>(spec, maps, N, oz, tz, plane, vol, s);
+        case 4: return launch_expand_kz<4>(spec, maps, N, oz, tz, plane, vol, s);
+        case 5: return launch_expand_kz<5>(spec, maps, N, oz, tz, plane, vol, s);
+        case 6: return launch_expand_kz<6>(spec, maps, N, oz, tz, plane, vol, s);
+        case 7: return launch_expand_kz<7>(spec, maps, N, oz, tz, plane, vol, s);
+        case 8: return launch_expand_kz<8>(spec, maps, N, oz, tz, plane, vol, s);
+        case 9: return launch_expand_kz<9>(spec, maps, N, oz, tz, plane, vol, s);
+        case 10: return launch_expand_kz<10>(spec, maps, N, oz, tz, plane, vol, s);
+        case 11: return launch_expand_kz<11>(spec, maps, N, oz, tz, plane, vol, s);
+        case 12: return launch_expand_kz<12>(spec, maps, N, oz, tz, plane, vol, s);
+        case 13: return launch_expand_kz<13>(spec, maps, N, oz, tz, plane, vol, s);
+        case 14: return launch_expand_kz<14>(spec, maps, N, oz, tz, plane, vol, s);
+        case 15: return launch_expand_kz<15>(spec, maps, N, oz, tz, plane, vol, s);
+        default: return launch_expand_kz<16>(spec, maps, N, oz, tz, plane, vol, s);
     }
 }
 
 // Pruned inverse DFT of the spectral products along the axis with element stride `plane`.
 template <int KZ>
-int launch_wgrad_dft_k(int f, int fo, int N, long plane, long vol, const float2* G, const float2* I, float2* T,
+int launch_wgrad_dft_k(int f, int fo, int N, int tz, long plane, long vol, const float2* G, const float2* I, float2* T,
                        hipStream_t s)
 {
     constexpr int JB = 2, IB = KZ <= 8 ? 4 : 2;
@@ -525,38 +528,39 @@ int launch_wgrad_dft_k(int f, int fo, int N, long plane, long vol, const float2*
         return fail(ZNN_EUNSUPPORTED, "too many edges or pencils for one launch");
     const dim3 grid((unsigned)(jblocks * iblocks), (unsigned)pchunks);
     ZNN_LAUNCH("pruned DFT of spectral products", s, (k_wgrad_zdft<KZ, JB, IB>), grid, dim3(kThreads), 0,
-               G, I, T, f, fo, N, plane, vol, iblocks);
+               G, I, T, f, fo, N, tz, plane, vol, iblocks);
     return check_launch("pruned DFT of spectral products");
 }
 
-int launch_wgrad_dft(int k, int f, int fo, int N, long plane, long vol, const float2* G, const float2* I, float2* T,
+int launch_wgrad_dft(int k, int f, int fo, int N, int tz, long plane, long vol, const float2* G, const float2* I, float2* T,
                      hipStream_t s)
 {
     switch (k) {
-        case 1: return launch_wgrad_dft_k<1>(f, fo, N, plane, vol, G, I, T, s);
-        case 2: return launch_wgrad_dft_k<2>(f, fo, N, plane, vol, G, I, T, s);
-        case 3: return launch_wgrad_dft_k<3>(f, fo, N, plane, vol, G, I, T, s);
-        case 4: return launch_wgrad_dft_k<4>(f, fo, N, plane, vol, G, I, T, s);
-        case 5: return launch_wgrad_dft_k<5>(f, fo, N, plane, vol, G, I, T, s);
-        case 6: return launch_wgrad_dft_k<6>(f, fo, N, plane, vol, G, I, T, s);
-        case 7: return launch_wgrad_dft_k<7>(f, fo, N, plane, vol, G, I, T, s);
-        case 8: return launch_wgrad_dft_k<8>(f, fo, N, plane, vol, G, I, T, s);
-        case 9: return launch_wgrad_dft_k<9>(f, fo, N, plane, vol, G, I, T, s);
-        case 10: return launch_wgrad_dft_k<10>(f, fo, N, plane, vol, G, I, T, s);
-        case 11: return launch_wgrad_dft_k<11>(f, fo, N, plane, vol, G, I, T, s);
-        case 12: return launch_wgrad_dft_k<12>(f, fo, N, plane, vol, G, I, T, s);
-        case 13: return launch_wgrad_dft_k<13>(f, fo, N, plane, vol, G, I, T, s);
-        case 14: return launch_wgrad_dft_k<14>(f, fo, N, plane, vol, G, I, T, s);
-        case 15: return launch_wgrad_dft_k<15>(f, fo, N, plane, vol, G, I, T, s);
-        default: return launch_wgrad_dft_k<16>(f, fo, N, plane, vol, G, I, T, s);
+        case 1: return launch_wgrad_dft_k<1>(f, fo, N, tz, plane, vol, G, I, T, s);
+        case 2: return launch_wgrad_dft_k<2>(f, fo, N, tz, plane, vol, G, I, T, s);
+        case 3: return launch_wgrad_dft_k<3>(f, fo, N, tz, plane, vol, G, I, T, s);
+        case 4: return launch_wgrad_dft_k<4>(f, fo, N, tz, plane, vol, G, I, T, s);
+        case 5: return launch_wgrad_dft_k<5>(f, fo, N, tz, plane, vol, G, I, T, s);
+        case 6: return launch_wgrad_dft_k<6>(f, fo, N, tz, plane, vol, G, I, T, s);
+        case 7: return launch_wgrad_dft_k<7>(f, fo, N, tz, plane, vol, G, I, T, s);
+        case 8: return launch_wgrad_dft_k<8>(f, fo, N, tz, plane, vol, G, I, T, s);
+        case 9: return launch_wgrad_dft_k<9>(f, fo, N, tz, plane, vol, G, I, T, s);
+        case 10: return launch_wgrad_dft_k<10>(f, fo, N, tz, plane, vol, G, I, T, s);
+        case 11: return launch_wgrad_dft_k<11>(f, fo, N, tz, plane, vol, G, I, T, s);
+        case 12: return launch_wgrad_dft_k<12>(f, fo, N, tz, plane, vol, G, I, T, s);
+        case 13: return launch_wgrad_dft_k<13>(f, fo, N, tz, plane, vol, G, I, T, s);
+        case 14: return launch_wgrad_dft_k<14>(f, fo, N, tz, plane, vol, G, I, T, s);
+        case 15: return launch_wgrad_dft_k<15>(f, fo, N, tz, plane, vol, G, I, T, s);
+        default: return launch_wgrad_dft_k<16>(f, fo, N, tz, plane, vol, G, I, T, s);
     }
 }
 
 // ---------------------------------------------------------------- launch helpers
 int launch_r2c(const float* src, float2* dst, long maps, int sz, int sy, int sx,
-               int Nz, int Ny, int Nx, int oz, int oy, int ox, hipStream_t s)
+               int Nz, int Ny, int Nx, int oz, int oy, int ox, int tz, int ty, int tx, hipStream_t s)
 {
     R2CParams P;
+    P.tz = tz; P.ty = ty; P.tx = tx;
     P.src = src; P.dst = dst;
     P.rows = maps * sz * sy;
     P.sz = sz; P.sy = sy; P.sx = sx;
@@ -573,9 +577,10 @@ int launch_r2c(const float* src, float2* dst, long maps, int sz, int sy, int sx,
 }
 
 int launch_c2r(const float2* src, float* dst, long maps, int Nz, int Ny, int Nx,
-               int cz, int cy, int cx, int dz, int dy, int dx, float scale, hipStream_t s)
+               int cz, int cy, int cx, int dz, int dy, int dx, int tx, float scale, hipStream_t s)
 {
     C2RParams P;
+    P.tx = tx;
     P.src = src; P.dst = dst;
     P.rows = maps * dz * dy;
     P.cz = cz; P.cy = cy; P.cx = cx;
@@ -595,6 +600,8 @@ int launch_c2r(const float2* src, float* dst, long maps, int Nz, int Ny, int Nx,
 // Fills the chunking fields and launches.  `P` arrives with everything else set.
 int launch_axis(AxisParams P, int dir, hipStream_t s)
 {
+    if (P.istep < 1) P.istep = 1;
+    if (P.ostep < 1) P.ostep = 1;
     if (P.N == 1 && !P.in2 && P.in == P.out && P.in_stride == P.out_stride &&
         P.in_sa == P.out_sa && P.in_sb == P.out_sb && P.in_sc == P.out_sc)
         return ZNN_OK;   // length-1 transform in place: nothing to do
@@ -622,37 +629,41 @@ int launch_axis(AxisParams P, int dir, hipStream_t s)
 }
 
 // Forward 3D transform of `maps` real volumes of extents (sz,sy,sx) embedded at
-// offset (oz,oy,ox) of the (Nz,Ny,Nx) volume.
+// offset (oz,oy,ox) of the (Nz,Ny,Nx) volume.  Neighbouring source samples land
+// (tz,ty,tx) voxels apart: 1 for images, the sparsity for kernels, whose taps are
+// spread out with zeros between them (Section 2, sparse convolution).
 int forward3d(const Geom& g, const float* src, float2* spec, long maps, int sz, int sy, int sx,
-              int oz, int oy, int ox, hipStream_t s)
+              int oz, int oy, int ox, int tz, int ty, int tx, hipStream_t s)
 {
-    int rc = launch_r2c(src, spec, maps, sz, sy, sx, g.Nz, g.Ny, g.Nx, oz, oy, ox, s);
+    int rc = launch_r2c(src, spec, maps, sz, sy, sx, g.Nz, g.Ny, g.Nx, oz, oy, ox, tz, ty, tx, s);
     if (rc != ZNN_OK) return rc;
     const long plane = (long)g.Ny * g.Nxh, vol = g.svol();
     if (maps > 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many maps");
     AxisParams P = {};
-    // y: only the sz planes that hold data, rows [oy, oy+sy) are non-zero
+    // y: only the sz planes that hold data; rows oy + e*ty, e < sy, are non-zero
     P.in = spec + oz * plane; P.in2 = nullptr; P.out = spec + oz * plane;
     P.N = g.Ny; P.i0 = oy; P.ni = sy; P.o0 = 0; P.no = g.Ny;
+    P.istep = ty; P.ostep = 1;
     P.in_stride = P.out_stride = g.Nxh;
     P.L = g.Nxh;
     P.Oa = (int)maps; P.Ob = sz; P.Oc = 1;
-    P.in_sa = P.out_sa = vol; P.in_sb = P.out_sb = plane; P.in_sc = P.out_sc = 0;
+    P.in_sa = P.out_sa = vol; P.in_sb = P.out_sb = plane * tz; P.in_sc = P.out_sc = 0;
     if (g.Ny != 1) {
         // 2D volumes with few non-zero rows (kernels): the y transform is a pruned DFT
-        if (g.Nz == 1 && sy <= kMaxPruned && sy < g.Ny) rc = launch_expand(sy, spec, maps, g.Ny, oy, g.Nxh, vol, s);
+        if (g.Nz == 1 && sy <= kMaxPruned && sy < g.Ny) rc = launch_expand(sy, spec, maps, g.Ny, oy, ty, g.Nxh, vol, s);
         else rc = launch_axis(P, -1, s);
         if (rc != ZNN_OK) return rc;
     }
-    // z: planes [oz, oz+sz) are non-zero
+    // z: planes oz + e*tz, e < sz, are non-zero
     P.in = spec; P.out = spec;
     P.N = g.Nz; P.i0 = oz; P.ni = sz; P.o0 = 0; P.no = g.Nz;
+    P.istep = tz;
     P.in_stride = P.out_stride = plane;
     P.L = (int)plane;
     P.Oa = (int)maps; P.Ob = 1; P.Oc = 1;
     P.in_sb = P.out_sb = 0;
     if (g.Nz == 1) return ZNN_OK;
-    if (sz <= kMaxPruned && sz < g.Nz) return launch_expand(sz, spec, maps, g.Nz, oz, plane, vol, s);
+    if (sz <= kMaxPruned && sz < g.Nz) return launch_expand(sz, spec, maps, g.Nz, oz, tz, plane, vol, s);
     return launch_axis(P, -1, s);
 }
 
@@ -680,7 +691,7 @@ int inverse3d(const Geom& g, float2* spec, float* dst, long maps, int cz, int cy
     P.in_sb = P.out_sb = plane;
     if (g.Ny != 1) { rc = launch_axis(P, +1, s); if (rc != ZNN_OK) return rc; }
     const float scale = (float)(1.0 / ((double)g.Nz * g.Ny * g.Nx));
-    return launch_c2r(spec, dst, maps, g.Nz, g.Ny, g.Nx, cz, cy, cx, dz, dy, dx, scale, s);
+    return launch_c2r(spec, dst, maps, g.Nz, g.Ny, g.Nx, cz, cy, cx, dz, dy, dx, 1, scale, s);
 }
 
 int launch_mac(bool backward, const Geom& g, const float2* What, const float2* a, float2* b, hipStream_t s)
@@ -733,7 +744,7 @@ FftWorkspace fft_workspace(const Geom& g, int pass, bool resident)
 
 int fft_kernel_spectra(const Geom& g, const float* w, float2* What, hipStream_t s)
 {
-    return forward3d(g, w, What, (long)g.f * g.fo, g.kz, g.ky, g.kx, 0, 0, 0, s);
+    return forward3d(g, w, What, (long)g.f * g.fo, g.kz, g.ky, g.kx, 0, 0, 0, g.spz, g.spy, g.spx, s);
 }
 
 int fft_fwd(const Geom& g, const float* in, const float* w, const float2* resident, float* out,
@@ -743,7 +754,7 @@ int fft_fwd(const Geom& g, const float* in, const float* w, const float2* reside
     float2* Ihat = memo_in ? memo_in : (float2*)((char*)ws + L.off_a);
     float2* Ohat = (float2*)((char*)ws + L.off_b);
     const float2* What = resident;
-    int rc = forward3d(g, in, Ihat, g.f, g.nz, g.ny, g.nx, 0, 0, 0, s);
+    int rc = forward3d(g, in, Ihat, g.f, g.nz, g.ny, g.nx, 0, 0, 0, 1, 1, 1, s);
     if (rc != ZNN_OK) return rc;
     if (!What) {
         float2* wbuf = (float2*)((char*)ws + L.off_w);
@@ -753,7 +764,8 @@ int fft_fwd(const Geom& g, const float* in, const float* w, const float2* reside
     }
     rc = launch_mac(false, g, What, Ihat, Ohat, s);
     if (rc != ZNN_OK) return rc;
-    return inverse3d(g, Ohat, out, g.fo, g.kz - 1, g.ky - 1, g.kx - 1, g.oz, g.oy, g.ox, s);
+    return inverse3d(g, Ohat, out, g.fo, g.spz * (g.kz - 1), g.spy * (g.ky - 1), g.spx * (g.kx - 1),
+                     g.oz, g.oy, g.ox, s);
 }
 
 int fft_bwd(const Geom& g, const float* gout, const float* w, const float2* resident, float* gin,
@@ -763,7 +775,8 @@ int fft_bwd(const Geom& g, const float* gout, const float* w, const float2* resi
     float2* Ghat = memo_gout ? memo_gout : (float2*)((char*)ws + L.off_a);
     float2* Ginhat = (float2*)((char*)ws + L.off_b);
     const float2* What = resident;
-    int rc = forward3d(g, gout, Ghat, g.fo, g.oz, g.oy, g.ox, g.kz - 1, g.ky - 1, g.kx - 1, s);
+    int rc = forward3d(g, gout, Ghat, g.fo, g.oz, g.oy, g.ox, g.spz * (g.kz - 1), g.spy * (g.ky - 1), g.spx * (g.kx - 1),
+                       1, 1, 1, s);
     if (rc != ZNN_OK) return rc;
     if (!What) {
         float2* wbuf = (float2*)((char*)ws + L.off_w);
@@ -781,9 +794,10 @@ int fft_wgrad(const Geom& g, const float* in, const float* gout, float* gw, void
     const FftWorkspace L = fft_workspace(g, ZNN_PASS_WGRAD, false);
     float2* Ihat = (float2*)((char*)ws + L.off_a);
     float2* Ghat = (float2*)((char*)ws + L.off_b);
-    int rc = forward3d(g, in, Ihat, g.f, g.nz, g.ny, g.nx, 0, 0, 0, s);
+    int rc = forward3d(g, in, Ihat, g.f, g.nz, g.ny, g.nx, 0, 0, 0, 1, 1, 1, s);
     if (rc != ZNN_OK) return rc;
-    rc = forward3d(g, gout, Ghat, g.fo, g.oz, g.oy, g.ox, g.kz - 1, g.ky - 1, g.kx - 1, s);
+    rc = forward3d(g, gout, Ghat, g.fo, g.oz, g.oy, g.ox, g.spz * (g.kz - 1), g.spy * (g.ky - 1), g.spx * (g.kx - 1),
+                       1, 1, 1, s);
     if (rc != ZNN_OK) return rc;
     return fft_wgrad_from_spectra(g, Ihat, Ghat, gw, ws, s);
 }
@@ -800,26 +814,28 @@ int fft_wgrad_from_spectra(const Geom& g, const float2* Ihat, const float2* Ghat
     const long plane = (long)g.Ny * g.Nxh, vol = g.svol();
     if (g.Nz == 1 && g.Ny > 1 && g.ky <= kMaxPruned) {
         // 2D: the y axis is the first one contracted; its ky outputs land directly in T2
-        rc = launch_wgrad_dft(g.ky, g.f, g.fo, g.Ny, g.Nxh, vol, Ghat, Ihat, T2, s);
+        rc = launch_wgrad_dft(g.ky, g.f, g.fo, g.Ny, g.spy, g.Nxh, vol, Ghat, Ihat, T2, s);
         if (rc != ZNN_OK) return rc;
     } else {
         // z: product G^[j] conj(I^[i]); only z in [0, kz) is kept
         AxisParams P = {};
         P.in = Ghat; P.in2 = Ihat; P.out = T1;
         P.N = g.Nz; P.i0 = 0; P.ni = g.Nz; P.o0 = 0; P.no = g.kz;
+        P.ostep = g.spz;                    // tap a is lag a*s of the correlation
         P.in_stride = plane; P.out_stride = plane;
         P.L = (int)plane;
         P.Oa = g.fo; P.Ob = g.f; P.Oc = 1;
         P.in_sa = vol; P.in_sb = 0;
         P.in2_sa = 0; P.in2_sb = vol;
         P.out_sa = (long)g.f * g.kz * plane; P.out_sb = (long)g.kz * plane;
-        if (g.kz <= kMaxPruned) rc = launch_wgrad_dft(g.kz, g.f, g.fo, g.Nz, plane, vol, Ghat, Ihat, T1, s);
+        if (g.kz <= kMaxPruned) rc = launch_wgrad_dft(g.kz, g.f, g.fo, g.Nz, g.spz, plane, vol, Ghat, Ihat, T1, s);
         else rc = launch_axis(P, +1, s);
         if (rc != ZNN_OK) return rc;
         // y: only y in [0, ky) is kept, written compactly
         P = AxisParams{};
         P.in = T1; P.in2 = nullptr; P.out = T2;
         P.N = g.Ny; P.i0 = 0; P.ni = g.Ny; P.o0 = 0; P.no = g.ky;
+        P.ostep = g.spy;
         P.in_stride = g.Nxh; P.out_stride = g.Nxh;
         P.L = g.Nxh;
         P.Oa = g.fo * g.f; P.Ob = g.kz; P.Oc = 1;
@@ -829,7 +845,7 @@ int fft_wgrad_from_spectra(const Geom& g, const float2* Ihat, const float2* Ghat
         if (rc != ZNN_OK) return rc;
     }
     const float scale = (float)(1.0 / ((double)g.Nz * g.Ny * g.Nx));
-    return launch_c2r(T2, gw, (long)g.f * g.fo, g.kz, g.ky, g.Nx, 0, 0, 0, g.kz, g.ky, g.kx, scale, s);
+    return launch_c2r(T2, gw, (long)g.f * g.fo, g.kz, g.ky, g.Nx, 0, 0, 0, g.kz, g.ky, g.kx, g.spx, scale, s);
 }
 
 }  // namespace znn

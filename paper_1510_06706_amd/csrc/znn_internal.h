@@ -35,7 +35,8 @@ struct Geom {
     int f, fo;            // fan-in, fan-out
     int nz, ny, nx;       // image extents n
     int kz, ky, kx;       // kernel extents k
-    int oz, oy, ox;       // n' = n - k + 1
+    int spz, spy, spx;    // sparsity s: neighbouring taps are s voxels apart (Section 2)
+    int oz, oy, ox;       // n' = n - s (k - 1)
     int Nz, Ny, Nx, Nxh;  // FFT extents and N_x/2+1
     __host__ __device__ long nvol() const { return (long)nz * ny * nx; }
     __host__ __device__ long kvol() const { return (long)kz * ky * kx; }

@@ -69,10 +69,11 @@ class LayerShape:
     kernel: Tuple[int, int, int]     # k  (z, y, x)
     kernel_scale: float = 1.0
     seed: int = 0
+    sparsity: Tuple[int, int, int] = (1, 1, 1)   # s (z, y, x): taps are s voxels apart
 
     @property
     def out(self) -> Tuple[int, int, int]:
-        return tuple(n - k + 1 for n, k in zip(self.image, self.kernel))
+        return tuple(n - s * (k - 1) for n, k, s in zip(self.image, self.kernel, self.sparsity))
 
     @property
     def macs(self) -> int:

@@ -45,7 +45,9 @@ def test_descriptor_validation():
     assert "exceeds" in znn.last_error()
     assert plan_rc(image=(0, 5, 6)) == znn.ZNN_EINVAL
     assert plan_rc(kernel=(1, 0, 1)) == znn.ZNN_EINVAL
-    assert plan_rc(sparsity=(2, 2, 2)) == znn.ZNN_EUNSUPPORTED
+    assert plan_rc(sparsity=(2, 2, 2)) == znn.ZNN_OK          # spans 3, 3, 5 fit 4, 5, 6
+    assert plan_rc(sparsity=(4, 1, 1)) == znn.ZNN_EINVAL      # span 5 exceeds 4
+    assert plan_rc(sparsity=(0, 1, 1)) == znn.ZNN_EINVAL
     assert plan_rc(mode=7) == znn.ZNN_EINVAL
     assert plan_rc(mode="fft", image=(1, 4, 2000), kernel=(1, 1, 1)) == znn.ZNN_EUNSUPPORTED
     assert znn.lib().znn_plan_create(None, ctypes.byref(ctypes.c_void_p(0))) == znn.ZNN_EINVAL

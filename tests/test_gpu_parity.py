@@ -68,6 +68,32 @@ def test_three_passes_match_the_oracle(f, fo, n, k, mode):
     p.close()
 
 
+SPARSE = [
+    # f, fo, n, k, s      (sparse convolution: taps s voxels apart, Section 2)
+    (3, 5, (11, 12, 13), (2, 3, 2), (2, 2, 3)),
+    (8, 6, (1, 30, 29), (1, 3, 4), (1, 4, 2)),
+    (20, 18, (14, 13, 22), (3, 3, 3), (2, 2, 2)),
+    (5, 4, (9, 17, 8), (3, 2, 1), (4, 1, 5)),
+    (2, 3, (36, 35, 8), (17, 17, 2), (2, 2, 3)),     # more taps than the pruned transforms take
+]
+
+
+@pytest.mark.parametrize("mode", ["direct", "fft"])
+@pytest.mark.parametrize("f,fo,n,k,s", SPARSE)
+def test_sparse_convolution_matches_the_oracle(f, fo, n, k, s, mode):
+    print("case", f, fo, n, k, s, mode, flush=True)
+    cfg = synth.LayerShape("t", f, fo, n, k, 1.0, 55 + f, s)
+    inp, w, gout = synth.layer_tensors(cfg)
+    p = znn.Plan(f, fo, n, k, mode, s)
+    assert p.o == oracle.out_extents(n, k, s)
+    d_in, d_w, d_g = dev(inp), dev(w), dev(gout)
+    tol = TOL[mode]
+    assert rel_err(host(p.fwd(d_in, d_w)), oracle.conv3d_fwd(inp, w, s)) <= tol
+    assert rel_err(host(p.bwd(d_g, d_w)), oracle.conv3d_bwd(gout, w, n, s)) <= tol
+    assert rel_err(host(p.wgrad(d_in, d_g)), oracle.conv3d_wgrad(inp, gout, s)) <= tol
+    p.close()
+
+
 def test_resident_kernel_spectra_give_the_same_result():
     f, fo, n, k = 6, 5, (10, 12, 9), (3, 4, 2)
     cfg = synth.LayerShape("t", f, fo, n, k, 1.0, 91)
