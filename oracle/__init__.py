@@ -150,26 +150,115 @@ def conv3d_wgrad_at(inp, gout, pos, sparsity=(1, 1, 1)):
     return _at(_load().znn_ref_conv3d_wgrad_at, "wgrad_at", f, fo, n, k, inp, gout, pos, sparsity)
 
 
-def maxfilter3d_fwd(inp, win):
-    """Sliding-window maximum and the flat input offset that supplied it."""
+def _ip(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def maxfilter3d_fwd(inp, win, sparsity=(1, 1, 1)):
+    """Sliding-window maximum and the flat input offset that supplied it (window taps
+    ``sparsity`` voxels apart; output extents n - s (win - 1))."""
     inp = _f64(inp)
     maps, n = inp.shape[0], inp.shape[1:]
-    o = tuple(n[d] - win[d] + 1 for d in range(3))
+    o = out_extents(n, win, sparsity)
+    if min(o) < 1:
+        raise ValueError("oracle maxfilter_fwd rejected its arguments (window span exceeds the image)")
     out = np.empty((maps,) + o, dtype=np.float64)
     idx = np.empty((maps,) + o, dtype=np.int32)
-    rc = _load().znn_ref_maxfilter3d_fwd(maps, _i3(n), _i3(win), _d(inp), _d(out),
-                                         idx.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
+    rc = _load().znn_ref_maxfilter3d_fwd(maps, _i3(n), _i3(win), _i3(sparsity), _d(inp), _d(out), _ip(idx))
     _check(rc, "maxfilter_fwd")
     return out, idx
 
 
-def maxfilter3d_bwd(gout, idx, n, win):
+def maxfilter3d_bwd(gout, idx, n, win, sparsity=(1, 1, 1)):
     """Max-filter Jacobian: scatter-add gout to the recorded argmax voxels."""
     gout = _f64(gout)
     idx = np.ascontiguousarray(np.asarray(idx, dtype=np.int32))
     maps = gout.shape[0]
+    assert gout.shape[1:] == out_extents(n, win, sparsity) and idx.shape == gout.shape
     gin = np.empty((maps,) + tuple(n), dtype=np.float64)
-    rc = _load().znn_ref_maxfilter3d_bwd(maps, _i3(n), _i3(win), _d(gout),
-                                         idx.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), _d(gin))
+    rc = _load().znn_ref_maxfilter3d_bwd(maps, _i3(n), _i3(win), _i3(sparsity), _d(gout), _ip(idx), _d(gin))
     _check(rc, "maxfilter_bwd")
     return gin
+
+
+def maxpool3d_fwd(inp, p):
+    """Block maximum over blocks of p voxels per axis and the flat input offset of each
+    maximum (Section 2, Max-pooling); n must be divisible by p."""
+    inp = _f64(inp)
+    maps, n = inp.shape[0], inp.shape[1:]
+    if any(int(n[d]) % int(p[d]) for d in range(3)):
+        raise ValueError("oracle maxpool_fwd rejected its arguments (n not divisible by p)")
+    o = tuple(int(n[d]) // int(p[d]) for d in range(3))
+    out = np.empty((maps,) + o, dtype=np.float64)
+    idx = np.empty((maps,) + o, dtype=np.int32)
+    _check(_load().znn_ref_maxpool3d_fwd(maps, _i3(n), _i3(p), _d(inp), _d(out), _ip(idx)), "maxpool_fwd")
+    return out, idx
+
+
+def maxpool3d_bwd(gout, idx, n, p):
+    """Max-pooling Jacobian (Section 3.1): every block is zero except at its forward maximum."""
+    gout = _f64(gout)
+    idx = np.ascontiguousarray(np.asarray(idx, dtype=np.int32))
+    maps = gout.shape[0]
+    assert idx.shape == gout.shape
+    gin = np.empty((maps,) + tuple(n), dtype=np.float64)
+    _check(_load().znn_ref_maxpool3d_bwd(maps, _i3(n), _i3(p), _d(gout), _ip(idx), _d(gin)), "maxpool_bwd")
+    return gin
+
+
+# ---------------------------------------------------------------- transfer functions and losses
+# Section 2, "Transfer function": a bias is added to every voxel, then a nondecreasing
+# nonlinearity is applied: the logistic function, the hyperbolic tangent or half-wave
+# rectification.  The backward edge multiplies by the derivative, written through the
+# forward output y (Section 3.1): rectifier 1 where y > 0 else 0; logistic y (1 - y);
+# tanh 1 - y^2.
+TRANSFER_FUNCTIONS = ("rectify", "logistic", "tanh")
+
+
+def transfer_fwd(x, bias, fn="rectify"):
+    v = _f64(x) + _f64(bias)[:, None, None, None]
+    if fn == "rectify":
+        return np.maximum(v, 0.0)
+    if fn == "logistic":
+        return 1.0 / (1.0 + np.exp(-v))
+    if fn == "tanh":
+        return np.tanh(v)
+    raise ValueError(fn)
+
+
+def transfer_bwd(gy, y, fn="rectify"):
+    gy, y = _f64(gy), _f64(y)
+    if fn == "rectify":
+        return gy * (y > 0.0)
+    if fn == "logistic":
+        return gy * y * (1.0 - y)
+    if fn == "tanh":
+        return gy * (1.0 - y * y)
+    raise ValueError(fn)
+
+
+# Section 3: the loss compares actual and desired output; its gradient with respect to
+# the actual output starts the backward pass.  The paper names the Euclidean distance and
+# leaves the others open; the second loss here is the cross-entropy between a target in
+# [0, 1] and an output in (0, 1) (the natural partner of a logistic output layer).
+#   square:        L = 1/2 sum (y - t)^2                       dL/dy = y - t
+#   cross-entropy: L = - sum t log y + (1 - t) log (1 - y)     dL/dy = (y - t) / (y (1 - y))
+LOSSES = ("square", "cross_entropy")
+
+
+def loss_value(y, t, loss="square"):
+    y, t = _f64(y), _f64(t)
+    if loss == "square":
+        return 0.5 * float(np.sum((y - t) ** 2))
+    if loss == "cross_entropy":
+        return -float(np.sum(t * np.log(y) + (1.0 - t) * np.log(1.0 - y)))
+    raise ValueError(loss)
+
+
+def loss_grad(y, t, loss="square"):
+    y, t = _f64(y), _f64(t)
+    if loss == "square":
+        return y - t
+    if loss == "cross_entropy":
+        return (y - t) / (y * (1.0 - y))
+    raise ValueError(loss)

@@ -3,18 +3,31 @@
 The round follows Section 3 of the paper: forward pass, gradient of the loss
 with respect to the output, backward pass through the transposed Jacobians
 (Section 3.1), then kernel and bias gradients and the update (Section 3.2,
-Algorithm 3).  Convolutions and max-filters call the nested-loop oracle; the
-transfer function (bias, then half-wave rectification), the square loss
-1/2 sum (out - target)^2 and the plain update p -= eta * g are written out in
-numpy.  Readings the paper leaves open: the rectifier's derivative is 1 where
-the forward output is > 0 and 0 elsewhere; the loss is not averaged; the
-network input receives no backward image.
+Algorithm 3).  Convolutions, max-filters and max-pooling call the nested-loop
+oracle; the transfer functions (bias, then nonlinearity), the losses and the
+plain update p -= eta * g are written out in numpy.  Readings the paper leaves
+open: the rectifier's derivative is 1 where the forward output is > 0 and 0
+elsewhere; the loss is not averaged; the network input receives no backward
+image.
+
+Layer specs (tuples; trailing fields optional):
+  ("conv", f, f', k[, s])      convolution layer, kernel extents k, sparsity s
+  ("transfer"[, fn])           bias + "rectify" (default) | "logistic" | "tanh"
+  ("maxfilter", win[, s])      sliding-window maximum, window taps s apart
+  ("maxpool", p)               block maximum
 """
 from __future__ import annotations
 
 import numpy as np
 
 import oracle
+
+
+ONES = (1, 1, 1)
+
+
+def _opt(spec, i, default):
+    return spec[i] if len(spec) > i else default
 
 
 def forward(layers, params, x):
@@ -25,11 +38,13 @@ def forward(layers, params, x):
     for l, spec in enumerate(layers):
         a = acts[-1]
         if spec[0] == "conv":
-            y = oracle.conv3d_fwd(a, params[l]["w"])
+            y = oracle.conv3d_fwd(a, params[l]["w"], _opt(spec, 4, ONES))
         elif spec[0] == "transfer":
-            y = np.maximum(a + params[l]["b"][:, None, None, None], 0.0)
+            y = oracle.transfer_fwd(a, params[l]["b"], _opt(spec, 1, "rectify"))
         elif spec[0] == "maxfilter":
-            y, aux[l] = oracle.maxfilter3d_fwd(a, spec[1])
+            y, aux[l] = oracle.maxfilter3d_fwd(a, spec[1], _opt(spec, 2, ONES))
+        elif spec[0] == "maxpool":
+            y, aux[l] = oracle.maxpool3d_fwd(a, spec[1])
         else:
             raise ValueError(spec)
         acts.append(y)
@@ -43,22 +58,25 @@ def backward(layers, params, acts, aux, gout):
     for l in range(len(layers) - 1, -1, -1):
         spec = layers[l]
         if spec[0] == "conv":
-            grads[l] = {"w": oracle.conv3d_wgrad(acts[l], g)}
-            g = oracle.conv3d_bwd(g, params[l]["w"], acts[l].shape[1:]) if l > 0 else None
+            sp = _opt(spec, 4, ONES)
+            grads[l] = {"w": oracle.conv3d_wgrad(acts[l], g, sp)}
+            g = oracle.conv3d_bwd(g, params[l]["w"], acts[l].shape[1:], sp) if l > 0 else None
         elif spec[0] == "transfer":
-            g = g * (acts[l + 1] > 0.0)
+            g = oracle.transfer_bwd(g, acts[l + 1], _opt(spec, 1, "rectify"))
             grads[l] = {"b": g.reshape(g.shape[0], -1).sum(axis=1)}
         elif spec[0] == "maxfilter":
-            g = oracle.maxfilter3d_bwd(g, aux[l], acts[l].shape[1:], spec[1])
+            g = oracle.maxfilter3d_bwd(g, aux[l], acts[l].shape[1:], spec[1], _opt(spec, 2, ONES))
+        elif spec[0] == "maxpool":
+            g = oracle.maxpool3d_bwd(g, aux[l], acts[l].shape[1:], spec[1])
     return grads
 
 
-def train_round(layers, params, x, target, eta):
-    """One round; returns (loss, acts, aux, grads, updated params)."""
+def train_round(layers, params, x, target, eta, loss="square"):
+    """One round; returns (loss value, acts, aux, grads, updated params)."""
     acts, aux = forward(layers, params, x)
-    diff = acts[-1] - np.asarray(target, dtype=np.float64)
-    loss = 0.5 * float(np.sum(diff * diff))
-    grads = backward(layers, params, acts, aux, diff)
+    value = oracle.loss_value(acts[-1], target, loss)
+    grads = backward(layers, params, acts, aux, oracle.loss_grad(acts[-1], target, loss))
+    loss = value
     new = []
     for p, g in zip(params, grads):
         new.append(None if p is None else {k: np.asarray(v, dtype=np.float64) - eta * g[k] for k, v in p.items()})

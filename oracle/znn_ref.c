@@ -303,20 +303,33 @@ int znn_ref_conv3d_wgrad_at(int f, int fo, const int n[3], const int k[3], const
 
 /*
  * Max-filtering (Section 2, "Max-filtering"): the maximum inside a sliding
- * window, output extent n - win + 1 per axis.  idx records which input voxel
- * supplied the maximum, as the flat offset (z*ny + y)*nx + x inside that map.
- * The paper does not fix which voxel wins among equal values; this oracle
- * scans the window in ascending flat order with a strict '>' so the smallest
- * flat index wins (-0.0 and +0.0 compare equal).
+ * window.  idx records which input voxel supplied the maximum, as the flat
+ * offset (z*ny + y)*nx + x inside that map.  The paper does not fix which
+ * voxel wins among equal values; this oracle scans the window in ascending
+ * flat order with a strict '>' so the smallest flat index wins (-0.0 and +0.0
+ * compare equal).
+ *
+ * The window may be sparse like a convolution's: its win taps lie s voxels
+ * apart, and the output extent is n - s (win - 1).  The paper states sparsity
+ * for convolutions only; a max-filter that follows an earlier max-filter in a
+ * max-filtering ConvNet needs the same treatment for the net to reproduce a
+ * sliding-window max-pooling ConvNet (Section 2, last paragraphs, and the
+ * figure there), so the filter takes a sparsity too.  s = 1 is the dense filter.
  */
-int znn_ref_maxfilter3d_fwd(int maps, const int n[3], const int win[3],
+static int bad_filter(int maps, const int n[3], const int win[3], const int s[3])
+{
+    if (maps < 1) return 1;
+    for (int d = 0; d < 3; ++d)
+        if (n[d] < 1 || win[d] < 1 || s[d] < 1 || (long)s[d] * (win[d] - 1) + 1 > n[d]) return 1;
+    return 0;
+}
+
+int znn_ref_maxfilter3d_fwd(int maps, const int n[3], const int win[3], const int s[3],
                             const double *in, double *out, int32_t *idx)
 {
-    if (maps < 1 || !in || !out || !idx) return ZNN_REF_EINVAL;
-    for (int d = 0; d < 3; ++d)
-        if (n[d] < 1 || win[d] < 1 || win[d] > n[d]) return ZNN_REF_EINVAL;
+    if (!in || !out || !idx || bad_filter(maps, n, win, s)) return ZNN_REF_EINVAL;
     const int nz = n[0], ny = n[1], nx = n[2];
-    const int oz = nz - win[0] + 1, oy = ny - win[1] + 1, ox = nx - win[2] + 1;
+    const int oz = nz - s[0] * (win[0] - 1), oy = ny - s[1] * (win[1] - 1), ox = nx - s[2] * (win[2] - 1);
     const size_t nvol = (size_t)nz * ny * nx, ovol = (size_t)oz * oy * ox;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int m = 0; m < maps; ++m) {
@@ -329,7 +342,7 @@ int znn_ref_maxfilter3d_fwd(int maps, const int n[3], const int win[3],
             for (int a = 0; a < win[0]; ++a)
             for (int b = 0; b < win[1]; ++b)
             for (int c = 0; c < win[2]; ++c) {
-                const size_t q = ((size_t)(z + a) * ny + (y + b)) * nx + (x + c);
+                const size_t q = ((size_t)(z + s[0] * a) * ny + (y + s[1] * b)) * nx + (x + s[2] * c);
                 if (img[q] > bv) { bv = img[q]; best = q; }
             }
             const size_t o = (size_t)m * ovol + ((size_t)z * oy + y) * ox + x;
@@ -345,14 +358,13 @@ int znn_ref_maxfilter3d_fwd(int maps, const int n[3], const int win[3],
  * filter's input size; for every window position add the incoming value to
  * the voxel that supplied the forward maximum of that window.
  */
-int znn_ref_maxfilter3d_bwd(int maps, const int n[3], const int win[3],
+int znn_ref_maxfilter3d_bwd(int maps, const int n[3], const int win[3], const int s[3],
                             const double *gout, const int32_t *idx, double *gin)
 {
-    if (maps < 1 || !gout || !idx || !gin) return ZNN_REF_EINVAL;
-    for (int d = 0; d < 3; ++d)
-        if (n[d] < 1 || win[d] < 1 || win[d] > n[d]) return ZNN_REF_EINVAL;
+    if (!gout || !idx || !gin || bad_filter(maps, n, win, s)) return ZNN_REF_EINVAL;
     const size_t nvol = (size_t)n[0] * n[1] * n[2];
-    const size_t ovol = (size_t)(n[0] - win[0] + 1) * (n[1] - win[1] + 1) * (n[2] - win[2] + 1);
+    const size_t ovol = (size_t)(n[0] - s[0] * (win[0] - 1)) * (n[1] - s[1] * (win[1] - 1)) *
+                        (n[2] - s[2] * (win[2] - 1));
     for (size_t p = 0; p < ovol * maps; ++p)
         if (idx[p] < 0 || (size_t)idx[p] >= nvol) return ZNN_REF_EINVAL;
 #pragma omp parallel for schedule(dynamic, 1)
@@ -361,6 +373,67 @@ int znn_ref_maxfilter3d_bwd(int maps, const int n[3], const int win[3],
         for (size_t q = 0; q < nvol; ++q) g[q] = 0.0;
         for (size_t p = 0; p < ovol; ++p)
             g[idx[(size_t)m * ovol + p]] += gout[(size_t)m * ovol + p];
+    }
+    return ZNN_REF_OK;
+}
+
+/*
+ * Max-pooling (Section 2, "Max-pooling"): the image is cut into blocks of
+ * p voxels per axis (n divisible by p) and every block yields its maximum;
+ * output extent n / p.  idx is the flat offset inside the input map of the
+ * voxel that supplied it; ties go to the smallest flat offset, as above.
+ */
+int znn_ref_maxpool3d_fwd(int maps, const int n[3], const int p[3],
+                          const double *in, double *out, int32_t *idx)
+{
+    if (maps < 1 || !in || !out || !idx) return ZNN_REF_EINVAL;
+    for (int d = 0; d < 3; ++d)
+        if (n[d] < 1 || p[d] < 1 || n[d] % p[d] != 0) return ZNN_REF_EINVAL;
+    const int ny = n[1], nx = n[2];
+    const int oz = n[0] / p[0], oy = n[1] / p[1], ox = n[2] / p[2];
+    const size_t nvol = (size_t)n[0] * ny * nx, ovol = (size_t)oz * oy * ox;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int m = 0; m < maps; ++m) {
+        const double *img = in + (size_t)m * nvol;
+        for (int z = 0; z < oz; ++z)
+        for (int y = 0; y < oy; ++y)
+        for (int x = 0; x < ox; ++x) {
+            size_t best = ((size_t)(z * p[0]) * ny + y * p[1]) * nx + x * p[2];
+            double bv = img[best];
+            for (int a = 0; a < p[0]; ++a)
+            for (int b = 0; b < p[1]; ++b)
+            for (int c = 0; c < p[2]; ++c) {
+                const size_t q = ((size_t)(z * p[0] + a) * ny + (y * p[1] + b)) * nx + (x * p[2] + c);
+                if (img[q] > bv) { bv = img[q]; best = q; }
+            }
+            const size_t o = (size_t)m * ovol + ((size_t)z * oy + y) * ox + x;
+            out[o] = bv;
+            idx[o] = (int32_t)best;
+        }
+    }
+    return ZNN_REF_OK;
+}
+
+/*
+ * Max-pooling Jacobian (Section 3.1): the pooled image is expanded back to
+ * the input size; inside every block all voxels are zero except the one that
+ * was the forward maximum, which receives the block's incoming value.
+ */
+int znn_ref_maxpool3d_bwd(int maps, const int n[3], const int p[3],
+                          const double *gout, const int32_t *idx, double *gin)
+{
+    if (maps < 1 || !gout || !idx || !gin) return ZNN_REF_EINVAL;
+    for (int d = 0; d < 3; ++d)
+        if (n[d] < 1 || p[d] < 1 || n[d] % p[d] != 0) return ZNN_REF_EINVAL;
+    const size_t nvol = (size_t)n[0] * n[1] * n[2];
+    const size_t ovol = (size_t)(n[0] / p[0]) * (n[1] / p[1]) * (n[2] / p[2]);
+    for (size_t q = 0; q < ovol * maps; ++q)
+        if (idx[q] < 0 || (size_t)idx[q] >= nvol) return ZNN_REF_EINVAL;
+    for (int m = 0; m < maps; ++m) {
+        double *g = gin + (size_t)m * nvol;
+        for (size_t q = 0; q < nvol; ++q) g[q] = 0.0;
+        for (size_t q = 0; q < ovol; ++q)
+            g[idx[(size_t)m * ovol + q]] = gout[(size_t)m * ovol + q];
     }
     return ZNN_REF_OK;
 }

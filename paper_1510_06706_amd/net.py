@@ -27,6 +27,27 @@ CONFIG3_INPUT = (1, 26, 26, 26)
 CONFIG3_ETA = 1e-3
 CONFIG3_SEED = 1003
 
+# The same network as a max-filtering ConvNet that reproduces a sliding-window max-pooling
+# ConvNet (Section 2, last paragraphs): every max-filter multiplies the sparsity of all
+# later layers by its window, so the layers after the first filter have sparsity 2 and
+# those after the second have sparsity 4.  Same 12^3 output patch => 43^3 input.
+S2, S4 = (2, 2, 2), (4, 4, 4)
+CONFIG3_SPARSE_LAYERS = [
+    ("conv", 1, WIDTH, (3, 3, 3)), ("transfer",),
+    ("conv", WIDTH, WIDTH, (3, 3, 3)), ("transfer",), ("maxfilter", (2, 2, 2)),
+    ("conv", WIDTH, WIDTH, (3, 3, 3), S2), ("transfer",),
+    ("conv", WIDTH, WIDTH, (3, 3, 3), S2), ("transfer",), ("maxfilter", (2, 2, 2), S2),
+    ("conv", WIDTH, WIDTH, (3, 3, 3), S4), ("transfer",),
+    ("conv", WIDTH, 3, (3, 3, 3), S4), ("transfer",),
+]
+CONFIG3_SPARSE_INPUT = (1, 43, 43, 43)
+
+ONES = (1, 1, 1)
+
+
+def _opt(spec, i, default):
+    return spec[i] if len(spec) > i else default
+
 
 def shapes(layers, in_shape):
     """Node shapes [maps, z, y, x] before every layer and after the last."""
@@ -35,11 +56,16 @@ def shapes(layers, in_shape):
         m, n = out[-1][0], out[-1][1:]
         if spec[0] == "conv":
             assert spec[1] == m
-            out.append((spec[2],) + tuple(a - b + 1 for a, b in zip(n, spec[3])))
+            out.append((spec[2],) + tuple(a - s * (b - 1) for a, b, s in zip(n, spec[3], _opt(spec, 4, ONES))))
         elif spec[0] == "transfer":
             out.append(out[-1])
         elif spec[0] == "maxfilter":
-            out.append((m,) + tuple(a - b + 1 for a, b in zip(n, spec[1])))
+            out.append((m,) + tuple(a - s * (b - 1) for a, b, s in zip(n, spec[1], _opt(spec, 2, ONES))))
+        elif spec[0] == "maxpool":
+            assert all(a % b == 0 for a, b in zip(n, spec[1])), "max-pooling needs n divisible by p"
+            out.append((m,) + tuple(a // b for a, b in zip(n, spec[1])))
+        else:
+            raise ValueError(spec)
     return out
 
 
@@ -48,7 +74,7 @@ def synthetic_params(layers, seed):
     params = []
     for l, spec in enumerate(layers):
         if spec[0] == "conv":
-            _, f, fo, k = spec
+            f, fo, k = spec[1:4]
             scale = float(np.sqrt(6.0 / (f * int(np.prod(k)))))
             params.append({"w": synth.uniform_pm1(seed + 17 * l, synth.STREAM_KERNEL, (fo, f) + tuple(k), scale)})
         elif spec[0] == "transfer":
@@ -59,11 +85,19 @@ def synthetic_params(layers, seed):
     return params
 
 
+def net_tensors(layers, in_shape, seed):
+    """(input, target, params) of a layered net: input uniform[-1,1), target uniform[0,1)."""
+    x = synth.uniform_pm1(seed, synth.STREAM_IMAGE, in_shape)
+    target = synth.uniform_01(seed, synth.STREAM_TARGET, shapes(layers, in_shape)[-1])
+    return x, target, synthetic_params(layers, seed)
+
+
 def config3_tensors():
-    x = synth.uniform_pm1(CONFIG3_SEED, synth.STREAM_IMAGE, CONFIG3_INPUT)
-    out_shape = shapes(CONFIG3_LAYERS, CONFIG3_INPUT)[-1]
-    target = synth.uniform_01(CONFIG3_SEED, synth.STREAM_TARGET, out_shape)
-    return x, target, synthetic_params(CONFIG3_LAYERS, CONFIG3_SEED)
+    return net_tensors(CONFIG3_LAYERS, CONFIG3_INPUT, CONFIG3_SEED)
+
+
+def config3_sparse_tensors():
+    return net_tensors(CONFIG3_SPARSE_LAYERS, CONFIG3_SPARSE_INPUT, CONFIG3_SEED + 1)
 
 
 class Net:
@@ -80,7 +114,7 @@ class Net:
         for l, spec in enumerate(self.layers):
             if spec[0] == "conv":
                 m = mode[l] if isinstance(mode, (list, tuple)) else mode
-                self.plans.append(znn.Plan(spec[1], spec[2], self.shapes[l][1:], spec[3], m))
+                self.plans.append(znn.Plan(spec[1], spec[2], self.shapes[l][1:], spec[3], m, _opt(spec, 4, ONES)))
             else:
                 self.plans.append(None)
 
@@ -94,9 +128,11 @@ class Net:
             if spec[0] == "conv":
                 y = self.plans[l].fwd(a, self.params[l]["w"])
             elif spec[0] == "transfer":
-                y = znn.transfer_fwd(a, self.params[l]["b"])
+                y = znn.transfer_fwd(a, self.params[l]["b"], _opt(spec, 1, "rectify"))
+            elif spec[0] == "maxfilter":
+                y, aux[l] = znn.maxfilter3d_fwd(a, spec[1], _opt(spec, 2, ONES))
             else:
-                y, aux[l] = znn.maxfilter3d_fwd(a, spec[1])
+                y, aux[l] = znn.maxpool3d_fwd(a, spec[1])
             acts.append(y)
         return acts, aux
 
@@ -112,15 +148,17 @@ class Net:
                 grads[l] = {"w": self.plans[l].wgrad(acts[l], g)}
                 g = self.plans[l].bwd(g, self.params[l]["w"]) if l > 0 else None
             elif spec[0] == "transfer":
-                g = znn.transfer_bwd(g, acts[l + 1])
+                g = znn.transfer_bwd(g, acts[l + 1], _opt(spec, 1, "rectify"))
                 grads[l] = {"b": znn.bias_grad(g)}
+            elif spec[0] == "maxfilter":
+                g = znn.maxfilter3d_bwd(g, aux[l], self.shapes[l][1:], spec[1], _opt(spec, 2, ONES))
             else:
-                g = znn.maxfilter3d_bwd(g, aux[l], self.shapes[l][1:], spec[1])
+                g = znn.maxpool3d_bwd(g, aux[l], self.shapes[l][1:], spec[1])
         return grads
 
-    def train_round(self, x, target, eta, record=None):
+    def train_round(self, x, target, eta, record=None, loss="square"):
         acts, aux = self.forward(x)
-        gout = znn.square_loss_grad(acts[-1], target)
+        gout = znn.loss_grad(acts[-1], target, loss)
         grads = self.backward(acts, aux, gout, record)
         for p, g in zip(self.params, grads):
             if p is not None:

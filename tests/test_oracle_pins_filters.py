@@ -1,0 +1,228 @@
+"""Pins of the oracle's sparse max-filter, max-pooling, transfer functions and losses.
+
+Independent checks: a sparse filter is a dense filter on every residue class of the
+image grid; max-pooling against a numpy reshape-max and against the max-filter sampled
+at block corners; the equivalence the paper's Section 2 (last paragraphs and the figure
+there) states between a sliding-window max-pooling ConvNet and a max-filtering ConvNet
+with sparse convolutions, which ties sparse convolution, sparse filtering and pooling to
+the dense definitions in one go; closed-form values and finite differences for the
+transfer functions and losses.
+"""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import net as onet
+from paper_1510_06706_amd import net as znet
+from paper_1510_06706_amd import synth
+
+
+def rnd(seed, stream, shape):
+    return synth.uniform_pm1(seed, stream, shape).astype(np.float64)
+
+
+# ---------------------------------------------------------------- sparse max-filter
+@pytest.mark.parametrize("n,win,s", [((9, 8, 10), (2, 2, 2), (2, 2, 2)), ((7, 9, 6), (2, 3, 1), (3, 2, 4)),
+                                     ((1, 12, 11), (1, 2, 3), (1, 4, 2)), ((5, 5, 5), (3, 2, 2), (1, 1, 1))])
+def test_sparse_maxfilter_is_a_dense_filter_on_every_residue_class(n, win, s):
+    x = rnd(71, 0, (2,) + n)
+    out, idx = oracle.maxfilter3d_fwd(x, win, s)
+    assert out.shape[1:] == tuple(n[d] - s[d] * (win[d] - 1) for d in range(3))
+    flat = np.arange(int(np.prod(n))).reshape(n)
+    for r in itertools.product(*[range(t) for t in s]):
+        sub = x[:, r[0]::s[0], r[1]::s[1], r[2]::s[2]]
+        if any(sub.shape[1 + d] < win[d] for d in range(3)):
+            continue
+        d_out, d_idx = oracle.maxfilter3d_fwd(sub, win)
+        sel = out[:, r[0]::s[0], r[1]::s[1], r[2]::s[2]]
+        o = d_out.shape[1:]
+        assert np.array_equal(sel[:, :o[0], :o[1], :o[2]], d_out)
+        # the dense filter's offsets index the sub-grid; map them back to the full grid
+        back = flat[r[0]::s[0], r[1]::s[1], r[2]::s[2]].ravel()[d_idx]
+        assert np.array_equal(idx[:, r[0]::s[0], r[1]::s[1], r[2]::s[2]][:, :o[0], :o[1], :o[2]], back)
+
+
+def test_sparse_maxfilter_brute_force_with_ties():
+    n, win, s = (5, 6, 7), (2, 2, 3), (2, 3, 2)
+    rs = np.random.RandomState(4)
+    x = rs.randint(0, 3, size=(1,) + n).astype(np.float64)
+    out, idx = oracle.maxfilter3d_fwd(x, win, s)
+    for p in itertools.product(*[range(t) for t in out.shape[1:]]):
+        cand = []
+        for a in itertools.product(*[range(t) for t in win]):
+            q = tuple(p[d] + s[d] * a[d] for d in range(3))
+            cand.append((-x[(0,) + q], int(np.ravel_multi_index(q, n))))
+        v, q = min(cand)                      # largest value, then smallest flat offset
+        assert out[(0,) + p] == -v and idx[(0,) + p] == q
+
+
+def test_sparse_maxfilter_jacobian_is_the_transposed_selection():
+    n, win, s = (7, 6, 8), (2, 2, 2), (2, 1, 3)
+    x = rnd(72, 0, (2,) + n)
+    out, idx = oracle.maxfilter3d_fwd(x, win, s)
+    g = rnd(72, 2, out.shape)
+    gin = oracle.maxfilter3d_bwd(g, idx, n, win, s)
+    xp = rnd(72, 3, x.shape)
+    sel = np.stack([xp[m].ravel()[idx[m]] for m in range(2)])
+    assert abs(np.sum(sel * g) - np.sum(xp * gin)) < 1e-12
+    with pytest.raises(ValueError):
+        oracle.maxfilter3d_fwd(x, (2, 2, 2), (7, 1, 1))
+
+
+# ---------------------------------------------------------------- max-pooling
+@pytest.mark.parametrize("n,p", [((4, 6, 8), (2, 2, 2)), ((6, 3, 4), (3, 1, 2)), ((1, 8, 9), (1, 4, 3)),
+                                 ((2, 2, 2), (2, 2, 2)), ((3, 4, 5), (1, 1, 1))])
+def test_maxpool_matches_reshape_max_and_the_filter_at_block_corners(n, p):
+    x = rnd(73, 0, (3,) + n)
+    out, idx = oracle.maxpool3d_fwd(x, p)
+    o = tuple(n[d] // p[d] for d in range(3))
+    blocks = x.reshape(3, o[0], p[0], o[1], p[1], o[2], p[2])
+    assert np.array_equal(out, blocks.max(axis=(2, 4, 6)))
+    assert np.array_equal(np.stack([x[m].ravel()[idx[m]] for m in range(3)]), out)
+    # pooling is the max-filter with window p kept only at multiples of p
+    f_out, f_idx = oracle.maxfilter3d_fwd(x, p)
+    assert np.array_equal(out, f_out[:, ::p[0], ::p[1], ::p[2]])
+    assert np.array_equal(idx, f_idx[:, ::p[0], ::p[1], ::p[2]])
+    # every recorded voxel lies inside its own block
+    z, y, xx = np.unravel_index(idx, n)
+    bz, by, bx = np.meshgrid(*[np.arange(t) for t in o], indexing="ij")
+    assert np.all((z // p[0] == bz) & (y // p[1] == by) & (xx // p[2] == bx))
+
+
+def test_maxpool_ties_and_rejections():
+    x = np.full((1, 4, 4, 4), 2.0)
+    _, idx = oracle.maxpool3d_fwd(x, (2, 2, 2))
+    bz, by, bx = np.meshgrid(*[np.arange(2)] * 3, indexing="ij")
+    assert np.array_equal(idx[0], (2 * bz * 4 + 2 * by) * 4 + 2 * bx)
+    with pytest.raises(ValueError):
+        oracle.maxpool3d_fwd(np.zeros((1, 5, 4, 4)), (2, 2, 2))
+
+
+def test_maxpool_jacobian_keeps_one_voxel_per_block():
+    n, p = (4, 6, 6), (2, 3, 2)
+    x = rnd(74, 0, (2,) + n)
+    out, idx = oracle.maxpool3d_fwd(x, p)
+    g = rnd(74, 2, out.shape)
+    gin = oracle.maxpool3d_bwd(g, idx, n, p)
+    assert gin.shape == x.shape
+    o = out.shape[1:]
+    blocks = gin.reshape(2, o[0], p[0], o[1], p[1], o[2], p[2])
+    assert np.array_equal(np.count_nonzero(blocks, axis=(2, 4, 6)), np.ones((2,) + o, dtype=int))
+    assert np.array_equal(blocks.sum(axis=(2, 4, 6)), g)
+    # non-zeros sit where the forward maxima were
+    assert np.array_equal((gin != 0), (x == np.repeat(np.repeat(np.repeat(out, p[0], 1), p[1], 2), p[2], 3)))
+    # finite difference of sum(g * pool(x)) with respect to x
+    h = 1e-6
+    rs = np.random.RandomState(1)
+    for _ in range(10):
+        q = (rs.randint(2),) + tuple(rs.randint(t) for t in n)
+        xp = x.copy(); xp[q] += h
+        xm = x.copy(); xm[q] -= h
+        fd = (np.sum(g * oracle.maxpool3d_fwd(xp, p)[0]) - np.sum(g * oracle.maxpool3d_fwd(xm, p)[0])) / (2 * h)
+        assert abs(fd - gin[q]) < 1e-8
+
+
+# ---------------------------------------------------------------- sliding-window equivalence
+def test_maxfilter_net_with_sparse_layers_equals_sliding_window_maxpool_net():
+    """Section 2, last paragraphs and the figure there: applying a max-pooling ConvNet to
+    every window of an image gives, voxel for voxel, the output of the max-filtering
+    ConvNet in which every filter multiplies the sparsity of all later layers by its window."""
+    k, two = (2, 2, 2), (2, 2, 2)
+    pool_net = [("conv", 1, 3, k), ("transfer", "tanh"), ("maxpool", two),
+                ("conv", 3, 2, k), ("transfer", "tanh"), ("maxpool", two),
+                ("conv", 2, 2, k), ("transfer", "logistic")]
+    filt_net = [("conv", 1, 3, k), ("transfer", "tanh"), ("maxfilter", two),
+                ("conv", 3, 2, k, (2, 2, 2)), ("transfer", "tanh"), ("maxfilter", two, (2, 2, 2)),
+                ("conv", 2, 2, k, (4, 4, 4)), ("transfer", "logistic")]
+    fov = 11                                   # 1 <- conv 2 <- pool 4 <- conv 5 <- pool 10 <- conv 11
+    assert znet.shapes(pool_net, (1, fov, fov, fov))[-1] == (2, 1, 1, 1)
+    n = (13, 12, 14)
+    params = [None if p is None else {a: v.astype(np.float64) for a, v in p.items()}
+              for p in znet.synthetic_params(pool_net, 77)]
+    x = rnd(78, 0, (1,) + n)
+    dense = onet.forward(filt_net, params, x)[0][-1]
+    assert dense.shape == (2,) + tuple(t - fov + 1 for t in n)
+    for p in itertools.product(*[range(t) for t in dense.shape[1:]]):
+        window = x[:, p[0]:p[0] + fov, p[1]:p[1] + fov, p[2]:p[2] + fov]
+        single = onet.forward(pool_net, params, window)[0][-1]
+        np.testing.assert_allclose(dense[(slice(None),) + p], single[:, 0, 0, 0], rtol=0, atol=1e-13)
+
+
+# ---------------------------------------------------------------- transfer functions and losses
+def test_transfer_function_values_and_derivatives():
+    b = np.array([0.0, np.log(3.0)])
+    x = np.zeros((2, 1, 1, 2))
+    np.testing.assert_allclose(oracle.transfer_fwd(x, b, "logistic")[:, 0, 0, 0], [0.5, 0.75], atol=1e-15)
+    np.testing.assert_allclose(oracle.transfer_fwd(x, np.array([0.0, np.arctanh(0.5)]), "tanh")[:, 0, 0, 0],
+                               [0.0, 0.5], atol=1e-15)
+    np.testing.assert_array_equal(oracle.transfer_fwd(x - 1.0, np.array([0.5, 2.0]), "rectify")[:, 0, 0, 0], [0.0, 1.0])
+    v = rnd(75, 0, (3, 2, 3, 4)) * 3
+    bias = rnd(75, 4, (3,))
+    # tanh(u) = 2 logistic(2u) - 1
+    np.testing.assert_allclose(oracle.transfer_fwd(v, bias, "tanh"),
+                               2 * oracle.transfer_fwd(2 * v, 2 * bias, "logistic") - 1, atol=1e-14)
+    g = rnd(75, 2, v.shape)
+    h = 1e-6
+    for fn in oracle.TRANSFER_FUNCTIONS:
+        y = oracle.transfer_fwd(v, bias, fn)
+        fd = (oracle.transfer_fwd(v + h, bias, fn) - oracle.transfer_fwd(v - h, bias, fn)) / (2 * h)
+        ok = np.abs(v + bias[:, None, None, None]) > 1e-3        # away from the rectifier's kink
+        np.testing.assert_allclose(oracle.transfer_bwd(g, y, fn)[ok], (g * fd)[ok], atol=1e-8)
+    with pytest.raises(ValueError):
+        oracle.transfer_fwd(v, bias, "step")
+
+
+def test_loss_gradients_match_finite_differences():
+    y = 0.05 + 0.9 * synth.uniform_01(76, 0, (2, 2, 3, 2)).astype(np.float64)
+    t = synth.uniform_01(76, 3, y.shape).astype(np.float64)
+    h = 1e-7
+    for loss in oracle.LOSSES:
+        g = oracle.loss_grad(y, t, loss)
+        for q in itertools.product(*[range(s) for s in y.shape]):
+            yp = y.copy(); yp[q] += h
+            ym = y.copy(); ym[q] -= h
+            fd = (oracle.loss_value(yp, t, loss) - oracle.loss_value(ym, t, loss)) / (2 * h)
+            assert abs(fd - g[q]) < 1e-5 * max(1.0, abs(fd))
+        assert np.all(oracle.loss_grad(t * 0.5 + 0.25, t * 0.5 + 0.25, loss) == 0.0)
+    assert oracle.loss_value(np.array([1.0, 3.0]), np.array([0.0, 1.0]), "square") == 2.5
+    # a target equal to the output's 0/1 class with y = 1/2 costs log 2 per voxel
+    assert abs(oracle.loss_value(np.full(4, 0.5), np.array([0.0, 1.0, 1.0, 0.0]), "cross_entropy") - 4 * np.log(2)) < 1e-15
+    # through a logistic output the two derivatives collapse to y - t
+    np.testing.assert_allclose(oracle.transfer_bwd(oracle.loss_grad(y, t, "cross_entropy"), y, "logistic"), y - t, atol=1e-14)
+
+
+def test_net_gradients_with_every_layer_kind_match_finite_differences():
+    layers = [("conv", 1, 2, (2, 2, 2)), ("transfer", "tanh"), ("maxfilter", (2, 1, 2)),
+              ("conv", 2, 3, (2, 2, 1), (2, 1, 2)), ("transfer",), ("maxfilter", (2, 2, 1), (2, 1, 2)),
+              ("maxpool", (1, 2, 2)), ("conv", 3, 2, (1, 2, 1)), ("transfer", "logistic")]
+    in_shape = (1, 8, 7, 8)
+    assert znet.shapes(layers, in_shape)[-1] == (2, 2, 1, 3)
+    params = [None if p is None else {a: v.astype(np.float64) for a, v in p.items()}
+              for p in znet.synthetic_params(layers, 9)]
+    for p in params:
+        if p and "b" in p:
+            p["b"] += 0.3
+    x = rnd(10, 0, in_shape)
+    t = synth.uniform_01(10, 3, znet.shapes(layers, in_shape)[-1]).astype(np.float64)
+
+    def loss_of():
+        return oracle.loss_value(onet.forward(layers, params, x)[0][-1], t, "cross_entropy")
+
+    loss, acts, aux, grads, new = onet.train_round(layers, params, x, t, 1e-3, "cross_entropy")
+    assert abs(loss - loss_of()) < 1e-12
+    rs = np.random.RandomState(3)
+    h = 1e-6
+    for l, p in enumerate(params):
+        if p is None:
+            continue
+        for name, v in p.items():
+            for _ in range(6):
+                q = tuple(rs.randint(0, s) for s in v.shape)
+                old = v[q]
+                v[q] = old + h; lp = loss_of()
+                v[q] = old - h; lm = loss_of()
+                v[q] = old
+                fd = (lp - lm) / (2 * h)
+                assert abs(fd - grads[l][name][q]) < 2e-6 * max(1.0, abs(fd)), (l, name, q, fd, grads[l][name][q])
