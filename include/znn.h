@@ -157,6 +157,34 @@ int  znn_maxfilter3d_bwd(int32_t maps, znn_vec3 n, znn_vec3 win, const float* go
                          const int32_t* idx, float* gin, void* stream);
 
 /*
+ * Max-filtering whose window taps lie `sparsity` voxels apart; extents
+ * n - s (win - 1).  In a max-filtering ConvNet every filter multiplies the
+ * sparsity of all later layers by its window (Section 2, last paragraphs and
+ * the figure there); that includes later filters, which is what makes the net
+ * reproduce a sliding-window max-pooling ConvNet voxel for voxel.  Same idx
+ * convention, tie rule and reproducible summation order as the dense calls
+ * above, which are these with sparsity {1,1,1}.
+ */
+int  znn_maxfilter3d_sparse_fwd(int32_t maps, znn_vec3 n, znn_vec3 win, znn_vec3 sparsity,
+                                const float* in, float* out, int32_t* idx, void* stream);
+int  znn_maxfilter3d_sparse_bwd(int32_t maps, znn_vec3 n, znn_vec3 win, znn_vec3 sparsity,
+                                const float* gout, const int32_t* idx, float* gin, void* stream);
+
+/*
+ * Max-pooling (Section 2) and its Jacobian (Section 3.1).  The image is cut into
+ * blocks of p voxels per axis; n must be divisible by p (ZNN_EINVAL otherwise).
+ *   fwd: in [maps][n] -> out [maps][n/p] (block maxima), idx [maps][n/p] (flat offset
+ *        inside the input map of the voxel that supplied each maximum; among equal
+ *        values the smallest offset wins)
+ *   bwd: gout [maps][n/p], idx -> gin [maps][n]: all voxels of a block are zero except
+ *        the recorded one, which receives the block's gout.  Every gin voxel is written.
+ */
+int  znn_maxpool3d_fwd(int32_t maps, znn_vec3 n, znn_vec3 p, const float* in,
+                       float* out, int32_t* idx, void* stream);
+int  znn_maxpool3d_bwd(int32_t maps, znn_vec3 n, znn_vec3 p, const float* gout,
+                       const int32_t* idx, float* gin, void* stream);
+
+/*
  * Transfer-function edges and the update step that a training round needs
  * around the convolutions (Sections 2, 3.1, 3.2).  All are elementwise or
  * per-map reductions over images [maps][voxels].
@@ -165,11 +193,29 @@ int  znn_maxfilter3d_bwd(int32_t maps, znn_vec3 n, znn_vec3 win, const float* go
  *   znn_bias_grad    : gb[m] = sum of all voxels of g[m]   (fixed summation order)
  *   znn_square_loss_grad : g = out - target                (loss 1/2 sum (out-target)^2)
  *   znn_sgd_update   : p -= eta * g                        (Algorithm 3)
+ * znn_transfer_fn_fwd / _bwd take the nonlinearity as an argument: the three the
+ * paper names (Section 2, "Transfer function").  The backward edge multiplies gy by
+ * the derivative written through the forward output y.  ZNN_EINVAL for other values.
+ *   znn_cross_entropy_loss_grad : g = (out - target) / (out (1 - out)), the gradient of
+ *       - sum target log out + (1 - target) log (1 - out); out must lie strictly
+ *       inside (0, 1) (the partner of a logistic output layer).  The paper names the
+ *       Euclidean loss and leaves the others open; this is the second one built.
  */
+typedef enum znn_transfer_fn {
+    ZNN_RECTIFY  = 0,   /* y = max(v, 0)              dy/dv = (y > 0)    */
+    ZNN_LOGISTIC = 1,   /* y = 1 / (1 + exp(-v))      dy/dv = y (1 - y)  */
+    ZNN_TANH     = 2    /* y = tanh(v)                dy/dv = 1 - y^2    */
+} znn_transfer_fn;
+
 int  znn_transfer_fwd(int32_t maps, int64_t voxels, const float* x, const float* bias, float* y, void* stream);
 int  znn_transfer_bwd(int32_t maps, int64_t voxels, const float* gy, const float* y, float* gx, void* stream);
 int  znn_bias_grad(int32_t maps, int64_t voxels, const float* g, float* gb, void* stream);
+int  znn_transfer_fn_fwd(int32_t fn, int32_t maps, int64_t voxels, const float* x, const float* bias, float* y,
+                         void* stream);
+int  znn_transfer_fn_bwd(int32_t fn, int32_t maps, int64_t voxels, const float* gy, const float* y, float* gx,
+                         void* stream);
 int  znn_square_loss_grad(int64_t count, const float* out, const float* target, float* g, void* stream);
+int  znn_cross_entropy_loss_grad(int64_t count, const float* out, const float* target, float* g, void* stream);
 int  znn_sgd_update(int64_t count, float eta, const float* g, float* p, void* stream);
 
 /*

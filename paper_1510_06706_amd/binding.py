@@ -26,7 +26,10 @@ EXPORTS = [
     "znn_bias_grad", "znn_square_loss_grad", "znn_sgd_update", "znn_autotune_workspace_bytes",
     "znn_autotune", "znn_last_error", "znn_trace_enable", "znn_trace_collect",
     "znn_plan_memo_bytes", "znn_conv_set_memo", "znn_conv3d_wgrad_memo",
+    "znn_maxfilter3d_sparse_fwd", "znn_maxfilter3d_sparse_bwd", "znn_maxpool3d_fwd", "znn_maxpool3d_bwd",
+    "znn_transfer_fn_fwd", "znn_transfer_fn_bwd", "znn_cross_entropy_loss_grad",
 ]
+TRANSFER_FNS = {"rectify": 0, "logistic": 1, "tanh": 2}
 
 
 class Vec3(ctypes.Structure):
@@ -77,6 +80,13 @@ def lib():
             getattr(L, name).argtypes = [vp, vp, vp, vp, vp, sz, vp]
         L.znn_maxfilter3d_fwd.argtypes = [i32, Vec3, Vec3, vp, vp, vp, vp]
         L.znn_maxfilter3d_bwd.argtypes = [i32, Vec3, Vec3, vp, vp, vp, vp]
+        L.znn_maxfilter3d_sparse_fwd.argtypes = [i32, Vec3, Vec3, Vec3, vp, vp, vp, vp]
+        L.znn_maxfilter3d_sparse_bwd.argtypes = [i32, Vec3, Vec3, Vec3, vp, vp, vp, vp]
+        L.znn_maxpool3d_fwd.argtypes = [i32, Vec3, Vec3, vp, vp, vp, vp]
+        L.znn_maxpool3d_bwd.argtypes = [i32, Vec3, Vec3, vp, vp, vp, vp]
+        L.znn_transfer_fn_fwd.argtypes = [i32, i32, i64, vp, vp, vp, vp]
+        L.znn_transfer_fn_bwd.argtypes = [i32, i32, i64, vp, vp, vp, vp]
+        L.znn_cross_entropy_loss_grad.argtypes = [i64, vp, vp, vp, vp]
         L.znn_transfer_fwd.argtypes = [i32, i64, vp, vp, vp, vp]
         L.znn_transfer_bwd.argtypes = [i32, i64, vp, vp, vp, vp]
         L.znn_bias_grad.argtypes = [i32, i64, vp, vp, vp]
@@ -276,43 +286,79 @@ class Plan:
         return gw
 
 
-def maxfilter3d_fwd(inp, win, stream=None):
+def maxfilter3d_fwd(inp, win, sparsity=(1, 1, 1), stream=None):
     import torch
     maps, n = inp.shape[0], tuple(inp.shape[1:])
-    o = tuple(a - b + 1 for a, b in zip(n, win))
+    o = tuple(a - s * (b - 1) for a, b, s in zip(n, win, sparsity))
     if min(o) < 1:
         o = (0, 0, 0)
     out = torch.empty((maps,) + o, dtype=torch.float32, device=inp.device)
     idx = torch.empty((maps,) + o, dtype=torch.int32, device=inp.device)
-    _check(lib().znn_maxfilter3d_fwd(maps, _v3(n), _v3(win), _ptr(inp, torch.float32), _ptr(out), _ptr(idx),
-                                     _stream_ptr(stream)))
+    if tuple(sparsity) == (1, 1, 1):
+        _check(lib().znn_maxfilter3d_fwd(maps, _v3(n), _v3(win), _ptr(inp, torch.float32), _ptr(out), _ptr(idx),
+                                         _stream_ptr(stream)))
+    else:
+        _check(lib().znn_maxfilter3d_sparse_fwd(maps, _v3(n), _v3(win), _v3(sparsity), _ptr(inp, torch.float32),
+                                                _ptr(out), _ptr(idx), _stream_ptr(stream)))
     return out, idx
 
 
-def maxfilter3d_bwd(gout, idx, n, win, stream=None):
+def maxfilter3d_bwd(gout, idx, n, win, sparsity=(1, 1, 1), stream=None):
     import torch
     maps = gout.shape[0]
     gin = torch.empty((maps,) + tuple(n), dtype=torch.float32, device=gout.device)
-    _check(lib().znn_maxfilter3d_bwd(maps, _v3(n), _v3(win), _ptr(gout, torch.float32), _ptr(idx, torch.int32),
-                                     _ptr(gin), _stream_ptr(stream)))
+    if tuple(sparsity) == (1, 1, 1):
+        _check(lib().znn_maxfilter3d_bwd(maps, _v3(n), _v3(win), _ptr(gout, torch.float32), _ptr(idx, torch.int32),
+                                         _ptr(gin), _stream_ptr(stream)))
+    else:
+        _check(lib().znn_maxfilter3d_sparse_bwd(maps, _v3(n), _v3(win), _v3(sparsity), _ptr(gout, torch.float32),
+                                                _ptr(idx, torch.int32), _ptr(gin), _stream_ptr(stream)))
     return gin
 
 
-def transfer_fwd(x, bias, stream=None):
+def maxpool3d_fwd(inp, p, stream=None):
+    import torch
+    maps, n = inp.shape[0], tuple(inp.shape[1:])
+    o = tuple(a // b if b > 0 else 0 for a, b in zip(n, p))
+    out = torch.empty((maps,) + o, dtype=torch.float32, device=inp.device)
+    idx = torch.empty((maps,) + o, dtype=torch.int32, device=inp.device)
+    _check(lib().znn_maxpool3d_fwd(maps, _v3(n), _v3(p), _ptr(inp, torch.float32), _ptr(out), _ptr(idx),
+                                   _stream_ptr(stream)))
+    return out, idx
+
+
+def maxpool3d_bwd(gout, idx, n, p, stream=None):
+    import torch
+    maps = gout.shape[0]
+    gin = torch.empty((maps,) + tuple(n), dtype=torch.float32, device=gout.device)
+    _check(lib().znn_maxpool3d_bwd(maps, _v3(n), _v3(p), _ptr(gout, torch.float32), _ptr(idx, torch.int32),
+                                   _ptr(gin), _stream_ptr(stream)))
+    return gin
+
+
+def transfer_fwd(x, bias, fn="rectify", stream=None):
     import torch
     y = torch.empty_like(x)
     maps = x.shape[0]
-    _check(lib().znn_transfer_fwd(maps, x.numel() // maps, _ptr(x, torch.float32), _ptr(bias, torch.float32),
-                                  _ptr(y), _stream_ptr(stream)))
+    if fn == "rectify":
+        _check(lib().znn_transfer_fwd(maps, x.numel() // maps, _ptr(x, torch.float32), _ptr(bias, torch.float32),
+                                      _ptr(y), _stream_ptr(stream)))
+    else:
+        _check(lib().znn_transfer_fn_fwd(TRANSFER_FNS[fn], maps, x.numel() // maps, _ptr(x, torch.float32),
+                                         _ptr(bias, torch.float32), _ptr(y), _stream_ptr(stream)))
     return y
 
 
-def transfer_bwd(gy, y, stream=None):
+def transfer_bwd(gy, y, fn="rectify", stream=None):
     import torch
     gx = torch.empty_like(gy)
     maps = gy.shape[0]
-    _check(lib().znn_transfer_bwd(maps, gy.numel() // maps, _ptr(gy, torch.float32), _ptr(y, torch.float32),
-                                  _ptr(gx), _stream_ptr(stream)))
+    if fn == "rectify":
+        _check(lib().znn_transfer_bwd(maps, gy.numel() // maps, _ptr(gy, torch.float32), _ptr(y, torch.float32),
+                                      _ptr(gx), _stream_ptr(stream)))
+    else:
+        _check(lib().znn_transfer_fn_bwd(TRANSFER_FNS[fn], maps, gy.numel() // maps, _ptr(gy, torch.float32),
+                                         _ptr(y, torch.float32), _ptr(gx), _stream_ptr(stream)))
     return gx
 
 
@@ -330,6 +376,22 @@ def square_loss_grad(out, target, stream=None):
     _check(lib().znn_square_loss_grad(out.numel(), _ptr(out, torch.float32), _ptr(target, torch.float32),
                                       _ptr(g), _stream_ptr(stream)))
     return g
+
+
+def cross_entropy_loss_grad(out, target, stream=None):
+    import torch
+    g = torch.empty_like(out)
+    _check(lib().znn_cross_entropy_loss_grad(out.numel(), _ptr(out, torch.float32), _ptr(target, torch.float32),
+                                             _ptr(g), _stream_ptr(stream)))
+    return g
+
+
+def loss_grad(out, target, loss="square", stream=None):
+    if loss == "square":
+        return square_loss_grad(out, target, stream)
+    if loss == "cross_entropy":
+        return cross_entropy_loss_grad(out, target, stream)
+    raise ValueError(loss)
 
 
 def sgd_update(p, g, eta, stream=None):

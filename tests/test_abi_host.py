@@ -103,6 +103,20 @@ def test_filter_and_pointwise_validation():
     assert L.znn_maxfilter3d_fwd(1, v(4, 4, 4), v(2, 2, 2), null, fake, fake, null) == znn.ZNN_EINVAL
     assert L.znn_maxfilter3d_bwd(1, v(4, 4, 4), v(2, 0, 2), fake, fake, fake, null) == znn.ZNN_EINVAL
     assert L.znn_maxfilter3d_fwd(1, v(2048, 2048, 1024), v(2, 2, 2), fake, fake, fake, null) == znn.ZNN_EUNSUPPORTED
+    one = v(1, 1, 1)
+    assert L.znn_maxfilter3d_sparse_fwd(1, v(4, 4, 4), v(2, 2, 2), v(4, 1, 1), fake, fake, fake, null) == znn.ZNN_EINVAL
+    assert L.znn_maxfilter3d_sparse_fwd(1, v(5, 4, 4), v(2, 2, 2), v(0, 1, 1), fake, fake, fake, null) == znn.ZNN_EINVAL
+    assert L.znn_maxfilter3d_sparse_bwd(1, v(5, 4, 4), v(2, 2, 2), v(4, 1, 1), null, fake, fake, null) == znn.ZNN_EINVAL
+    assert L.znn_maxfilter3d_sparse_bwd(1, v(4, 4, 4), v(2, 2, 2), one, fake, fake, null, null) == znn.ZNN_EINVAL
+    assert L.znn_maxpool3d_fwd(1, v(5, 4, 4), v(2, 2, 2), fake, fake, fake, null) == znn.ZNN_EINVAL
+    assert "divisible" in znn.last_error()
+    assert L.znn_maxpool3d_fwd(1, v(4, 4, 4), v(2, 2, 2), fake, null, fake, null) == znn.ZNN_EINVAL
+    assert L.znn_maxpool3d_bwd(1, v(4, 4, 4), v(2, 0, 2), fake, fake, fake, null) == znn.ZNN_EINVAL
+    assert L.znn_transfer_fn_fwd(3, 1, 10, fake, fake, fake, null) == znn.ZNN_EINVAL
+    assert L.znn_transfer_fn_bwd(-1, 1, 10, fake, fake, fake, null) == znn.ZNN_EINVAL
+    assert L.znn_transfer_fn_fwd(1, 1, 10, null, fake, fake, null) == znn.ZNN_EINVAL
+    assert L.znn_cross_entropy_loss_grad(0, fake, fake, fake, null) == znn.ZNN_EINVAL
+    assert L.znn_cross_entropy_loss_grad(5, fake, null, fake, null) == znn.ZNN_EINVAL
     assert L.znn_transfer_fwd(0, 10, fake, fake, fake, null) == znn.ZNN_EINVAL
     assert L.znn_bias_grad(2, 10, null, fake, null) == znn.ZNN_EINVAL
     assert L.znn_sgd_update(0, 0.1, fake, fake, null) == znn.ZNN_EINVAL

@@ -72,19 +72,38 @@ def test_config5_large_layer_with_resident_kernel_spectra():
     sampled_layer_check(synth.CONFIG5, "fft", True, 4096, 4096, 1024)
 
 
+ONES = (1, 1, 1)
+
+
+def opt(spec, i, default):
+    return spec[i] if len(spec) > i else default
+
+
 @pytest.mark.parametrize("mode", ["direct", "fft", "auto"])
 def test_config3_training_round(mode):
+    check_training_round("config 3", znet.CONFIG3_LAYERS, znet.CONFIG3_INPUT, znet.config3_tensors(), mode)
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("mode", ["direct", "fft"])
+def test_config3_as_a_max_filtering_net_with_sparse_layers(mode):
+    """The same network with the sparsity doubling after every max-filter (Section 2, last
+    paragraphs): sparse convolutions and a sparse filter inside one training round."""
+    check_training_round("config 3 sparse", znet.CONFIG3_SPARSE_LAYERS, znet.CONFIG3_SPARSE_INPUT,
+                         znet.config3_sparse_tensors(), mode)
+
+
+def check_training_round(name, layers, in_shape, tensors, mode):
     import torch
-    layers = znet.CONFIG3_LAYERS
-    x, target, params = znet.config3_tensors()
+    x, target, params = tensors
     if mode == "auto":      # let the autotuner measure every convolutional layer first
-        sh = znet.shapes(layers, znet.CONFIG3_INPUT)
+        sh = znet.shapes(layers, in_shape)
         for l, spec in enumerate(layers):
             if spec[0] == "conv":
                 chosen, ms = znn.autotune(spec[1], spec[2], sh[l][1:], spec[3])
                 print("  autotune layer %d: %s  direct %.3f ms, fft %.3f ms"
                       % (l, "fft" if chosen == znn.ZNN_FFT else "direct", sum(ms[0]), sum(ms[1])), flush=True)
-    net = znet.Net(layers, znet.CONFIG3_INPUT, params, mode)
+    net = znet.Net(layers, in_shape, params, mode)
     record = []
     acts, aux, gout, grads = net.train_round(dev(x), dev(target), znet.CONFIG3_ETA, record)
     torch.cuda.synchronize()
@@ -101,8 +120,9 @@ def test_config3_training_round(mode):
         g_out = host(arriving[l]).astype(np.float64)
         if spec[0] == "conv":
             w = params[l]["w"]
-            assert rel_err(y, oracle.conv3d_fwd(a, w)) <= tol_of(l), ("fwd", l)
-            assert rel_err(host(grads[l]["w"]), oracle.conv3d_wgrad(a, g_out)) <= tol_of(l), ("wgrad", l)
+            sp = opt(spec, 4, ONES)
+            assert rel_err(y, oracle.conv3d_fwd(a, w, sp)) <= tol_of(l), ("fwd", l)
+            assert rel_err(host(grads[l]["w"]), oracle.conv3d_wgrad(a, g_out, sp)) <= tol_of(l), ("wgrad", l)
         elif spec[0] == "transfer":
             want = np.maximum(a + params[l]["b"].astype(np.float64)[:, None, None, None], 0.0)
             assert rel_err(y, want) <= 1e-6, ("transfer", l)
@@ -110,7 +130,7 @@ def test_config3_training_round(mode):
             g_in = g_out * (y > 0)
             assert rel_err(host(grads[l]["b"]), g_in.reshape(g_in.shape[0], -1).sum(1)) <= 1e-5, ("bias", l)
         else:
-            r_out, r_idx = oracle.maxfilter3d_fwd(a, spec[1])
+            r_out, r_idx = oracle.maxfilter3d_fwd(a, spec[1], opt(spec, 2, ONES))
             assert np.array_equal(y.astype(np.float64), r_out), ("maxfilter", l)
             assert np.array_equal(host(aux[l]), r_idx), ("maxfilter idx", l)
     # backward images: conv Jacobian and max-filter Jacobian, fed the GPU's incoming gradient
@@ -120,10 +140,10 @@ def test_config3_training_round(mode):
         g_out = host(arriving[l]).astype(np.float64)
         g_in = host(arriving[l - 1]).astype(np.float64)
         if spec[0] == "conv":
-            want = oracle.conv3d_bwd(g_out, params[l]["w"], net.shapes[l][1:])
+            want = oracle.conv3d_bwd(g_out, params[l]["w"], net.shapes[l][1:], opt(spec, 4, ONES))
             assert rel_err(g_in, want) <= tol_of(l), ("bwd", l)
         elif spec[0] == "maxfilter":
-            want = oracle.maxfilter3d_bwd(g_out, host(aux[l]), net.shapes[l][1:], spec[1])
+            want = oracle.maxfilter3d_bwd(g_out, host(aux[l]), net.shapes[l][1:], spec[1], opt(spec, 2, ONES))
             assert rel_err(g_in, want) <= 1e-6, ("maxfilter bwd", l)
 
     # end to end against the float64 round started from the same fp32 inputs
@@ -148,10 +168,26 @@ def test_config3_training_round(mode):
         for m, z, y, xx in bad:
             q = int(g_idx[m, z, y, xx])
             qz, qy, qx = np.unravel_index(q, a.shape[1:])
-            assert z <= qz < z + spec[1][0] and y <= qy < y + spec[1][1] and xx <= qx < xx + spec[1][2]
+            for got, at, w_, s_ in zip((qz, qy, qx), (z, y, xx), spec[1], opt(spec, 2, ONES)):
+                assert got in [at + s_ * t for t in range(w_)]
             assert abs(a[m].ravel()[q] - r_acts[l + 1][m, z, y, xx]) <= 1e-5 * np.max(np.abs(a))
         r_aux_sel[l] = g_idx
-    r_grads = onet.backward(layers, p64, r_acts, r_aux_sel, r_acts[-1] - target.astype(np.float64))
+    # The rectifier's gate is the same kind of decision: where the oracle's pre-activation is
+    # zero to rounding, an fp32 difference may open or close it.  Such voxels must be near
+    # zero in the oracle's own image; its backward pass then takes the GPU's gate there.
+    r_acts_sel = list(r_acts)
+    for l, spec in enumerate(layers):
+        if spec[0] != "transfer" or opt(spec, 1, "rectify") != "rectify":
+            continue
+        g_y = host(acts[l + 1])
+        bad = (g_y > 0) != (r_acts[l + 1] > 0)
+        if bad.any():
+            pre = r_acts[l] + p64[l]["b"][:, None, None, None]
+            assert np.max(np.abs(pre[bad])) <= 1e-5 * np.max(np.abs(pre))
+            fixed = r_acts[l + 1].copy()
+            fixed[bad] = g_y[bad]
+            r_acts_sel[l + 1] = fixed
+    r_grads = onet.backward(layers, p64, r_acts_sel, r_aux_sel, r_acts[-1] - target.astype(np.float64))
     r_new = [None if p is None else {k: v - znet.CONFIG3_ETA * r_grads[l][k] for k, v in p.items()}
              for l, p in enumerate(p64)]
     worst_g, worst_p = 0.0, 0.0
@@ -166,7 +202,7 @@ def test_config3_training_round(mode):
     flips = sum(int(np.sum(host(aux[l]) != r_aux[l])) for l in range(len(layers)) if r_aux[l] is not None)
     relu_flips = sum(int(np.sum((host(acts[l + 1]) > 0) != (r_acts[l + 1] > 0)))
                      for l, spec in enumerate(layers) if spec[0] == "transfer")
-    print("config 3 %s: modes %s loss %.6f (ref %.6f) worst gradient rel-err %.2e, worst parameter rel-err %.2e, "
+    print(name + " %s: modes %s loss %.6f (ref %.6f) worst gradient rel-err %.2e, worst parameter rel-err %.2e, "
           "argmax flips %d, rectifier flips %d" % (mode, [m for m in plan_modes if m is not None], gpu_loss, loss,
                                                    worst_g, worst_p, flips, relu_flips), flush=True)
     assert worst_g <= e2e and worst_p <= e2e

@@ -165,6 +165,95 @@ def test_maxfilter_is_exact_and_its_jacobian_matches(n, win, kind):
     assert rel_err(gin, ref_gin) <= 1e-6
 
 
+SPARSE_FILTERS = [((9, 8, 10), (2, 2, 2), (2, 2, 2)), ((7, 9, 6), (2, 3, 1), (3, 2, 4)),
+                  ((1, 30, 17), (1, 2, 3), (1, 4, 2)), ((30, 30, 30), (2, 2, 2), (4, 4, 4))]
+
+
+@pytest.mark.parametrize("kind", ["random", "ties"])
+@pytest.mark.parametrize("n,win,s", SPARSE_FILTERS)
+def test_sparse_maxfilter_is_exact_and_its_jacobian_matches(n, win, s, kind):
+    print("case", n, win, s, kind, flush=True)
+    maps = 4
+    x = synth.uniform_pm1(15, 0, (maps,) + n)
+    if kind == "ties":
+        x = np.maximum(np.round(x * 2), 0).astype(np.float32)
+    ref_out, ref_idx = oracle.maxfilter3d_fwd(x, win, s)
+    out, idx = znn.maxfilter3d_fwd(dev(x), win, s)
+    assert np.array_equal(host(out).astype(np.float64), ref_out)
+    assert np.array_equal(host(idx), ref_idx)
+    g = synth.uniform_pm1(16, 2, ref_out.shape)
+    gin = host(znn.maxfilter3d_bwd(dev(g), idx, n, win, s))
+    assert rel_err(gin, oracle.maxfilter3d_bwd(g, ref_idx, n, win, s)) <= 1e-6
+
+
+POOLS = [((4, 6, 8), (2, 2, 2)), ((6, 3, 4), (3, 1, 2)), ((1, 32, 27), (1, 4, 3)), ((2, 2, 2), (2, 2, 2)),
+         ((3, 4, 5), (1, 1, 1)), ((24, 26, 22), (2, 2, 2))]
+
+
+@pytest.mark.parametrize("kind", ["random", "ties"])
+@pytest.mark.parametrize("n,p", POOLS)
+def test_maxpool_is_exact_and_its_jacobian_matches(n, p, kind):
+    print("case", n, p, kind, flush=True)
+    maps = 5
+    x = synth.uniform_pm1(17, 0, (maps,) + n)
+    if kind == "ties":
+        x = np.maximum(np.round(x * 2), 0).astype(np.float32)
+        x[0].flat[::3] = -0.0
+    ref_out, ref_idx = oracle.maxpool3d_fwd(x, p)
+    out, idx = znn.maxpool3d_fwd(dev(x), p)
+    assert np.array_equal(host(out).astype(np.float64), ref_out)
+    assert np.array_equal(host(idx), ref_idx)
+    g = synth.uniform_pm1(18, 2, ref_out.shape)
+    gin = host(znn.maxpool3d_bwd(dev(g), idx, n, p))
+    assert np.array_equal(gin.astype(np.float64), oracle.maxpool3d_bwd(g, ref_idx, n, p))
+
+
+@pytest.mark.parametrize("fn", ["rectify", "logistic", "tanh"])
+def test_transfer_functions_match_the_oracle(fn):
+    maps = 6
+    x = synth.uniform_pm1(19, 0, (maps, 9, 10, 11), 4.0)
+    b = synth.uniform_pm1(19, 4, (maps,), 0.5)
+    y = host(znn.transfer_fwd(dev(x), dev(b), fn))
+    assert rel_err(y, oracle.transfer_fwd(x, b, fn)) <= 1e-6
+    gy = synth.uniform_pm1(19, 2, x.shape)
+    gx = host(znn.transfer_bwd(dev(gy), dev(y), fn))
+    assert rel_err(gx, oracle.transfer_bwd(gy, y, fn)) <= 1e-6
+
+
+def test_cross_entropy_loss_gradient_matches_the_oracle():
+    y = (0.02 + 0.96 * synth.uniform_01(20, 0, (3, 7, 8, 9))).astype(np.float32)
+    t = synth.uniform_01(20, 3, y.shape)
+    g = host(znn.loss_grad(dev(y), dev(t), "cross_entropy"))
+    assert rel_err(g, oracle.loss_grad(y, t, "cross_entropy")) <= 1e-6
+    assert np.array_equal(host(znn.loss_grad(dev(y), dev(t), "square")), y - t)
+
+
+def test_small_net_with_every_layer_kind_matches_the_oracle_round():
+    """conv (dense and sparse), all three transfer functions, dense and sparse max-filter,
+    max-pooling and the cross-entropy loss in one training round."""
+    from oracle import net as onet
+    from paper_1510_06706_amd import net as znet
+    layers = [("conv", 2, 5, (2, 3, 2)), ("transfer", "tanh"), ("maxfilter", (2, 1, 2)),
+              ("conv", 5, 4, (2, 2, 1), (2, 1, 2)), ("transfer",), ("maxfilter", (2, 2, 1), (2, 1, 2)),
+              ("maxpool", (1, 2, 2)), ("conv", 4, 3, (1, 2, 2)), ("transfer", "logistic")]
+    in_shape = (2, 10, 12, 14)
+    x, target, params = znet.net_tensors(layers, in_shape, 31)
+    for mode in ("direct", "fft"):
+        net = znet.Net(layers, in_shape, params, mode)
+        acts, aux, gout, grads = net.train_round(dev(x), dev(target), 1e-2, loss="cross_entropy")
+        p64 = [None if p is None else {k: v.astype(np.float64) for k, v in p.items()} for p in params]
+        loss, r_acts, r_aux, r_grads, r_new = onet.train_round(layers, p64, x, target, 1e-2, "cross_entropy")
+        assert rel_err(host(acts[-1]), r_acts[-1]) <= TOL[mode]
+        for l, a in enumerate(r_aux):
+            if a is not None:
+                assert np.array_equal(host(aux[l]), a), ("argmax", l)
+        for l, g in enumerate(r_grads):
+            if g is not None:
+                for k in g:
+                    assert rel_err(host(grads[l][k]), g[k]) <= TOL[mode], (mode, l, k)
+                    assert rel_err(host(net.params[l][k]), r_new[l][k]) <= TOL[mode], (mode, l, k)
+
+
 def test_pointwise_steps_of_a_training_round():
     maps, vox = 7, 1000
     x = synth.uniform_pm1(8, 0, (maps, 10, 10, 10))
