@@ -232,6 +232,44 @@ int  znn_autotune(const znn_conv_desc* desc, void* ws, size_t ws_bytes, void* st
                   int32_t* chosen_mode, float ms[2][3]);
 
 /*
+ * Whole-round choice under a memory budget (Section 4: memoizing the transforms
+ * of images and kernels trades memory for a third fewer transforms, Table 2).
+ * Three ways to run one training round of a layer are timed as a whole
+ * (forward, then backward, then kernel gradient; 2 warm-up rounds, 5 timed):
+ *   ZNN_STRATEGY_DIRECT    the direct method in all three passes
+ *   ZNN_STRATEGY_FFT       the FFT method, every pass transforms what it needs
+ *   ZNN_STRATEGY_FFT_MEMO  the FFT method with the kernels transformed once per
+ *                          round and shared by forward and backward
+ *                          (znn_conv_prepare_kernels) and with the node spectra
+ *                          of forward and backward kept for the kernel gradient
+ *                          (znn_conv_set_memo + znn_conv3d_wgrad_memo)
+ * bytes[t] is the device memory strategy t holds during a round beyond the
+ * layer's own tensors (workspace, kernel spectra, memoized node spectra).  A
+ * strategy whose bytes exceed memory_budget is not run (ms[t] = INFINITY) and
+ * cannot be chosen; ZNN_EWORKSPACE if none fits.  `chosen` is the fastest one
+ * that ran; its method (direct / FFT) is also stored in the cache that
+ * ZNN_AUTO plans consult.  `ws` must hold the layer's tensors plus the largest
+ * strategy that fits the budget; znn_autotune_round_workspace_bytes returns
+ * that size for an unlimited budget, which is always enough.  Synchronises
+ * `stream` with the host.
+ */
+typedef enum znn_strategy {
+    ZNN_STRATEGY_DIRECT   = 0,
+    ZNN_STRATEGY_FFT      = 1,
+    ZNN_STRATEGY_FFT_MEMO = 2
+} znn_strategy;
+
+typedef struct znn_round_report {
+    float    ms[3];      /* mean milliseconds per round, indexed by znn_strategy */
+    uint64_t bytes[3];   /* device bytes held during a round, indexed by znn_strategy */
+    int32_t  chosen;     /* znn_strategy */
+} znn_round_report;
+
+int  znn_autotune_round_workspace_bytes(const znn_conv_desc* desc, size_t* bytes);
+int  znn_autotune_round(const znn_conv_desc* desc, uint64_t memory_budget, void* ws, size_t ws_bytes,
+                        void* stream, znn_round_report* report);
+
+/*
  * Kernel-level timing for benchmarks and roofline reports.  While enabled, every
  * kernel the library launches is bracketed by two HIP events on its stream.
  * znn_trace_collect waits for the recorded launches, returns them in launch

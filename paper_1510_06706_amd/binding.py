@@ -28,7 +28,9 @@ EXPORTS = [
     "znn_plan_memo_bytes", "znn_conv_set_memo", "znn_conv3d_wgrad_memo",
     "znn_maxfilter3d_sparse_fwd", "znn_maxfilter3d_sparse_bwd", "znn_maxpool3d_fwd", "znn_maxpool3d_bwd",
     "znn_transfer_fn_fwd", "znn_transfer_fn_bwd", "znn_cross_entropy_loss_grad",
+    "znn_autotune_round_workspace_bytes", "znn_autotune_round",
 ]
+STRATEGIES = ("direct", "fft", "fft_memo")
 TRANSFER_FNS = {"rectify": 0, "logistic": 1, "tanh": 2}
 
 
@@ -43,6 +45,10 @@ class ConvDesc(ctypes.Structure):
 
 class TraceRecord(ctypes.Structure):
     _fields_ = [("name", ctypes.c_char * 56), ("ms", ctypes.c_float)]
+
+
+class RoundReport(ctypes.Structure):
+    _fields_ = [("ms", ctypes.c_float * 3), ("bytes", ctypes.c_uint64 * 3), ("chosen", ctypes.c_int32)]
 
 
 class ZnnError(RuntimeError):
@@ -95,6 +101,9 @@ def lib():
         L.znn_autotune_workspace_bytes.argtypes = [ctypes.POINTER(ConvDesc), ctypes.POINTER(sz)]
         L.znn_autotune.argtypes = [ctypes.POINTER(ConvDesc), vp, sz, vp, ctypes.POINTER(i32),
                                    ctypes.POINTER(ctypes.c_float * 3 * 2)]
+        L.znn_autotune_round_workspace_bytes.argtypes = [ctypes.POINTER(ConvDesc), ctypes.POINTER(sz)]
+        L.znn_autotune_round.argtypes = [ctypes.POINTER(ConvDesc), ctypes.c_uint64, vp, sz, vp,
+                                         ctypes.POINTER(RoundReport)]
         L.znn_plan_memo_bytes.argtypes = [vp, ctypes.POINTER(sz)]
         L.znn_conv_set_memo.argtypes = [vp, vp, sz]
         L.znn_conv3d_wgrad_memo.argtypes = [vp, vp, vp, sz, vp]
@@ -209,7 +218,9 @@ class Plan:
         """Transforms all kernels once; the spectra stay resident in a buffer this object owns."""
         import torch
         need = self.spectra_bytes()
-        buf = torch.empty(need + 256, dtype=torch.uint8, device=w.device)
+        buf = getattr(self, "_spectra", None)
+        if buf is None or buf.numel() != need + 256 or buf.device != w.device:
+            buf = torch.empty(need + 256, dtype=torch.uint8, device=w.device)
         aligned = (buf.data_ptr() + 255) & ~255
         ws, wsb = self._workspace(ZNN_PASS_FWD, w.device)
         _check(lib().znn_conv_prepare_kernels(self._h, _ptr(w, torch.float32), ctypes.c_void_p(aligned), need,
@@ -407,10 +418,10 @@ def autotune_workspace_bytes(desc: ConvDesc) -> int:
     return b.value
 
 
-def autotune(fan_in, fan_out, image, kernel, device="cuda:0", stream=None):
+def autotune(fan_in, fan_out, image, kernel, device="cuda:0", stream=None, sparsity=(1, 1, 1)):
     """Returns (chosen mode, ms[method][pass]) and caches the choice for mode='auto' plans."""
     import torch
-    desc = make_desc(fan_in, fan_out, image, kernel, "auto")
+    desc = make_desc(fan_in, fan_out, image, kernel, "auto", sparsity)
     need = autotune_workspace_bytes(desc)
     buf = torch.empty(need + 256, dtype=torch.uint8, device=device)
     aligned = (buf.data_ptr() + 255) & ~255
@@ -419,6 +430,25 @@ def autotune(fan_in, fan_out, image, kernel, device="cuda:0", stream=None):
     _check(lib().znn_autotune(ctypes.byref(desc), ctypes.c_void_p(aligned), need, _stream_ptr(stream),
                               ctypes.byref(chosen), ctypes.byref(ms)))
     return chosen.value, [[ms[m][p] for p in range(3)] for m in range(2)]
+
+
+def autotune_round(fan_in, fan_out, image, kernel, memory_budget=None, sparsity=(1, 1, 1), device="cuda:0",
+                   stream=None):
+    """Times a whole training round of the layer as direct / FFT / FFT with memoized spectra,
+    leaving out what exceeds ``memory_budget`` bytes (None = no limit).  Returns
+    (chosen strategy name, {name: ms}, {name: bytes})."""
+    import torch
+    desc = make_desc(fan_in, fan_out, image, kernel, "auto", sparsity)
+    b = ctypes.c_size_t(0)
+    _check(lib().znn_autotune_round_workspace_bytes(ctypes.byref(desc), ctypes.byref(b)))
+    budget = (1 << 62) if memory_budget is None else int(memory_budget)
+    buf = torch.empty(b.value + 256, dtype=torch.uint8, device=device)
+    aligned = (buf.data_ptr() + 255) & ~255
+    rep = RoundReport()
+    _check(lib().znn_autotune_round(ctypes.byref(desc), budget, ctypes.c_void_p(aligned), b.value,
+                                    _stream_ptr(stream), ctypes.byref(rep)))
+    return (STRATEGIES[rep.chosen], {n: float(rep.ms[i]) for i, n in enumerate(STRATEGIES)},
+            {n: int(rep.bytes[i]) for i, n in enumerate(STRATEGIES)})
 
 
 def trace_enable(on: bool):

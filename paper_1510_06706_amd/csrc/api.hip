@@ -12,6 +12,8 @@
 
 #include "znn_internal.h"
 
+#include <algorithm>
+
 namespace znn {
 
 static thread_local char g_err[512] = "";
@@ -452,6 +454,135 @@ int znn_autotune(const znn_conv_desc* desc, void* ws, size_t ws_bytes, void* str
         g_tune[key_of(*desc)] = choice;
     }
     *chosen_mode = choice;
+    return ZNN_OK;
+}
+
+// ---- whole-round strategies under a memory budget (Section 4, memoization)
+struct RoundNeeds {
+    size_t scratch[3];      // workspace, kernel spectra, memoized node spectra per strategy (summed below)
+    size_t total[3];
+};
+
+static RoundNeeds round_needs(const Geom& g, bool fft_ok)
+{
+    RoundNeeds r = {};
+    size_t d = 0, f = 0, fm = 0;
+    for (int pass = 0; pass < 3; ++pass) {
+        d = std::max(d, direct_workspace_bytes(g, pass));
+        if (fft_ok) {
+            f = std::max(f, fft_workspace(g, pass, false).total);
+            fm = std::max(fm, fft_workspace(g, pass, true).total);
+        }
+    }
+    r.total[ZNN_STRATEGY_DIRECT] = d;
+    r.total[ZNN_STRATEGY_FFT] = f;
+    r.total[ZNN_STRATEGY_FFT_MEMO] = fft_ok
+        ? fm + fft_spectra_bytes(g) + align256(sizeof(float2) * (size_t)(g.f + g.fo) * g.svol()) : 0;
+    return r;
+}
+
+int znn_autotune_round_workspace_bytes(const znn_conv_desc* desc, size_t* bytes)
+{
+    if (!bytes) return fail(ZNN_EINVAL, "NULL argument");
+    Geom g;
+    int rc = validate_desc(desc, &g);
+    if (rc != ZNN_OK) return rc;
+    const bool fft_ok = g.Nz <= kMaxFftExtent && g.Ny <= kMaxFftExtent && g.Nx <= kMaxFftExtent;
+    const RoundNeeds need = round_needs(g, fft_ok);
+    size_t off[6];
+    *bytes = tune_tensor_bytes(g, off) + std::max(need.total[0], std::max(need.total[1], need.total[2]));
+    return ZNN_OK;
+}
+
+int znn_autotune_round(const znn_conv_desc* desc, uint64_t memory_budget, void* ws, size_t ws_bytes,
+                       void* stream, znn_round_report* report)
+{
+    if (!report) return fail(ZNN_EINVAL, "NULL argument");
+    Geom g;
+    int rc = validate_desc(desc, &g);
+    if (rc != ZNN_OK) return rc;
+    const bool fft_ok = g.Nz <= kMaxFftExtent && g.Ny <= kMaxFftExtent && g.Nx <= kMaxFftExtent;
+    const RoundNeeds need = round_needs(g, fft_ok);
+    bool run[3];
+    size_t scratch = 0;
+    int candidates = 0;
+    for (int t = 0; t < 3; ++t) {
+        report->ms[t] = INFINITY;
+        report->bytes[t] = need.total[t];
+        run[t] = (t == ZNN_STRATEGY_DIRECT || fft_ok) && need.total[t] <= memory_budget;
+        if (run[t]) { scratch = std::max(scratch, need.total[t]); ++candidates; }
+    }
+    report->chosen = -1;
+    if (!candidates)
+        return fail(ZNN_EWORKSPACE, "no strategy fits the memory budget of %llu bytes (direct needs %zu)",
+                    (unsigned long long)memory_budget, need.total[0]);
+    size_t off[6];
+    const size_t tensors = tune_tensor_bytes(g, off);
+    if (!ws) return fail(ZNN_EWORKSPACE, "workspace is NULL");
+    if (!aligned256(ws)) return fail(ZNN_EWORKSPACE, "workspace is not 256-byte aligned");
+    if (ws_bytes < tensors + scratch)
+        return fail(ZNN_EWORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, tensors + scratch);
+    hipStream_t s = (hipStream_t)stream;
+    char* base = (char*)ws;
+    float* in = (float*)(base + off[0]);
+    float* w = (float*)(base + off[1]);
+    float* gout = (float*)(base + off[2]);
+    float* gin = (float*)(base + off[3]);
+    float* gw = (float*)(base + off[4]);
+    float* out = (float*)(base + off[5]);
+    char* scr = base + tensors;
+    if ((rc = fill_pattern(in, (long)g.f * g.nvol(), 1.0f, s)) != ZNN_OK) return rc;
+    if ((rc = fill_pattern(w, (long)g.fo * g.f * g.kvol(), 1.0f / std::sqrt((float)(g.f * g.kvol())), s)) != ZNN_OK) return rc;
+    if ((rc = fill_pattern(gout, (long)g.fo * g.ovol(), 1.0f, s)) != ZNN_OK) return rc;
+    // memoized strategy: [pass workspace | kernel spectra | node spectra]
+    size_t memo_ws = 0;
+    if (fft_ok)
+        for (int pass = 0; pass < 3; ++pass) memo_ws = std::max(memo_ws, fft_workspace(g, pass, true).total);
+    float2* What = (float2*)(scr + memo_ws);
+    float2* Ihat = (float2*)(scr + memo_ws + fft_spectra_bytes(g));
+    float2* Ghat = Ihat + (size_t)g.f * g.svol();
+
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
+        return fail(ZNN_EHIP, "hipEventCreate failed");
+    const int warm = 2, timed = 5;
+    for (int t = 0; t < 3 && rc == ZNN_OK; ++t) {
+        if (!run[t]) continue;
+        for (int it = 0; it < warm + timed && rc == ZNN_OK; ++it) {
+            if (it == warm) (void)hipEventRecord(e0, s);
+            if (t == ZNN_STRATEGY_DIRECT) {
+                rc = direct_fwd(g, in, w, out, scr, s);
+                if (rc == ZNN_OK) rc = direct_bwd(g, gout, w, gin, scr, s);
+                if (rc == ZNN_OK) rc = direct_wgrad(g, in, gout, gw, scr, s);
+            } else if (t == ZNN_STRATEGY_FFT) {
+                rc = fft_fwd(g, in, w, nullptr, out, scr, nullptr, s);
+                if (rc == ZNN_OK) rc = fft_bwd(g, gout, w, nullptr, gin, scr, nullptr, s);
+                if (rc == ZNN_OK) rc = fft_wgrad(g, in, gout, gw, scr, s);
+            } else {
+                rc = fft_kernel_spectra(g, w, What, s);
+                if (rc == ZNN_OK) rc = fft_fwd(g, in, nullptr, What, out, scr, Ihat, s);
+                if (rc == ZNN_OK) rc = fft_bwd(g, gout, nullptr, What, gin, scr, Ghat, s);
+                if (rc == ZNN_OK) rc = fft_wgrad_from_spectra(g, Ihat, Ghat, gw, scr, s);
+            }
+        }
+        if (rc != ZNN_OK) break;
+        (void)hipEventRecord(e1, s);
+        if (hipEventSynchronize(e1) != hipSuccess) { rc = fail(ZNN_EHIP, "hipEventSynchronize failed"); break; }
+        float ms = 0.f;
+        (void)hipEventElapsedTime(&ms, e0, e1);
+        report->ms[t] = ms / timed;
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc != ZNN_OK) return rc;
+    int best = -1;
+    for (int t = 0; t < 3; ++t)
+        if (run[t] && (best < 0 || report->ms[t] < report->ms[best])) best = t;
+    report->chosen = best;
+    {
+        std::lock_guard<std::mutex> lk(g_tune_mu);
+        g_tune[key_of(*desc)] = best == ZNN_STRATEGY_DIRECT ? ZNN_DIRECT : ZNN_FFT;
+    }
     return ZNN_OK;
 }
 

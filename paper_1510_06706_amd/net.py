@@ -101,9 +101,15 @@ def config3_sparse_tensors():
 
 
 class Net:
-    """Device-side state of a layered net: plans per convolution, parameters as CUDA tensors."""
+    """Device-side state of a layered net: plans per convolution, parameters as CUDA tensors.
 
-    def __init__(self, layers, in_shape, params, mode="auto", device="cuda:0"):
+    ``mode`` is "direct", "fft", "auto" (cached autotuner choice or cost model), a list with
+    one entry per layer, or "tuned": every convolutional layer is timed as a whole round in
+    the three strategies direct / FFT / FFT with memoized spectra (Section 4) and takes the
+    fastest one whose buffers fit ``memory_budget`` bytes (per layer; None = no limit).
+    """
+
+    def __init__(self, layers, in_shape, params, mode="auto", device="cuda:0", memory_budget=None):
         import torch
         self.layers = list(layers)
         self.shapes = shapes(layers, in_shape)
@@ -111,10 +117,21 @@ class Net:
         self.params = [None if p is None else {k: torch.from_numpy(np.ascontiguousarray(v)).to(device)
                                                for k, v in p.items()} for p in params]
         self.plans = []
+        self.strategy = [None] * len(self.layers)
+        self.tuning = {}
         for l, spec in enumerate(self.layers):
             if spec[0] == "conv":
                 m = mode[l] if isinstance(mode, (list, tuple)) else mode
-                self.plans.append(znn.Plan(spec[1], spec[2], self.shapes[l][1:], spec[3], m, _opt(spec, 4, ONES)))
+                sp = _opt(spec, 4, ONES)
+                if m == "tuned":
+                    m, ms, nbytes = znn.autotune_round(spec[1], spec[2], self.shapes[l][1:], spec[3],
+                                                       memory_budget, sp, device)
+                    self.tuning[l] = (m, ms, nbytes)
+                plan = znn.Plan(spec[1], spec[2], self.shapes[l][1:], spec[3], "fft" if m == "fft_memo" else m, sp)
+                if m == "fft_memo":
+                    plan.enable_memo(device)
+                self.strategy[l] = m
+                self.plans.append(plan)
             else:
                 self.plans.append(None)
 
@@ -125,7 +142,10 @@ class Net:
         acts, aux = [x], [None] * len(self.layers)
         for l, spec in enumerate(self.layers):
             a = acts[-1]
-            if spec[0] == "conv":
+            if spec[0] == "conv" and self.strategy[l] == "fft_memo":
+                self.plans[l].prepare_kernels(self.params[l]["w"])      # once per round: w changes every update
+                y = self.plans[l].fwd(a, None)
+            elif spec[0] == "conv":
                 y = self.plans[l].fwd(a, self.params[l]["w"])
             elif spec[0] == "transfer":
                 y = znn.transfer_fwd(a, self.params[l]["b"], _opt(spec, 1, "rectify"))
@@ -144,7 +164,11 @@ class Net:
             spec = self.layers[l]
             if record is not None:
                 record.append((l, g))
-            if spec[0] == "conv":
+            if spec[0] == "conv" and self.strategy[l] == "fft_memo" and l > 0:
+                # backward first: it leaves the spectra of g next to those of the forward input
+                g = self.plans[l].bwd(g, None)
+                grads[l] = {"w": self.plans[l].wgrad_memo(device=self.device)}
+            elif spec[0] == "conv":
                 grads[l] = {"w": self.plans[l].wgrad(acts[l], g)}
                 g = self.plans[l].bwd(g, self.params[l]["w"]) if l > 0 else None
             elif spec[0] == "transfer":

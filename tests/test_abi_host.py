@@ -144,3 +144,23 @@ def test_memo_entry_points_validate_their_state():
     assert "forward and the backward" in znn.last_error()
     assert L.znn_conv_set_memo(p._h, null, 0) == znn.ZNN_OK
     p.close()
+
+
+def test_round_autotuner_validates_before_launching():
+    L = znn.lib()
+    fake, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
+    d = znn.make_desc(4, 4, (12, 12, 12), (3, 3, 3), "auto")
+    rep = znn.RoundReport()
+    need, single = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    assert L.znn_autotune_round_workspace_bytes(ctypes.byref(d), ctypes.byref(need)) == znn.ZNN_OK
+    assert L.znn_autotune_workspace_bytes(ctypes.byref(d), ctypes.byref(single)) == znn.ZNN_OK
+    assert need.value >= single.value > 0
+    assert L.znn_autotune_round_workspace_bytes(ctypes.byref(d), None) == znn.ZNN_EINVAL
+    assert L.znn_autotune_round(ctypes.byref(d), 1 << 40, fake, need.value, null, None) == znn.ZNN_EINVAL
+    assert L.znn_autotune_round(ctypes.byref(d), 0, fake, need.value, null, ctypes.byref(rep)) == znn.ZNN_EWORKSPACE
+    assert "budget" in znn.last_error()
+    assert rep.bytes[2] > rep.bytes[1] > rep.bytes[0] > 0 and rep.chosen == -1
+    assert L.znn_autotune_round(ctypes.byref(d), 1 << 40, null, need.value, null, ctypes.byref(rep)) == znn.ZNN_EWORKSPACE
+    assert L.znn_autotune_round(ctypes.byref(d), 1 << 40, fake, 16, null, ctypes.byref(rep)) == znn.ZNN_EWORKSPACE
+    bad = znn.make_desc(4, 4, (2, 12, 12), (3, 3, 3), "auto")
+    assert L.znn_autotune_round(ctypes.byref(bad), 1 << 40, fake, need.value, null, ctypes.byref(rep)) == znn.ZNN_EINVAL

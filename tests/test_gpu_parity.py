@@ -282,3 +282,51 @@ def test_autotuner_times_both_methods_and_caches_its_choice():
     p = znn.Plan(f, fo, n, k, "auto")
     assert p.mode == chosen
     p.close()
+
+
+def test_round_autotuner_respects_the_memory_budget():
+    f, fo, n, k = 8, 8, (20, 20, 20), (3, 3, 3)
+    chosen, ms, nbytes = znn.autotune_round(f, fo, n, k)
+    assert all(np.isfinite(v) and v > 0 for v in ms.values())
+    assert chosen == min(ms, key=ms.get)
+    assert nbytes["fft_memo"] > nbytes["fft"] > nbytes["direct"] > 0
+    p = znn.Plan(f, fo, n, k, "auto")
+    assert p.mode == (znn.ZNN_DIRECT if chosen == "direct" else znn.ZNN_FFT)
+    p.close()
+    # a budget just below what memoization holds rules it out, and only it
+    chosen2, ms2, _ = znn.autotune_round(f, fo, n, k, memory_budget=nbytes["fft_memo"] - 1)
+    assert np.isinf(ms2["fft_memo"]) and np.isfinite(ms2["fft"]) and np.isfinite(ms2["direct"])
+    assert chosen2 in ("direct", "fft") and chosen2 == min(ms2, key=ms2.get)
+    chosen3, ms3, _ = znn.autotune_round(f, fo, n, k, memory_budget=nbytes["direct"])
+    assert chosen3 == "direct" and np.isinf(ms3["fft"]) and np.isinf(ms3["fft_memo"])
+    with pytest.raises(znn.ZnnError) as e:
+        znn.autotune_round(f, fo, n, k, memory_budget=nbytes["direct"] - 1)
+    assert e.value.code == znn.ZNN_EWORKSPACE
+
+
+@pytest.mark.parametrize("mode", ["fft_memo", "tuned"])
+def test_training_round_with_memoized_spectra_matches_the_oracle(mode):
+    """Kernels transformed once per round and shared by forward and backward, node spectra
+    kept for the kernel gradient (Section 4, memoization); two rounds, so that the kernel
+    spectra are refreshed after the update."""
+    from oracle import net as onet
+    from paper_1510_06706_amd import net as znet
+    layers = [("conv", 2, 6, (3, 3, 3)), ("transfer",), ("maxfilter", (2, 2, 2)),
+              ("conv", 6, 5, (2, 3, 2), (2, 2, 2)), ("transfer", "tanh"),
+              ("conv", 5, 3, (3, 1, 2)), ("transfer", "logistic")]
+    in_shape = (2, 14, 15, 16)
+    x, target, params = znet.net_tensors(layers, in_shape, 41)
+    net = znet.Net(layers, in_shape, params, mode)
+    if mode == "tuned":
+        assert set(net.tuning) == {0, 3, 5}
+        print("tuned strategies", {l: t[0] for l, t in net.tuning.items()}, flush=True)
+    p64 = [None if p is None else {k: v.astype(np.float64) for k, v in p.items()} for p in params]
+    for rnd in range(2):
+        acts, aux, gout, grads = net.train_round(dev(x), dev(target), 0.05)
+        loss, r_acts, r_aux, r_grads, p64 = onet.train_round(layers, p64, x, target, 0.05)
+        assert rel_err(host(acts[-1]), r_acts[-1]) <= 1e-3, rnd
+        for l, g in enumerate(r_grads):
+            if g is not None:
+                for k in g:
+                    assert rel_err(host(grads[l][k]), g[k]) <= 1e-3, (rnd, l, k)
+                    assert rel_err(host(net.params[l][k]), p64[l][k]) <= 1e-3, (rnd, l, k)
