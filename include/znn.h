@@ -219,6 +219,15 @@ int  znn_cross_entropy_loss_grad(int64_t count, const float* out, const float* t
 int  znn_sgd_update(int64_t count, float eta, const float* g, float* p, void* stream);
 
 /*
+ * Node sum of a general computation graph (Section 2: a node's image is the sum of the
+ * outputs of the edges converging on it; Section 3.1: a node's backward image is the
+ * sum over its outgoing edges): y += x, elementwise.  The convolution calls above sum
+ * the edges of ONE fully connected bundle themselves; this adds the results of several
+ * bundles (branches with different kernels or sparsity) that meet at one node.
+ */
+int  znn_accumulate(int64_t count, const float* x, float* y, void* stream);
+
+/*
  * Layer-wise choice between the direct and the FFT method (Section 4): times
  * forward + backward + kernel gradient in both methods on the given shape
  * (2 warm-up rounds, 5 timed), stores the faster one in a process-wide cache

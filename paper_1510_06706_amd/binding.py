@@ -28,7 +28,7 @@ EXPORTS = [
     "znn_plan_memo_bytes", "znn_conv_set_memo", "znn_conv3d_wgrad_memo",
     "znn_maxfilter3d_sparse_fwd", "znn_maxfilter3d_sparse_bwd", "znn_maxpool3d_fwd", "znn_maxpool3d_bwd",
     "znn_transfer_fn_fwd", "znn_transfer_fn_bwd", "znn_cross_entropy_loss_grad",
-    "znn_autotune_round_workspace_bytes", "znn_autotune_round",
+    "znn_autotune_round_workspace_bytes", "znn_autotune_round", "znn_accumulate",
 ]
 STRATEGIES = ("direct", "fft", "fft_memo")
 TRANSFER_FNS = {"rectify": 0, "logistic": 1, "tanh": 2}
@@ -97,6 +97,7 @@ def lib():
         L.znn_transfer_bwd.argtypes = [i32, i64, vp, vp, vp, vp]
         L.znn_bias_grad.argtypes = [i32, i64, vp, vp, vp]
         L.znn_square_loss_grad.argtypes = [i64, vp, vp, vp, vp]
+        L.znn_accumulate.argtypes = [i64, vp, vp, vp]
         L.znn_sgd_update.argtypes = [i64, ctypes.c_float, vp, vp, vp]
         L.znn_autotune_workspace_bytes.argtypes = [ctypes.POINTER(ConvDesc), ctypes.POINTER(sz)]
         L.znn_autotune.argtypes = [ctypes.POINTER(ConvDesc), vp, sz, vp, ctypes.POINTER(i32),
@@ -403,6 +404,14 @@ def loss_grad(out, target, loss="square", stream=None):
     if loss == "cross_entropy":
         return cross_entropy_loss_grad(out, target, stream)
     raise ValueError(loss)
+
+
+def accumulate(y, x, stream=None):
+    """y += x (node sum of a computation graph)."""
+    import torch
+    assert y.shape == x.shape
+    _check(lib().znn_accumulate(y.numel(), _ptr(x, torch.float32), _ptr(y, torch.float32), _stream_ptr(stream)))
+    return y
 
 
 def sgd_update(p, g, eta, stream=None):

@@ -186,6 +186,13 @@ k_sub(long total, const float* __restrict__ a, const float* __restrict__ b, floa
 }
 
 __global__ void __launch_bounds__(256)
+k_accumulate(long total, const float* __restrict__ x, float* __restrict__ y)
+{
+    const long t = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < total) y[t] = y[t] + x[t];
+}
+
+__global__ void __launch_bounds__(256)
 k_sgd(long total, float eta, const float* __restrict__ g, float* __restrict__ p)
 {
     const long t = (long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -402,6 +409,16 @@ int znn_cross_entropy_loss_grad(int64_t count, const float* out, const float* ta
     ZNN_LAUNCH("loss gradient (cross-entropy)", (hipStream_t)stream, k_cross_entropy_grad,
                dim3((unsigned)((count + 255) / 256)), dim3(256), 0, (long)count, out, target, g);
     return check_launch("loss gradient");
+}
+
+int znn_accumulate(int64_t count, const float* x, float* y, void* stream)
+{
+    int rc = check_count(count);
+    if (rc != ZNN_OK) return rc;
+    if (!x || !y) return fail(ZNN_EINVAL, "NULL argument");
+    ZNN_LAUNCH("node sum", (hipStream_t)stream, k_accumulate, dim3((unsigned)((count + 255) / 256)), dim3(256), 0,
+               (long)count, x, y);
+    return check_launch("node sum");
 }
 
 int znn_sgd_update(int64_t count, float eta, const float* g, float* p, void* stream)

@@ -2,102 +2,19 @@
 
 This module only sequences library calls (Section 3 of the paper: forward pass,
 loss gradient, backward pass, gradients, update); every arithmetic step runs in
-libznn's kernels.  It also names the benchmark network and builds its seeded
-synthetic parameters.
+libznn's kernels.  The layer lists of the benchmark networks and their seeded
+synthetic tensors live in ``synth`` and are re-exported here.
 """
 from __future__ import annotations
 
 import numpy as np
 
 from . import binding as znn
-from . import synth
-
-# 6 convolutional layers of width 40 with 3^3 kernels, a transfer function after each,
-# 2^3 max-filters after the 2nd and 4th, 3 output images, 12^3 output patch => 26^3 input.
-WIDTH = 40
-CONFIG3_LAYERS = [
-    ("conv", 1, WIDTH, (3, 3, 3)), ("transfer",),
-    ("conv", WIDTH, WIDTH, (3, 3, 3)), ("transfer",), ("maxfilter", (2, 2, 2)),
-    ("conv", WIDTH, WIDTH, (3, 3, 3)), ("transfer",),
-    ("conv", WIDTH, WIDTH, (3, 3, 3)), ("transfer",), ("maxfilter", (2, 2, 2)),
-    ("conv", WIDTH, WIDTH, (3, 3, 3)), ("transfer",),
-    ("conv", WIDTH, 3, (3, 3, 3)), ("transfer",),
-]
-CONFIG3_INPUT = (1, 26, 26, 26)
-CONFIG3_ETA = 1e-3
-CONFIG3_SEED = 1003
-
-# The same network as a max-filtering ConvNet that reproduces a sliding-window max-pooling
-# ConvNet (Section 2, last paragraphs): every max-filter multiplies the sparsity of all
-# later layers by its window, so the layers after the first filter have sparsity 2 and
-# those after the second have sparsity 4.  Same 12^3 output patch => 43^3 input.
-S2, S4 = (2, 2, 2), (4, 4, 4)
-CONFIG3_SPARSE_LAYERS = [
-    ("conv", 1, WIDTH, (3, 3, 3)), ("transfer",),
-    ("conv", WIDTH, WIDTH, (3, 3, 3)), ("transfer",), ("maxfilter", (2, 2, 2)),
-    ("conv", WIDTH, WIDTH, (3, 3, 3), S2), ("transfer",),
-    ("conv", WIDTH, WIDTH, (3, 3, 3), S2), ("transfer",), ("maxfilter", (2, 2, 2), S2),
-    ("conv", WIDTH, WIDTH, (3, 3, 3), S4), ("transfer",),
-    ("conv", WIDTH, 3, (3, 3, 3), S4), ("transfer",),
-]
-CONFIG3_SPARSE_INPUT = (1, 43, 43, 43)
-
-ONES = (1, 1, 1)
-
-
-def _opt(spec, i, default):
-    return spec[i] if len(spec) > i else default
-
-
-def shapes(layers, in_shape):
-    """Node shapes [maps, z, y, x] before every layer and after the last."""
-    out = [tuple(in_shape)]
-    for spec in layers:
-        m, n = out[-1][0], out[-1][1:]
-        if spec[0] == "conv":
-            assert spec[1] == m
-            out.append((spec[2],) + tuple(a - s * (b - 1) for a, b, s in zip(n, spec[3], _opt(spec, 4, ONES))))
-        elif spec[0] == "transfer":
-            out.append(out[-1])
-        elif spec[0] == "maxfilter":
-            out.append((m,) + tuple(a - s * (b - 1) for a, b, s in zip(n, spec[1], _opt(spec, 2, ONES))))
-        elif spec[0] == "maxpool":
-            assert all(a % b == 0 for a, b in zip(n, spec[1])), "max-pooling needs n divisible by p"
-            out.append((m,) + tuple(a // b for a, b in zip(n, spec[1])))
-        else:
-            raise ValueError(spec)
-    return out
-
-
-def synthetic_params(layers, seed):
-    """fp32 kernels uniform[-1,1) * sqrt(6 / (f k^3)) and biases uniform[-0.1,0.1), seeded per layer."""
-    params = []
-    for l, spec in enumerate(layers):
-        if spec[0] == "conv":
-            f, fo, k = spec[1:4]
-            scale = float(np.sqrt(6.0 / (f * int(np.prod(k)))))
-            params.append({"w": synth.uniform_pm1(seed + 17 * l, synth.STREAM_KERNEL, (fo, f) + tuple(k), scale)})
-        elif spec[0] == "transfer":
-            maps = [s for s in layers[:l] if s[0] == "conv"][-1][2]
-            params.append({"b": synth.uniform_pm1(seed + 17 * l, synth.STREAM_BIAS, (maps,), 0.1)})
-        else:
-            params.append(None)
-    return params
-
-
-def net_tensors(layers, in_shape, seed):
-    """(input, target, params) of a layered net: input uniform[-1,1), target uniform[0,1)."""
-    x = synth.uniform_pm1(seed, synth.STREAM_IMAGE, in_shape)
-    target = synth.uniform_01(seed, synth.STREAM_TARGET, shapes(layers, in_shape)[-1])
-    return x, target, synthetic_params(layers, seed)
-
-
-def config3_tensors():
-    return net_tensors(CONFIG3_LAYERS, CONFIG3_INPUT, CONFIG3_SEED)
-
-
-def config3_sparse_tensors():
-    return net_tensors(CONFIG3_SPARSE_LAYERS, CONFIG3_SPARSE_INPUT, CONFIG3_SEED + 1)
+from .synth import (CONFIG3_ETA, CONFIG3_INPUT, CONFIG3_LAYERS, CONFIG3_SEED, CONFIG3_SPARSE_INPUT,  # noqa: F401
+                    CONFIG3_SPARSE_LAYERS, CONFIG2D_INPUT, CONFIG2D_LAYERS, CONFIG2D_SEED, ONES, WIDTH,
+                    config2d_tensors, config3_sparse_tensors, config3_tensors, net_tensors, shapes,
+                    synthetic_params)
+from .synth import _opt
 
 
 class Net:
