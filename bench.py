@@ -121,6 +121,38 @@ def report_all_configs(path):
         rows.append({"config": "c3_training_round", "mode": mode, "layer_ms": ms, "voxels_per_s": 3 * 12 ** 3 / (ms * 1e-3)})
         print("%-24s %-6s round %.3f ms  %.3g output voxels/s" % ("c3_training_round", mode, ms, rows[-1]["voxels_per_s"]),
               file=sys.stderr, flush=True)
+    # whole rounds of the other networks: tuned strategies (direct / FFT / FFT with memoized
+    # spectra per layer), the max-filtering net with sparse layers, the paper's 2D network
+    for name, layers, in_shape, tensors in (
+            ("c3_training_round", znet.CONFIG3_LAYERS, znet.CONFIG3_INPUT, (x, target, params)),
+            ("c3_sparse_round", synth.CONFIG3_SPARSE_LAYERS, synth.CONFIG3_SPARSE_INPUT, synth.config3_sparse_tensors()),
+            ("net2d_round", synth.CONFIG2D_LAYERS, synth.CONFIG2D_INPUT, synth.config2d_tensors())):
+        xx, tt, pp = tensors
+        d_x, d_t = torch.from_numpy(xx).to("cuda:0"), torch.from_numpy(tt).to("cuda:0")
+        out_vox = int(np.prod(synth.shapes(layers, in_shape)[-1]))
+        for mode in (("tuned",) if name == "c3_training_round" else ("direct", "fft", "tuned")):
+            net = znet.Net(layers, in_shape, pp, mode)
+            ms = timed(lambda: net.train_round(d_x, d_t, 1e-4), 10)
+            row = {"config": name, "mode": mode, "layer_ms": ms, "voxels_per_s": out_vox / (ms * 1e-3)}
+            if mode == "tuned":
+                row["strategies"] = [net.strategy[l] for l in sorted(net.tuning)]
+            rows.append(row)
+            print("%-24s %-6s round %.3f ms  %.3g output voxels/s %s" % (name, mode, ms, row["voxels_per_s"],
+                  row.get("strategies", "")), file=sys.stderr, flush=True)
+            del net
+        torch.cuda.empty_cache()
+    # a multi-scale graph with converging branches, as a launch DAG on 1 and on 4 streams
+    from paper_1510_06706_amd import graph as zgraph
+    g = synth.multiscale_graph(width=40, n=40)
+    inputs, targets, gp = synth.graph_tensors(g, 77)
+    d_in = {n: torch.from_numpy(v).to("cuda:0") for n, v in inputs.items()}
+    d_tg = {n: torch.from_numpy(v).to("cuda:0") for n, v in targets.items()}
+    for streams in (1, 4):
+        gn = zgraph.GraphNet(g, gp, "auto", streams=streams)
+        ms = timed(lambda: gn.train_round(d_in, d_tg, 1e-4, "cross_entropy"), 10)
+        rows.append({"config": "multiscale_graph_w40_n40", "mode": "auto, %d stream(s)" % streams, "layer_ms": ms})
+        print("%-24s streams %d round %.3f ms" % ("multiscale_graph_w40_n40", streams, ms), file=sys.stderr, flush=True)
+        del gn
     os.makedirs(os.path.dirname(path) or ".", exist_ok=True)
     with open(path, "w") as fh:
         json.dump(rows, fh, indent=1)

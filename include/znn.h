@@ -76,7 +76,12 @@ int  znn_plan_fft_extents(const znn_plan* plan, znn_vec3* N);
 /* Bytes of workspace the given pass (znn_pass) needs with the plan's method and
  * its current state (resident kernel spectra make forward/backward smaller). */
 int  znn_plan_workspace_bytes(const znn_plan* plan, int32_t pass, size_t* bytes);
-/* Bytes of the kernel spectra W^[f'][f][N_z][N_y][N_x/2+1] (complex fp32). */
+/* Bytes of the resident kernel spectra (complex fp32).  Their layout is private to the
+ * library: full spectra W^[f'][f][N_z][N_y][N_x/2+1], or, for layers whose slowest
+ * non-trivial axis has an FFT extent divisible by 4, at most 16 taps one voxel apart and
+ * enough frequencies to fill the chip, "half spectra" [f'][f][k_z][N_y][N_x/2+1] that are
+ * transformed along the fast axes only (the sum over the k_z planes is then taken inside
+ * the multiply-accumulate, which cuts the kernel traffic by N_z / k_z). */
 int  znn_plan_spectra_bytes(const znn_plan* plan, size_t* bytes);
 
 /*

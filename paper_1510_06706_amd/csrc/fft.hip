@@ -21,6 +21,8 @@
 //   gradient  gw  = crop_{[0, k)}     IFFT( G_s^[j] conj(I^[i]) )
 #include "znn_internal.h"
 
+#include <cstdlib>
+
 namespace znn {
 
 namespace {
@@ -694,8 +696,37 @@ int inverse3d(const Geom& g, float2* spec, float* dst, long maps, int cz, int cy
     return launch_c2r(spec, dst, maps, g.Nz, g.Ny, g.Nx, cz, cy, cx, dz, dy, dx, 1, scale, s);
 }
 
+// Layers whose kernel spectra are kept as half spectra (transformed along the fast axes
+// only) and expanded inside the multiply-accumulate: the slowest non-trivial axis must
+// have a length divisible by 4, few taps, and taps one voxel apart.
+struct Fold { bool on; int N, taps, P, z0; };
+
+Fold fold_of(const Geom& g)
+{
+    Fold F = {false, 0, 0, 0, 0};
+    if (getenv("ZNN_FFT_FULL_SPECTRA")) return F;
+    if (g.Nz > 1) { F.N = g.Nz; F.taps = g.kz; F.P = g.Ny * g.Nxh; F.on = g.spz == 1; }
+    else if (g.Ny > 1) { F.N = g.Ny; F.taps = g.ky; F.P = g.Nxh; F.on = g.spy == 1; }
+    F.on = F.on && F.N % 4 == 0 && F.taps <= kMaxFoldedTaps && F.taps < F.N;
+    if (!F.on) return F;
+    // the folded kernel has (N/4/z0) * P threads per group of result nodes: small layers
+    // would leave most of the chip idle, they keep the full spectra
+    const int nmin = g.f < g.fo ? g.f : g.fo;
+    F.z0 = 0;
+    for (int z0 = 4; z0 >= 1 && !F.z0; z0 /= 4) {
+        if ((F.N / 4) % z0) continue;
+        const int G = fft_mac_group(z0);
+        const long blocks = (((long)(F.N / 4 / z0) * F.P + 255) / 256) * ((nmin + G - 1) / G);
+        if (blocks >= 128) F.z0 = z0;
+    }
+    F.on = F.z0 != 0;
+    return F;
+}
+
 int launch_mac(bool backward, const Geom& g, const float2* What, const float2* a, float2* b, hipStream_t s)
 {
+    const Fold F = fold_of(g);
+    if (F.on) return fft_mac_fused(backward, F.taps, F.z0, g.f, g.fo, F.N, F.P, What, a, b, s);
     const long svol = g.svol();
     const int outs = backward ? g.f : g.fo;
     const int V = (svol % 2 == 0) ? 2 : 1;
@@ -716,6 +747,8 @@ int launch_mac(bool backward, const Geom& g, const float2* What, const float2* a
 // ---------------------------------------------------------------- public (library-internal) entry points
 size_t fft_spectra_bytes(const Geom& g)
 {
+    const Fold F = fold_of(g);
+    if (F.on) return align256(sizeof(float2) * (size_t)g.f * g.fo * F.taps * F.P);
     return align256(sizeof(float2) * (size_t)g.f * g.fo * g.svol());
 }
 
@@ -744,6 +777,26 @@ FftWorkspace fft_workspace(const Geom& g, int pass, bool resident)
 
 int fft_kernel_spectra(const Geom& g, const float* w, float2* What, hipStream_t s)
 {
+    const Fold F = fold_of(g);
+    if (F.on) {
+        // half spectra [pair][tap][P]: x (and, in 3D, y) transforms of the planes that hold taps
+        const long pairs = (long)g.f * g.fo;
+        if (pairs * F.taps > 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many kernel planes");
+        if (g.Nz == 1)
+            return launch_r2c(w, What, pairs, 1, g.ky, g.kx, 1, g.ky, g.Nx, 0, 0, 0, 1, 1, g.spx, s);
+        int rc = launch_r2c(w, What, pairs, g.kz, g.ky, g.kx, g.kz, g.Ny, g.Nx, 0, 0, 0, 1, g.spy, g.spx, s);
+        if (rc != ZNN_OK || g.Ny == 1) return rc;
+        const long plane = (long)g.Ny * g.Nxh;
+        AxisParams P = {};
+        P.in = What; P.in2 = nullptr; P.out = What;
+        P.N = g.Ny; P.i0 = 0; P.ni = g.ky; P.o0 = 0; P.no = g.Ny;
+        P.istep = g.spy; P.ostep = 1;
+        P.in_stride = P.out_stride = g.Nxh;
+        P.L = g.Nxh;
+        P.Oa = (int)(pairs * g.kz); P.Ob = 1; P.Oc = 1;
+        P.in_sa = P.out_sa = plane;
+        return launch_axis(P, -1, s);
+    }
     return forward3d(g, w, What, (long)g.f * g.fo, g.kz, g.ky, g.kx, 0, 0, 0, g.spz, g.spy, g.spx, s);
 }
 

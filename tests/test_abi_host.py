@@ -65,10 +65,23 @@ def test_fft_extents_are_the_next_5_smooth_numbers(n, N):
 def test_workspace_and_spectra_sizes():
     p = znn.Plan(40, 40, (64, 64, 64), (5, 5, 5), "fft")
     spec = 64 * 64 * 33 * 8
-    assert p.spectra_bytes() == 40 * 40 * spec
-    assert p.workspace_bytes(znn.ZNN_PASS_FWD) == 80 * spec + 1600 * spec
-    assert p.workspace_bytes(znn.ZNN_PASS_BWD) == 80 * spec + 1600 * spec
+    # kernels are kept transformed along y and x only: 5 planes of taps instead of 64
+    kspec = 40 * 40 * 5 * 64 * 33 * 8
+    assert p.spectra_bytes() == kspec
+    assert p.workspace_bytes(znn.ZNN_PASS_FWD) == 80 * spec + kspec
+    assert p.workspace_bytes(znn.ZNN_PASS_BWD) == 80 * spec + kspec
     assert p.workspace_bytes(znn.ZNN_PASS_WGRAD) >= 80 * spec
+    p.close()
+    # a small layer, an extent not divisible by 4 and taps more than one voxel apart along z
+    # keep full spectra
+    for n, k, s, N in (((12, 12, 12), (3, 3, 3), (1, 1, 1), (12, 12, 12)),
+                       ((26, 64, 64), (5, 5, 5), (1, 1, 1), (27, 64, 64)),
+                       ((64, 64, 64), (5, 5, 5), (2, 1, 1), (64, 64, 64))):
+        p = znn.Plan(40, 40, n, k, "fft", s)
+        assert p.spectra_bytes() == 40 * 40 * N[0] * N[1] * (N[2] // 2 + 1) * 8, (n, k, s)
+        p.close()
+    p = znn.Plan(80, 80, (1, 256, 256), (1, 11, 11), "fft")       # 2D: the y axis is the folded one
+    assert p.spectra_bytes() == 80 * 80 * 11 * 129 * 8
     b = ctypes.c_size_t(0)
     assert znn.lib().znn_plan_workspace_bytes(p._h, 5, ctypes.byref(b)) == znn.ZNN_EINVAL
     p.close()

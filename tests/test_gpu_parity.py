@@ -94,6 +94,36 @@ def test_sparse_convolution_matches_the_oracle(f, fo, n, k, s, mode):
     p.close()
 
 
+FOLDED = [
+    # f, fo, n, k, s: FFT layers large enough for the multiply-accumulate that folds the kernel
+    # transform's last axis in; N_z = 40 takes the one-base variant, N_z = 64 the four-base one
+    (32, 32, (40, 40, 40), (3, 3, 3), (1, 1, 1)),
+    (40, 36, (64, 40, 40), (3, 3, 3), (1, 2, 2)),
+    (64, 64, (1, 256, 250), (1, 6, 3), (1, 1, 2)),
+]
+
+
+@pytest.mark.parametrize("f,fo,n,k,s", FOLDED)
+def test_fft_layers_with_folded_kernel_transform_match_the_oracle(f, fo, n, k, s):
+    print("case", f, fo, n, k, s, flush=True)
+    cfg = synth.LayerShape("t", f, fo, n, k, 1.0 / np.sqrt(f * np.prod(k)), 91 + f, s)
+    inp, w, gout = synth.layer_tensors(cfg)
+    p = znn.Plan(f, fo, n, k, "fft", s)
+    N = p.fft_extents
+    full = f * fo * N[0] * N[1] * (N[2] // 2 + 1) * 8
+    assert p.spectra_bytes() < full          # half spectra: the folded path is the one that runs
+    d_in, d_w, d_g = dev(inp), dev(w), dev(gout)
+    out = host(p.fwd(d_in, d_w))
+    gin = host(p.bwd(d_g, d_w))
+    assert rel_err(out, oracle.conv3d_fwd(inp, w, s)) <= TOL["fft"]
+    assert rel_err(gin, oracle.conv3d_bwd(gout, w, n, s)) <= TOL["fft"]
+    assert rel_err(host(p.wgrad(d_in, d_g)), oracle.conv3d_wgrad(inp, gout, s)) <= TOL["fft"]
+    p.prepare_kernels(d_w)                   # resident half spectra give the same bits
+    assert np.array_equal(out, host(p.fwd(d_in, None)))
+    assert np.array_equal(gin, host(p.bwd(d_g, None)))
+    p.close()
+
+
 def test_resident_kernel_spectra_give_the_same_result():
     f, fo, n, k = 6, 5, (10, 12, 9), (3, 4, 2)
     cfg = synth.LayerShape("t", f, fo, n, k, 1.0, 91)
