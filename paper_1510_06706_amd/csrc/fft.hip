@@ -21,6 +21,7 @@
 //   gradient  gw  = crop_{[0, k)}     IFFT( G_s^[j] conj(I^[i]) )
 #include "znn_internal.h"
 
+#include <algorithm>
 #include <cstdlib>
 
 namespace znn {
@@ -30,15 +31,21 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kLdsBudget = 64 * 1024;
 
-struct Radices { int n; int r[12]; };
+// Radix sequence of a transform; fs[i] divides by the stride s of pass i (the product of
+// the radices before it) and fw by the number of pencils per batch, so that the
+// butterfly loops decompose their flat index without integer division.
+struct Radices { int n; int r[12]; FastDiv fs[12]; FastDiv fw; };
 
-Radices factorize(int N)
+Radices factorize(int N, int W)
 {
     Radices R; R.n = 0;
     while (N % 4 == 0) { R.r[R.n++] = 4; N /= 4; }
     while (N % 2 == 0) { R.r[R.n++] = 2; N /= 2; }
     while (N % 3 == 0) { R.r[R.n++] = 3; N /= 3; }
     while (N % 5 == 0) { R.r[R.n++] = 5; N /= 5; }
+    int s = 1;
+    for (int i = 0; i < R.n; ++i) { R.fs[i] = make_fastdiv((unsigned)s); s *= R.r[i]; }
+    R.fw = make_fastdiv((unsigned)W);
     return R;
 }
 
@@ -88,11 +95,12 @@ __device__ float2* lds_fft(float2* src, float2* dst, const float2* tw, int N, in
         const int units = m * s * W;
         const int xs = s * m * Wp;   // distance between the r inputs of a butterfly
         const int ys = s * Wp;       // distance between its r outputs
+        const FastDiv fs = R.fs[ri];
         for (int u = threadIdx.x; u < units; u += kThreads) {
-            const int p = u % W;
-            const int t = u / W;
-            const int q = t % s;
-            const int pp = t / s;
+            const int t = (int)fdiv((unsigned)u, R.fw);
+            const int p = u - t * W;
+            const int pp = (int)fdiv((unsigned)t, fs);
+            const int q = t - pp * s;
             const float2* x = src + (q + s * pp) * Wp + p;
             float2* y = dst + (q + s * r * pp) * Wp + p;
             const int ti = pp * s;   // twiddle index for output 1: exp(DIR 2 pi i pp / n)
@@ -153,6 +161,7 @@ struct R2CParams {
     int oz, oy, ox;
     int tz, ty, tx;     // spacing of the source samples inside the volume (1 except for sparse kernels)
     int W, Wp;
+    FastDiv fsx, fnxh, fsy, fsz;    // divisions of small block-local numbers by sx, Nxh, sy, sz
     Radices rad;
 };
 
@@ -169,20 +178,35 @@ __global__ void __launch_bounds__(kThreads) k_fft_r2c_x(R2CParams P)
     const long row0 = (long)blockIdx.x * (2 * P.W);
     const int nrows = (int)min((long)(2 * P.W), P.rows - row0);
     float* af = reinterpret_cast<float*>(a);
-    for (int t = threadIdx.x; t < nrows * P.sx; t += kThreads) {
-        const int r = t / P.sx, x = t % P.sx;
-        af[2 * ((x * P.tx + P.ox) * Wp + (r >> 1)) + (r & 1)] = P.src[(row0 + r) * P.sx + x];
+    const float* srow = P.src + row0 * P.sx;
+    if (P.tx == 1) {
+        for (int t = threadIdx.x; t < nrows * P.sx; t += kThreads) {
+            const int r = (int)fdiv((unsigned)t, P.fsx), x = t - r * P.sx;
+            af[2 * ((x + P.ox) * Wp + (r >> 1)) + (r & 1)] = srow[t];
+        }
+    } else {
+        for (int t = threadIdx.x; t < nrows * P.sx; t += kThreads) {
+            const int r = (int)fdiv((unsigned)t, P.fsx), x = t - r * P.sx;
+            af[2 * ((x * P.tx + P.ox) * Wp + (r >> 1)) + (r & 1)] = srow[t];
+        }
     }
     __syncthreads();
-    const int npen = (nrows + 1) >> 1;
-    const float2* res = lds_fft<-1>(a, b, tw, N, npen, Wp, P.rad);
+    const float2* res = lds_fft<-1>(a, b, tw, N, P.W, Wp, P.rad);
+    // (map, z, y) of the block's first row: one exact division per block, the rest is
+    // block-local and small
+    const long map0 = row0 / ((long)P.sy * P.sz);
+    const int rem0 = (int)(row0 - map0 * ((long)P.sy * P.sz));
+    const int z0 = rem0 / P.sy, y0 = rem0 - z0 * P.sy;
     // split the packed transform: A = (Z[k] + conj Z[N-k]) / 2,  B = (Z[k] - conj Z[N-k]) / (2i)
     for (int t = threadIdx.x; t < nrows * P.Nxh; t += kThreads) {
-        const int r = t / P.Nxh, k = t % P.Nxh;
-        const long row = row0 + r;
-        const int y = (int)(row % P.sy);
-        const int z = (int)((row / P.sy) % P.sz);
-        const long map = row / ((long)P.sy * P.sz);
+        const int r = (int)fdiv((unsigned)t, P.fnxh), k = t - r * P.Nxh;
+        const int yy = y0 + r;
+        const int zc = (int)fdiv((unsigned)yy, P.fsy);
+        const int y = yy - zc * P.sy;
+        const int zz = z0 + zc;
+        const int mc = (int)fdiv((unsigned)zz, P.fsz);
+        const int z = zz - mc * P.sz;
+        const long map = map0 + mc;
         const float2 z1 = res[k * Wp + (r >> 1)];
         const float2 z2 = res[(k == 0 ? 0 : N - k) * Wp + (r >> 1)];
         float2 v;
@@ -204,6 +228,7 @@ struct C2RParams {
     float scale;
     int tx;             // spacing of the wanted samples along x (1 except for sparse kernel gradients)
     int W, Wp;
+    FastDiv fdx, fnxh, fdy, fdz;
     Radices rad;
 };
 
@@ -218,22 +243,29 @@ __global__ void __launch_bounds__(kThreads) k_fft_c2r_x(C2RParams P)
     const long row0 = (long)blockIdx.x * (2 * P.W);
     const int nrows = (int)min((long)(2 * P.W), P.rows - row0);
     const int npen = (nrows + 1) >> 1;
+    const long map0 = row0 / ((long)P.dy * P.dz);
+    const int rem0 = (int)(row0 - map0 * ((long)P.dy * P.dz));
+    const int z0 = rem0 / P.dy, y0 = rem0 - z0 * P.dy;
     for (int t = threadIdx.x; t < npen * P.Nxh; t += kThreads) {
-        const int p = t / P.Nxh, k = t % P.Nxh;
+        const int p = (int)fdiv((unsigned)t, P.fnxh), k = t - p * P.Nxh;
         float2 A, B = make_float2(0.f, 0.f);
         {
-            const long row = row0 + 2 * p;
-            const int y = (int)(row % P.dy);
-            const int z = (int)((row / P.dy) % P.dz);
-            const long map = row / ((long)P.dy * P.dz);
-            A = P.src[((map * P.Nz + z + P.cz) * P.Ny + (y + P.cy)) * P.Nxh + k];
+            const int yy = y0 + 2 * p;
+            const int zc = (int)fdiv((unsigned)yy, P.fdy);
+            const int y = yy - zc * P.dy;
+            const int zz = z0 + zc;
+            const int mc = (int)fdiv((unsigned)zz, P.fdz);
+            const int z = zz - mc * P.dz;
+            A = P.src[(((map0 + mc) * P.Nz + z + P.cz) * P.Ny + (y + P.cy)) * P.Nxh + k];
         }
         if (2 * p + 1 < nrows) {
-            const long row = row0 + 2 * p + 1;
-            const int y = (int)(row % P.dy);
-            const int z = (int)((row / P.dy) % P.dz);
-            const long map = row / ((long)P.dy * P.dz);
-            B = P.src[((map * P.Nz + z + P.cz) * P.Ny + (y + P.cy)) * P.Nxh + k];
+            const int yy = y0 + 2 * p + 1;
+            const int zc = (int)fdiv((unsigned)yy, P.fdy);
+            const int y = yy - zc * P.dy;
+            const int zz = z0 + zc;
+            const int mc = (int)fdiv((unsigned)zz, P.fdz);
+            const int z = zz - mc * P.dz;
+            B = P.src[(((map0 + mc) * P.Nz + z + P.cz) * P.Ny + (y + P.cy)) * P.Nxh + k];
         }
         // Z = A + iB on the stored half, Hermitian extension on the rest; the
         // imaginary parts of the DC and Nyquist bins of a real line are zero.
@@ -245,11 +277,12 @@ __global__ void __launch_bounds__(kThreads) k_fft_c2r_x(C2RParams P)
         }
     }
     __syncthreads();
-    const float2* res = lds_fft<+1>(a, b, tw, N, npen, Wp, P.rad);
+    const float2* res = lds_fft<+1>(a, b, tw, N, P.W, Wp, P.rad);
     const float* rf = reinterpret_cast<const float*>(res);
+    float* drow = P.dst + row0 * P.dx;
     for (int t = threadIdx.x; t < nrows * P.dx; t += kThreads) {
-        const int r = t / P.dx, x = t % P.dx;
-        P.dst[(row0 + r) * P.dx + x] = P.scale * rf[2 * ((x * P.tx + P.cx) * Wp + (r >> 1)) + (r & 1)];
+        const int r = (int)fdiv((unsigned)t, P.fdx), x = t - r * P.dx;
+        drow[t] = P.scale * rf[2 * ((x * P.tx + P.cx) * Wp + (r >> 1)) + (r & 1)];
     }
 }
 
@@ -270,7 +303,8 @@ struct AxisParams {
     long in_sa, in_sb, in_sc;
     long in2_sa, in2_sb, in2_sc;
     long out_sa, out_sb, out_sc;
-    Radices rad;
+    FastDiv fchunks, foc, fob;      // block index -> (chunk, oc, ob, oa)
+    Radices rad;                    // rad.fw divides by W
 };
 
 template <int DIR, bool PRODUCT>
@@ -282,12 +316,14 @@ __global__ void __launch_bounds__(kThreads) k_fft_axis(AxisParams P)
     float2* b = lds + N * Wp;
     float2* tw = lds + 2 * N * Wp;
     make_twiddles(tw, N, DIR);
-    const long blk = blockIdx.x;
-    const int chunk = (int)(blk % P.chunks);
-    long o = blk / P.chunks;
-    const int oc = (int)(o % P.Oc); o /= P.Oc;
-    const int ob = (int)(o % P.Ob);
-    const int oa = (int)(o / P.Ob);
+    // the launcher keeps the grid below 2^31 / (largest divisor), so these are exact
+    const unsigned blk = blockIdx.x;
+    unsigned o = fdiv(blk, P.fchunks);
+    const int chunk = (int)(blk - o * P.chunks);
+    const unsigned o2 = fdiv(o, P.foc);
+    const int oc = (int)(o - o2 * P.Oc);
+    const int oa = (int)fdiv(o2, P.fob);
+    const int ob = (int)(o2 - (unsigned)oa * P.Ob);
     const int p0 = chunk * P.W;
     const int w = min(P.W, P.L - p0);
     if (P.ni < N || P.istep > 1) {
@@ -296,8 +332,11 @@ __global__ void __launch_bounds__(kThreads) k_fft_axis(AxisParams P)
     }
     const float2* in = P.in + (oa * P.in_sa + ob * P.in_sb + oc * P.in_sc) + p0;
     const float2* in2 = PRODUCT ? P.in2 + (oa * P.in2_sa + ob * P.in2_sb + oc * P.in2_sc) + p0 : nullptr;
+    // rows of w pencils; the ragged last chunk (w < W) pays for a real division
+    const bool full = w == P.W;
     for (int t = threadIdx.x; t < P.ni * w; t += kThreads) {
-        const int e = (t / w) * P.istep + P.i0, p = t % w;
+        const int row = full ? (int)fdiv((unsigned)t, P.rad.fw) : t / w;
+        const int e = row * P.istep + P.i0, p = t - row * w;
         float2 v = in[e * P.in_stride + p];
         if (PRODUCT) {
             const float2 c = in2[e * P.in_stride + p];
@@ -306,10 +345,11 @@ __global__ void __launch_bounds__(kThreads) k_fft_axis(AxisParams P)
         a[e * Wp + p] = v;
     }
     __syncthreads();
-    const float2* res = lds_fft<DIR>(a, b, tw, N, w, Wp, P.rad);
+    const float2* res = lds_fft<DIR>(a, b, tw, N, P.W, Wp, P.rad);
     float2* out = P.out + (oa * P.out_sa + ob * P.out_sb + oc * P.out_sc) + p0;
     for (int t = threadIdx.x; t < P.no * w; t += kThreads) {
-        const int q = t / w, p = t % w;
+        const int q = full ? (int)fdiv((unsigned)t, P.rad.fw) : t / w;
+        const int p = t - q * w;
         out[(q + P.o0) * P.out_stride + p] = res[(q * P.ostep + P.o0) * Wp + p];
     }
 }
@@ -571,7 +611,9 @@ int launch_r2c(const float* src, float2* dst, long maps, int sz, int sy, int sx,
     int wp = max_row_len(Nx);
     if (wp > 33) wp = 33;
     P.W = wp; P.Wp = wp;
-    P.rad = factorize(Nx);
+    P.rad = factorize(Nx, P.W);
+    P.fsx = make_fastdiv((unsigned)sx); P.fnxh = make_fastdiv((unsigned)P.Nxh);
+    P.fsy = make_fastdiv((unsigned)sy); P.fsz = make_fastdiv((unsigned)sz);
     const long blocks = (P.rows + 2 * P.W - 1) / (2 * P.W);
     if (blocks >= 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many rows for one launch");
     ZNN_LAUNCH("fft r2c x", s, k_fft_r2c_x, dim3((unsigned)blocks), dim3(kThreads), lds_bytes(Nx, P.Wp), P);
@@ -592,7 +634,9 @@ int launch_c2r(const float2* src, float* dst, long maps, int Nz, int Ny, int Nx,
     int wp = max_row_len(Nx);
     if (wp > 33) wp = 33;
     P.W = wp; P.Wp = wp;
-    P.rad = factorize(Nx);
+    P.rad = factorize(Nx, P.W);
+    P.fdx = make_fastdiv((unsigned)dx); P.fnxh = make_fastdiv((unsigned)P.Nxh);
+    P.fdy = make_fastdiv((unsigned)dy); P.fdz = make_fastdiv((unsigned)dz);
     const long blocks = (P.rows + 2 * P.W - 1) / (2 * P.W);
     if (blocks >= 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many rows for one launch");
     ZNN_LAUNCH("fft c2r x", s, k_fft_c2r_x, dim3((unsigned)blocks), dim3(kThreads), lds_bytes(Nx, P.Wp), P);
@@ -615,9 +659,14 @@ int launch_axis(AxisParams P, int dir, hipStream_t s)
     P.chunks = chunks;
     P.W = P.L > wmax ? wmax : P.L;
     P.Wp = P.W | 1;
-    P.rad = factorize(P.N);
+    P.rad = factorize(P.N, P.W);
+    P.fchunks = make_fastdiv((unsigned)chunks);
+    P.foc = make_fastdiv((unsigned)P.Oc);
+    P.fob = make_fastdiv((unsigned)P.Ob);
     const long blocks = (long)P.Oa * P.Ob * P.Oc * chunks;
-    if (blocks >= 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many pencils for one launch");
+    // the block index is taken apart with multiply-high divisions, exact while index * divisor < 2^32
+    const long dmax = std::max((long)chunks, std::max((long)P.Oc, (long)P.Ob));
+    if (blocks * dmax >= 4294967296L) return fail(ZNN_EUNSUPPORTED, "too many pencils for one launch");
     const size_t lds = lds_bytes(P.N, P.Wp);
     const dim3 grid((unsigned)blocks), block(kThreads);
     if (P.in2) {
