@@ -52,9 +52,14 @@ struct WgradTile {
     int vec4;           // 16-byte global->LDS loads are legal for this shape
 };
 
-template <int NJ, int NT>
-__global__ void __launch_bounds__(256) k_wgrad_mfma(WgradTile P)
+// NH = 1: four waves share every column tile and split the voxel steps four ways.
+// NH = 2: eight waves; waves 0-3 own the first NT column tiles of the group, waves 4-7 the
+// next NT, and each half splits the voxel steps four ways.  Two waves per SIMD: while one
+// waits for its global->LDS loads to be queued the other keeps the matrix cores busy.
+template <int NJ, int NT, int NH>
+__global__ void __launch_bounds__(256 * NH) k_wgrad_mfma(WgradTile P)
 {
+    constexpr int NW = 4 * NH;
     __shared__ __attribute__((aligned(16))) float bufA[kBufFloats];
     __shared__ __attribute__((aligned(16))) float bufB[kBufFloats];
     // The tile buffers are filled by global_load_lds only, which the optimizer does not
@@ -65,13 +70,14 @@ __global__ void __launch_bounds__(256) k_wgrad_mfma(WgradTile P)
         bufB[threadIdx.x] = P.gout[threadIdx.x];
     }
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int half = wave >> 2, kw = wave & 3;
     const int col = lane & 15, grp = lane >> 4;
     const int s = blockIdx.x, ab = blockIdx.y;
     const int a = ab / P.ky, b = ab % P.ky;
     const int cg = blockIdx.z % P.G, jg = blockIdx.z / P.G;
     const int ncols = P.f * P.kx;
-    const int n0 = cg * NT * 16;
-    const int n1 = min(n0 + NT * 16, ncols);
+    const int n0 = cg * NT * NH * 16;
+    const int n1 = min(n0 + NT * NH * 16, ncols);
     const int cmin = n0 / P.f, cmax = (n1 - 1) / P.f;
     int imin = 0, imax = P.f - 1;
     if (cmin == cmax) { imin = n0 % P.f; imax = (n1 - 1) % P.f; }
@@ -84,7 +90,7 @@ __global__ void __launch_bounds__(256) k_wgrad_mfma(WgradTile P)
     for (int jt = 0; jt < NJ; ++jt) aoff[jt] = (jt * 16 + col) * P.GS;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        const int n = n0 + nt * 16 + col;
+        const int n = n0 + (half * NT + nt) * 16 + col;
         int o = 0;
         if (n < n1) {
             const int c = n / P.f, i = n % P.f;
@@ -92,6 +98,9 @@ __global__ void __launch_bounds__(256) k_wgrad_mfma(WgradTile P)
         }
         boff[nt] = itoff + o;
     }
+
+    // column tiles of this half that hold real columns (wave-uniform): the rest is skipped
+    const int ntw = max(0, min(NT, ((n1 - n0 + 15) >> 4) - half * NT));
 
     floatx4 acc[NJ][NT];
 #pragma unroll
@@ -126,7 +135,7 @@ __global__ void __launch_bounds__(256) k_wgrad_mfma(WgradTile P)
                 const bool ok = rho < rows && gx < P.ox;
                 const long off = (long)rho * P.ox + gx;
                 if (e < RT) {
-                    for (int m = wave; m < NJ * 16; m += 4) {
+                    for (int m = wave; m < NJ * 16; m += NW) {
                         const int j = jg * NJ * 16 + m;
                         const float* src = (ok && j < P.fo) ? P.gout + j * oplane + off : zero4;
                         __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(buf + m * P.GS + k * 256), 16, 0, 0);
@@ -141,7 +150,7 @@ __global__ void __launch_bounds__(256) k_wgrad_mfma(WgradTile P)
                 const int z = (int)fdiv((unsigned)rho, P.dOY), y = rho - z * P.oy;
                 const long off = (long)(z + (P.kz - 1 - a) * P.spz) * iplane + (long)(y + (P.ky - 1 - b) * P.spy) * P.nx + ix;
                 if (e < RTH) {
-                    for (int m = wave; m < nmaps; m += 4) {
+                    for (int m = wave; m < nmaps; m += NW) {
                         const float* src = ok ? P.in + (imin + m) * ivol + off : zero4;
                         __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(buf + itoff + m * P.IS + k * 256), 16, 0, 0);
                     }
@@ -156,7 +165,7 @@ __global__ void __launch_bounds__(256) k_wgrad_mfma(WgradTile P)
             const bool ok = rho < rows && gx < P.ox;
             const long off = (long)rho * P.ox + gx;
             if (e < RT) {
-                for (int m = wave; m < NJ * 16; m += 4) {
+                for (int m = wave; m < NJ * 16; m += NW) {
                     const int j = jg * NJ * 16 + m;
                     const float* src = (ok && j < P.fo) ? P.gout + j * oplane + off : zero;
                     __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(buf + m * P.GS + k * 64), 4, 0, 0);
@@ -171,7 +180,7 @@ __global__ void __launch_bounds__(256) k_wgrad_mfma(WgradTile P)
             const int z = (int)fdiv((unsigned)rho, P.dOY), y = rho - z * P.oy;
             const long off = (long)(z + (P.kz - 1 - a) * P.spz) * iplane + (long)(y + (P.ky - 1 - b) * P.spy) * P.nx + ix;
             if (e < RTH) {
-                for (int m = wave; m < nmaps; m += 4) {
+                for (int m = wave; m < nmaps; m += NW) {
                     const float* src = ok ? P.in + (imin + m) * ivol + off : zero;
                     __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(buf + itoff + m * P.IS + k * 64), 4, 0, 0);
                 }
@@ -181,8 +190,8 @@ __global__ void __launch_bounds__(256) k_wgrad_mfma(WgradTile P)
 
     // All MFMAs of one staged tile.  A step covers 8 consecutive voxels: lane group g
     // (= lane/16) reads the voxel pair (2g, 2g+1) of every operand with one two-dword
-    // LDS read and feeds two MFMAs from it.  This wave takes steps wave, wave+4, ...
-    auto compute_tile = [&](const float* buf) {
+    // LDS read and feeds two MFMAs from it.  This wave takes steps kw, kw+4, ...
+    auto compute_tile = [&](const float* buf, int k0, int k1) {
         auto offsets = [&](int kp, int& ao, int& bo) {
             const int e = 8 * kp + 2 * grp;
             const int r = (int)fdiv((unsigned)e, P.dTX), x = e - r * P.TX;
@@ -192,34 +201,42 @@ __global__ void __launch_bounds__(256) k_wgrad_mfma(WgradTile P)
         float2 an[NJ], bn[NT];
         {
             int ao, bo;
-            offsets(min(wave, nkp - 1), ao, bo);
+            offsets(min(k0 + kw, nkp - 1), ao, bo);
 #pragma unroll
             for (int jt = 0; jt < NJ; ++jt) an[jt] = make_float2(buf[aoff[jt] + ao], buf[aoff[jt] + ao + 1]);
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) bn[nt] = make_float2(buf[boff[nt] + bo], buf[boff[nt] + bo + 1]);
         }
-        for (int kp = wave; kp < nkp; kp += 4) {
+        for (int kp = k0 + kw; kp < k1; kp += 4) {
             float2 av[NJ], bv[NT];
 #pragma unroll
             for (int jt = 0; jt < NJ; ++jt) av[jt] = an[jt];
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) bv[nt] = bn[nt];
             int ao, bo;
-            offsets(kp + 4 < nkp ? kp + 4 : kp, ao, bo);
+            offsets(kp + 4 < k1 ? kp + 4 : kp, ao, bo);
 #pragma unroll
             for (int jt = 0; jt < NJ; ++jt) an[jt] = make_float2(buf[aoff[jt] + ao], buf[aoff[jt] + ao + 1]);
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) bn[nt] = make_float2(buf[boff[nt] + bo], buf[boff[nt] + bo + 1]);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int jt = 0; jt < NJ; ++jt)
+            for (int nt = 0; nt < NT; ++nt) {
+                if (NH == 1 || nt < ntw) {
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    acc[jt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[jt].x, bv[nt].x, acc[jt][nt], 0, 0, 0);
-                    acc[jt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[jt].y, bv[nt].y, acc[jt][nt], 0, 0, 0);
+                    for (int jt = 0; jt < NJ; ++jt) {
+                        acc[jt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[jt].x, bv[nt].x, acc[jt][nt], 0, 0, 0);
+                        acc[jt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[jt].y, bv[nt].y, acc[jt][nt], 0, 0, 0);
+                    }
                 }
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
+    };
+
+    auto run_tile = [&](const float* cur, float* nxt, int next_tile) {
+        if (next_tile < t_end) issue_tile(next_tile, nxt);
+        compute_tile(cur, 0, nkp);
     };
 
     // Two tiles per trip so that each copy of the code names its buffers statically.
@@ -228,29 +245,27 @@ __global__ void __launch_bounds__(256) k_wgrad_mfma(WgradTile P)
     while (tile < t_end) {
         __builtin_amdgcn_s_waitcnt(0);     // this wave's loads have landed
         __syncthreads();                   // everyone's have, and nobody still reads bufB
-        if (tile + 1 < t_end) issue_tile(tile + 1, bufB);
-        compute_tile(bufA);
+        run_tile(bufA, bufB, tile + 1);
         ++tile;
         if (tile >= t_end) break;
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        if (tile + 1 < t_end) issue_tile(tile + 1, bufA);
-        compute_tile(bufB);
+        run_tile(bufB, bufA, tile + 1);
         ++tile;
     }
 
-    // add the four waves' accumulators in the order 0 + 1 + 2 + 3
-    floatx4* red = reinterpret_cast<floatx4*>(bufA);
+    // add the accumulators of the four waves of each half in the order 0 + 1 + 2 + 3
+    floatx4* red = reinterpret_cast<floatx4*>(bufA) + half * (NJ * NT * 64);
     for (int w = 1; w < 4; ++w) {
         __syncthreads();
-        if (wave == w) {
+        if (kw == w) {
 #pragma unroll
             for (int jt = 0; jt < NJ; ++jt)
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) red[(jt * NT + nt) * 64 + lane] = acc[jt][nt];
         }
         __syncthreads();
-        if (wave == 0) {
+        if (kw == 0) {
 #pragma unroll
             for (int jt = 0; jt < NJ; ++jt)
 #pragma unroll
@@ -260,8 +275,8 @@ __global__ void __launch_bounds__(256) k_wgrad_mfma(WgradTile P)
                 }
         }
     }
-    if (wave == 0) {
-        float* out = P.partial + ((long)(s * P.AB + ab) * P.Mpad + jg * NJ * 16) * P.Npad + cg * NT * 16;
+    if (kw == 0) {
+        float* out = P.partial + ((long)(s * P.AB + ab) * P.Mpad + jg * NJ * 16) * P.Npad + (cg * NH + half) * NT * 16;
 #pragma unroll
         for (int jt = 0; jt < NJ; ++jt)
 #pragma unroll
@@ -296,48 +311,55 @@ using WgradFn = void (*)(WgradTile);
 
 constexpr int kMaxTiles = 40;   // accumulator tiles per wave (4 registers each)
 
-template <int NJ, int NT> WgradFn inst()
+// Per-wave tile budget: 40 tiles with four waves (one per SIMD), 24 with eight (two per
+// SIMD share the register file).
+template <int NJ, int NT, int NH> WgradFn inst()
 {
-    if constexpr (NJ * NT <= kMaxTiles) return k_wgrad_mfma<NJ, NT>;
+    if constexpr (NJ * NT <= (NH == 1 ? kMaxTiles : NH == 2 ? 24 : 12)) return k_wgrad_mfma<NJ, NT, NH>;
     else return nullptr;
 }
 
-template <int NJ> WgradFn pick_nt(int nt)
+template <int NJ, int NH> WgradFn pick_nt(int nt)
 {
     switch (nt) {
-        case 1: return inst<NJ, 1>();
-        case 2: return inst<NJ, 2>();
-        case 3: return inst<NJ, 3>();
-        case 4: return inst<NJ, 4>();
-        case 5: return inst<NJ, 5>();
-        case 6: return inst<NJ, 6>();
-        case 7: return inst<NJ, 7>();
-        case 8: return inst<NJ, 8>();
-        case 10: return inst<NJ, 10>();
-        case 13: return inst<NJ, 13>();
-        case 16: return inst<NJ, 16>();
+        case 1: return inst<NJ, 1, NH>();
+        case 2: return inst<NJ, 2, NH>();
+        case 3: return inst<NJ, 3, NH>();
+        case 4: return inst<NJ, 4, NH>();
+        case 5: return inst<NJ, 5, NH>();
+        case 6: return inst<NJ, 6, NH>();
+        case 7: return inst<NJ, 7, NH>();
+        case 8: return inst<NJ, 8, NH>();
+        case 10: return inst<NJ, 10, NH>();
+        case 13: return inst<NJ, 13, NH>();
+        case 16: return inst<NJ, 16, NH>();
     }
     return nullptr;
 }
 
-WgradFn pick_wgrad(int nj, int nt)
+template <int NH> WgradFn pick_nj(int nj, int nt)
 {
     switch (nj) {
-        case 1: return pick_nt<1>(nt);
-        case 2: return pick_nt<2>(nt);
-        case 3: return pick_nt<3>(nt);
-        case 4: return pick_nt<4>(nt);
-        case 5: return pick_nt<5>(nt);
-        case 6: return pick_nt<6>(nt);
-        case 7: return pick_nt<7>(nt);
-        case 8: return pick_nt<8>(nt);
+        case 1: return pick_nt<1, NH>(nt);
+        case 2: return pick_nt<2, NH>(nt);
+        case 3: return pick_nt<3, NH>(nt);
+        case 4: return pick_nt<4, NH>(nt);
+        case 5: return pick_nt<5, NH>(nt);
+        case 6: return pick_nt<6, NH>(nt);
+        case 7: return pick_nt<7, NH>(nt);
+        case 8: return pick_nt<8, NH>(nt);
     }
     return nullptr;
+}
+
+WgradFn pick_wgrad(int nj, int nt, int nh)
+{
+    return nh == 4 ? pick_nj<4>(nj, nt) : nh == 2 ? pick_nj<2>(nj, nt) : pick_nj<1>(nj, nt);
 }
 
 struct WgradChoice {
     bool ok;
-    int NJ, JG, NT, G;
+    int NJ, JG, NT, G, NH;
     int TX, XT, R, GS, IS, TXH;
     int Mpad, Npad;
     int tiles, tps, ksplit;
@@ -374,21 +396,33 @@ WgradChoice choose_wgrad(const Geom& g)
     for (int k = 10; k >= 0; --k)
         if (allowed[k] >= want && c.NJ * allowed[k] <= kMaxTiles) c.NT = allowed[k];
     c.G = (nt_tot + c.NT - 1) / c.NT;
-    if (!pick_wgrad(c.NJ, c.NT)) return c;
+    // eight waves: the column tiles of a group are dealt to two halves of four waves each
+    static const int halves = [] { const char* e = getenv("ZNN_WGRAD_HALVES"); return e ? atoi(e) : 2; }();
+    c.NH = 1;
+    for (int nh = halves; nh >= 2; nh /= 2) {
+        const int nt = (c.NT + nh - 1) / nh;
+        if ((nh == 2 || nh == 4) && c.NT >= nh && pick_wgrad(c.NJ, nt, nh)) {
+            c.NH = nh;
+            c.NT = nt;
+            c.G = (nt_tot + c.NT * c.NH - 1) / (c.NT * c.NH);
+            break;
+        }
+    }
+    if (!pick_wgrad(c.NJ, c.NT, c.NH)) return c;
     c.Mpad = c.JG * c.NJ * 16;
-    c.Npad = c.G * c.NT * 16;
+    c.Npad = c.G * c.NT * c.NH * 16;
     // widest x-tap span and largest input-map range over the column groups
     int cspan = 0, nmaps = 1;
     for (int cg = 0; cg < c.G; ++cg) {
-        const int n0 = cg * c.NT * 16;
-        const int n1 = n0 + c.NT * 16 < ncols ? n0 + c.NT * 16 : ncols;
+        const int n0 = cg * c.NT * c.NH * 16;
+        const int n1 = n0 + c.NT * c.NH * 16 < ncols ? n0 + c.NT * c.NH * 16 : ncols;
         const int cmin = n0 / g.f, cmax = (n1 - 1) / g.f;
         const int span = cmax - cmin;
         const int maps = span == 0 ? (n1 - 1) % g.f - n0 % g.f + 1 : g.f;
         if (span > cspan) cspan = span;
         if (maps > nmaps) nmaps = maps;
     }
-    if ((size_t)c.NJ * c.NT * 64 * 4 > (size_t)kBufFloats) return c;   // cross-wave reduction needs this
+    if ((size_t)c.NJ * c.NT * c.NH * 64 * 4 > (size_t)kBufFloats) return c;   // cross-wave reduction needs this
     const int rows = g.oz * g.oy;
     // fewest x-segments whose tile fits a buffer, then as many rows as fit
     for (int XT = 1; XT <= g.ox; ++XT) {
@@ -456,11 +490,11 @@ int mfma_wgrad(const Geom& g, const float* in, const float* gout, float* gw, voi
     P.vec4 = c.vec4;
     P.dTX = make_fastdiv(c.TX); P.dTXH = make_fastdiv(c.TXH); P.dOY = make_fastdiv(g.oy);
     if (log_enabled())
-        fprintf(stderr, "[znn] wgrad mfma: NJ=%d JG=%d NT=%d G=%d TX=%d XT=%d R=%d lds=%zu ksplit=%d tiles=%d\n",
-                c.NJ, c.JG, c.NT, c.G, c.TX, c.XT, c.R, c.lds, c.ksplit, c.tiles);
-    WgradFn fn = pick_wgrad(c.NJ, c.NT);
+        fprintf(stderr, "[znn] wgrad mfma: NJ=%d JG=%d NT=%d NH=%d G=%d TX=%d XT=%d R=%d lds=%zu ksplit=%d tiles=%d\n",
+                c.NJ, c.JG, c.NT, c.NH, c.G, c.TX, c.XT, c.R, c.lds, c.ksplit, c.tiles);
+    WgradFn fn = pick_wgrad(c.NJ, c.NT, c.NH);
     if (!fn) return fail(ZNN_EUNSUPPORTED, "no kernel instance for tile %dx%d", c.NJ, c.NT);
-    ZNN_LAUNCH("direct kernel gradient (MFMA)", s, fn, dim3((unsigned)c.ksplit, (unsigned)P.AB, (unsigned)(c.G * c.JG)), dim3(256), 0, P);
+    ZNN_LAUNCH("direct kernel gradient (MFMA)", s, fn, dim3((unsigned)c.ksplit, (unsigned)P.AB, (unsigned)(c.G * c.JG)), dim3(256 * c.NH), 0, P);
     int rc = check_launch("direct kernel gradient (MFMA)");
     if (rc != ZNN_OK) return rc;
     const long total = (long)g.fo * g.f * g.kvol();
