@@ -82,7 +82,7 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma(ConvTile P)
     const int taps = P.kz * P.ky * P.kx;
     int* tapoff = reinterpret_cast<int*>(lds);      // [taps]
     float* halo = lds + ((taps + 63) & ~63);        // [4][MS]
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar
     const int col = lane & 15, grp = lane >> 4;
 
     int b = blockIdx.x;

@@ -52,6 +52,67 @@ struct WgradTile {
     int vec4;           // 16-byte global->LDS loads are legal for this shape
 };
 
+// The MFMAs of this wave's share of one staged tile.  A step covers 8 consecutive voxels:
+// lane group g (= lane/16) reads the voxel pair (2g, 2g+1) of every operand with one
+// two-dword LDS read and feeds two MFMAs from it.  The wave takes steps kp, kp+4, ... < k1.
+// Two register sets take turns, so the LDS reads of the next step are queued before the
+// MFMAs of the current one and only waited for after them; the code is kept free of
+// branches around loads and MFMAs (a step past the end re-reads the last one, NTA is the
+// compile-time number of column tiles that hold real columns) because the compiler can
+// only count outstanding loads exactly in straight-line code.  NTA < 0: the number of
+// live tiles is the run-time value ntw (any ragged column group; slower).
+template <int NJ, int NT, int NTA>
+__device__ __forceinline__ void wgrad_steps(floatx4 (&acc)[NJ][NT], const float* buf, const int (&aoff)[NJ],
+                                            const int (&boff)[NT], int kp, int k1, int grp, FastDiv dTX, int TX,
+                                            int TXH, int ntw)
+{
+    if (kp >= k1) return;
+    const int klast = kp + ((k1 - 1 - kp) & ~3);
+    auto load_step = [&](int k, float2 (&av)[NJ], float2 (&bv)[NT]) {
+        const int e = 8 * k + 2 * grp;
+        const int r = (int)fdiv((unsigned)e, dTX), x = e - r * TX;
+        const int ao = e, bo = r * TXH + x;
+#pragma unroll
+        for (int jt = 0; jt < NJ; ++jt) av[jt] = make_float2(buf[aoff[jt] + ao], buf[aoff[jt] + ao + 1]);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+            if (NTA < 0 || nt < NTA) bv[nt] = make_float2(buf[boff[nt] + bo], buf[boff[nt] + bo + 1]);
+    };
+    // first voxel of every pair for all tiles, then the second: consecutive MFMAs never wait
+    // for each other's accumulator
+    auto mfma_step = [&](const float2 (&av)[NJ], const float2 (&bv)[NT]) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+            if (NTA < 0 ? nt < ntw : nt < NTA) {
+#pragma unroll
+                for (int jt = 0; jt < NJ; ++jt)
+                    acc[jt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[jt].x, bv[nt].x, acc[jt][nt], 0, 0, 0);
+            }
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+            if (NTA < 0 ? nt < ntw : nt < NTA) {
+#pragma unroll
+                for (int jt = 0; jt < NJ; ++jt)
+                    acc[jt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[jt].y, bv[nt].y, acc[jt][nt], 0, 0, 0);
+            }
+    };
+    float2 a0[NJ], b0[NT], a1[NJ], b1[NT];
+    load_step(kp, a0, b0);
+    for (;;) {
+        load_step(min(kp + 4, klast), a1, b1);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_step(a0, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (kp + 4 >= k1) break;
+        load_step(min(kp + 8, klast), a0, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_step(a1, b1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (kp + 8 >= k1) break;
+        kp += 8;
+    }
+}
+
 // NH = 1: four waves share every column tile and split the voxel steps four ways.
 // NH = 2: eight waves; waves 0-3 own the first NT column tiles of the group, waves 4-7 the
 // next NT, and each half splits the voxel steps four ways.  Two waves per SIMD: while one
@@ -69,7 +130,9 @@ __global__ void __launch_bounds__(256 * NH) k_wgrad_mfma(WgradTile P)
         bufA[threadIdx.x] = P.in[threadIdx.x];
         bufB[threadIdx.x] = P.gout[threadIdx.x];
     }
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // the wave index is the same in all 64 lanes: telling the compiler so keeps everything
+    // derived from it (loop counters, tile predicates) in scalar registers and branches
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int half = wave >> 2, kw = wave & 3;
     const int col = lane & 15, grp = lane >> 4;
     const int s = blockIdx.x, ab = blockIdx.y;
@@ -188,50 +251,13 @@ __global__ void __launch_bounds__(256 * NH) k_wgrad_mfma(WgradTile P)
         }
     };
 
-    // All MFMAs of one staged tile.  A step covers 8 consecutive voxels: lane group g
-    // (= lane/16) reads the voxel pair (2g, 2g+1) of every operand with one two-dword
-    // LDS read and feeds two MFMAs from it.  This wave takes steps kw, kw+4, ...
     auto compute_tile = [&](const float* buf, int k0, int k1) {
-        auto offsets = [&](int kp, int& ao, int& bo) {
-            const int e = 8 * kp + 2 * grp;
-            const int r = (int)fdiv((unsigned)e, P.dTX), x = e - r * P.TX;
-            ao = e;
-            bo = r * TXH + x;
-        };
-        float2 an[NJ], bn[NT];
-        {
-            int ao, bo;
-            offsets(min(k0 + kw, nkp - 1), ao, bo);
-#pragma unroll
-            for (int jt = 0; jt < NJ; ++jt) an[jt] = make_float2(buf[aoff[jt] + ao], buf[aoff[jt] + ao + 1]);
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) bn[nt] = make_float2(buf[boff[nt] + bo], buf[boff[nt] + bo + 1]);
-        }
-        for (int kp = k0 + kw; kp < k1; kp += 4) {
-            float2 av[NJ], bv[NT];
-#pragma unroll
-            for (int jt = 0; jt < NJ; ++jt) av[jt] = an[jt];
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) bv[nt] = bn[nt];
-            int ao, bo;
-            offsets(kp + 4 < k1 ? kp + 4 : kp, ao, bo);
-#pragma unroll
-            for (int jt = 0; jt < NJ; ++jt) an[jt] = make_float2(buf[aoff[jt] + ao], buf[aoff[jt] + ao + 1]);
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) bn[nt] = make_float2(buf[boff[nt] + bo], buf[boff[nt] + bo + 1]);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                if (NH == 1 || nt < ntw) {
-#pragma unroll
-                    for (int jt = 0; jt < NJ; ++jt) {
-                        acc[jt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[jt].x, bv[nt].x, acc[jt][nt], 0, 0, 0);
-                        acc[jt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[jt].y, bv[nt].y, acc[jt][nt], 0, 0, 0);
-                    }
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
+        if (NH == 1 || ntw == NT)
+            wgrad_steps<NJ, NT, NT>(acc, buf, aoff, boff, k0 + kw, k1, grp, P.dTX, P.TX, TXH, NT);
+        else if (NT > 1 && ntw == NT - 1)
+            wgrad_steps<NJ, NT, (NT > 1 ? NT - 1 : 1)>(acc, buf, aoff, boff, k0 + kw, k1, grp, P.dTX, P.TX, TXH, ntw);
+        else
+            wgrad_steps<NJ, NT, -1>(acc, buf, aoff, boff, k0 + kw, k1, grp, P.dTX, P.TX, TXH, ntw);
     };
 
     auto run_tile = [&](const float* cur, float* nxt, int next_tile) {
