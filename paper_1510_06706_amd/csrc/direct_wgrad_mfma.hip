@@ -100,14 +100,10 @@ __device__ __forceinline__ void wgrad_steps(floatx4 (&acc)[NJ][NT], const float*
     load_step(kp, a0, b0);
     for (;;) {
         load_step(min(kp + 4, klast), a1, b1);
-        __builtin_amdgcn_sched_barrier(0);
         mfma_step(a0, b0);
-        __builtin_amdgcn_sched_barrier(0);
         if (kp + 4 >= k1) break;
         load_step(min(kp + 8, klast), a0, b0);
-        __builtin_amdgcn_sched_barrier(0);
         mfma_step(a1, b1);
-        __builtin_amdgcn_sched_barrier(0);
         if (kp + 8 >= k1) break;
         kp += 8;
     }

@@ -758,15 +758,25 @@ Fold fold_of(const Geom& g)
     else if (g.Ny > 1) { F.N = g.Ny; F.taps = g.ky; F.P = g.Nxh; F.on = g.spy == 1; }
     F.on = F.on && F.N % 4 == 0 && F.taps <= kMaxFoldedTaps && F.taps < F.N;
     if (!F.on) return F;
-    // the folded kernel has (N/4/z0) * P threads per group of result nodes: small layers
+    // the folded kernel has about (N/4/z0) * P threads per group of result nodes: small layers
     // would leave most of the chip idle, they keep the full spectra
     const int nmin = g.f < g.fo ? g.f : g.fo;
-    F.z0 = 0;
-    for (int z0 = 4; z0 >= 1 && !F.z0; z0 /= 4) {
-        if ((F.N / 4) % z0) continue;
+    // Four base frequencies per thread reuse every loaded value most but leave the fewest
+    // threads: they win on layers with thousands of workgroups (config 5: 30.0 ms against
+    // 31.2 ms), two win below that (config 2: 1.26 against 1.33 ms; config 4: 1.54 against
+    // 1.76 ms), one is the fallback for extents not divisible by 8.  ZNN_FFT_MAC_Z0 pins it.
+    static const int pin = [] { const char* e = getenv("ZNN_FFT_MAC_Z0"); return e ? atoi(e) : 0; }();
+    auto blocks_of = [&](int z0) {
         const int G = fft_mac_group(z0);
-        const long blocks = (((long)(F.N / 4 / z0) * F.P + 255) / 256) * ((nmin + G - 1) / G);
-        if (blocks >= 128) F.z0 = z0;
+        return (long)((F.P + 63) / 64) * ((F.N / 4 / z0 + 3) / 4) * ((nmin + G - 1) / G);
+    };
+    const bool big = (F.N / 4) % 4 == 0 && blocks_of(4) >= 2048;
+    const int order[3] = {big ? 4 : 2, big ? 2 : 4, 1};
+    F.z0 = 0;
+    for (int k = 0; k < 3 && !F.z0; ++k) {
+        const int z0 = order[k];
+        if ((pin && z0 != pin) || (F.N / 4) % z0) continue;
+        if (blocks_of(z0) >= 128) F.z0 = z0;
     }
     F.on = F.z0 != 0;
     return F;

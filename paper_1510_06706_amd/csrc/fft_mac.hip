@@ -17,8 +17,8 @@
 // frequencies cost a radix-4 butterfly of additions (taps with equal a mod 4 are folded
 // first).  Every thread walks the reduction index (input nodes forward, output nodes
 // backward) for G result nodes, so a loaded node-spectrum value is used G times and a
-// loaded half-spectrum value 4*Z0 times.  Threads are laid out with p fastest: loads and
-// stores of a wave are contiguous runs of one plane row.
+// loaded half-spectrum value 4*Z0 times.  A wave owns 64 neighbouring p: its loads and
+// stores are contiguous runs of one plane row.
 //
 // Needs N divisible by 4 and taps one voxel apart along the axis; other layers use the
 // full-spectrum multiply-accumulate.
@@ -40,9 +40,14 @@ __global__ void __launch_bounds__(kThreads)
 k_mac_fused(int f, int fo, int N, int P, int nzi, const float2* __restrict__ Wh,
             const float2* __restrict__ X, float2* __restrict__ Y)
 {
-    const long t = (long)blockIdx.x * kThreads + threadIdx.x;      // (zi, p), p fastest
-    if (t >= (long)nzi * P) return;
-    const int zi = (int)(t / P), p = (int)(t - (long)zi * P);
+    // A workgroup is four waves that share 64 in-plane frequencies and differ in their
+    // frequencies along the folded axis: all four request the same half-spectrum lines,
+    // which then come out of the compute unit's cache instead of four times out of L2/HBM.
+    const int npc = (P + 63) >> 6;
+    const int pc = blockIdx.x % npc, zb = blockIdx.x / npc;
+    const int zi = zb * 4 + (threadIdx.x >> 6);
+    const int p = pc * 64 + (threadIdx.x & 63);
+    if (zi >= nzi || p >= P) return;
     const int o0 = blockIdx.y * G;
     const int nred = BWD ? fo : f, nout = BWD ? f : fo;
     const int Q = N >> 2;
@@ -137,7 +142,7 @@ int launch_variant(int f, int fo, int N, int P, const float2* Wh, const float2* 
     constexpr int G = fft_mac_group(Z0);
     const int nout = BWD ? f : fo;
     const int nzi = N / 4 / Z0;
-    const long blocks = ((long)nzi * P + kThreads - 1) / kThreads;
+    const long blocks = (long)((P + 63) / 64) * ((nzi + 3) / 4);
     if (blocks >= 2147483647L || (nout + G - 1) / G > 65535) return fail(ZNN_EUNSUPPORTED, "too many frequencies");
     ZNN_LAUNCH(BWD ? "spectral mac backward (taps folded in)" : "spectral mac forward (taps folded in)", s,
                (k_mac_fused<BWD, KZ, Z0, G>), dim3((unsigned)blocks, (unsigned)((nout + G - 1) / G)),
@@ -149,6 +154,7 @@ template <bool BWD, int KZ>
 int launch_kz(int z0, int f, int fo, int N, int P, const float2* Wh, const float2* X, float2* Y, hipStream_t s)
 {
     if (z0 == 4) return launch_variant<BWD, KZ, 4>(f, fo, N, P, Wh, X, Y, s);
+    if (z0 == 2) return launch_variant<BWD, KZ, 2>(f, fo, N, P, Wh, X, Y, s);
     return launch_variant<BWD, KZ, 1>(f, fo, N, P, Wh, X, Y, s);
 }
 
@@ -181,7 +187,7 @@ int launch_dir(int taps, int z0, int f, int fo, int N, int P, const float2* Wh, 
 int fft_mac_fused(bool backward, int taps, int z0, int f, int fo, int N, int P, const float2* Wh,
                   const float2* X, float2* Y, hipStream_t s)
 {
-    if (N % 4 != 0 || taps < 1 || taps > kMaxFoldedTaps || (z0 != 1 && z0 != 4) || (N / 4) % z0 != 0)
+    if (N % 4 != 0 || taps < 1 || taps > kMaxFoldedTaps || (z0 != 1 && z0 != 2 && z0 != 4) || (N / 4) % z0 != 0)
         return fail(ZNN_EUNSUPPORTED, "layer does not fit the folded multiply-accumulate");
     return backward ? launch_dir<true>(taps, z0, f, fo, N, P, Wh, X, Y, s)
                     : launch_dir<false>(taps, z0, f, fo, N, P, Wh, X, Y, s);

@@ -98,9 +98,9 @@ int fft_wgrad_from_spectra(const Geom& g, const float2* Ihat, const float2* Ghat
 // Multiply-accumulate with the kernel transform's last axis folded in (fft_mac.hip):
 // Wh holds half spectra [pair][tap][P]; X, Y are node spectra [node][N][P].
 constexpr int kMaxFoldedTaps = 16;
-// z0 = 4 or 1: frequencies per thread along the folded axis are 4 * z0; a thread serves
+// z0 = 4, 2 or 1: frequencies per thread along the folded axis are 4 * z0; a thread serves
 // fft_mac_group(z0) result nodes.
-constexpr int fft_mac_group(int z0) { return z0 == 4 ? 4 : 8; }
+constexpr int fft_mac_group(int z0) { return z0 == 1 ? 8 : 4; }
 int fft_mac_fused(bool backward, int taps, int z0, int f, int fo, int N, int P, const float2* Wh,
                   const float2* X, float2* Y, hipStream_t s);
 
