@@ -40,6 +40,7 @@ struct ConvTile {
     int HZ, HY, HX, MS; // halo box and LDS stride between the four staged maps
     int cz, cy, cx;     // workgroups per axis
     int nchunk;         // ceil(fK / 4)
+    FastDiv dHX, dHY, dHZ;  // the halo loader takes its flat index apart without integer division
 };
 
 // Packs w[f'][f][k] so that lane l of a wave finds its A element of tile jt at
@@ -120,11 +121,9 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma(ConvTile P)
     for (int ic = 0; ic < P.nchunk; ++ic) {
         __syncthreads();   // everyone is done reading the previous chunk
         for (int t = threadIdx.x; t < 4 * hvol; t += 256) {
-            const int hx = t % P.HX;
-            int r = t / P.HX;
-            const int hy = r % P.HY; r /= P.HY;
-            const int hz = r % P.HZ;
-            const int m = r / P.HZ;
+            const int r1 = (int)fdiv((unsigned)t, P.dHX), hx = t - r1 * P.HX;
+            const int r2 = (int)fdiv((unsigned)r1, P.dHY), hy = r1 - r2 * P.HY;
+            const int m = (int)fdiv((unsigned)r2, P.dHZ), hz = r2 - m * P.HZ;
             const int gz = z0 + hz - P.pz, gy = y0 + hy - P.py, gx = x0 + hx - P.px;
             const int i = ic * 4 + m;
             float v = 0.f;
@@ -329,6 +328,7 @@ int mfma_conv(const Geom& g, bool backward, const float* src, const float* w, fl
     if (!c.ok) return fail(ZNN_EUNSUPPORTED, "no tile configuration fits this shape");
     P.Tz = c.Tz; P.Ty = c.Ty; P.Tx = c.Tx;
     P.HZ = c.HZ; P.HY = c.HY; P.HX = c.HX; P.MS = c.MS;
+    P.dHX = make_fastdiv((unsigned)c.HX); P.dHY = make_fastdiv((unsigned)c.HY); P.dHZ = make_fastdiv((unsigned)c.HZ);
     P.cz = c.cz; P.cy = c.cy; P.cx = c.cx;
     P.nchunk = (P.fK + 3) / 4;
     if (log_enabled())
