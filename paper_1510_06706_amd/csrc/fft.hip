@@ -525,6 +525,90 @@ k_wgrad_zdft(const float2* __restrict__ G, const float2* __restrict__ I, float2*
         }
 }
 
+// The same sums for N divisible by 4 and lags one voxel apart, four z a quarter period apart at
+// a time: with z = z0 + q N/4,
+//   T1[a] = sum_z0 exp(+2 pi i a z0 / N) * sum_q prod[z0 + q N/4] i^(a q),
+// so the four products are first combined by a radix-4 butterfly of additions into the four
+// classes a mod 4, and each lag then costs one complex multiply-add per FOUR z instead of one
+// per z (KZ + 1 -> KZ/4 + 2 complex operations per product).
+template <int KZ, int JB, int IB>
+__global__ void __launch_bounds__(kThreads)
+k_wgrad_zdft4(const float2* __restrict__ G, const float2* __restrict__ I, float2* __restrict__ T1,
+              int f, int fo, int N, long plane, long vol, int iblocks)
+{
+    __shared__ float2 tw[kMaxFftExtent];
+    make_twiddles(tw, N, +1);
+    __syncthreads();
+    const long p = (long)blockIdx.y * kThreads + threadIdx.x;
+    if (p >= plane) return;
+    const int j0 = (blockIdx.x / iblocks) * JB, i0 = (blockIdx.x % iblocks) * IB;
+    const int Q = N >> 2;
+    const float2* gp[JB];
+    const float2* ip[IB];
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb) gp[jb] = G + (long)min(j0 + jb, fo - 1) * vol + p;
+#pragma unroll
+    for (int ib = 0; ib < IB; ++ib) ip[ib] = I + (long)min(i0 + ib, f - 1) * vol + p;
+    float2 acc[JB][IB][KZ];
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+        for (int ib = 0; ib < IB; ++ib)
+#pragma unroll
+            for (int a = 0; a < KZ; ++a) acc[jb][ib][a] = make_float2(0.f, 0.f);
+    for (int z0 = 0; z0 < Q; ++z0) {
+        float2 gv[JB][4], xv[IB][4], t[KZ];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+#pragma unroll
+            for (int jb = 0; jb < JB; ++jb) gv[jb][q] = gp[jb][(long)(z0 + q * Q) * plane];
+#pragma unroll
+            for (int ib = 0; ib < IB; ++ib) xv[ib][q] = ip[ib][(long)(z0 + q * Q) * plane];
+        }
+#pragma unroll
+        for (int a = 1; a < KZ; ++a) t[a] = tw[(a * z0) % N];       // wave-uniform LDS reads
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+            for (int ib = 0; ib < IB; ++ib) {
+                float2 pr[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {       // g * conj(x)
+                    pr[q].x = fmaf(gv[jb][q].x, xv[ib][q].x, gv[jb][q].y * xv[ib][q].y);
+                    pr[q].y = fmaf(gv[jb][q].y, xv[ib][q].x, -gv[jb][q].x * xv[ib][q].y);
+                }
+                // u[c] = sum_q pr[q] i^(c q)
+                const float2 s02 = make_float2(pr[0].x + pr[2].x, pr[0].y + pr[2].y);
+                const float2 d02 = make_float2(pr[0].x - pr[2].x, pr[0].y - pr[2].y);
+                const float2 s13 = make_float2(pr[1].x + pr[3].x, pr[1].y + pr[3].y);
+                const float2 d13 = make_float2(pr[1].x - pr[3].x, pr[1].y - pr[3].y);
+                float2 u[4];
+                u[0] = make_float2(s02.x + s13.x, s02.y + s13.y);
+                u[2] = make_float2(s02.x - s13.x, s02.y - s13.y);
+                u[1] = make_float2(d02.x - d13.y, d02.y + d13.x);      // d02 + i d13
+                u[3] = make_float2(d02.x + d13.y, d02.y - d13.x);      // d02 - i d13
+                acc[jb][ib][0].x += u[0].x;
+                acc[jb][ib][0].y += u[0].y;
+#pragma unroll
+                for (int a = 1; a < KZ; ++a) {
+                    const float2 v = u[a & 3];
+                    acc[jb][ib][a].x = fmaf(v.x, t[a].x, fmaf(-v.y, t[a].y, acc[jb][ib][a].x));
+                    acc[jb][ib][a].y = fmaf(v.x, t[a].y, fmaf(v.y, t[a].x, acc[jb][ib][a].y));
+                }
+            }
+    }
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+        for (int ib = 0; ib < IB; ++ib) {
+            const int j = j0 + jb, i = i0 + ib;
+            if (j < fo && i < f) {
+#pragma unroll
+                for (int a = 0; a < KZ; ++a) T1[(((long)j * f + i) * KZ + a) * plane + p] = acc[jb][ib][a];
+            }
+        }
+}
+
 template <int KZ>
 int launch_expand_kz(float2* spec, long maps, int N, int oz, int tz, long plane, long vol, hipStream_t s)
 {
@@ -569,8 +653,13 @@ int launch_wgrad_dft_k(int f, int fo, int N, int tz, long plane, long vol, const
     if ((long)jblocks * iblocks >= 2147483647L || pchunks > 65535)
         return fail(ZNN_EUNSUPPORTED, "too many edges or pencils for one launch");
     const dim3 grid((unsigned)(jblocks * iblocks), (unsigned)pchunks);
-    ZNN_LAUNCH("pruned DFT of spectral products", s, (k_wgrad_zdft<KZ, JB, IB>), grid, dim3(kThreads), 0,
-               G, I, T, f, fo, N, tz, plane, vol, iblocks);
+    static const bool plain = getenv("ZNN_FFT_WGRAD_PLAIN") != nullptr;
+    if (N % 4 == 0 && tz == 1 && !plain)
+        ZNN_LAUNCH("pruned DFT of spectral products", s, (k_wgrad_zdft4<KZ, JB, IB>), grid, dim3(kThreads), 0,
+                   G, I, T, f, fo, N, plane, vol, iblocks);
+    else
+        ZNN_LAUNCH("pruned DFT of spectral products", s, (k_wgrad_zdft<KZ, JB, IB>), grid, dim3(kThreads), 0,
+                   G, I, T, f, fo, N, tz, plane, vol, iblocks);
     return check_launch("pruned DFT of spectral products");
 }
 
