@@ -609,6 +609,104 @@ k_wgrad_zdft4(const float2* __restrict__ G, const float2* __restrict__ I, float2
         }
 }
 
+// Pruned inverse DFT along an axis of length N whose elements are L apart, for data that is
+// already small in every other respect (second axis of the kernel gradient):
+//   out[o][b][l] = sum_n in[o][n][l] exp(+2 pi i b t n / N),   b < KY.
+// One thread per (o, l); with N divisible by 4 and t = 1 four n a quarter period apart share
+// one radix-4 butterfly, as above.  Memory-bound: every input element is read once.
+template <int KY>
+__global__ void __launch_bounds__(kThreads)
+k_prune_idft(const float2* __restrict__ in, float2* __restrict__ out, long outer, int N, int L, int t, int grouped)
+{
+    __shared__ float2 tw[kMaxFftExtent];
+    make_twiddles(tw, N, +1);
+    __syncthreads();
+    const long id = (long)blockIdx.x * kThreads + threadIdx.x;
+    if (id >= outer * L) return;
+    const long o = id / L;
+    const int l = (int)(id - o * L);
+    const float2* src = in + o * (long)N * L + l;
+    float2 acc[KY];
+#pragma unroll
+    for (int b = 0; b < KY; ++b) acc[b] = make_float2(0.f, 0.f);
+    if (grouped) {
+        const int Q = N >> 2;
+        for (int n0 = 0; n0 < Q; ++n0) {
+            float2 v[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[q] = src[(long)(n0 + q * Q) * L];
+            const float2 s02 = make_float2(v[0].x + v[2].x, v[0].y + v[2].y);
+            const float2 d02 = make_float2(v[0].x - v[2].x, v[0].y - v[2].y);
+            const float2 s13 = make_float2(v[1].x + v[3].x, v[1].y + v[3].y);
+            const float2 d13 = make_float2(v[1].x - v[3].x, v[1].y - v[3].y);
+            float2 u[4];
+            u[0] = make_float2(s02.x + s13.x, s02.y + s13.y);
+            u[2] = make_float2(s02.x - s13.x, s02.y - s13.y);
+            u[1] = make_float2(d02.x - d13.y, d02.y + d13.x);
+            u[3] = make_float2(d02.x + d13.y, d02.y - d13.x);
+            acc[0].x += u[0].x;
+            acc[0].y += u[0].y;
+#pragma unroll
+            for (int b = 1; b < KY; ++b) {
+                const float2 w = tw[(b * n0) % N];
+                const float2 x = u[b & 3];
+                acc[b].x = fmaf(x.x, w.x, fmaf(-x.y, w.y, acc[b].x));
+                acc[b].y = fmaf(x.x, w.y, fmaf(x.y, w.x, acc[b].y));
+            }
+        }
+    } else {
+        int idx[KY];
+#pragma unroll
+        for (int b = 0; b < KY; ++b) idx[b] = 0;
+        for (int n = 0; n < N; ++n) {
+            const float2 x = src[(long)n * L];
+#pragma unroll
+            for (int b = 0; b < KY; ++b) {
+                const float2 w = tw[idx[b]];
+                acc[b].x = fmaf(x.x, w.x, fmaf(-x.y, w.y, acc[b].x));
+                acc[b].y = fmaf(x.x, w.y, fmaf(x.y, w.x, acc[b].y));
+                idx[b] += b * t;            // lag b*t < N
+                if (idx[b] >= N) idx[b] -= N;
+            }
+        }
+    }
+    float2* dst = out + o * (long)KY * L + l;
+#pragma unroll
+    for (int b = 0; b < KY; ++b) dst[(long)b * L] = acc[b];
+}
+
+template <int KY>
+int launch_prune_k(const float2* in, float2* out, long outer, int N, int L, int t, hipStream_t s)
+{
+    const long blocks = (outer * L + kThreads - 1) / kThreads;
+    if (blocks >= 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many pencils for one launch");
+    ZNN_LAUNCH("pruned DFT, second axis of the kernel gradient", s, k_prune_idft<KY>, dim3((unsigned)blocks),
+               dim3(kThreads), 0, in, out, outer, N, L, t, (N % 4 == 0 && t == 1) ? 1 : 0);
+    return check_launch("pruned DFT");
+}
+
+int launch_prune(int ky, const float2* in, float2* out, long outer, int N, int L, int t, hipStream_t s)
+{
+    switch (ky) {
+        case 1: return launch_prune_k<1>(in, out, outer, N, L, t, s);
+        case 2: return launch_prune_k<2>(in, out, outer, N, L, t, s);
+        case 3: return launch_prune_k<3>(in, out, outer, N, L, t, s);
+        case 4: return launch_prune_k<4>(in, out, outer, N, L, t, s);
+        case 5: return launch_prune_k<5>(in, out, outer, N, L, t, s);
+        case 6: return launch_prune_k<6>(in, out, outer, N, L, t, s);
+        case 7: return launch_prune_k<7>(in, out, outer, N, L, t, s);
+        case 8: return launch_prune_k<8>(in, out, outer, N, L, t, s);
+        case 9: return launch_prune_k<9>(in, out, outer, N, L, t, s);
+        case 10: return launch_prune_k<10>(in, out, outer, N, L, t, s);
+        case 11: return launch_prune_k<11>(in, out, outer, N, L, t, s);
+        case 12: return launch_prune_k<12>(in, out, outer, N, L, t, s);
+        case 13: return launch_prune_k<13>(in, out, outer, N, L, t, s);
+        case 14: return launch_prune_k<14>(in, out, outer, N, L, t, s);
+        case 15: return launch_prune_k<15>(in, out, outer, N, L, t, s);
+        default: return launch_prune_k<16>(in, out, outer, N, L, t, s);
+    }
+}
+
 template <int KZ>
 int launch_expand_kz(float2* spec, long maps, int N, int oz, int tz, long plane, long vol, hipStream_t s)
 {
@@ -1042,7 +1140,10 @@ int fft_wgrad_from_spectra(const Geom& g, const float2* Ihat, const float2* Ghat
         P.Oa = g.fo * g.f; P.Ob = g.kz; P.Oc = 1;
         P.in_sa = (long)g.kz * plane; P.in_sb = plane;
         P.out_sa = (long)g.kz * g.ky * g.Nxh; P.out_sb = (long)g.ky * g.Nxh;
-        rc = launch_axis(P, +1, s);
+        if (g.ky <= kMaxPruned && !getenv("ZNN_FFT_WGRAD_PLAIN"))
+            rc = launch_prune(g.ky, T1, T2, (long)g.fo * g.f * g.kz, g.Ny, g.Nxh, g.spy, s);
+        else
+            rc = launch_axis(P, +1, s);
         if (rc != ZNN_OK) return rc;
     }
     const float scale = (float)(1.0 / ((double)g.Nz * g.Ny * g.Nx));
