@@ -838,6 +838,21 @@ int launch_axis(AxisParams P, int dir, hipStream_t s)
     if (P.N == 1 && !P.in2 && P.in == P.out && P.in_stride == P.out_stride &&
         P.in_sa == P.out_sa && P.in_sb == P.out_sb && P.in_sc == P.out_sc)
         return ZNN_OK;   // length-1 transform in place: nothing to do
+    // extents that fit the register file: one pencil per thread, no LDS
+    static const bool lds_only = getenv("ZNN_FFT_LDS_PASSES") != nullptr;
+    if (!lds_only && !P.in2 && P.istep == 1 && P.ostep == 1 && P.Oc == 1 && P.in_stride == P.L &&
+        P.out_stride == P.L && fft_axis_reg_supported(P.N)) {
+        RegAxis R = {};
+        R.in = P.in; R.out = P.out;
+        R.N = P.N; R.i0 = P.i0; R.ni = P.ni; R.o0 = P.o0; R.no = P.no;
+        R.stride = P.L; R.L = P.L; R.Oa = P.Oa; R.Ob = P.Ob;
+        R.in_sa = P.in_sa; R.in_sb = P.in_sb; R.out_sa = P.out_sa; R.out_sb = P.out_sb;
+        if (P.Ob == 1) {    // one run of pencils per outer index: let the threads run across outer indices
+            R.Oa = 1; R.Ob = P.Oa;
+            R.in_sb = P.in_sa; R.out_sb = P.out_sa;
+        }
+        if (R.Oa <= 65535 && (long)R.Ob * R.L * R.L < 4294967296L) return fft_axis_reg(R, dir, s);
+    }
     // chunk width: a whole line when it fits, else a multiple of 16 pencils (128 bytes) so
     // that every chunk starts on a cache-line boundary
     int wmax = max_row_len(P.N) > 63 ? 63 : max_row_len(P.N);

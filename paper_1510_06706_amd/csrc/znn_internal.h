@@ -104,6 +104,20 @@ constexpr int fft_mac_group(int z0) { return z0 == 1 ? 8 : 4; }
 int fft_mac_fused(bool backward, int taps, int z0, int f, int fo, int N, int P, const float2* Wh,
                   const float2* X, float2* Y, hipStream_t s);
 
+// Strided-axis FFT pass with one pencil per thread, whole pencil in registers (fft_reg.hip).
+// Pencil (oa, ob, l), l < L, has its element e at in + oa*in_sa + ob*in_sb + l + e*stride;
+// elements outside [i0, i0+ni) are taken as zero, only [o0, o0+no) are written.
+struct RegAxis {
+    const float2* in; float2* out;
+    int N, i0, ni, o0, no;
+    long stride;
+    int L, Oa, Ob;
+    long in_sa, in_sb, out_sa, out_sb;
+    FastDiv fL;
+};
+bool fft_axis_reg_supported(int N);
+int  fft_axis_reg(RegAxis P, int dir, hipStream_t s);
+
 // ---------------------------------------------------------------- fill (autotuner)
 int fill_pattern(float* p, long count, float scale, hipStream_t s);
 
