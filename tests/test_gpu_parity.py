@@ -124,6 +124,27 @@ def test_fft_layers_with_folded_kernel_transform_match_the_oracle(f, fo, n, k, s
     p.close()
 
 
+REG_EXTENTS = [8, 9, 10, 12, 15, 16, 18, 20, 24, 25, 27, 30, 32, 36, 40, 45, 48, 50, 54, 60, 64, 72, 75, 80, 81,
+               90, 96]
+
+
+@pytest.mark.parametrize("N", REG_EXTENTS)
+def test_fft_passes_with_register_resident_pencils_for_every_extent(N):
+    """Every extent the register-resident y / z passes are instantiated for, on both axes
+    (the x axis always takes the LDS pass), plus 100 (> 96: LDS passes on all axes)."""
+    print("case", N, flush=True)
+    for n, k in (((N, 6, 7), (3, 2, 2)), ((4, N, 7), (2, 3, 2))):
+        cfg = synth.LayerShape("t", 2, 3, n, k, 1.0, 200 + N)
+        inp, w, gout = synth.layer_tensors(cfg)
+        p = znn.Plan(2, 3, n, k, "fft")
+        assert p.fft_extents[0 if n[0] == N else 1] == N
+        d_in, d_w, d_g = dev(inp), dev(w), dev(gout)
+        assert rel_err(host(p.fwd(d_in, d_w)), oracle.conv3d_fwd(inp, w)) <= TOL["fft"], (n, "fwd")
+        assert rel_err(host(p.bwd(d_g, d_w)), oracle.conv3d_bwd(gout, w, n)) <= TOL["fft"], (n, "bwd")
+        assert rel_err(host(p.wgrad(d_in, d_g)), oracle.conv3d_wgrad(inp, gout)) <= TOL["fft"], (n, "wgrad")
+        p.close()
+
+
 def test_resident_kernel_spectra_give_the_same_result():
     f, fo, n, k = 6, 5, (10, 12, 9), (3, 4, 2)
     cfg = synth.LayerShape("t", f, fo, n, k, 1.0, 91)
