@@ -139,6 +139,13 @@ def report_all_configs(path):
             rows.append(row)
             print("%-24s %-6s round %.3f ms  %.3g output voxels/s %s" % (name, mode, ms, row["voxels_per_s"],
                   row.get("strategies", "")), file=sys.stderr, flush=True)
+            if mode == "tuned":     # the same round recorded once into a HIP graph and replayed
+                replay, _ = net.capture_round(d_x, d_t, 1e-4)
+                ms = timed(replay, 10)
+                rows.append({"config": name, "mode": "tuned, HIP graph", "layer_ms": ms,
+                             "voxels_per_s": out_vox / (ms * 1e-3)})
+                print("%-24s %-6s round %.3f ms  %.3g output voxels/s (HIP graph replay)" %
+                      (name, mode, ms, out_vox / (ms * 1e-3)), file=sys.stderr, flush=True)
             del net
         torch.cuda.empty_cache()
     # a multi-scale graph with converging branches, as a launch DAG on 1 and on 4 streams

@@ -106,3 +106,26 @@ class Net:
                 for k in p:
                     znn.sgd_update(p[k], g[k], eta)
         return acts, aux, gout, grads
+
+    def capture_round(self, x, target, eta, loss="square"):
+        """Records one training round (all library launches on the current HIP stream, no host
+        synchronisation, no memset) into a HIP graph and returns ``(replay, outputs)``:
+        ``replay()`` re-runs the round on the same buffers - new inputs are copied into ``x`` and
+        ``target`` in place, the parameters are updated in place - without per-launch host cost;
+        ``outputs = (acts, aux, gout, grads)`` are the graph's own output tensors.  Workspaces and
+        resident spectra are allocated by a warm-up round before the capture."""
+        import torch
+        side = torch.cuda.Stream(device=self.device)
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):       # warm-up outside the graph: plans grow their workspaces
+            saved = [None if p is None else {k: v.clone() for k, v in p.items()} for p in self.params]
+            self.train_round(x, target, eta, loss=loss)
+            for p, q in zip(self.params, saved):
+                if p is not None:
+                    for k in p:
+                        p[k].copy_(q[k])
+        torch.cuda.current_stream().wait_stream(side)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            outputs = self.train_round(x, target, eta, loss=loss)
+        return graph.replay, outputs

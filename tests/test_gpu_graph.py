@@ -107,3 +107,35 @@ def test_two_dimensional_benchmark_network_round(mode):
     print("2D net %s: modes %s worst gradient rel-err %.2e" % (mode, [m for m in net.modes() if m is not None], worst),
           flush=True)
     assert worst <= 1e-3
+
+
+def test_captured_training_round_replays_bit_for_bit():
+    """A round recorded into a HIP graph gives, replay after replay and with eager work in
+    between, exactly the parameters of the same number of eager rounds (the kernels are
+    deterministic, the graph holds no memset nodes)."""
+    import torch
+    layers = [("conv", 2, 6, (3, 3, 3)), ("transfer",), ("maxfilter", (2, 2, 2)),
+              ("conv", 6, 5, (2, 3, 2), (2, 2, 2)), ("transfer", "tanh"),
+              ("conv", 5, 3, (3, 1, 2)), ("transfer", "logistic")]
+    in_shape = (2, 14, 15, 16)
+    x, target, params = synth.net_tensors(layers, in_shape, 61)
+    for mode in ("direct", "fft"):
+        eager = znet.Net(layers, in_shape, params, mode)
+        graphed = znet.Net(layers, in_shape, params, mode)
+        d_x, d_t = dev(x), dev(target)
+        g_x, g_t = dev(x), dev(target)
+        replay, outputs = graphed.capture_round(g_x, g_t, 0.05)
+        for rnd in range(4):
+            xr = synth.uniform_pm1(70 + rnd, 0, in_shape)         # new input every round
+            d_x.copy_(dev(xr)); g_x.copy_(dev(xr))
+            e_acts, _, _, e_grads = eager.train_round(d_x, d_t, 0.05)
+            replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(host(outputs[0][-1]), host(e_acts[-1])), (mode, rnd, "output")
+            for l, p in enumerate(eager.params):
+                if p is not None:
+                    for k in p:
+                        assert np.array_equal(host(graphed.params[l][k]), host(p[k])), (mode, rnd, l, k)
+            # unrelated eager work between replays
+            scratch = znn.transfer_fwd(d_x, dev(np.zeros(in_shape[0], dtype=np.float32)))
+            del scratch
