@@ -12,7 +12,10 @@ HIP streams after waiting for the event of its source node, so independent branc
 overlap on the device, and the kernel-gradient of an edge runs on another stream than
 its backward image (they only share inputs).  Sums at nodes are taken in the fixed order
 of the edge list (every converging edge writes its own buffer, then the buffers are added
-one by one), so results do not depend on which stream finished first.
+one by one), so results do not depend on which stream finished first.  Every tensor of a
+round stays referenced until the round has joined the calling stream, and the next round
+starts from events recorded after that join, so memory handed back to the allocator is never
+reused while another stream still reads it.
 
 This module only sequences library calls; every arithmetic step runs in libznn's kernels.
 The graph format is the one of ``synth.graph_shapes``.
@@ -93,12 +96,9 @@ class GraphNet:
             stream.wait_event(events[name])
         total = parts[order[0]]
         if len(order) > 1:
-            total.record_stream(stream)
             total = total.clone()       # the first part stays intact (it may be an edge's kept output)
         for name in order[1:]:
-            parts[name].record_stream(stream)
             znn.accumulate(total, parts[name])
-        total.record_stream(stream)
         return total
 
     # ------------------------------------------------------------ passes
@@ -117,7 +117,6 @@ class GraphNet:
             s.wait_event(ready[src])
             with torch.cuda.stream(s):
                 a = img[src]
-                a.record_stream(s)
                 if kind == "conv":
                     y = self.plans[name].fwd(a, self.params[name]["w"])
                 elif kind == "transfer":
@@ -167,14 +166,11 @@ class GraphNet:
             s.wait_event(start)
             with torch.cuda.stream(s):
                 g = back[dst]
-                g.record_stream(s)
                 if kind == "conv":
                     sw = self._stream_of(i + 1 + len(self.streams) // 2)
                     sw.wait_event(ready[dst])
                     sw.wait_event(start)
                     with torch.cuda.stream(sw):
-                        g.record_stream(sw)
-                        img[src].record_stream(sw)
                         grads[name] = {"w": self.plans_w[name].wgrad(img[src], g)}
                         ev = torch.cuda.Event()
                         ev.record(sw)
