@@ -65,6 +65,7 @@ class GraphNet:
         self.params = {n: {k: torch.from_numpy(np.ascontiguousarray(v)).to(device) for k, v in p.items()}
                        for n, p in params.items()}
         self.streams = [torch.cuda.Stream(device=device) for _ in range(max(1, int(streams)))]
+        self._events, self._next_event = [], 0      # events are reused from round to round
         self.incoming, self.outgoing = {}, {}
         for e in self.edges:
             self.incoming.setdefault(e[3], []).append(e[1])
@@ -89,16 +90,28 @@ class GraphNet:
     def _stream_of(self, i):
         return self.streams[i % len(self.streams)]
 
+    def _event(self, stream):
+        """An event from the pool, recorded on `stream`."""
+        import torch
+        if self._next_event == len(self._events):
+            self._events.append(torch.cuda.Event())
+        ev = self._events[self._next_event]
+        self._next_event += 1
+        ev.record(stream)
+        return ev
+
     @staticmethod
     def _sum_in_order(parts, order, events, stream):
         """parts[name] are separate buffers; adds them in `order` on `stream` after their events."""
+        import torch
         for name in order:
             stream.wait_event(events[name])
         total = parts[order[0]]
         if len(order) > 1:
-            total = total.clone()       # the first part stays intact (it may be an edge's kept output)
+            with torch.cuda.stream(stream):
+                total = total.clone()   # the first part stays intact (it may be an edge's kept output)
         for name in order[1:]:
-            znn.accumulate(total, parts[name])
+            znn.accumulate(total, parts[name], stream=stream)
         return total
 
     # ------------------------------------------------------------ passes
@@ -106,32 +119,30 @@ class GraphNet:
         """inputs: {node: CUDA tensor}.  Returns (node images, per-edge aux, node events)."""
         import torch
         main = torch.cuda.current_stream()
+        self._next_event = 0
         img, aux, ready = dict(inputs), {}, {}
+        first = self._event(main)
         for n in inputs:
-            ready[n] = torch.cuda.Event()
-            ready[n].record(main)
+            ready[n] = first
         parts, part_ev = {}, {}
         for i, e in enumerate(self.edges):
             kind, name, src, dst = e[:4]
             s = self._stream_of(i)
             s.wait_event(ready[src])
-            with torch.cuda.stream(s):
-                a = img[src]
-                if kind == "conv":
-                    y = self.plans[name].fwd(a, self.params[name]["w"])
-                elif kind == "transfer":
-                    y = aux[name] = znn.transfer_fwd(a, self.params[name]["b"], _opt(e, 4, "rectify"))
-                elif kind == "maxfilter":
-                    y, aux[name] = znn.maxfilter3d_fwd(a, e[4], _opt(e, 5, ONES))
-                else:
-                    y, aux[name] = znn.maxpool3d_fwd(a, e[4])
-                parts.setdefault(dst, {})[name] = y
-                part_ev[name] = torch.cuda.Event()
-                part_ev[name].record(s)
-                if len(parts[dst]) == len(self.incoming[dst]):       # last edge into dst: take the sum
-                    img[dst] = self._sum_in_order(parts[dst], self.incoming[dst], part_ev, s)
-                    ready[dst] = torch.cuda.Event()
-                    ready[dst].record(s)
+            a = img[src]
+            if kind == "conv":
+                y = self.plans[name].fwd(a, self.params[name]["w"], stream=s)
+            elif kind == "transfer":
+                y = aux[name] = znn.transfer_fwd(a, self.params[name]["b"], _opt(e, 4, "rectify"), stream=s)
+            elif kind == "maxfilter":
+                y, aux[name] = znn.maxfilter3d_fwd(a, e[4], _opt(e, 5, ONES), stream=s)
+            else:
+                y, aux[name] = znn.maxpool3d_fwd(a, e[4], stream=s)
+            parts.setdefault(dst, {})[name] = y
+            part_ev[name] = self._event(s)
+            if len(parts[dst]) == len(self.incoming[dst]):       # last edge into dst: take the sum
+                img[dst] = self._sum_in_order(parts[dst], self.incoming[dst], part_ev, s)
+                ready[dst] = part_ev[name] if len(self.incoming[dst]) == 1 else self._event(s)
         for n in self.graph["outputs"]:
             main.wait_event(ready[n])
         return img, aux, ready
@@ -143,8 +154,7 @@ class GraphNet:
         main = torch.cuda.current_stream()
         back, ready, grads, grad_ev = {}, {}, {}, []
         parts, part_ev = {}, {}
-        start = torch.cuda.Event()
-        start.record(main)        # forward images and gout are complete at this point of `main`
+        start = self._event(main)     # forward images and gout are complete at this point of `main`
         for n, g in gout.items():
             parts.setdefault(n, {})["loss"] = g
             part_ev["loss:" + n] = start
@@ -153,8 +163,7 @@ class GraphNet:
             order = ["loss"] * (node in gout) + list(reversed(self.outgoing.get(node, [])))
             evs = {k: part_ev["loss:" + node] if k == "loss" else part_ev[k] for k in order}
             back[node] = self._sum_in_order(parts[node], order, evs, stream)
-            ready[node] = torch.cuda.Event()
-            ready[node].record(stream)
+            ready[node] = self._event(stream)
 
         for n in gout:
             if n not in self.outgoing:
@@ -164,34 +173,29 @@ class GraphNet:
             s = self._stream_of(i)
             s.wait_event(ready[dst])
             s.wait_event(start)
-            with torch.cuda.stream(s):
-                g = back[dst]
-                if kind == "conv":
-                    sw = self._stream_of(i + 1 + len(self.streams) // 2)
-                    sw.wait_event(ready[dst])
-                    sw.wait_event(start)
-                    with torch.cuda.stream(sw):
-                        grads[name] = {"w": self.plans_w[name].wgrad(img[src], g)}
-                        ev = torch.cuda.Event()
-                        ev.record(sw)
-                        grad_ev.append(ev)
-                    gs = None if src in self.graph["inputs"] else self.plans[name].bwd(g, self.params[name]["w"])
-                elif kind == "transfer":
-                    gs = znn.transfer_bwd(g, aux[name], _opt(e, 4, "rectify"))
-                    grads[name] = {"b": znn.bias_grad(gs)}
-                elif kind == "maxfilter":
-                    gs = znn.maxfilter3d_bwd(g, aux[name], self.shapes[src][1:], e[4], _opt(e, 5, ONES))
-                else:
-                    gs = znn.maxpool3d_bwd(g, aux[name], self.shapes[src][1:], e[4])
-                ev = torch.cuda.Event()
-                ev.record(s)
-                grad_ev.append(ev)
-                if gs is None:
-                    continue
-                parts.setdefault(src, {})[name] = gs
-                part_ev[name] = ev
-                if len(parts[src]) == len(self.outgoing[src]) + (src in gout):
-                    finish(src, s)
+            g = back[dst]
+            if kind == "conv":
+                sw = self._stream_of(i + 1 + len(self.streams) // 2)
+                sw.wait_event(ready[dst])
+                sw.wait_event(start)
+                grads[name] = {"w": self.plans_w[name].wgrad(img[src], g, stream=sw)}
+                grad_ev.append(self._event(sw))
+                gs = None if src in self.graph["inputs"] else self.plans[name].bwd(g, self.params[name]["w"], stream=s)
+            elif kind == "transfer":
+                gs = znn.transfer_bwd(g, aux[name], _opt(e, 4, "rectify"), stream=s)
+                grads[name] = {"b": znn.bias_grad(gs, stream=s)}
+            elif kind == "maxfilter":
+                gs = znn.maxfilter3d_bwd(g, aux[name], self.shapes[src][1:], e[4], _opt(e, 5, ONES), stream=s)
+            else:
+                gs = znn.maxpool3d_bwd(g, aux[name], self.shapes[src][1:], e[4], stream=s)
+            ev = self._event(s)
+            grad_ev.append(ev)
+            if gs is None:
+                continue
+            parts.setdefault(src, {})[name] = gs
+            part_ev[name] = ev
+            if len(parts[src]) == len(self.outgoing[src]) + (src in gout):
+                finish(src, s)
         for ev in grad_ev:
             main.wait_event(ev)
         return grads, back
