@@ -43,6 +43,8 @@ SMALL = [
     (17, 33, (8, 9, 35), (2, 2, 3)),
     (9, 130, (6, 7, 8), (2, 2, 2)),       # more than 128 output maps: several map groups
     (131, 5, (5, 6, 9), (2, 1, 3)),
+    (3, 4, (81, 50, 36), (3, 4, 2)),      # three different transform extents, all register-resident passes
+    (2, 3, (40, 100, 30), (2, 3, 3)),     # y extent above 96: LDS pass between two register passes
 ]
 
 
