@@ -96,18 +96,33 @@ static DescKey key_of(const znn_conv_desc& d)
                    d.sparsity.z, d.sparsity.y, d.sparsity.x);
 }
 
-// Work model of Table 2 turned into a time guess with rates measured on MI355X: the direct
-// method is a dense fp32 contraction (about 75 effective TFLOP/s over a layer), the FFT
-// method is bound by writing the kernel spectra once, streaming them twice, and by the
-// node transforms; both pay a few microseconds per launch.
+// Cost model behind mode = auto when no measurement is cached, calibrated on the five
+// benchmark configurations and the layers of the benchmark networks.  Direct: a dense fp32
+// contraction at about 80 effective TFLOP/s, scaled down when the output has too few voxel
+// tiles to occupy the 256 compute units.  FFT: the two multiply-accumulates and the pruned
+// DFTs of the kernel gradient are ALU work (kernel taps folded in) or stream the full kernel
+// spectra from HBM (small layers, extents not divisible by 4), the node transforms move
+// 16 bytes per frequency and pass at about 3.5 TB/s effective; both pay per launch.
 static int model_choice(const Geom& g)
 {
     const double macs = (double)g.f * g.fo * (double)g.ovol() * (double)g.kvol();
-    const double t_direct = 3.0 * 2.0 * macs / 75e12 + 4 * 6e-6;
-    const double spec = 8.0 * (double)g.svol();
-    const double S = spec * g.f * g.fo;
-    const double nodes = spec * (g.f + g.fo);
-    const double t_fft = S / 4.5e12 + 2.0 * S / 5.5e12 + 0.3 * S / 5e12 + 12.0 * nodes / 3e12 + 25 * 6e-6;
+    const double tiles = std::ceil((double)g.ovol() / 128.0) * std::ceil((double)g.fo / 128.0);
+    const double util = tiles >= 256.0 ? 1.0 : tiles / 256.0;
+    const double t_direct = 3.0 * 2.0 * macs / (80e12 * util) + 5 * 6e-6;
+    const double sv = (double)g.svol();
+    const double pairs = (double)g.f * g.fo;
+    const int taps = g.Nz > 1 ? g.kz : g.ky;
+    const int N = g.Nz > 1 ? g.Nz : g.Ny;
+    const int sp = g.Nz > 1 ? g.spz : g.spy;
+    const double P = g.Nz > 1 ? (double)g.Ny * g.Nxh : (double)g.Nxh;
+    const bool folded = N % 4 == 0 && taps <= 16 && taps < N && sp == 1 &&
+                        std::ceil(P / 64.0) * std::ceil(N / 32.0) * std::ceil(std::min(g.f, g.fo) / 4.0) >= 128.0;
+    double t_mac;
+    if (folded) t_mac = 2.0 * 8.0 * taps * sv * pairs / 55e12 + 8.0 * taps * P * pairs / 3e12;
+    else t_mac = 8.0 * sv * pairs * (1.0 / 4.5e12 + 2.0 / 5.5e12 + 0.3 / 5e12);
+    const double t_dft = (taps / 4.0 + 2.0) * 8.0 * sv * pairs / 45e12;
+    const double t_nodes = 3.0 * (g.f + g.fo) * 3.0 * 16.0 * sv / 3.5e12;
+    const double t_fft = t_mac + t_dft + t_nodes + 25 * 6e-6;
     return t_fft < t_direct ? ZNN_FFT : ZNN_DIRECT;
 }
 
