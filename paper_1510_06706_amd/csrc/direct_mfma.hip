@@ -76,13 +76,17 @@ k_pack_weights(const float* __restrict__ w, float* __restrict__ wp, int f, int f
     wp[t] = v;
 }
 
-template <int NJ, int NV>
+// WL: the packed weights of the current 4-map chunk are copied to LDS once per chunk and
+// the A operands come from there.  Small kernels (few taps) go with small output boxes and
+// few waves per SIMD, where a global load per tap would leave its whole latency exposed.
+template <int NJ, int NV, bool WL>
 __global__ void __launch_bounds__(256, 2) k_conv_mfma(ConvTile P)
 {
     extern __shared__ float lds[];
     const int taps = P.kz * P.ky * P.kx;
     int* tapoff = reinterpret_cast<int*>(lds);      // [taps]
     float* halo = lds + ((taps + 63) & ~63);        // [4][MS]
+    float* wl = halo + 4 * P.MS;                    // [taps][NJ][64] when WL
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar
     const int col = lane & 15, grp = lane >> 4;
 
@@ -131,11 +135,16 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma(ConvTile P)
                 v = P.src[(long)i * P.sz * splane + gz * splane + (long)gy * P.sx + gx];
             halo[m * P.MS + (hz * P.HY + hy) * P.HX + hx] = v;
         }
+        if (WL) {
+            const floatx4* src4 = reinterpret_cast<const floatx4*>(wq - lane);
+            floatx4* dst4 = reinterpret_cast<floatx4*>(wl);
+            for (int t = threadIdx.x; t < taps * NJ * 16; t += 256) dst4[t] = src4[t];
+        }
         __syncthreads();
 
         float an[NJ], bn[NV];
 #pragma unroll
-        for (int jt = 0; jt < NJ; ++jt) an[jt] = wq[jt * 64];
+        for (int jt = 0; jt < NJ; ++jt) an[jt] = WL ? wl[jt * 64 + lane] : wq[jt * 64];
         {
             const int o = tapoff[0];
 #pragma unroll
@@ -151,7 +160,7 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma(ConvTile P)
             const int tn = t + 1 < taps ? t + 1 : t;
             const float* wn = wq + (long)tn * NJ * 64;
 #pragma unroll
-            for (int jt = 0; jt < NJ; ++jt) an[jt] = wn[jt * 64];
+            for (int jt = 0; jt < NJ; ++jt) an[jt] = WL ? wl[(tn * NJ + jt) * 64 + lane] : wn[jt * 64];
             const int o = tapoff[tn];
 #pragma unroll
             for (int nv = 0; nv < NV; ++nv) bn[nv] = halo[voff[nv] + o];
@@ -186,32 +195,44 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma(ConvTile P)
 
 using ConvFn = void (*)(ConvTile);
 
-template <int NJ> ConvFn pick_nv(int nv)
+template <int NJ, bool WL> ConvFn pick_nv(int nv)
 {
     switch (nv) {
-        case 2: return k_conv_mfma<NJ, 2>;
-        case 4: return k_conv_mfma<NJ, 4>;
-        case 5: if (NJ * 5 <= 40) return k_conv_mfma<NJ, (NJ * 5 <= 40 ? 5 : 2)>; break;
-        case 6: if (NJ * 6 <= 40) return k_conv_mfma<NJ, (NJ * 6 <= 40 ? 6 : 2)>; break;
-        case 7: if (NJ * 7 <= 40) return k_conv_mfma<NJ, (NJ * 7 <= 40 ? 7 : 2)>; break;
-        case 8: if (NJ * 8 <= 40) return k_conv_mfma<NJ, (NJ * 8 <= 40 ? 8 : 2)>; break;
+        case 2: return k_conv_mfma<NJ, 2, WL>;
+        case 4: return k_conv_mfma<NJ, 4, WL>;
+        case 5: if (NJ * 5 <= 40) return k_conv_mfma<NJ, (NJ * 5 <= 40 ? 5 : 2), WL>; break;
+        case 6: if (NJ * 6 <= 40) return k_conv_mfma<NJ, (NJ * 6 <= 40 ? 6 : 2), WL>; break;
+        case 7: if (NJ * 7 <= 40) return k_conv_mfma<NJ, (NJ * 7 <= 40 ? 7 : 2), WL>; break;
+        case 8: if (NJ * 8 <= 40) return k_conv_mfma<NJ, (NJ * 8 <= 40 ? 8 : 2), WL>; break;
     }
     return nullptr;
 }
 
-ConvFn pick_kernel(int nj, int nv)
+template <bool WL> ConvFn pick_nj(int nj, int nv)
 {
     switch (nj) {
-        case 1: return pick_nv<1>(nv);
-        case 2: return pick_nv<2>(nv);
-        case 3: return pick_nv<3>(nv);
-        case 4: return pick_nv<4>(nv);
-        case 5: return pick_nv<5>(nv);
-        case 6: return pick_nv<6>(nv);
-        case 7: return pick_nv<7>(nv);
-        case 8: return pick_nv<8>(nv);
+        case 1: return pick_nv<1, WL>(nv);
+        case 2: return pick_nv<2, WL>(nv);
+        case 3: return pick_nv<3, WL>(nv);
+        case 4: return pick_nv<4, WL>(nv);
+        case 5: return pick_nv<5, WL>(nv);
+        case 6: return pick_nv<6, WL>(nv);
+        case 7: return pick_nv<7, WL>(nv);
+        case 8: return pick_nv<8, WL>(nv);
     }
     return nullptr;
+}
+
+ConvFn pick_kernel(int nj, int nv, bool wl = false)
+{
+    return wl ? pick_nj<true>(nj, nv) : pick_nj<false>(nj, nv);
+}
+
+// Weights of one chunk in LDS: when they take at most 32 KiB.
+bool weights_in_lds(int taps, int NJ)
+{
+    static const bool off = getenv("ZNN_CONV_NO_WL") != nullptr;
+    return !off && (size_t)taps * NJ * 256 <= 32 * 1024;
 }
 
 struct TileChoice {
@@ -219,6 +240,7 @@ struct TileChoice {
     int NJ, jgroups, NV;
     int Tz, Ty, Tx, HZ, HY, HX, MS;
     int cz, cy, cx;
+    bool wl;
     size_t lds;
 };
 
@@ -259,7 +281,8 @@ TileChoice choose_tile(int fM, int dz, int dy, int dx, int kz, int ky, int kx, i
                 long hvol = (long)HZ * HY * HX;
                 long MS = hvol;
                 while (MS % 32 != 16) ++MS;
-                const size_t lds = (size_t)(((taps + 63) & ~63) + 4 * MS) * 4;
+                const bool wl = weights_in_lds(taps, NJ);
+                const size_t lds = (size_t)(((taps + 63) & ~63) + 4 * MS) * 4 + (wl ? (size_t)taps * NJ * 256 : 0);
                 if (lds > kConvLdsMax) continue;
                 const int cz = (dz + Tz - 1) / Tz, cy = (dy + Ty - 1) / Ty, cx = (dx + Tx - 1) / Tx;
                 const long blocks = (long)cz * cy * cx * jgroups;
@@ -275,6 +298,7 @@ TileChoice choose_tile(int fM, int dz, int dy, int dx, int kz, int ky, int kx, i
                     best.Tz = Tz; best.Ty = Ty; best.Tx = Tx;
                     best.HZ = HZ; best.HY = HY; best.HX = HX; best.MS = (int)MS;
                     best.cz = cz; best.cy = cy; best.cx = cx;
+                    best.wl = wl;
                     best.lds = lds;
                 }
             }
@@ -343,7 +367,7 @@ int mfma_conv(const Geom& g, bool backward, const float* src, const float* w, fl
                w, wp, g.f, g.fo, g.kz, g.ky, g.kx, backward ? 1 : 0, c.NJ, c.jgroups, P.nchunk);
     int rc = check_launch("weight packing");
     if (rc != ZNN_OK) return rc;
-    ConvFn fn = pick_kernel(c.NJ, c.NV);
+    ConvFn fn = pick_kernel(c.NJ, c.NV, c.wl);
     if (!fn) return fail(ZNN_EUNSUPPORTED, "no kernel instance for tile %dx%d", c.NJ, c.NV);
     const long blocks = (long)c.cz * c.cy * c.cx;
     if (blocks >= 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many tiles for one launch");
