@@ -40,6 +40,8 @@ struct ConvTile {
     int HZ, HY, HX, MS; // halo box and LDS stride between the four staged maps
     int cz, cy, cx;     // workgroups per axis
     int nchunk;         // ceil(fK / 4)
+    int cps;            // chunks per workgroup along gridDim.z (all of them unless the input maps are split)
+    float* partial;     // [splits][fM][dz][dy][dx] partial sums when the input maps are split, else unused
     FastDiv dHX, dHY, dHZ;  // the halo loader takes its flat index apart without integer division
 };
 
@@ -120,9 +122,11 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma(ConvTile P)
 
     const int hvol = P.HZ * P.HY * P.HX;
     const long splane = (long)P.sy * P.sx;
-    const float* wq = P.wp + (long)jg * P.nchunk * taps * NJ * 64 + lane;
+    // this workgroup's share of the input-map chunks (all of them unless gridDim.z > 1)
+    const int ic0 = blockIdx.z * P.cps, ic1 = min(P.nchunk, ic0 + P.cps);
+    const float* wq = P.wp + ((long)jg * P.nchunk + ic0) * taps * NJ * 64 + lane;
 
-    for (int ic = 0; ic < P.nchunk; ++ic) {
+    for (int ic = ic0; ic < ic1; ++ic) {
         __syncthreads();   // everyone is done reading the previous chunk
         for (int t = threadIdx.x; t < 4 * hvol; t += 256) {
             const int r1 = (int)fdiv((unsigned)t, P.dHX), hx = t - r1 * P.HX;
@@ -175,6 +179,7 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma(ConvTile P)
 
     // D[m][n]: lane holds rows m = 4*(lane/16) + r, column n = lane%16
     const long dplane = (long)P.dy * P.dx;
+    float* out = gridDim.z > 1 ? P.partial + (long)blockIdx.z * P.fM * P.dz * dplane : P.dst;
 #pragma unroll
     for (int nv = 0; nv < NV; ++nv) {
         const int t = (wave * NV + nv) * 16 + col;
@@ -188,9 +193,20 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma(ConvTile P)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int j = (jg * NJ + jt) * 16 + grp * 4 + r;
-                if (j < P.fM) P.dst[(long)j * P.dz * dplane + vox] = acc[jt][nv][r];
+                if (j < P.fM) out[(long)j * P.dz * dplane + vox] = acc[jt][nv][r];
             }
     }
+}
+
+// dst = partial[0] + partial[1] + ... in ascending order (input maps split over workgroups).
+__global__ void __launch_bounds__(256)
+k_conv_reduce(const float* __restrict__ partial, float* __restrict__ dst, long count, int splits)
+{
+    const long t = (long)blockIdx.x * 256 + threadIdx.x;
+    if (t >= count) return;
+    float acc = partial[t];
+    for (int s = 1; s < splits; ++s) acc += partial[(long)s * count + t];
+    dst[t] = acc;
 }
 
 using ConvFn = void (*)(ConvTile);
@@ -241,6 +257,7 @@ struct TileChoice {
     int Tz, Ty, Tx, HZ, HY, HX, MS;
     int cz, cy, cx;
     bool wl;
+    int cps, splits;    // input-map chunks per workgroup and number of such shares
     size_t lds;
 };
 
@@ -249,7 +266,7 @@ constexpr size_t kConvLdsMax = 64 * 1024;
 
 // Picks the tile box and the per-wave tile count so that the launch fills the
 // 256 compute units in as few, as full rounds as possible.
-TileChoice choose_tile(int fM, int dz, int dy, int dx, int kz, int ky, int kx, int spz, int spy, int spx)
+TileChoice choose_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, int kx, int spz, int spy, int spx)
 {
     TileChoice best = {};
     best.ok = false;
@@ -304,7 +321,24 @@ TileChoice choose_tile(int fM, int dz, int dy, int dx, int kz, int ky, int kx, i
             }
         }
     }
+    // A layer with few output voxels leaves most compute units without a workgroup (and the
+    // rest with one wave per SIMD): below one workgroup per unit the input maps are split over
+    // gridDim.z until about three per unit exist; the shares' partial sums are added in a fixed order afterwards.
+    if (best.ok) {
+        const int nchunk = (fK + 3) / 4;
+        static const bool nosplit = getenv("ZNN_CONV_NO_SPLIT") != nullptr;
+        const long blocks = (long)best.cz * best.cy * best.cx * best.jgroups;
+        long want = nosplit || blocks >= kCUs ? 1 : (3 * kCUs + blocks - 1) / blocks;
+        if (want > nchunk) want = nchunk;
+        best.cps = (int)(nchunk / want);        // rounded down: shares of equal length, a few more of them
+        best.splits = (nchunk + best.cps - 1) / best.cps;
+    }
     return best;
+}
+
+size_t partial_bytes(const TileChoice& c, int fM, long dvol)
+{
+    return c.splits > 1 ? align256((size_t)c.splits * fM * dvol * sizeof(float)) : 0;
 }
 
 size_t packed_bytes(const TileChoice& c, int fK, int taps)
@@ -317,17 +351,18 @@ size_t packed_bytes(const TileChoice& c, int fK, int taps)
 // The tiled path takes every shape whose halo box fits LDS; otherwise the caller falls back.
 bool mfma_conv_supported(const Geom& g, bool backward)
 {
-    const TileChoice c = backward ? choose_tile(g.f, g.nz, g.ny, g.nx, g.kz, g.ky, g.kx, g.spz, g.spy, g.spx)
-                                  : choose_tile(g.fo, g.oz, g.oy, g.ox, g.kz, g.ky, g.kx, g.spz, g.spy, g.spx);
+    const TileChoice c = backward ? choose_tile(g.f, g.fo, g.nz, g.ny, g.nx, g.kz, g.ky, g.kx, g.spz, g.spy, g.spx)
+                                  : choose_tile(g.fo, g.f, g.oz, g.oy, g.ox, g.kz, g.ky, g.kx, g.spz, g.spy, g.spx);
     return c.ok;
 }
 
 size_t mfma_conv_workspace(const Geom& g, bool backward)
 {
-    const TileChoice c = backward ? choose_tile(g.f, g.nz, g.ny, g.nx, g.kz, g.ky, g.kx, g.spz, g.spy, g.spx)
-                                  : choose_tile(g.fo, g.oz, g.oy, g.ox, g.kz, g.ky, g.kx, g.spz, g.spy, g.spx);
+    const TileChoice c = backward ? choose_tile(g.f, g.fo, g.nz, g.ny, g.nx, g.kz, g.ky, g.kx, g.spz, g.spy, g.spx)
+                                  : choose_tile(g.fo, g.f, g.oz, g.oy, g.ox, g.kz, g.ky, g.kx, g.spz, g.spy, g.spx);
     if (!c.ok) return 0;
-    return packed_bytes(c, backward ? g.fo : g.f, (int)g.kvol());
+    return packed_bytes(c, backward ? g.fo : g.f, (int)g.kvol()) +
+           partial_bytes(c, backward ? g.f : g.fo, backward ? g.nvol() : g.ovol());
 }
 
 int mfma_conv(const Geom& g, bool backward, const float* src, const float* w, float* dst, void* ws,
@@ -348,20 +383,22 @@ int mfma_conv(const Geom& g, bool backward, const float* src, const float* w, fl
         P.pz = g.spz * (g.kz - 1); P.py = g.spy * (g.ky - 1); P.px = g.spx * (g.kx - 1);
         P.dz = g.nz; P.dy = g.ny; P.dx = g.nx;
     }
-    const TileChoice c = choose_tile(P.fM, P.dz, P.dy, P.dx, g.kz, g.ky, g.kx, g.spz, g.spy, g.spx);
+    const TileChoice c = choose_tile(P.fM, P.fK, P.dz, P.dy, P.dx, g.kz, g.ky, g.kx, g.spz, g.spy, g.spx);
     if (!c.ok) return fail(ZNN_EUNSUPPORTED, "no tile configuration fits this shape");
     P.Tz = c.Tz; P.Ty = c.Ty; P.Tx = c.Tx;
     P.HZ = c.HZ; P.HY = c.HY; P.HX = c.HX; P.MS = c.MS;
     P.dHX = make_fastdiv((unsigned)c.HX); P.dHY = make_fastdiv((unsigned)c.HY); P.dHZ = make_fastdiv((unsigned)c.HZ);
     P.cz = c.cz; P.cy = c.cy; P.cx = c.cx;
     P.nchunk = (P.fK + 3) / 4;
+    P.cps = c.cps;
     if (log_enabled())
-        fprintf(stderr, "[znn] conv mfma (%s): NJ=%d jgroups=%d NV=%d tile=%dx%dx%d halo=%dx%dx%d blocks=%d lds=%zu\n",
+        fprintf(stderr, "[znn] conv mfma (%s): NJ=%d jgroups=%d NV=%d tile=%dx%dx%d halo=%dx%dx%d blocks=%d splits=%d lds=%zu\n",
                 backward ? "bwd" : "fwd", c.NJ, c.jgroups, c.NV, c.Tz, c.Ty, c.Tx, c.HZ, c.HY, c.HX,
-                c.cz * c.cy * c.cx, c.lds);
+                c.cz * c.cy * c.cx, c.splits, c.lds);
     const int taps = (int)g.kvol();
     float* wp = (float*)ws;
     P.wp = wp;
+    P.partial = (float*)((char*)ws + packed_bytes(c, P.fK, taps));
     const long total = (long)c.jgroups * P.nchunk * taps * c.NJ * 64;
     ZNN_LAUNCH("weight packing", s, k_pack_weights, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
                w, wp, g.f, g.fo, g.kz, g.ky, g.kx, backward ? 1 : 0, c.NJ, c.jgroups, P.nchunk);
@@ -372,8 +409,13 @@ int mfma_conv(const Geom& g, bool backward, const float* src, const float* w, fl
     const long blocks = (long)c.cz * c.cy * c.cx;
     if (blocks >= 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many tiles for one launch");
     ZNN_LAUNCH(backward ? "direct backward (MFMA)" : "direct forward (MFMA)", s, fn,
-               dim3((unsigned)blocks, (unsigned)c.jgroups), dim3(256), c.lds, P);
-    return check_launch(backward ? "direct backward (MFMA)" : "direct forward (MFMA)");
+               dim3((unsigned)blocks, (unsigned)c.jgroups, (unsigned)c.splits), dim3(256), c.lds, P);
+    rc = check_launch(backward ? "direct backward (MFMA)" : "direct forward (MFMA)");
+    if (rc != ZNN_OK || c.splits == 1) return rc;
+    const long count = (long)P.fM * P.dz * P.dy * P.dx;
+    ZNN_LAUNCH("sum over input-map shares", s, k_conv_reduce, dim3((unsigned)((count + 255) / 256)), dim3(256), 0,
+               (const float*)P.partial, dst, count, c.splits);
+    return check_launch("sum over input-map shares");
 }
 
 }  // namespace znn
