@@ -15,6 +15,9 @@
 // loader and the weight packer provide; no separate kernel is needed.
 #include <cstdio>
 #include <cstdlib>
+#include <cstring>
+#include <mutex>
+#include <vector>
 
 #include "znn_internal.h"
 
@@ -266,7 +269,7 @@ constexpr size_t kConvLdsMax = 64 * 1024;
 
 // Picks the tile box and the per-wave tile count so that the launch fills the
 // 256 compute units in as few, as full rounds as possible.
-TileChoice choose_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, int kx, int spz, int spy, int spx)
+TileChoice search_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, int kx, int spz, int spy, int spx)
 {
     TileChoice best = {};
     best.ok = false;
@@ -334,6 +337,28 @@ TileChoice choose_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, i
         best.splits = (nchunk + best.cps - 1) / best.cps;
     }
     return best;
+}
+
+// The search walks thousands of candidate boxes (a fraction of a millisecond on the host),
+// and every call of a pass asks for the same answer up to three times: remembered per shape.
+TileChoice choose_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, int kx, int spz, int spy, int spx)
+{
+    struct Entry { int key[11]; TileChoice choice; };
+    static std::mutex lock;
+    static std::vector<Entry> memo;
+    const int key[11] = {fM, fK, dz, dy, dx, kz, ky, kx, spz, spy, spx};
+    {
+        std::lock_guard<std::mutex> hold(lock);
+        for (const Entry& e : memo)
+            if (memcmp(e.key, key, sizeof(key)) == 0) return e.choice;
+    }
+    Entry e;
+    memcpy(e.key, key, sizeof(key));
+    e.choice = search_tile(fM, fK, dz, dy, dx, kz, ky, kx, spz, spy, spx);
+    std::lock_guard<std::mutex> hold(lock);
+    if (memo.size() >= 256) memo.erase(memo.begin());
+    memo.push_back(e);
+    return e.choice;
 }
 
 size_t partial_bytes(const TileChoice& c, int fM, long dvol)
