@@ -1,52 +1,28 @@
 // Direct method on the fp32 matrix cores: forward and backward pass as an
 // implicit GEMM whose reduction runs over (fan-in x kernel volume), i.e. the
-// sum over the edges converging on a node is part of the GEMM's K loop.
-//
-//   D[m][n] += A[m][k] * B[k][n]      v_mfma_f32_16x16x4_f32
-//     m : 16 output maps            (A = packed kernel weights, one coalesced load)
-//     n : 16 output voxels          (B = input voxels read from an LDS halo tile)
-//     k : 4 input maps at one kernel tap
-//
-// A workgroup of four waves owns a box of output voxels for up to 128 output
-// maps; per chunk of four input maps it stages the input halo box in LDS once
-// and walks all taps over it.  The backward pass is the same contraction with
-// the roles of the two node sets swapped, the kernel reflected and the output
-// gradient zero-extended by k-1 on every side (Section 3.1), which the halo
-// loader and the weight packer provide; no separate kernel is needed.
+// sum over the edges converging on a node is part of the GEMM's K loop.  The
+// kernel is in direct_mfma_impl.h; this file holds the weight packer, the
+// search for the workgroup's output box and the launch.  The backward pass is
+// the same contraction with the roles of the two node sets swapped, the kernel
+// reflected and the output gradient zero-extended by k-1 on every side
+// (Section 3.1), which the halo loader and the weight packer provide; no
+// separate kernel is needed.
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <vector>
 
-#include "znn_internal.h"
+#include "direct_mfma_impl.h"
 
 namespace znn {
 
 namespace {
 
-typedef float floatx4 __attribute__((ext_vector_type(4)));
+using conv::ConvFn;
+using conv::ConvTile;
 
 constexpr int kMaxTaps = 4096;
-
-struct ConvTile {
-    const float* src;   // K-side images [fK][sz][sy][sx]
-    const float* wp;    // packed weights [jgroup][chunk][tap][NJ][64]
-    float* dst;         // M-side images [fM][dz][dy][dx]
-    int fK, fM;
-    int sz, sy, sx;     // source extents
-    int pz, py, px;     // zeros virtually in front of the source on each axis
-    int dz, dy, dx;     // output extents
-    int kz, ky, kx;
-    int spz, spy, spx;  // sparsity: taps are this many voxels apart
-    int Tz, Ty, Tx;     // output voxels per workgroup
-    int HZ, HY, HX, MS; // halo box and LDS stride between the four staged maps
-    int cz, cy, cx;     // workgroups per axis
-    int nchunk;         // ceil(fK / 4)
-    int cps;            // chunks per workgroup along gridDim.z (all of them unless the input maps are split)
-    float* partial;     // [splits][fM][dz][dy][dx] partial sums when the input maps are split, else unused
-    FastDiv dHX, dHY, dHZ;  // the halo loader takes its flat index apart without integer division
-};
 
 // Packs w[f'][f][k] so that lane l of a wave finds its A element of tile jt at
 // [..][jt][l]: output map jt*16 + l%16, input map chunk*4 + l/16.  For the
@@ -81,126 +57,6 @@ k_pack_weights(const float* __restrict__ w, float* __restrict__ wp, int f, int f
     wp[t] = v;
 }
 
-// WL: the packed weights of the current 4-map chunk are copied to LDS once per chunk and
-// the A operands come from there.  Small kernels (few taps) go with small output boxes and
-// few waves per SIMD, where a global load per tap would leave its whole latency exposed.
-template <int NJ, int NV, bool WL>
-__global__ void __launch_bounds__(256, 2) k_conv_mfma(ConvTile P)
-{
-    extern __shared__ float lds[];
-    const int taps = P.kz * P.ky * P.kx;
-    int* tapoff = reinterpret_cast<int*>(lds);      // [taps]
-    float* halo = lds + ((taps + 63) & ~63);        // [4][MS]
-    float* wl = halo + 4 * P.MS;                    // [taps][NJ][64] when WL
-    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar
-    const int col = lane & 15, grp = lane >> 4;
-
-    int b = blockIdx.x;
-    const int bxi = b % P.cx; b /= P.cx;
-    const int byi = b % P.cy;
-    const int bzi = b / P.cy;
-    const int jg = blockIdx.y;
-    const int z0 = bzi * P.Tz, y0 = byi * P.Ty, x0 = bxi * P.Tx;
-    const int Ttot = P.Tz * P.Ty * P.Tx;
-
-    for (int t = threadIdx.x; t < taps; t += 256) {
-        const int c = t % P.kx, bb = (t / P.kx) % P.ky, a = t / (P.kx * P.ky);
-        tapoff[t] = ((P.kz - 1 - a) * P.spz * P.HY + (P.ky - 1 - bb) * P.spy) * P.HX + (P.kx - 1 - c) * P.spx;
-    }
-
-    int voff[NV];
-#pragma unroll
-    for (int nv = 0; nv < NV; ++nv) {
-        int t = (wave * NV + nv) * 16 + col;
-        if (t >= Ttot) t = 0;
-        const int tx = t % P.Tx, ty = (t / P.Tx) % P.Ty, tz = t / (P.Tx * P.Ty);
-        voff[nv] = grp * P.MS + (tz * P.HY + ty) * P.HX + tx;
-    }
-
-    floatx4 acc[NJ][NV];
-#pragma unroll
-    for (int jt = 0; jt < NJ; ++jt)
-#pragma unroll
-        for (int nv = 0; nv < NV; ++nv) acc[jt][nv] = floatx4{0.f, 0.f, 0.f, 0.f};
-
-    const int hvol = P.HZ * P.HY * P.HX;
-    const long splane = (long)P.sy * P.sx;
-    // this workgroup's share of the input-map chunks (all of them unless gridDim.z > 1)
-    const int ic0 = blockIdx.z * P.cps, ic1 = min(P.nchunk, ic0 + P.cps);
-    const float* wq = P.wp + ((long)jg * P.nchunk + ic0) * taps * NJ * 64 + lane;
-
-    for (int ic = ic0; ic < ic1; ++ic) {
-        __syncthreads();   // everyone is done reading the previous chunk
-        for (int t = threadIdx.x; t < 4 * hvol; t += 256) {
-            const int r1 = (int)fdiv((unsigned)t, P.dHX), hx = t - r1 * P.HX;
-            const int r2 = (int)fdiv((unsigned)r1, P.dHY), hy = r1 - r2 * P.HY;
-            const int m = (int)fdiv((unsigned)r2, P.dHZ), hz = r2 - m * P.HZ;
-            const int gz = z0 + hz - P.pz, gy = y0 + hy - P.py, gx = x0 + hx - P.px;
-            const int i = ic * 4 + m;
-            float v = 0.f;
-            if (i < P.fK && gz >= 0 && gz < P.sz && gy >= 0 && gy < P.sy && gx >= 0 && gx < P.sx)
-                v = P.src[(long)i * P.sz * splane + gz * splane + (long)gy * P.sx + gx];
-            halo[m * P.MS + (hz * P.HY + hy) * P.HX + hx] = v;
-        }
-        if (WL) {
-            const floatx4* src4 = reinterpret_cast<const floatx4*>(wq - lane);
-            floatx4* dst4 = reinterpret_cast<floatx4*>(wl);
-            for (int t = threadIdx.x; t < taps * NJ * 16; t += 256) dst4[t] = src4[t];
-        }
-        __syncthreads();
-
-        float an[NJ], bn[NV];
-#pragma unroll
-        for (int jt = 0; jt < NJ; ++jt) an[jt] = WL ? wl[jt * 64 + lane] : wq[jt * 64];
-        {
-            const int o = tapoff[0];
-#pragma unroll
-            for (int nv = 0; nv < NV; ++nv) bn[nv] = halo[voff[nv] + o];
-        }
-        for (int t = 0; t < taps; ++t) {
-            float av[NJ], bv[NV];
-#pragma unroll
-            for (int jt = 0; jt < NJ; ++jt) av[jt] = an[jt];
-#pragma unroll
-            for (int nv = 0; nv < NV; ++nv) bv[nv] = bn[nv];
-            // operands of the next tap are fetched while this tap's MFMAs run
-            const int tn = t + 1 < taps ? t + 1 : t;
-            const float* wn = wq + (long)tn * NJ * 64;
-#pragma unroll
-            for (int jt = 0; jt < NJ; ++jt) an[jt] = WL ? wl[(tn * NJ + jt) * 64 + lane] : wn[jt * 64];
-            const int o = tapoff[tn];
-#pragma unroll
-            for (int nv = 0; nv < NV; ++nv) bn[nv] = halo[voff[nv] + o];
-#pragma unroll
-            for (int jt = 0; jt < NJ; ++jt)
-#pragma unroll
-                for (int nv = 0; nv < NV; ++nv)
-                    acc[jt][nv] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[jt], bv[nv], acc[jt][nv], 0, 0, 0);
-        }
-        wq += (long)taps * NJ * 64;
-    }
-
-    // D[m][n]: lane holds rows m = 4*(lane/16) + r, column n = lane%16
-    const long dplane = (long)P.dy * P.dx;
-    float* out = gridDim.z > 1 ? P.partial + (long)blockIdx.z * P.fM * P.dz * dplane : P.dst;
-#pragma unroll
-    for (int nv = 0; nv < NV; ++nv) {
-        const int t = (wave * NV + nv) * 16 + col;
-        if (t >= Ttot) continue;
-        const int tx = t % P.Tx, ty = (t / P.Tx) % P.Ty, tz = t / (P.Tx * P.Ty);
-        const int z = z0 + tz, y = y0 + ty, x = x0 + tx;
-        if (z >= P.dz || y >= P.dy || x >= P.dx) continue;
-        const long vox = z * dplane + (long)y * P.dx + x;
-#pragma unroll
-        for (int jt = 0; jt < NJ; ++jt)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int j = (jg * NJ + jt) * 16 + grp * 4 + r;
-                if (j < P.fM) out[(long)j * P.dz * dplane + vox] = acc[jt][nv][r];
-            }
-    }
-}
-
 // dst = partial[0] + partial[1] + ... in ascending order (input maps split over workgroups).
 __global__ void __launch_bounds__(256)
 k_conv_reduce(const float* __restrict__ partial, float* __restrict__ dst, long count, int splits)
@@ -212,39 +68,35 @@ k_conv_reduce(const float* __restrict__ partial, float* __restrict__ dst, long c
     dst[t] = acc;
 }
 
-using ConvFn = void (*)(ConvTile);
-
-template <int NJ, bool WL> ConvFn pick_nv(int nv)
+// Instances exist for 1..8 map tiles and 2, 4..8 voxel tiles per wave with at most 40 accumulator tiles.
+bool have_kernel(int nj, int nv)
 {
-    switch (nv) {
-        case 2: return k_conv_mfma<NJ, 2, WL>;
-        case 4: return k_conv_mfma<NJ, 4, WL>;
-        case 5: if (NJ * 5 <= 40) return k_conv_mfma<NJ, (NJ * 5 <= 40 ? 5 : 2), WL>; break;
-        case 6: if (NJ * 6 <= 40) return k_conv_mfma<NJ, (NJ * 6 <= 40 ? 6 : 2), WL>; break;
-        case 7: if (NJ * 7 <= 40) return k_conv_mfma<NJ, (NJ * 7 <= 40 ? 7 : 2), WL>; break;
-        case 8: if (NJ * 8 <= 40) return k_conv_mfma<NJ, (NJ * 8 <= 40 ? 8 : 2), WL>; break;
-    }
-    return nullptr;
+    return nj >= 1 && nj <= 8 && (nv == 2 || nv == 4 || (nv >= 5 && nv <= 8 && nj * nv <= 40));
 }
 
-template <bool WL> ConvFn pick_nj(int nj, int nv)
+// Taps along x are walked in groups of U (direct_mfma_impl.h): the widest divisor of the
+// kernel width that has an instance; 1 for sparse taps.
+int group_width(int kx, int spx)
 {
-    switch (nj) {
-        case 1: return pick_nv<1, WL>(nv);
-        case 2: return pick_nv<2, WL>(nv);
-        case 3: return pick_nv<3, WL>(nv);
-        case 4: return pick_nv<4, WL>(nv);
-        case 5: return pick_nv<5, WL>(nv);
-        case 6: return pick_nv<6, WL>(nv);
-        case 7: return pick_nv<7, WL>(nv);
-        case 8: return pick_nv<8, WL>(nv);
-    }
-    return nullptr;
+    static const bool off = getenv("ZNN_CONV_U1") != nullptr;
+    if (off || spx != 1) return 1;
+    const int widths[5] = {7, 5, 4, 3, 2};
+    for (int i = 0; i < 5; ++i)
+        if (kx % widths[i] == 0) return widths[i];
+    return 1;
 }
 
-ConvFn pick_kernel(int nj, int nv, bool wl = false)
+ConvFn pick_kernel(int U, int nj, int nv, bool wl)
 {
-    return wl ? pick_nj<true>(nj, nv) : pick_nj<false>(nj, nv);
+    switch (U) {
+        case 1: return conv_kernel_u1(nj, nv, wl);
+        case 2: return conv_kernel_u2(nj, nv, wl);
+        case 3: return conv_kernel_u3(nj, nv, wl);
+        case 4: return conv_kernel_u4(nj, nv, wl);
+        case 5: return conv_kernel_u5(nj, nv, wl);
+        case 7: return conv_kernel_u7(nj, nv, wl);
+    }
+    return nullptr;
 }
 
 // Weights of one chunk in LDS: when they take at most 32 KiB.
@@ -285,7 +137,7 @@ TileChoice search_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, i
     const int nvs[6] = {2, 4, 5, 6, 7, 8};
     for (int ni = 0; ni < 6; ++ni) {
         const int NV = nvs[ni];
-        if (NJ * NV > 40 || !pick_kernel(NJ, NV)) continue;
+        if (!have_kernel(NJ, NV)) continue;
         if (pin[0] && NV != pin[0]) continue;
         const int cap = 64 * NV;
         for (int Tx = 1; Tx <= dx && Tx <= cap; ++Tx) {
@@ -302,7 +154,7 @@ TileChoice search_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, i
                 long MS = hvol;
                 while (MS % 32 != 16) ++MS;
                 const bool wl = weights_in_lds(taps, NJ);
-                const size_t lds = (size_t)(((taps + 63) & ~63) + 4 * MS) * 4 + (wl ? (size_t)taps * NJ * 256 : 0);
+                const size_t lds = (size_t)4 * MS * 4 + (wl ? (size_t)taps * NJ * 256 : 0);
                 if (lds > kConvLdsMax) continue;
                 const int cz = (dz + Tz - 1) / Tz, cy = (dy + Ty - 1) / Ty, cx = (dx + Tx - 1) / Tx;
                 const long blocks = (long)cz * cy * cx * jgroups;
@@ -417,8 +269,8 @@ int mfma_conv(const Geom& g, bool backward, const float* src, const float* w, fl
     P.nchunk = (P.fK + 3) / 4;
     P.cps = c.cps;
     if (log_enabled())
-        fprintf(stderr, "[znn] conv mfma (%s): NJ=%d jgroups=%d NV=%d tile=%dx%dx%d halo=%dx%dx%d blocks=%d splits=%d lds=%zu\n",
-                backward ? "bwd" : "fwd", c.NJ, c.jgroups, c.NV, c.Tz, c.Ty, c.Tx, c.HZ, c.HY, c.HX,
+        fprintf(stderr, "[znn] conv mfma (%s): NJ=%d jgroups=%d NV=%d U=%d tile=%dx%dx%d halo=%dx%dx%d blocks=%d splits=%d lds=%zu\n",
+                backward ? "bwd" : "fwd", c.NJ, c.jgroups, c.NV, group_width(g.kx, g.spx), c.Tz, c.Ty, c.Tx, c.HZ, c.HY, c.HX,
                 c.cz * c.cy * c.cx, c.splits, c.lds);
     const int taps = (int)g.kvol();
     float* wp = (float*)ws;
@@ -429,7 +281,8 @@ int mfma_conv(const Geom& g, bool backward, const float* src, const float* w, fl
                w, wp, g.f, g.fo, g.kz, g.ky, g.kx, backward ? 1 : 0, c.NJ, c.jgroups, P.nchunk);
     int rc = check_launch("weight packing");
     if (rc != ZNN_OK) return rc;
-    ConvFn fn = pick_kernel(c.NJ, c.NV, c.wl);
+    const int U = group_width(g.kx, g.spx);
+    ConvFn fn = pick_kernel(U, c.NJ, c.NV, c.wl);
     if (!fn) return fail(ZNN_EUNSUPPORTED, "no kernel instance for tile %dx%d", c.NJ, c.NV);
     const long blocks = (long)c.cz * c.cy * c.cx;
     if (blocks >= 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many tiles for one launch");
