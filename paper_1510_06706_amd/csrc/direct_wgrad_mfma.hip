@@ -19,6 +19,7 @@
 // ascending split order, so the result is bit-reproducible (no atomics).
 #include <cstdio>
 #include <cstdlib>
+#include <type_traits>
 
 #include "znn_internal.h"
 
@@ -33,7 +34,6 @@ typedef __attribute__((address_space(3))) void* lds_ptr;
 // Two tile buffers as separate LDS objects: the compiler then knows that loads
 // landing in one buffer do not alias reads of the other and lets them overlap.
 constexpr int kBufFloats = 18432;                 // 72 KiB each
-__device__ float g_zero_words[64];                // source of tile elements outside the images
 
 struct WgradTile {
     const float* in; const float* gout; float* partial;
@@ -174,76 +174,63 @@ __global__ void __launch_bounds__(256 * NH) k_wgrad_mfma(WgradTile P)
     const int t_end = min((s + 1) * P.tps, P.tiles);
     const int RT = P.R * P.TX, RTH = P.R * TXH;
     const int nkp = RT / 8;     // 8-voxel steps per tile (R * TX is a multiple of 8)
-    const int nsegG = (RT + 63) >> 6, nsegI = (RTH + 63) >> 6;
-    const float* zero = g_zero_words + lane;
-    const float* zero4 = g_zero_words;
+    // rows of the gout tile that hold real maps; the padding rows up to NJ*16 never change:
+    // they are zeroed once, in both buffers, and never loaded
+    const int mreal = min(NJ * 16, P.fo - jg * NJ * 16);
+    for (int m = mreal + wave; m < NJ * 16; m += NW)
+        for (int e = lane; e < RT; e += 64) { bufA[m * P.GS + e] = 0.f; bufB[m * P.GS + e] = 0.f; }
 
-    // Queue the global->LDS loads of one tile.  A wave-load moves 64 (or, with 16-byte
-    // loads, 256) consecutive tile elements of one map; elements outside the images come
-    // from a zero word.  The 16-byte form needs every group of four x-neighbours to be
-    // entirely inside or outside the image (P.vec4, decided on the host).
+    // Queue the global->LDS loads of one tile.  A wave-load moves 64 * W consecutive tile
+    // elements of one map (W = 4: 16-byte loads, legal when every group of four x-neighbours
+    // is entirely inside or outside the image, P.vec4).  The vector arithmetic is kept to one
+    // byte offset per lane and 64 * W elements, shared by all maps: the map bases are wave-
+    // uniform (scalar registers), lanes outside the images are masked off the load, and only
+    // tiles that have such lanes store zeros for them.  (Vector instructions issued here hold
+    // up the other waves' MFMAs on the same SIMD.)
+    auto issue_part = [&](float* dst, int stride, const float* base, long mapvol, int nm, int width, int total,
+                          FastDiv dw, int rho0, int xg0, int xlim, bool is_in, auto WT) {
+        constexpr int W = decltype(WT)::value;
+        for (int k = 0; k * 64 * W < total; ++k) {
+            const int e = k * 64 * W + lane * W;
+            const int r = (int)fdiv((unsigned)e, dw), x = e - r * width;
+            const int rho = rho0 + r, gx = xg0 + x;
+            const bool inside = e < total;
+            const bool ok = inside && rho < rows && gx < xlim;
+            unsigned voff;
+            if (is_in) {
+                const int z = (int)fdiv((unsigned)rho, P.dOY), y = rho - z * P.oy;
+                voff = (unsigned)((z + (P.kz - 1 - a) * P.spz) * (int)iplane + (y + (P.ky - 1 - b) * P.spy) * P.nx + gx) * 4u;
+            } else {
+                voff = (unsigned)(rho * P.ox + gx) * 4u;
+            }
+            const bool fix = inside && !ok;
+            const bool anyfix = __builtin_amdgcn_ballot_w64(fix) != 0;      // wave-uniform
+            for (int m = wave; m < nm; m += NW) {
+                const char* mb = reinterpret_cast<const char*>(base + (long)m * mapvol);   // uniform
+                float* row = dst + m * stride + k * 64 * W;                                 // uniform
+                if (ok) {
+                    if constexpr (W == 4) __builtin_amdgcn_global_load_lds((global_cptr)(mb + voff), (lds_ptr)row, 16, 0, 0);
+                    else __builtin_amdgcn_global_load_lds((global_cptr)(mb + voff), (lds_ptr)row, 4, 0, 0);
+                }
+                if (anyfix && fix) {
+#pragma unroll
+                    for (int q = 0; q < W; ++q) row[lane * W + q] = 0.f;
+                }
+            }
+        }
+    };
     auto issue_tile = [&](int tile, float* buf) {
         const int xt = tile % P.XT, rt = tile / P.XT;
         const int rho0 = rt * P.R, xs0 = xt * P.TX;
         const int xin0 = xs0 + (P.kx - 1 - cmax) * P.spx;
+        const float* gbase = P.gout + (long)(jg * NJ * 16) * oplane;
+        const float* ibase = P.in + (long)imin * ivol;
         if (P.vec4) {
-            for (int k = 0; k * 256 < RT; ++k) {
-                const int e = k * 256 + lane * 4;
-                const int r = (int)fdiv((unsigned)e, P.dTX), x = e - r * P.TX;
-                const int rho = rho0 + r, gx = xs0 + x;
-                const bool ok = rho < rows && gx < P.ox;
-                const long off = (long)rho * P.ox + gx;
-                if (e < RT) {
-                    for (int m = wave; m < NJ * 16; m += NW) {
-                        const int j = jg * NJ * 16 + m;
-                        const float* src = (ok && j < P.fo) ? P.gout + j * oplane + off : zero4;
-                        __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(buf + m * P.GS + k * 256), 16, 0, 0);
-                    }
-                }
-            }
-            for (int k = 0; k * 256 < RTH; ++k) {
-                const int e = k * 256 + lane * 4;
-                const int r = (int)fdiv((unsigned)e, P.dTXH), x = e - r * TXH;
-                const int rho = rho0 + r, ix = xin0 + x;
-                const bool ok = rho < rows && ix < P.nx;
-                const int z = (int)fdiv((unsigned)rho, P.dOY), y = rho - z * P.oy;
-                const long off = (long)(z + (P.kz - 1 - a) * P.spz) * iplane + (long)(y + (P.ky - 1 - b) * P.spy) * P.nx + ix;
-                if (e < RTH) {
-                    for (int m = wave; m < nmaps; m += NW) {
-                        const float* src = ok ? P.in + (imin + m) * ivol + off : zero4;
-                        __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(buf + itoff + m * P.IS + k * 256), 16, 0, 0);
-                    }
-                }
-            }
-            return;
-        }
-        for (int k = 0; k < nsegG; ++k) {
-            const int e = k * 64 + lane;
-            const int r = (int)fdiv((unsigned)e, P.dTX), x = e - r * P.TX;
-            const int rho = rho0 + r, gx = xs0 + x;
-            const bool ok = rho < rows && gx < P.ox;
-            const long off = (long)rho * P.ox + gx;
-            if (e < RT) {
-                for (int m = wave; m < NJ * 16; m += NW) {
-                    const int j = jg * NJ * 16 + m;
-                    const float* src = (ok && j < P.fo) ? P.gout + j * oplane + off : zero;
-                    __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(buf + m * P.GS + k * 64), 4, 0, 0);
-                }
-            }
-        }
-        for (int k = 0; k < nsegI; ++k) {
-            const int e = k * 64 + lane;
-            const int r = (int)fdiv((unsigned)e, P.dTXH), x = e - r * TXH;
-            const int rho = rho0 + r, ix = xin0 + x;
-            const bool ok = rho < rows && ix < P.nx;
-            const int z = (int)fdiv((unsigned)rho, P.dOY), y = rho - z * P.oy;
-            const long off = (long)(z + (P.kz - 1 - a) * P.spz) * iplane + (long)(y + (P.ky - 1 - b) * P.spy) * P.nx + ix;
-            if (e < RTH) {
-                for (int m = wave; m < nmaps; m += NW) {
-                    const float* src = ok ? P.in + (imin + m) * ivol + off : zero;
-                    __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(buf + itoff + m * P.IS + k * 64), 4, 0, 0);
-                }
-            }
+            issue_part(buf, P.GS, gbase, oplane, mreal, P.TX, RT, P.dTX, rho0, xs0, P.ox, false, std::integral_constant<int, 4>{});
+            issue_part(buf + itoff, P.IS, ibase, ivol, nmaps, TXH, RTH, P.dTXH, rho0, xin0, P.nx, true, std::integral_constant<int, 4>{});
+        } else {
+            issue_part(buf, P.GS, gbase, oplane, mreal, P.TX, RT, P.dTX, rho0, xs0, P.ox, false, std::integral_constant<int, 1>{});
+            issue_part(buf + itoff, P.IS, ibase, ivol, nmaps, TXH, RTH, P.dTXH, rho0, xin0, P.nx, true, std::integral_constant<int, 1>{});
         }
     };
 
@@ -478,6 +465,8 @@ WgradChoice choose_wgrad(const Geom& g)
     c.tps = (int)((c.tiles + ks - 1) / ks);
     c.ksplit = (c.tiles + c.tps - 1) / c.tps;
     if ((long)g.kz * g.ky > 65535 || (long)c.G * c.JG > 65535) c.ok = false;
+    // the tile loader addresses a map with a 32-bit byte offset
+    if (g.nvol() >= (1L << 30) || g.ovol() >= (1L << 30)) c.ok = false;
     return c;
 }
 
