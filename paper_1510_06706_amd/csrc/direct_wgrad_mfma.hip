@@ -234,34 +234,35 @@ __global__ void __launch_bounds__(256 * NH) k_wgrad_mfma(WgradTile P)
         }
     };
 
-    auto compute_tile = [&](const float* buf, int k0, int k1) {
-        if (NH == 1 || ntw == NT)
-            wgrad_steps<NJ, NT, NT>(acc, buf, aoff, boff, k0 + kw, k1, grp, P.dTX, P.TX, TXH, NT);
-        else if (NT > 1 && ntw == NT - 1)
-            wgrad_steps<NJ, NT, (NT > 1 ? NT - 1 : 1)>(acc, buf, aoff, boff, k0 + kw, k1, grp, P.dTX, P.TX, TXH, ntw);
-        else
-            wgrad_steps<NJ, NT, -1>(acc, buf, aoff, boff, k0 + kw, k1, grp, P.dTX, P.TX, TXH, ntw);
-    };
-
-    auto run_tile = [&](const float* cur, float* nxt, int next_tile) {
-        if (next_tile < t_end) issue_tile(next_tile, nxt);
-        compute_tile(cur, 0, nkp);
-    };
-
+    // The whole tile loop is instantiated once per variant of the MFMA steps (all column tiles
+    // live, one padded tile skipped, run-time count) and the variant is chosen once, out here:
+    // choosing per tile would merge the variants' register assignments after every tile, which
+    // costs a copy of every accumulator (vector moves that hold up the matrix pipeline).
     // Two tiles per trip so that each copy of the code names its buffers statically.
-    int tile = s * P.tps;
-    if (tile < t_end) issue_tile(tile, bufA);
-    while (tile < t_end) {
-        __builtin_amdgcn_s_waitcnt(0);     // this wave's loads have landed
-        __syncthreads();                   // everyone's have, and nobody still reads bufB
-        run_tile(bufA, bufB, tile + 1);
-        ++tile;
-        if (tile >= t_end) break;
-        __builtin_amdgcn_s_waitcnt(0);
-        __syncthreads();
-        run_tile(bufB, bufA, tile + 1);
-        ++tile;
-    }
+    auto tile_loop = [&](auto NTA_TAG) {
+        constexpr int NTA = decltype(NTA_TAG)::value;
+        int tile = s * P.tps;
+        if (tile < t_end) issue_tile(tile, bufA);
+        while (tile < t_end) {
+            __builtin_amdgcn_s_waitcnt(0);     // this wave's loads have landed
+            __syncthreads();                   // everyone's have, and nobody still reads bufB
+            if (tile + 1 < t_end) issue_tile(tile + 1, bufB);
+            wgrad_steps<NJ, NT, NTA>(acc, bufA, aoff, boff, kw, nkp, grp, P.dTX, P.TX, TXH, ntw);
+            ++tile;
+            if (tile >= t_end) break;
+            __builtin_amdgcn_s_waitcnt(0);
+            __syncthreads();
+            if (tile + 1 < t_end) issue_tile(tile + 1, bufA);
+            wgrad_steps<NJ, NT, NTA>(acc, bufB, aoff, boff, kw, nkp, grp, P.dTX, P.TX, TXH, ntw);
+            ++tile;
+        }
+    };
+    if (NH == 1 || ntw == NT)
+        tile_loop(std::integral_constant<int, NT>{});
+    else if (NT > 1 && ntw == NT - 1)
+        tile_loop(std::integral_constant<int, (NT > 1 ? NT - 1 : 1)>{});
+    else
+        tile_loop(std::integral_constant<int, -1>{});
 
     // add the accumulators of the four waves of each half in the order 0 + 1 + 2 + 3
     floatx4* red = reinterpret_cast<floatx4*>(bufA) + half * (NJ * NT * 64);
