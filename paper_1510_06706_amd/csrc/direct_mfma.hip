@@ -154,7 +154,9 @@ TileChoice search_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, i
                 long MS = hvol;
                 while (MS % 32 != 16) ++MS;
                 const bool wl = weights_in_lds(taps, NJ);
-                const size_t lds = (size_t)4 * MS * 4 + (wl ? (size_t)taps * NJ * 256 : 0);
+                // two halo buffers, the loader's table (one map's box, padded to the workgroup size), weights
+                const long MSP = (MS + 255) & ~255L;
+                const size_t lds = (size_t)(8 * MS + MSP) * 4 + (wl ? (size_t)taps * NJ * 256 : 0);
                 if (lds > kConvLdsMax) continue;
                 const int cz = (dz + Tz - 1) / Tz, cy = (dy + Ty - 1) / Ty, cx = (dx + Tx - 1) / Tx;
                 const long blocks = (long)cz * cy * cx * jgroups;
@@ -230,7 +232,9 @@ bool mfma_conv_supported(const Geom& g, bool backward)
 {
     const TileChoice c = backward ? choose_tile(g.f, g.fo, g.nz, g.ny, g.nx, g.kz, g.ky, g.kx, g.spz, g.spy, g.spx)
                                   : choose_tile(g.fo, g.f, g.oz, g.oy, g.ox, g.kz, g.ky, g.kx, g.spz, g.spy, g.spx);
-    return c.ok;
+    // the halo loader addresses a source map with a signed 32-bit byte offset
+    const long svol = backward ? g.ovol() : g.nvol();
+    return c.ok && svol < (1L << 29);
 }
 
 size_t mfma_conv_workspace(const Geom& g, bool backward)

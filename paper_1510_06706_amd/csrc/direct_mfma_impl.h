@@ -30,6 +30,8 @@ namespace znn {
 namespace conv {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(1))) const void* global_cptr;
+typedef __attribute__((address_space(3))) void* lds_ptr;
 
 struct ConvTile {
     const float* src;   // K-side images [fK][sz][sy][sx]
@@ -140,8 +142,11 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma(ConvTile P)
 {
     extern __shared__ float lds[];
     const int taps = P.kz * P.ky * P.kx;
-    float* halo = lds;                              // [4][MS]
-    float* wl = halo + 4 * P.MS;                    // [taps][NJ][64] when WL
+    // LDS: two halo buffers [4][MS] that take turns, the table of the halo loader [MSP],
+    // the chunk's weights [taps][NJ][64] when WL
+    const int MSP = (P.MS + 255) & ~255;
+    int* tab = reinterpret_cast<int*>(lds + 8 * P.MS);
+    float* wl = lds + 8 * P.MS + MSP;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar
     const int col = lane & 15, grp = lane >> 4;
 
@@ -176,30 +181,69 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma(ConvTile P)
     const int groups_per_row = P.kx / U;
     const int ngroups = P.kz * P.ky * groups_per_row;
 
-    for (int ic = ic0; ic < ic1; ++ic) {
-        __syncthreads();   // everyone is done reading the previous chunk
-        for (int t = threadIdx.x; t < 4 * hvol; t += 256) {
-            const int r1 = (int)fdiv((unsigned)t, P.dHX), hx = t - r1 * P.HX;
-            const int r2 = (int)fdiv((unsigned)r1, P.dHY), hy = r1 - r2 * P.HY;
-            const int m = (int)fdiv((unsigned)r2, P.dHZ), hz = r2 - m * P.HZ;
+    // Halo loader.  Which voxel of a source map lands in which LDS word is the same for every
+    // chunk, so it is worked out once: tab[r] = byte offset inside a map for word r of a map's
+    // halo box, or -1 for words outside the image (zero padding) and behind the box.  Per chunk
+    // a lane then needs no arithmetic: the map base is wave-uniform, the offset comes from the
+    // table, and the data goes from global memory straight into LDS (no registers), so the
+    // next chunk's box is fetched while this chunk's taps run.  Words with tab < 0 are zeroed
+    // once and never written again.
+    if (P.nchunk < 0) lds[threadIdx.x] = P.src[threadIdx.x];    // never taken: tells the optimizer that LDS holds data
+    for (int r = threadIdx.x; r < MSP; r += 256) {
+        int v = -1;
+        if (r < hvol) {
+            const int r1 = (int)fdiv((unsigned)r, P.dHX), hx = r - r1 * P.HX;
+            const int hz = (int)fdiv((unsigned)r1, P.dHY), hy = r1 - hz * P.HY;
             const int gz = z0 + hz - P.pz, gy = y0 + hy - P.py, gx = x0 + hx - P.px;
-            const int i = ic * 4 + m;
-            float v = 0.f;
-            if (i < P.fK && gz >= 0 && gz < P.sz && gy >= 0 && gy < P.sy && gx >= 0 && gx < P.sx)
-                v = P.src[(long)i * P.sz * splane + gz * splane + (long)gy * P.sx + gx];
-            halo[m * P.MS + (hz * P.HY + hy) * P.HX + hx] = v;
+            if (gz >= 0 && gz < P.sz && gy >= 0 && gy < P.sy && gx >= 0 && gx < P.sx)
+                v = ((gz * P.sy + gy) * P.sx + gx) * 4;
         }
+        tab[r] = v;
+    }
+    for (int q = threadIdx.x; q < 8 * P.MS; q += 256) lds[q] = 0.f;
+    __syncthreads();
+
+    const long svol = (long)P.sz * splane;
+    auto issue_chunk = [&](int ic, float* buf) {
+        const int nvalid = min(4, P.fK - ic * 4);
+        const char* cb = reinterpret_cast<const char*>(P.src + (long)ic * 4 * svol);    // uniform
+        if (nvalid < 4)     // last chunk of a fan-in that is no multiple of four: the missing maps read as zero
+            for (int q = nvalid * P.MS + threadIdx.x; q < 4 * P.MS; q += 256) buf[q] = 0.f;
+        for (int r0 = 0; r0 < P.MS; r0 += 1024) {
+            int tv[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) tv[j] = r0 + j * 256 < MSP ? tab[r0 + j * 256 + threadIdx.x] : -1;
+            for (int m = 0; m < nvalid; ++m) {
+                const char* mb = cb + (long)m * svol * 4;       // uniform
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int q0 = r0 + j * 256 + wave * 64;    // uniform
+                    if (q0 < P.MS && tv[j] >= 0)
+                        __builtin_amdgcn_global_load_lds((global_cptr)(mb + (unsigned)tv[j]), (lds_ptr)(buf + m * P.MS + q0), 4, 0, 0);
+                }
+            }
+        }
+    };
+
+    if (ic0 < ic1) issue_chunk(ic0, lds);
+    for (int ic = ic0; ic < ic1; ++ic) {
+        const int cur = (ic - ic0) & 1;
+        __builtin_amdgcn_s_waitcnt(0);      // this wave's share of the box has landed
+        __syncthreads();                    // everyone's has, and nobody still reads the other buffer
         if (WL) {
             const floatx4* src4 = reinterpret_cast<const floatx4*>(wq);
             floatx4* dst4 = reinterpret_cast<floatx4*>(wl);
             for (int t = threadIdx.x; t < taps * NJ * 16; t += 256) dst4[t] = src4[t];
+            __syncthreads();
         }
-        __syncthreads();
+        if (ic + 1 < ic1) issue_chunk(ic + 1, lds + (cur ^ 1) * 4 * P.MS);
+        const float* halo = lds;            // the buffer's offset rides in the scalar tap offset
 
         float a0[NJ], b0[NV], a1[NJ], b1[NV];
         int vb[NV];
         GroupWalk<U> walk;
         walk.start(P);
+        walk.o += cur * 4 * P.MS;
         const float* wg = wq;
         int wlo = lane;
 #pragma unroll
