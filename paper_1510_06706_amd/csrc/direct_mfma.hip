@@ -111,7 +111,7 @@ struct TileChoice {
     int NJ, jgroups, NV;
     int Tz, Ty, Tx, HZ, HY, HX, MS;
     int cz, cy, cx;
-    bool wl;
+    bool wl, dbuf;
     int cps, splits;    // input-map chunks per workgroup and number of such shares
     size_t lds;
 };
@@ -154,16 +154,21 @@ TileChoice search_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, i
                 long MS = hvol;
                 while (MS % 32 != 16) ++MS;
                 const bool wl = weights_in_lds(taps, NJ);
-                // two halo buffers, the loader's table (one map's box, padded to the workgroup size), weights
+                // halo buffers (two that take turns if they fit, else one), the loader's table (one
+                // map's box, padded to the workgroup size), the chunk's weights
                 const long MSP = (MS + 255) & ~255L;
-                const size_t lds = (size_t)(8 * MS + MSP) * 4 + (wl ? (size_t)taps * NJ * 256 : 0);
+                const size_t wbytes = wl ? (size_t)taps * NJ * 256 : 0;
+                bool dbuf = true;
+                size_t lds = (size_t)(8 * MS + MSP) * 4 + wbytes;
+                if (lds > kConvLdsMax) { dbuf = false; lds = (size_t)(4 * MS + MSP) * 4 + wbytes; }
                 if (lds > kConvLdsMax) continue;
                 const int cz = (dz + Tz - 1) / Tz, cy = (dy + Ty - 1) / Ty, cx = (dx + Tx - 1) / Tx;
                 const long blocks = (long)cz * cy * cx * jgroups;
                 const long rounds = (blocks + kCUs - 1) / kCUs;
                 // time ~ rounds x (MFMA work of a workgroup + halo staging)
                 const double mfma = (double)taps * NJ * NV * 32.0;
-                const double stage = (double)hvol * 4.0 / 256.0 * 12.0;
+                // halo fetch per chunk: hidden behind the taps with two buffers, else one exposed memory latency
+                const double stage = dbuf ? 300.0 + (double)hvol * 4.0 / 256.0 * 2.0 : 1500.0 + (double)hvol * 4.0 / 256.0 * 6.0;
                 const double cost = (double)rounds * (mfma + stage);
                 if (cost < best_cost) {
                     best_cost = cost;
@@ -173,6 +178,7 @@ TileChoice search_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, i
                     best.HZ = HZ; best.HY = HY; best.HX = HX; best.MS = (int)MS;
                     best.cz = cz; best.cy = cy; best.cx = cx;
                     best.wl = wl;
+                    best.dbuf = dbuf;
                     best.lds = lds;
                 }
             }
@@ -272,10 +278,11 @@ int mfma_conv(const Geom& g, bool backward, const float* src, const float* w, fl
     P.cz = c.cz; P.cy = c.cy; P.cx = c.cx;
     P.nchunk = (P.fK + 3) / 4;
     P.cps = c.cps;
+    P.dbuf = c.dbuf ? 1 : 0;
     if (log_enabled())
-        fprintf(stderr, "[znn] conv mfma (%s): NJ=%d jgroups=%d NV=%d U=%d tile=%dx%dx%d halo=%dx%dx%d blocks=%d splits=%d lds=%zu\n",
+        fprintf(stderr, "[znn] conv mfma (%s): NJ=%d jgroups=%d NV=%d U=%d tile=%dx%dx%d halo=%dx%dx%d blocks=%d splits=%d lds=%zu buffers=%d\n",
                 backward ? "bwd" : "fwd", c.NJ, c.jgroups, c.NV, group_width(g.kx, g.spx), c.Tz, c.Ty, c.Tx, c.HZ, c.HY, c.HX,
-                c.cz * c.cy * c.cx, c.splits, c.lds);
+                c.cz * c.cy * c.cx, c.splits, c.lds, c.dbuf ? 2 : 1);
     const int taps = (int)g.kvol();
     float* wp = (float*)ws;
     P.wp = wp;

@@ -48,6 +48,7 @@ struct ConvTile {
     int cz, cy, cx;     // workgroups per axis
     int nchunk;         // ceil(fK / 4)
     int cps;            // chunks per workgroup along gridDim.z (all of them unless the input maps are split)
+    int dbuf;           // 1: two halo buffers take turns (next chunk in flight during the taps), 0: one buffer
     float* partial;     // [splits][fM][dz][dy][dx] partial sums when the input maps are split, else unused
     FastDiv dHX, dHY, dHZ;  // the halo loader takes its flat index apart without integer division
 };
@@ -142,11 +143,12 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma(ConvTile P)
 {
     extern __shared__ float lds[];
     const int taps = P.kz * P.ky * P.kx;
-    // LDS: two halo buffers [4][MS] that take turns, the table of the halo loader [MSP],
-    // the chunk's weights [taps][NJ][64] when WL
+    // LDS: one or two halo buffers [4][MS] (two take turns when they fit), the table of the halo
+    // loader [MSP], the chunk's weights [taps][NJ][64] when WL
     const int MSP = (P.MS + 255) & ~255;
-    int* tab = reinterpret_cast<int*>(lds + 8 * P.MS);
-    float* wl = lds + 8 * P.MS + MSP;
+    const int nbuf = P.dbuf ? 2 : 1;
+    int* tab = reinterpret_cast<int*>(lds + nbuf * 4 * P.MS);
+    float* wl = lds + nbuf * 4 * P.MS + MSP;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar
     const int col = lane & 15, grp = lane >> 4;
 
@@ -200,7 +202,7 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma(ConvTile P)
         }
         tab[r] = v;
     }
-    for (int q = threadIdx.x; q < 8 * P.MS; q += 256) lds[q] = 0.f;
+    for (int q = threadIdx.x; q < nbuf * 4 * P.MS; q += 256) lds[q] = 0.f;
     __syncthreads();
 
     const long svol = (long)P.sz * splane;
@@ -225,9 +227,13 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma(ConvTile P)
         }
     };
 
-    if (ic0 < ic1) issue_chunk(ic0, lds);
+    if (P.dbuf && ic0 < ic1) issue_chunk(ic0, lds);
     for (int ic = ic0; ic < ic1; ++ic) {
-        const int cur = (ic - ic0) & 1;
+        const int cur = P.dbuf ? (ic - ic0) & 1 : 0;
+        if (!P.dbuf) {
+            __syncthreads();                // everyone is done reading the previous chunk
+            issue_chunk(ic, lds);
+        }
         __builtin_amdgcn_s_waitcnt(0);      // this wave's share of the box has landed
         __syncthreads();                    // everyone's has, and nobody still reads the other buffer
         if (WL) {
@@ -236,7 +242,7 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma(ConvTile P)
             for (int t = threadIdx.x; t < taps * NJ * 16; t += 256) dst4[t] = src4[t];
             __syncthreads();
         }
-        if (ic + 1 < ic1) issue_chunk(ic + 1, lds + (cur ^ 1) * 4 * P.MS);
+        if (P.dbuf && ic + 1 < ic1) issue_chunk(ic + 1, lds + (cur ^ 1) * 4 * P.MS);
         const float* halo = lds;            // the buffer's offset rides in the scalar tap offset
 
         float a0[NJ], b0[NV], a1[NJ], b1[NV];
