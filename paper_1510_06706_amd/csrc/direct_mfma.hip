@@ -119,6 +119,19 @@ struct TileChoice {
 constexpr int kCUs = 256;
 constexpr size_t kConvLdsMax = 64 * 1024;
 
+// A layer with few output voxels leaves most compute units without a workgroup (and the rest
+// with one wave per SIMD): below one workgroup per unit the input-map chunks are split over
+// gridDim.z until about three per unit exist; the shares' partial sums are added in a fixed
+// order afterwards.
+void split_chunks(long blocks, int nchunk, int& cps, int& splits)
+{
+    static const bool nosplit = getenv("ZNN_CONV_NO_SPLIT") != nullptr;
+    long want = nosplit || blocks >= kCUs ? 1 : (3 * kCUs + blocks - 1) / blocks;
+    if (want > nchunk) want = nchunk;
+    cps = (int)(nchunk / want);        // rounded down: shares of equal length, a few more of them
+    splits = (nchunk + cps - 1) / cps;
+}
+
 // Picks the tile box and the per-wave tile count so that the launch fills the
 // 256 compute units in as few, as full rounds as possible.
 TileChoice search_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, int kx, int spz, int spy, int spx)
@@ -131,6 +144,7 @@ TileChoice search_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, i
     const int jgroups = (tiles + 7) / 8;
     const int NJ = (tiles + jgroups - 1) / jgroups;
     double best_cost = 1e300;
+    const int nchunk = (fK + 3) / 4;
     // tuning aid: ZNN_CONV_TILE="NV,Tz,Ty,Tx" pins the configuration
     int pin[4] = {0, 0, 0, 0};
     if (const char* e = getenv("ZNN_CONV_TILE")) sscanf(e, "%d,%d,%d,%d", &pin[0], &pin[1], &pin[2], &pin[3]);
@@ -164,12 +178,20 @@ TileChoice search_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, i
                 if (lds > kConvLdsMax) continue;
                 const int cz = (dz + Tz - 1) / Tz, cy = (dy + Ty - 1) / Ty, cx = (dx + Tx - 1) / Tx;
                 const long blocks = (long)cz * cy * cx * jgroups;
-                const long rounds = (blocks + kCUs - 1) / kCUs;
-                // time ~ rounds x (MFMA work of a workgroup + halo staging)
+                // shares of the input maps along gridDim.z when the output gives few workgroups (see below)
+                int cps, splits;
+                split_chunks(blocks, nchunk, cps, splits);
+                // time ~ workgroups per compute unit (they share its matrix cores whether they run side
+                // by side or one after the other) x (fixed cost of a workgroup + its chunks x (MFMA work +
+                // halo fetch)); a unit with a single workgroup has one wave per SIMD and nothing to overlap
+                // its waits with (measured on the 2D benchmark layer: 1.4x)
+                const long groups = blocks * splits;
+                const double rounds = (double)((groups + kCUs - 1) / kCUs) * (groups <= kCUs ? 1.4 : 1.0);
                 const double mfma = (double)taps * NJ * NV * 32.0;
                 // halo fetch per chunk: hidden behind the taps with two buffers, else one exposed memory latency
                 const double stage = dbuf ? 300.0 + (double)hvol * 4.0 / 256.0 * 2.0 : 1500.0 + (double)hvol * 4.0 / 256.0 * 6.0;
-                const double cost = (double)rounds * (mfma + stage);
+                const double fixed = 3000.0 + (double)MS / 256.0 * 300.0;      // launch, table, zero fill, epilogue
+                const double cost = rounds * (fixed + cps * (mfma + stage));
                 if (cost < best_cost) {
                     best_cost = cost;
                     best.ok = true;
@@ -179,22 +201,11 @@ TileChoice search_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, i
                     best.cz = cz; best.cy = cy; best.cx = cx;
                     best.wl = wl;
                     best.dbuf = dbuf;
+                    best.cps = cps; best.splits = splits;
                     best.lds = lds;
                 }
             }
         }
-    }
-    // A layer with few output voxels leaves most compute units without a workgroup (and the
-    // rest with one wave per SIMD): below one workgroup per unit the input maps are split over
-    // gridDim.z until about three per unit exist; the shares' partial sums are added in a fixed order afterwards.
-    if (best.ok) {
-        const int nchunk = (fK + 3) / 4;
-        static const bool nosplit = getenv("ZNN_CONV_NO_SPLIT") != nullptr;
-        const long blocks = (long)best.cz * best.cy * best.cx * best.jgroups;
-        long want = nosplit || blocks >= kCUs ? 1 : (3 * kCUs + blocks - 1) / blocks;
-        if (want > nchunk) want = nchunk;
-        best.cps = (int)(nchunk / want);        // rounded down: shares of equal length, a few more of them
-        best.splits = (nchunk + best.cps - 1) / best.cps;
     }
     return best;
 }
@@ -207,6 +218,7 @@ TileChoice choose_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, i
     static std::mutex lock;
     static std::vector<Entry> memo;
     const int key[11] = {fM, fK, dz, dy, dx, kz, ky, kx, spz, spy, spx};
+    if (getenv("ZNN_CONV_TILE")) return search_tile(fM, fK, dz, dy, dx, kz, ky, kx, spz, spy, spx);   // tuning aid: not remembered
     {
         std::lock_guard<std::mutex> hold(lock);
         for (const Entry& e : memo)

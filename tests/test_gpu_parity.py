@@ -70,6 +70,43 @@ def test_three_passes_match_the_oracle(f, fo, n, k, mode):
     p.close()
 
 
+DIRECT_TAPS = [
+    # f, fo, n, k, s: shapes that steer the direct kernels through every way they walk the taps and
+    # fetch the halo boxes (x-tap groups of 7, 5, 4, 3, 2 and single taps; odd and even numbers of
+    # groups; a last chunk of fewer than four input maps behind several full ones; input maps split
+    # over workgroups with a ragged last share; boxes too wide for two halo buffers)
+    (10, 7, (9, 9, 20), (2, 2, 7), (1, 1, 1)),
+    (6, 5, (8, 9, 16), (3, 1, 6), (1, 1, 1)),
+    (9, 4, (7, 8, 19), (1, 3, 9), (1, 1, 1)),
+    (5, 6, (6, 7, 22), (2, 1, 10), (1, 1, 1)),
+    (4, 3, (5, 6, 24), (1, 2, 11), (1, 1, 1)),
+    (7, 8, (5, 8, 30), (2, 2, 14), (1, 1, 1)),
+    (11, 5, (6, 6, 20), (1, 1, 8), (1, 1, 1)),
+    (13, 6, (10, 10, 10), (3, 3, 2), (1, 1, 1)),
+    (27, 40, (14, 14, 14), (3, 3, 3), (1, 1, 1)),
+    (40, 3, (20, 20, 20), (3, 3, 3), (4, 4, 4)),
+    (21, 24, (26, 26, 26), (3, 3, 3), (4, 4, 4)),
+    (18, 40, (30, 30, 30), (5, 5, 5), (1, 1, 1)),
+]
+
+
+@pytest.mark.parametrize("f,fo,n,k,s", DIRECT_TAPS)
+def test_direct_kernels_on_every_tap_walk_and_halo_mode(f, fo, n, k, s):
+    print("case", f, fo, n, k, s, flush=True)
+    cfg = synth.LayerShape("t", f, fo, n, k, 1.0, 300 + f + fo, s)
+    inp, w, gout = synth.layer_tensors(cfg)
+    p = znn.Plan(f, fo, n, k, "direct", s)
+    d_in, d_w, d_g = dev(inp), dev(w), dev(gout)
+    out, gin, gw = host(p.fwd(d_in, d_w)), host(p.bwd(d_g, d_w)), host(p.wgrad(d_in, d_g))
+    assert rel_err(out, oracle.conv3d_fwd(inp, w, s)) <= TOL["direct"]
+    assert rel_err(gin, oracle.conv3d_bwd(gout, w, n, s)) <= TOL["direct"]
+    assert rel_err(gw, oracle.conv3d_wgrad(inp, gout, s)) <= TOL["direct"]
+    # a second call on the same plan (LDS contents of an earlier launch must not matter)
+    assert np.array_equal(out, host(p.fwd(d_in, d_w)))
+    assert np.array_equal(gin, host(p.bwd(d_g, d_w)))
+    p.close()
+
+
 SPARSE = [
     # f, fo, n, k, s      (sparse convolution: taps s voxels apart, Section 2)
     (3, 5, (11, 12, 13), (2, 3, 2), (2, 2, 3)),
