@@ -98,8 +98,8 @@ static DescKey key_of(const znn_conv_desc& d)
 
 // Cost model behind mode = auto when no measurement is cached, calibrated on the five
 // benchmark configurations and the layers of the benchmark networks.  Direct: a dense fp32
-// contraction at about 80 effective TFLOP/s, scaled down when the output has too few voxel
-// tiles to occupy the 256 compute units.  FFT: the two multiply-accumulates and the pruned
+// contraction at about 92 effective TFLOP/s, scaled down when the output has too few voxel
+// tiles (times the shares its input maps can be split into) to occupy the 256 compute units.  FFT: the two multiply-accumulates and the pruned
 // DFTs of the kernel gradient are ALU work (kernel taps folded in) or stream the full kernel
 // spectra from HBM (small layers, extents not divisible by 4), the node transforms move
 // 16 bytes per frequency and pass at about 3.5 TB/s effective; both pay per launch.
@@ -107,8 +107,10 @@ static int model_choice(const Geom& g)
 {
     const double macs = (double)g.f * g.fo * (double)g.ovol() * (double)g.kvol();
     const double tiles = std::ceil((double)g.ovol() / 128.0) * std::ceil((double)g.fo / 128.0);
-    const double util = tiles >= 256.0 ? 1.0 : tiles / 256.0;
-    const double t_direct = 3.0 * 2.0 * macs / (80e12 * util) + 5 * 6e-6;
+    const double nchunk = std::ceil(g.f / 4.0);
+    const double splits = tiles >= 256.0 ? 1.0 : std::min(nchunk, std::ceil(768.0 / tiles));
+    const double util = std::min(1.0, tiles * splits / 1024.0);
+    const double t_direct = 3.0 * 2.0 * macs / (92e12 * util) + 7 * 10e-6;
     const double sv = (double)g.svol();
     const double pairs = (double)g.f * g.fo;
     const int taps = g.Nz > 1 ? g.kz : g.ky;
