@@ -50,6 +50,8 @@ struct WgradTile {
     int AB;             // kz * ky
     FastDiv dTX, dTXH, dOY;
     int vec4;           // 16-byte global->LDS loads are legal for this shape
+    int fast;           // the tile loader may use offsets worked out once per workgroup (see the kernel)
+    FastDiv dGS, dIS;
 };
 
 // The MFMAs of this wave's share of one staged tile.  A step covers 8 consecutive voxels:
@@ -219,7 +221,56 @@ __global__ void __launch_bounds__(256 * NH) k_wgrad_mfma(WgradTile P)
             }
         }
     };
+    // Fast loader (P.fast, decided on the host: one x-segment per row, 16-byte loads, tiles that
+    // neither straddle a z-plane nor end behind the last row).  A wave-load then fills 256
+    // consecutive floats of a tile region regardless of where map rows begin and end; which map and
+    // which voxel a lane's four floats belong to is the same for every tile, so the lane's byte offset
+    // from the tile's origin and its validity are worked out once, here, and a tile costs this wave a
+    // handful of loads with no vector arithmetic at all.  Spans are dealt to the waves round-robin.
+    constexpr int kMaxSpans = 5;
+    unsigned fg_off[kMaxSpans], fi_off[kMaxSpans];
+    bool fg_ok[kMaxSpans], fi_ok[kMaxSpans];
+    const int nspan_g = (mreal * P.GS + 255) >> 8, nspan_i = (nmaps * P.IS + 255) >> 8;
+    if (P.fast) {
+#pragma unroll
+        for (int q = 0; q < kMaxSpans; ++q) {
+            const int L = (wave + q * NW) * 256 + lane * 4;
+            {
+                const int m = (int)fdiv((unsigned)L, P.dGS), e = L - m * P.GS;
+                const int r = (int)fdiv((unsigned)e, P.dTX), x = e - r * P.TX;
+                fg_ok[q] = m < mreal && e < RT && x < P.ox;
+                fg_off[q] = (unsigned)(m * (int)oplane + r * P.ox + x) * 4u;
+            }
+            {
+                const int m = (int)fdiv((unsigned)L, P.dIS), e = L - m * P.IS;
+                const int r = (int)fdiv((unsigned)e, P.dTXH), x = e - r * TXH;
+                const int ix = (P.kx - 1 - cmax) * P.spx + x;
+                fi_ok[q] = m < nmaps && e < RTH && ix < P.nx;
+                fi_off[q] = (unsigned)(m * (int)ivol + r * P.nx + ix) * 4u;
+            }
+        }
+    }
+    auto issue_tile_fast = [&](int tile, float* buf) {
+        const int rho0 = tile * P.R;                                    // XT == 1
+        const int z = (int)fdiv((unsigned)rho0, P.dOY), y = rho0 - z * P.oy;
+        const char* gb = reinterpret_cast<const char*>(P.gout + (long)(jg * NJ * 16) * oplane + (long)rho0 * P.ox);
+        const char* ib = reinterpret_cast<const char*>(P.in + (long)imin * ivol + (long)(z + (P.kz - 1 - a) * P.spz) * iplane +
+                                                       (long)(y + (P.ky - 1 - b) * P.spy) * P.nx);
+#pragma unroll
+        for (int q = 0; q < kMaxSpans; ++q) {
+            const int sp = wave + q * NW;                               // uniform
+            if (sp < nspan_g && fg_ok[q])
+                __builtin_amdgcn_global_load_lds((global_cptr)(gb + fg_off[q]), (lds_ptr)(buf + sp * 256), 16, 0, 0);
+        }
+#pragma unroll
+        for (int q = 0; q < kMaxSpans; ++q) {
+            const int sp = wave + q * NW;
+            if (sp < nspan_i && fi_ok[q])
+                __builtin_amdgcn_global_load_lds((global_cptr)(ib + fi_off[q]), (lds_ptr)(buf + itoff + sp * 256), 16, 0, 0);
+        }
+    };
     auto issue_tile = [&](int tile, float* buf) {
+        if (P.fast) { issue_tile_fast(tile, buf); return; }
         const int xt = tile % P.XT, rt = tile / P.XT;
         const int rho0 = rt * P.R, xs0 = xt * P.TX;
         const int xin0 = xs0 + (P.kx - 1 - cmax) * P.spx;
@@ -373,7 +424,7 @@ struct WgradChoice {
     int TX, XT, R, GS, IS, TXH;
     int Mpad, Npad;
     int tiles, tps, ksplit;
-    int vec4;
+    int vec4, fast;
     size_t lds;
 };
 
@@ -465,6 +516,15 @@ WgradChoice choose_wgrad(const Geom& g)
     if (ks > c.tiles) ks = c.tiles;
     c.tps = (int)((c.tiles + ks - 1) / ks);
     c.ksplit = (c.tiles + c.tps - 1) / c.tps;
+    {
+        // fast tile loader: see the kernel.  Spans per wave must fit its register arrays, and a lane's
+        // offset from the tile origin (up to a whole group of maps) must fit 32 bits.
+        const int nw = 4 * c.NH;
+        const long span_g = ((long)c.NJ * 16 * c.GS + 255) / 256, span_i = ((long)g.f * c.IS + 255) / 256;
+        c.fast = (c.vec4 && c.XT == 1 && g.oy % c.R == 0 && (span_g + nw - 1) / nw <= 5 && (span_i + nw - 1) / nw <= 5 &&
+                  (double)g.fo * g.ovol() * 4.0 < 2147483648.0 && (double)g.f * g.nvol() * 4.0 < 2147483648.0 &&
+                  !getenv("ZNN_WGRAD_SLOW_LOADER")) ? 1 : 0;
+    }
     if ((long)g.kz * g.ky > 65535 || (long)c.G * c.JG > 65535) c.ok = false;
     // the tile loader addresses a map with a 32-bit byte offset
     if (g.nvol() >= (1L << 30) || g.ovol() >= (1L << 30)) c.ok = false;
@@ -500,6 +560,8 @@ int mfma_wgrad(const Geom& g, const float* in, const float* gout, float* gw, voi
     P.tiles = c.tiles; P.tps = c.tps;
     P.AB = g.kz * g.ky;
     P.vec4 = c.vec4;
+    P.fast = c.fast;
+    P.dGS = make_fastdiv(c.GS); P.dIS = make_fastdiv(c.IS);
     P.dTX = make_fastdiv(c.TX); P.dTXH = make_fastdiv(c.TXH); P.dOY = make_fastdiv(g.oy);
     if (log_enabled())
         fprintf(stderr, "[znn] wgrad mfma: NJ=%d JG=%d NT=%d NH=%d G=%d TX=%d XT=%d R=%d lds=%zu ksplit=%d tiles=%d\n",
