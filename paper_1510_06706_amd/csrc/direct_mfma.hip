@@ -80,8 +80,8 @@ int group_width(int kx, int spx)
 {
     static const bool off = getenv("ZNN_CONV_U1") != nullptr;
     if (off || spx != 1) return 1;
-    const int widths[5] = {7, 5, 4, 3, 2};
-    for (int i = 0; i < 5; ++i)
+    const int widths[6] = {11, 7, 5, 4, 3, 2};
+    for (int i = 0; i < 6; ++i)
         if (kx % widths[i] == 0) return widths[i];
     return 1;
 }
@@ -95,6 +95,7 @@ ConvFn pick_kernel(int U, int nj, int nv, bool wl)
         case 4: return conv_kernel_u4(nj, nv, wl);
         case 5: return conv_kernel_u5(nj, nv, wl);
         case 7: return conv_kernel_u7(nj, nv, wl);
+        case 11: return conv_kernel_u11(nj, nv, wl);
     }
     return nullptr;
 }

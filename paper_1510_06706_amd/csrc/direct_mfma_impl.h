@@ -338,5 +338,6 @@ conv::ConvFn conv_kernel_u3(int nj, int nv, bool wl);
 conv::ConvFn conv_kernel_u4(int nj, int nv, bool wl);
 conv::ConvFn conv_kernel_u5(int nj, int nv, bool wl);
 conv::ConvFn conv_kernel_u7(int nj, int nv, bool wl);
+conv::ConvFn conv_kernel_u11(int nj, int nv, bool wl);
 
 }  // namespace znn

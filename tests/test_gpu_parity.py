@@ -72,7 +72,7 @@ def test_three_passes_match_the_oracle(f, fo, n, k, mode):
 
 DIRECT_TAPS = [
     # f, fo, n, k, s: shapes that steer the direct kernels through every way they walk the taps and
-    # fetch the halo boxes (x-tap groups of 7, 5, 4, 3, 2 and single taps; odd and even numbers of
+    # fetch the halo boxes (x-tap groups of 11, 7, 5, 4, 3, 2 and single taps; odd and even numbers of
     # groups; a last chunk of fewer than four input maps behind several full ones; input maps split
     # over workgroups with a ragged last share; boxes too wide for two halo buffers)
     (10, 7, (9, 9, 20), (2, 2, 7), (1, 1, 1)),
@@ -81,6 +81,8 @@ DIRECT_TAPS = [
     (5, 6, (6, 7, 22), (2, 1, 10), (1, 1, 1)),
     (4, 3, (5, 6, 24), (1, 2, 11), (1, 1, 1)),
     (7, 8, (5, 8, 30), (2, 2, 14), (1, 1, 1)),
+    (6, 5, (4, 7, 28), (1, 2, 13), (1, 1, 1)),
+    (5, 9, (3, 14, 40), (1, 3, 22), (1, 1, 1)),
     (11, 5, (6, 6, 20), (1, 1, 8), (1, 1, 1)),
     (13, 6, (10, 10, 10), (3, 3, 2), (1, 1, 1)),
     (27, 40, (14, 14, 14), (3, 3, 3), (1, 1, 1)),
