@@ -117,10 +117,11 @@ static int model_choice(const Geom& g)
     const int N = g.Nz > 1 ? g.Nz : g.Ny;
     const int sp = g.Nz > 1 ? g.spz : g.spy;
     const double P = g.Nz > 1 ? (double)g.Ny * g.Nxh : (double)g.Nxh;
-    const bool folded = N % 4 == 0 && taps <= 16 && taps < N && sp == 1 &&
-                        std::ceil(P / 64.0) * std::ceil(N / 32.0) * std::ceil(std::min(g.f, g.fo) / 4.0) >= 128.0;
+    const double mac_blocks = std::ceil(P / 64.0) * std::ceil(N / 32.0) * std::ceil(std::min(g.f, g.fo) / 4.0);
+    const bool folded = N % 4 == 0 && taps <= 16 && taps < N && sp == 1 && mac_blocks >= 128.0;
     double t_mac;
-    if (folded) t_mac = 2.0 * 8.0 * taps * sv * pairs / 55e12 + 8.0 * taps * P * pairs / 3e12;
+    // the folded multiply-accumulate needs about four workgroups per compute unit to reach its rate
+    if (folded) t_mac = 2.0 * 8.0 * taps * sv * pairs / (55e12 * std::min(1.0, mac_blocks / 1024.0)) + 8.0 * taps * P * pairs / 3e12;
     else t_mac = 8.0 * sv * pairs * (1.0 / 4.5e12 + 2.0 / 5.5e12 + 0.3 / 5e12);
     const double t_dft = (taps / 4.0 + 2.0) * 8.0 * sv * pairs / 45e12;
     const double t_nodes = 3.0 * (g.f + g.fo) * 3.0 * 16.0 * sv / 3.5e12;

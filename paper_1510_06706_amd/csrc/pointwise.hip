@@ -161,17 +161,24 @@ k_cross_entropy_grad(long total, const float* __restrict__ y, const float* __res
     g[t] = (v - t_[t]) / (v * (1.0f - v));
 }
 
-// One block per map; every thread sums a fixed strided subset, then a fixed tree.
-__global__ void __launch_bounds__(256)
+// One block per map; every thread sums a fixed strided subset in four independent partial
+// sums (the loads of one trip are in flight together), then a fixed tree: the order of the
+// additions depends on nothing but the shape.
+__global__ void __launch_bounds__(1024)
 k_bias_grad(long voxels, const float* __restrict__ g, float* __restrict__ gb)
 {
-    __shared__ float red[256];
+    __shared__ float red[1024];
     const float* p = g + (long)blockIdx.x * voxels;
-    float acc = 0.f;
-    for (long t = threadIdx.x; t < voxels; t += 256) acc += p[t];
-    red[threadIdx.x] = acc;
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    for (long t = threadIdx.x; t < voxels; t += 4096) {
+        a0 += p[t];
+        if (t + 1024 < voxels) a1 += p[t + 1024];
+        if (t + 2048 < voxels) a2 += p[t + 2048];
+        if (t + 3072 < voxels) a3 += p[t + 3072];
+    }
+    red[threadIdx.x] = (a0 + a1) + (a2 + a3);
     __syncthreads();
-    for (int s = 128; s > 0; s >>= 1) {
+    for (int s = 512; s > 0; s >>= 1) {
         if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
         __syncthreads();
     }
@@ -387,7 +394,7 @@ int znn_bias_grad(int32_t maps, int64_t voxels, const float* g, float* gb, void*
 {
     if (maps < 1 || voxels < 1) return fail(ZNN_EINVAL, "maps and voxels must be >= 1");
     if (!g || !gb) return fail(ZNN_EINVAL, "NULL argument");
-    ZNN_LAUNCH("bias gradient", (hipStream_t)stream, k_bias_grad, dim3((unsigned)maps), dim3(256), 0, (long)voxels, g, gb);
+    ZNN_LAUNCH("bias gradient", (hipStream_t)stream, k_bias_grad, dim3((unsigned)maps), dim3(1024), 0, (long)voxels, g, gb);
     return check_launch("bias gradient");
 }
 
