@@ -192,7 +192,9 @@ TileChoice search_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, i
                 // halo fetch per chunk: hidden behind the taps with two buffers, else one exposed memory latency
                 const double stage = dbuf ? 300.0 + (double)hvol * 4.0 / 256.0 * 2.0 : 1500.0 + (double)hvol * 4.0 / 256.0 * 6.0;
                 const double fixed = 3000.0 + (double)MS / 256.0 * 300.0;      // launch, table, zero fill, epilogue
-                const double cost = rounds * (fixed + cps * (mfma + stage));
+                // among boxes of equal cost the one that is longest along x: longer contiguous runs in the
+                // epilogue's stores and in the halo fetch (config 2: 12x6x6 -> 6x6x12, 2 % faster)
+                const double cost = rounds * (fixed + cps * (mfma + stage)) - 0.01 * Tx;
                 if (cost < best_cost) {
                     best_cost = cost;
                     best.ok = true;
