@@ -175,12 +175,15 @@ __global__ void __launch_bounds__(256 * NH) k_wgrad_mfma(WgradTile P)
     const long ivol = (long)P.nz * iplane;
     const int t_end = min((s + 1) * P.tps, P.tiles);
     const int RT = P.R * P.TX, RTH = P.R * TXH;
-    const int nkp = RT / 8;     // 8-voxel steps per tile (R * TX is a multiple of 8)
-    // rows of the gout tile that hold real maps; the padding rows up to NJ*16 never change:
-    // they are zeroed once, in both buffers, and never loaded
+    // 8-voxel steps per tile.  R * TX is a multiple of 4; when it is no multiple of 8 the last step
+    // runs half into the padding behind a map row, which holds zeros in the gout tile.
+    const int nkp = (RT + 7) / 8;
+    // Both buffers are zeroed once: the loaders never write padding (rows of maps past the last real
+    // one, words behind a row's voxels, lanes outside the images on tiles that have none), so it
+    // stays zero, and whatever an MFMA step reads next to a zero gout word is a finite number.
     const int mreal = min(NJ * 16, P.fo - jg * NJ * 16);
-    for (int m = mreal + wave; m < NJ * 16; m += NW)
-        for (int e = lane; e < RT; e += 64) { bufA[m * P.GS + e] = 0.f; bufB[m * P.GS + e] = 0.f; }
+    for (int q = threadIdx.x; q < kBufFloats; q += 64 * NW) { bufA[q] = 0.f; bufB[q] = 0.f; }
+    __syncthreads();
 
     // Queue the global->LDS loads of one tile.  A wave-load moves 64 * W consecutive tile
     // elements of one map (W = 4: 16-byte loads, legal when every group of four x-neighbours
@@ -493,13 +496,15 @@ WgradChoice choose_wgrad(const Geom& g)
         const int TXH = (TX + cspan * g.spx + 3) & ~3;
         int bestR = 0;
         for (int R = 1; R <= 32 && R <= rows; ++R) {
-            if ((R * TX) % 8 != 0) continue;    // the MFMA loop walks 8 voxels per step
-            const long floats = (long)c.NJ * 16 * pad_stride(R * TX) + (long)nmaps * pad_stride(R * TXH);
+            // the MFMA loop walks 8 voxels per step; a tile that ends on half a step reads its last four
+            // voxels from the zero padding behind the row (gout) and from whatever follows (in)
+            const int rtp = (R * TX + 7) & ~7;
+            const long floats = (long)c.NJ * 16 * pad_stride(rtp) + (long)nmaps * pad_stride(R * TXH) + 64;
             if (floats <= kBufFloats) bestR = R;
         }
         if (bestR == 0) continue;
         c.XT = XT; c.TX = TX; c.TXH = TXH; c.R = bestR;
-        c.GS = pad_stride(bestR * TX); c.IS = pad_stride(bestR * TXH);
+        c.GS = pad_stride((bestR * TX + 7) & ~7); c.IS = pad_stride(bestR * TXH);
         c.lds = 2 * (size_t)kBufFloats * 4;
         // 16-byte loads: groups of four x-neighbours must be wholly inside or outside the
         // images and start on multiples of four in both tensors
