@@ -67,8 +67,8 @@ def cpu_baseline(cfg, inp, w, gout, budget_s=18.0):
 
 
 def report_all_configs(path):
-    """Per-pass times of every benchmark configuration (not part of the timed step): configs 1, 2, 4 in
-    both methods, config 5 with resident kernel spectra, config 3 as a whole training round."""
+    """Per-pass times of every benchmark configuration (not part of the timed step): configs 1, 2, 4, 5 in
+    both methods (config 5's FFT rows with resident kernel spectra), config 3 as a whole training round."""
     import torch
     from paper_1510_06706_amd import binding as znn
     from paper_1510_06706_amd import net as znet
@@ -86,7 +86,7 @@ def report_all_configs(path):
 
     rows = []
     for cfg, modes in ((synth.CONFIG1, ("direct", "fft")), (synth.CONFIG2, ("direct", "fft")),
-                       (synth.CONFIG4, ("direct", "fft")), (synth.CONFIG5, ("fft",))):
+                       (synth.CONFIG4, ("direct", "fft")), (synth.CONFIG5, ("direct", "fft"))):
         inp, w, gout = synth.layer_tensors(cfg)
         d_in, d_w, d_g = (torch.from_numpy(a).to("cuda:0") for a in (inp, w, gout))
         del inp, w, gout
