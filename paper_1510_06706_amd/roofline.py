@@ -16,7 +16,7 @@ PEAK_HBM_GBS = 8000.0           # HBM3E
 # separate profiler run, not measured by the benchmark itself.
 MIB = 1024.0 * 1024.0
 MEASURED_TRAFFIC_CONFIG2 = {
-    "direct forward (MFMA)": (326.3 * MIB, 72.5 * MIB),
+    "direct forward (MFMA)": (253.8 * MIB, 45.4 * MIB),
     "direct backward (MFMA)": (188.5 * MIB, 40.0 * MIB),
     "direct kernel gradient (MFMA)": (847.2 * MIB, 10.3 * MIB),
     "spectral mac forward (taps folded in)": (451.2 * MIB, 41.3 * MIB),
