@@ -72,6 +72,21 @@ def test_config5_large_layer_with_resident_kernel_spectra():
     sampled_layer_check(synth.CONFIG5, "fft", True, 4096, 4096, 1024)
 
 
+@pytest.mark.timeout(600)
+def test_config5_by_the_direct_method():
+    """The paper runs its largest layer by the FFT method only; the direct kernels take it too
+    (single halo buffer, seven-tap groups, eight map tiles per wave)."""
+    sampled_layer_check(synth.CONFIG5, "direct", False, 2048, 2048, 512)
+
+
+@pytest.mark.parametrize("f,fo,n,k", [(37, 50, (40, 41, 42), (4, 3, 4)), (22, 40, (36, 36, 36), (3, 3, 3))])
+def test_ragged_mid_size_layers_by_the_direct_method(f, fo, n, k):
+    """Fan-ins that are no multiple of four behind several full chunks, output boxes that overhang
+    the image on every axis, kernel-gradient tiles with and without the 16-byte loader."""
+    cfg = synth.LayerShape("ragged", f, fo, n, k, 1.0 / np.sqrt(f * np.prod(k)), 400 + f)
+    sampled_layer_check(cfg, "direct", False, 4096, 4096, 1024)
+
+
 ONES = (1, 1, 1)
 
 
