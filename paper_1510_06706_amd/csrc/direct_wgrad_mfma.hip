@@ -51,6 +51,7 @@ struct WgradTile {
     FastDiv dTX, dTXH, dOY;
     int vec4;           // 16-byte global->LDS loads are legal for this shape
     int fast;           // the tile loader may use offsets worked out once per workgroup (see the kernel)
+    int mapmajor;       // GEMM columns ordered n = i*kx + c instead of n = c*f + i (see choose_wgrad)
     FastDiv dGS, dIS;
 };
 
@@ -139,9 +140,17 @@ __global__ void __launch_bounds__(256 * NH) k_wgrad_mfma(WgradTile P)
     const int ncols = P.f * P.kx;
     const int n0 = cg * NT * NH * 16;
     const int n1 = min(n0 + NT * NH * 16, ncols);
-    const int cmin = n0 / P.f, cmax = (n1 - 1) / P.f;
-    int imin = 0, imax = P.f - 1;
-    if (cmin == cmax) { imin = n0 % P.f; imax = (n1 - 1) % P.f; }
+    // the group's range of x-taps [cmin, cmax] and of input maps [imin, imax]
+    int cmin, cmax, imin, imax;
+    if (P.mapmajor) {
+        imin = n0 / P.kx; imax = (n1 - 1) / P.kx;
+        cmin = 0; cmax = P.kx - 1;
+        if (imin == imax) { cmin = n0 % P.kx; cmax = (n1 - 1) % P.kx; }
+    } else {
+        cmin = n0 / P.f; cmax = (n1 - 1) / P.f;
+        imin = 0; imax = P.f - 1;
+        if (cmin == cmax) { imin = n0 % P.f; imax = (n1 - 1) % P.f; }
+    }
     const int nmaps = imax - imin + 1;
     const int TXH = P.TXH;
     const int itoff = NJ * 16 * P.GS;       // the in tile follows the gout tile in a buffer
@@ -154,7 +163,7 @@ __global__ void __launch_bounds__(256 * NH) k_wgrad_mfma(WgradTile P)
         const int n = n0 + (half * NT + nt) * 16 + col;
         int o = 0;
         if (n < n1) {
-            const int c = n / P.f, i = n % P.f;
+            const int c = P.mapmajor ? n % P.kx : n / P.f, i = P.mapmajor ? n / P.kx : n % P.f;
             o = (i - imin) * P.IS + (cmax - c) * P.spx;
         }
         boff[nt] = itoff + o;
@@ -354,7 +363,7 @@ __global__ void __launch_bounds__(256 * NH) k_wgrad_mfma(WgradTile P)
 // gw[j][i][a][b][c] = sum over splits of partial[s][ab][j][c*f + i], ascending s.
 __global__ void __launch_bounds__(256)
 k_wgrad_reduce(const float* __restrict__ partial, float* __restrict__ gw, int f, int fo, int kz, int ky, int kx,
-               int ksplit, int Mpad, int Npad)
+               int ksplit, int Mpad, int Npad, int mapmajor)
 {
     const int taps = kz * ky * kx;
     const long total = (long)fo * f * taps;
@@ -365,7 +374,7 @@ k_wgrad_reduce(const float* __restrict__ partial, float* __restrict__ gw, int f,
     const int i = (int)(e % f), j = (int)(e / f);
     const int c = tap % kx, ab = tap / kx;
     const int AB = kz * ky;
-    const int n = c * f + i;
+    const int n = mapmajor ? i * kx + c : c * f + i;
     float acc = 0.f;
     for (int s = 0; s < ksplit; ++s) acc += partial[((long)(s * AB + ab) * Mpad + j) * Npad + n];
     gw[t] = acc;
@@ -428,7 +437,7 @@ struct WgradChoice {
     int TX, XT, R, GS, IS, TXH;
     int Mpad, Npad;
     int tiles, tps, ksplit;
-    int vec4, fast;
+    int vec4, fast, mapmajor;
     size_t lds;
 };
 
@@ -476,16 +485,31 @@ WgradChoice choose_wgrad(const Geom& g)
     if (!pick_wgrad(c.NJ, c.NT, c.NH)) return c;
     c.Mpad = c.JG * c.NJ * 16;
     c.Npad = c.G * c.NT * c.NH * 16;
-    // widest x-tap span and largest input-map range over the column groups
+    // Column order.  With n = c*f + i (x-tap major) a column group spans all f input maps as soon as
+    // it is wider than f, so the LDS tile of a layer with many input maps holds few voxels; with
+    // n = i*kx + c (map major) a group holds only the maps of its own columns.  One group: the same
+    // either way (tap major kept).  Several groups: map major.
+    c.mapmajor = c.G > 1 ? 1 : 0;
+    // widest x-tap span and largest input-map range over the column groups; whether every group's
+    // tile starts at x-tap kx-1 (then rows of the in tile start 16-byte aligned)
     int cspan = 0, nmaps = 1;
+    bool aligned_rows = true;
     for (int cg = 0; cg < c.G; ++cg) {
         const int n0 = cg * c.NT * c.NH * 16;
         const int n1 = n0 + c.NT * c.NH * 16 < ncols ? n0 + c.NT * c.NH * 16 : ncols;
-        const int cmin = n0 / g.f, cmax = (n1 - 1) / g.f;
-        const int span = cmax - cmin;
-        const int maps = span == 0 ? (n1 - 1) % g.f - n0 % g.f + 1 : g.f;
-        if (span > cspan) cspan = span;
+        int cmin, cmax, maps;
+        if (c.mapmajor) {
+            const int imin = n0 / g.kx, imax = (n1 - 1) / g.kx;
+            cmin = 0; cmax = g.kx - 1;
+            if (imin == imax) { cmin = n0 % g.kx; cmax = (n1 - 1) % g.kx; }
+            maps = imax - imin + 1;
+        } else {
+            cmin = n0 / g.f; cmax = (n1 - 1) / g.f;
+            maps = cmax == cmin ? (n1 - 1) % g.f - n0 % g.f + 1 : g.f;
+        }
+        if (cmax - cmin > cspan) cspan = cmax - cmin;
         if (maps > nmaps) nmaps = maps;
+        if (cmax != g.kx - 1) aligned_rows = false;
     }
     if ((size_t)c.NJ * c.NT * c.NH * 64 * 4 > (size_t)kBufFloats) return c;   // cross-wave reduction needs this
     const int rows = g.oz * g.oy;
@@ -509,7 +533,7 @@ WgradChoice choose_wgrad(const Geom& g)
         c.lds = 2 * (size_t)kBufFloats * 4;
         // 16-byte loads: groups of four x-neighbours must be wholly inside or outside the
         // images and start on multiples of four in both tensors
-        c.vec4 = (g.ox % 4 == 0 && g.nx % 4 == 0 && c.G == 1) ? 1 : 0;
+        c.vec4 = (g.ox % 4 == 0 && g.nx % 4 == 0 && aligned_rows) ? 1 : 0;
         c.ok = true;
         break;
     }
@@ -526,7 +550,7 @@ WgradChoice choose_wgrad(const Geom& g)
         // fast tile loader: see the kernel.  Spans per wave must fit its register arrays, and a lane's
         // offset from the tile origin (up to a whole group of maps) must fit 32 bits.
         const int nw = 4 * c.NH;
-        const long span_g = ((long)c.NJ * 16 * c.GS + 255) / 256, span_i = ((long)g.f * c.IS + 255) / 256;
+        const long span_g = ((long)c.NJ * 16 * c.GS + 255) / 256, span_i = ((long)nmaps * c.IS + 255) / 256;
         c.fast = (c.vec4 && c.XT == 1 && g.oy % c.R == 0 && (span_g + nw - 1) / nw <= 5 && (span_i + nw - 1) / nw <= 5 &&
                   (double)g.fo * g.ovol() * 4.0 < 2147483648.0 && (double)g.f * g.nvol() * 4.0 < 2147483648.0 &&
                   !getenv("ZNN_WGRAD_SLOW_LOADER")) ? 1 : 0;
@@ -567,6 +591,7 @@ int mfma_wgrad(const Geom& g, const float* in, const float* gout, float* gw, voi
     P.AB = g.kz * g.ky;
     P.vec4 = c.vec4;
     P.fast = c.fast;
+    P.mapmajor = c.mapmajor;
     P.dGS = make_fastdiv(c.GS); P.dIS = make_fastdiv(c.IS);
     P.dTX = make_fastdiv(c.TX); P.dTXH = make_fastdiv(c.TXH); P.dOY = make_fastdiv(g.oy);
     if (log_enabled())
@@ -579,7 +604,7 @@ int mfma_wgrad(const Geom& g, const float* in, const float* gout, float* gw, voi
     if (rc != ZNN_OK) return rc;
     const long total = (long)g.fo * g.f * g.kvol();
     ZNN_LAUNCH("kernel gradient reduction", s, k_wgrad_reduce, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
-                       (const float*)ws, gw, g.f, g.fo, g.kz, g.ky, g.kx, c.ksplit, c.Mpad, c.Npad);
+                       (const float*)ws, gw, g.f, g.fo, g.kz, g.ky, g.kx, c.ksplit, c.Mpad, c.Npad, c.mapmajor);
     return check_launch("kernel gradient reduction");
 }
 
