@@ -456,7 +456,10 @@ WgradChoice choose_wgrad(const Geom& g)
     WgradChoice c = {};
     c.ok = false;
     const int mt = (g.fo + 15) / 16;
-    c.JG = (mt + 7) / 8;
+    // at most six 16-map tiles per workgroup: with seven or eight the gout half of the LDS tile leaves
+    // too few voxels per tile (config 5: 187 -> 160 ms with two groups of four)
+    static const int maxnj = [] { const char* e = getenv("ZNN_WGRAD_MAXNJ"); const int v = e ? atoi(e) : 6; return v >= 1 && v <= 8 ? v : 6; }();
+    c.JG = (mt + maxnj - 1) / maxnj;
     c.NJ = (mt + c.JG - 1) / c.JG;
     const int ncols = g.f * g.kx;
     const int nt_tot = (ncols + 15) / 16;
