@@ -177,3 +177,16 @@ def test_round_autotuner_validates_before_launching():
     assert L.znn_autotune_round(ctypes.byref(d), 1 << 40, fake, 16, null, ctypes.byref(rep)) == znn.ZNN_EWORKSPACE
     bad = znn.make_desc(4, 4, (2, 12, 12), (3, 3, 3), "auto")
     assert L.znn_autotune_round(ctypes.byref(bad), 1 << 40, fake, need.value, null, ctypes.byref(rep)) == znn.ZNN_EINVAL
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """Every box of this build has one GPU: bench.py says so and exits instead of pretending to scale."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr
+    assert r.stdout.strip() == ""
