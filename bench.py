@@ -175,6 +175,9 @@ def main():
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE`: run two steps and a plain 1 GiB device "
                          "copy whose known size calibrates the counters, then exit")
+    ap.add_argument("--direct-probe", action="store_true",
+                    help="for `rocprofv3 --pmc <SQ counters>`: run the three direct-method passes of config 2 "
+                         "three times and exit")
     ap.add_argument("--report-all", metavar="JSON", default=None,
                     help="also time every configuration pass by pass, print the table to stderr and write it here")
     args = ap.parse_args()
@@ -221,6 +224,12 @@ def main():
         _, idx = znn.maxfilter3d_fwd(d_mf, mf_win)
         znn.maxfilter3d_bwd(d_mfg, idx, mf_n, mf_win)
 
+    if args.direct_probe:
+        for _ in range(3):
+            run_mode("direct")
+        torch.cuda.synchronize()
+        print(json.dumps({"direct_probe": "done", "launches_of_each_pass": 3}))
+        return
     if args.traffic_probe:
         step(); step()
         a = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
