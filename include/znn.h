@@ -76,12 +76,32 @@ int  znn_plan_fft_extents(const znn_plan* plan, znn_vec3* N);
 /* Bytes of workspace the given pass (znn_pass) needs with the plan's method and
  * its current state (resident kernel spectra make forward/backward smaller). */
 int  znn_plan_workspace_bytes(const znn_plan* plan, int32_t pass, size_t* bytes);
-/* Bytes of the resident kernel spectra (complex fp32).  Their layout is private to the
- * library: full spectra W^[f'][f][N_z][N_y][N_x/2+1], or, for layers whose slowest
- * non-trivial axis has an FFT extent divisible by 4, at most 16 taps one voxel apart and
- * enough frequencies to fill the chip, "half spectra" [f'][f][k_z][N_y][N_x/2+1] that are
- * transformed along the fast axes only (the sum over the k_z planes is then taken inside
- * the multiply-accumulate, which cuts the kernel traffic by N_z / k_z). */
+/*
+ * Layout of a layer's kernel spectra (complex fp32), a property of the plan (Section 4,
+ * "FFT memoization"; Table 2, column "FFT-based (Memoized)").
+ *   ZNN_SPECTRA_FULL    the transforms themselves, W^[f'][f][N_z][N_y][N_x/2+1]: what the
+ *                       paper memoizes.  The multiply-accumulate streams them from HBM once
+ *                       per pass and is bound by that stream (8 bytes per 8 FLOP).
+ *   ZNN_SPECTRA_FOLDED  "half spectra" [f'][f][k_z][N_y][N_x/2+1] (2D: [f'][f][k_y][N_x/2+1]),
+ *                       transformed along the fast axes only; the sum over the k_z planes of
+ *                       the slowest axis is taken inside the multiply-accumulate.  N_z / k_z
+ *                       times fewer bytes, arithmetic-bound.  Needs the slowest non-trivial
+ *                       axis to have an FFT extent divisible by 4 and at most 16 taps one
+ *                       voxel apart along it (ZNN_EUNSUPPORTED otherwise).
+ *   ZNN_SPECTRA_AUTO    the library's choice: folded where it applies and the layer has
+ *                       enough frequencies to fill the chip, else full.  This is what
+ *                       znn_plan_create selects.
+ * The choice is stored in the plan when it is created or set and read from there by the size
+ * queries, the kernel transform and both multiply-accumulates.  znn_plan_set_spectra_layout
+ * is host only, valid for FFT plans, and fails with ZNN_EINVAL while resident spectra are
+ * attached (release them first): a buffer is only ever read in the layout it was written in.
+ * Workspace and spectra sizes must be queried again after a change.
+ * znn_plan_spectra_layout reports ZNN_SPECTRA_FULL or ZNN_SPECTRA_FOLDED, never AUTO.
+ */
+typedef enum { ZNN_SPECTRA_AUTO = 0, ZNN_SPECTRA_FULL = 1, ZNN_SPECTRA_FOLDED = 2 } znn_spectra_layout;
+int  znn_plan_set_spectra_layout(znn_plan* plan, int32_t layout);
+int  znn_plan_spectra_layout(const znn_plan* plan, int32_t* layout);
+/* Bytes of the kernel spectra in the plan's layout. */
 int  znn_plan_spectra_bytes(const znn_plan* plan, size_t* bytes);
 
 /*

@@ -29,7 +29,9 @@ EXPORTS = [
     "znn_maxfilter3d_sparse_fwd", "znn_maxfilter3d_sparse_bwd", "znn_maxpool3d_fwd", "znn_maxpool3d_bwd",
     "znn_transfer_fn_fwd", "znn_transfer_fn_bwd", "znn_cross_entropy_loss_grad",
     "znn_autotune_round_workspace_bytes", "znn_autotune_round", "znn_accumulate",
+    "znn_plan_set_spectra_layout", "znn_plan_spectra_layout",
 ]
+SPECTRA_LAYOUTS = {"auto": 0, "full": 1, "folded": 2}
 STRATEGIES = ("direct", "fft", "fft_memo")
 TRANSFER_FNS = {"rectify": 0, "logistic": 1, "tanh": 2}
 
@@ -80,6 +82,8 @@ def lib():
         L.znn_plan_fft_extents.argtypes = [vp, ctypes.POINTER(Vec3)]
         L.znn_plan_workspace_bytes.argtypes = [vp, i32, ctypes.POINTER(sz)]
         L.znn_plan_spectra_bytes.argtypes = [vp, ctypes.POINTER(sz)]
+        L.znn_plan_set_spectra_layout.argtypes = [vp, i32]
+        L.znn_plan_spectra_layout.argtypes = [vp, ctypes.POINTER(i32)]
         L.znn_conv_prepare_kernels.argtypes = [vp, vp, vp, sz, vp, sz, vp]
         L.znn_conv_release_kernels.argtypes = [vp]
         for name in ("znn_conv3d_fwd", "znn_conv3d_bwd", "znn_conv3d_wgrad"):
@@ -201,6 +205,16 @@ class Plan:
         b = ctypes.c_size_t(0)
         _check(lib().znn_plan_spectra_bytes(self._h, ctypes.byref(b)))
         return b.value
+
+    def set_spectra_layout(self, layout: str):
+        """'auto', 'full' (the kernel transforms themselves) or 'folded' (half spectra)."""
+        _check(lib().znn_plan_set_spectra_layout(self._h, SPECTRA_LAYOUTS[layout]))
+
+    @property
+    def spectra_layout(self) -> str:
+        v = ctypes.c_int32(-1)
+        _check(lib().znn_plan_spectra_layout(self._h, ctypes.byref(v)))
+        return {1: "full", 2: "folded"}[v.value]
 
     def _workspace(self, which: int, device):
         """Grows (never shrinks) a torch byte buffer used as the caller workspace."""

@@ -68,10 +68,31 @@ TraceScope::~TraceScope()
     if (slot < (int)g_trace.size()) (void)hipEventRecord(g_trace[slot].e1, stream);
 }
 
-bool log_enabled()
+const Tuning& tuning()
 {
-    static const bool on = [] { const char* e = getenv("ZNN_LOG"); return e && *e && *e != '0'; }();
-    return on;
+    static const Tuning t = [] {
+        auto flag = [](const char* name) { const char* e = getenv(name); return e && *e && *e != '0'; };
+        auto num = [](const char* name, int dflt) { const char* e = getenv(name); return e && *e ? atoi(e) : dflt; };
+        Tuning v = {};
+        v.log = flag("ZNN_LOG");
+        v.conv_u1 = flag("ZNN_CONV_U1");
+        v.conv_no_wl = flag("ZNN_CONV_NO_WL");
+        v.conv_no_split = flag("ZNN_CONV_NO_SPLIT");
+        if (const char* e = getenv("ZNN_CONV_TILE"))
+            if (sscanf(e, "%d,%d,%d,%d", &v.conv_tile[0], &v.conv_tile[1], &v.conv_tile[2], &v.conv_tile[3]) != 4)
+                v.conv_tile[0] = v.conv_tile[1] = v.conv_tile[2] = v.conv_tile[3] = 0;
+        v.wgrad_halves = num("ZNN_WGRAD_HALVES", 2);
+        v.wgrad_maxnj = num("ZNN_WGRAD_MAXNJ", 6);
+        if (v.wgrad_maxnj < 1 || v.wgrad_maxnj > 8) v.wgrad_maxnj = 6;
+        v.wgrad_stride_mod = num("ZNN_WGRAD_STRIDE_MOD", 4);
+        if (v.wgrad_stride_mod < 0 || v.wgrad_stride_mod > 28 || v.wgrad_stride_mod % 4) v.wgrad_stride_mod = 4;
+        v.wgrad_slow_loader = flag("ZNN_WGRAD_SLOW_LOADER");
+        v.fft_mac_z0 = num("ZNN_FFT_MAC_Z0", 0);
+        v.fft_wgrad_plain = flag("ZNN_FFT_WGRAD_PLAIN");
+        v.fft_lds_passes = flag("ZNN_FFT_LDS_PASSES");
+        return v;
+    }();
+    return t;
 }
 
 int next_fft_extent(int n)
@@ -230,6 +251,7 @@ int znn_plan_create(const znn_conv_desc* desc, znn_plan** plan)
     p->desc = *desc;
     p->g = g;
     p->mode = mode;
+    p->fold = mode == ZNN_FFT ? fold_default(g) : fold_full();
     p->resident = nullptr;
     p->memo = nullptr;
     p->memo_has_in = p->memo_has_gout = false;
@@ -258,14 +280,39 @@ int znn_plan_workspace_bytes(const znn_plan* plan, int32_t pass, size_t* bytes)
     if (!plan || !bytes) return fail(ZNN_EINVAL, "NULL argument");
     if (pass < ZNN_PASS_FWD || pass > ZNN_PASS_WGRAD) return fail(ZNN_EINVAL, "unknown pass %d", pass);
     if (plan->mode == ZNN_DIRECT) *bytes = direct_workspace_bytes(plan->g, pass);
-    else *bytes = fft_workspace(plan->g, pass, plan->resident != nullptr).total;
+    else *bytes = fft_workspace(plan->g, plan->fold, pass, plan->resident != nullptr).total;
     return ZNN_OK;
 }
 
 int znn_plan_spectra_bytes(const znn_plan* plan, size_t* bytes)
 {
     if (!plan || !bytes) return fail(ZNN_EINVAL, "NULL argument");
-    *bytes = fft_spectra_bytes(plan->g);
+    *bytes = fft_spectra_bytes(plan->g, plan->fold);
+    return ZNN_OK;
+}
+
+int znn_plan_spectra_layout(const znn_plan* plan, int32_t* layout)
+{
+    if (!plan || !layout) return fail(ZNN_EINVAL, "NULL argument");
+    *layout = plan->fold.on ? ZNN_SPECTRA_FOLDED : ZNN_SPECTRA_FULL;
+    return ZNN_OK;
+}
+
+int znn_plan_set_spectra_layout(znn_plan* plan, int32_t layout)
+{
+    if (!plan) return fail(ZNN_EINVAL, "NULL argument");
+    if (plan->mode != ZNN_FFT) return fail(ZNN_EINVAL, "kernel spectra exist only for the FFT method");
+    if (plan->resident)
+        return fail(ZNN_EINVAL, "resident kernel spectra are attached in the current layout; release them first");
+    if (layout == ZNN_SPECTRA_AUTO) plan->fold = fold_default(plan->g);
+    else if (layout == ZNN_SPECTRA_FULL) plan->fold = fold_full();
+    else if (layout == ZNN_SPECTRA_FOLDED) {
+        const Fold F = fold_forced(plan->g);
+        if (!F.on)
+            return fail(ZNN_EUNSUPPORTED, "half spectra need a slowest axis whose FFT extent is divisible by 4 "
+                                          "with at most %d taps one voxel apart", kMaxFoldedTaps);
+        plan->fold = F;
+    } else return fail(ZNN_EINVAL, "unknown spectra layout %d", layout);
     return ZNN_OK;
 }
 
@@ -275,11 +322,11 @@ int znn_conv_prepare_kernels(znn_plan* plan, const float* w, void* spectra, size
     (void)ws; (void)ws_bytes;
     if (!plan || !w) return fail(ZNN_EINVAL, "NULL argument");
     if (plan->mode != ZNN_FFT) return fail(ZNN_EINVAL, "kernel spectra exist only for the FFT method");
-    const size_t need = fft_spectra_bytes(plan->g);
+    const size_t need = fft_spectra_bytes(plan->g, plan->fold);
     if (!spectra) return fail(ZNN_EWORKSPACE, "spectra buffer is NULL");
     if (!aligned256(spectra)) return fail(ZNN_EWORKSPACE, "spectra buffer is not 256-byte aligned");
     if (spectra_bytes < need) return fail(ZNN_EWORKSPACE, "spectra buffer has %zu bytes, %zu needed", spectra_bytes, need);
-    int rc = fft_kernel_spectra(plan->g, w, (float2*)spectra, (hipStream_t)stream);
+    int rc = fft_kernel_spectra(plan->g, plan->fold, w, (float2*)spectra, (hipStream_t)stream);
     if (rc != ZNN_OK) return rc;
     plan->resident = (const float2*)spectra;
     return ZNN_OK;
@@ -335,7 +382,7 @@ int znn_conv3d_fwd(znn_plan* plan, const float* in, const float* w, float* out,
     int rc = check_ws(plan, ZNN_PASS_FWD, ws, ws_bytes);
     if (rc != ZNN_OK) return rc;
     if (plan->mode == ZNN_DIRECT) return direct_fwd(plan->g, in, w, out, ws, (hipStream_t)stream);
-    rc = fft_fwd(plan->g, in, w, plan->resident, out, ws, plan->memo, (hipStream_t)stream);
+    rc = fft_fwd(plan->g, plan->fold, in, w, plan->resident, out, ws, plan->memo, (hipStream_t)stream);
     if (plan->memo) plan->memo_has_in = rc == ZNN_OK;
     return rc;
 }
@@ -348,7 +395,7 @@ int znn_conv3d_bwd(znn_plan* plan, const float* gout, const float* w, float* gin
     int rc = check_ws(plan, ZNN_PASS_BWD, ws, ws_bytes);
     if (rc != ZNN_OK) return rc;
     if (plan->mode == ZNN_DIRECT) return direct_bwd(plan->g, gout, w, gin, ws, (hipStream_t)stream);
-    rc = fft_bwd(plan->g, gout, w, plan->resident, gin, ws,
+    rc = fft_bwd(plan->g, plan->fold, gout, w, plan->resident, gin, ws,
                  plan->memo ? plan->memo + (size_t)plan->g.f * plan->g.svol() : nullptr, (hipStream_t)stream);
     if (plan->memo) plan->memo_has_gout = rc == ZNN_OK;
     return rc;
@@ -379,12 +426,13 @@ static size_t tune_tensor_bytes(const Geom& g, size_t off[6])
 
 static size_t tune_scratch_bytes(const Geom& g, bool fft_ok)
 {
+    const Fold F = fold_default(g);
     size_t m = 0;
     for (int pass = 0; pass < 3; ++pass) {
         size_t d = direct_workspace_bytes(g, pass);
         if (d > m) m = d;
         if (fft_ok) {
-            size_t f = fft_workspace(g, pass, false).total;
+            size_t f = fft_workspace(g, F, pass, false).total;
             if (f > m) m = f;
         }
     }
@@ -435,6 +483,7 @@ int znn_autotune(const znn_conv_desc* desc, void* ws, size_t ws_bytes, void* str
     if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
         return fail(ZNN_EHIP, "hipEventCreate failed");
     const int warm = 2, timed = 5;
+    const Fold F = fold_default(g);
     for (int m = 0; m < 2; ++m)
         for (int p = 0; p < 3; ++p) ms[m][p] = INFINITY;
     rc = ZNN_OK;
@@ -448,8 +497,8 @@ int znn_autotune(const znn_conv_desc* desc, void* ws, size_t ws_bytes, void* str
                     else if (pass == 1) rc = direct_bwd(g, gout, w, gin, scr, s);
                     else rc = direct_wgrad(g, in, gout, gw, scr, s);
                 } else {
-                    if (pass == 0) rc = fft_fwd(g, in, w, nullptr, out, scr, nullptr, s);
-                    else if (pass == 1) rc = fft_bwd(g, gout, w, nullptr, gin, scr, nullptr, s);
+                    if (pass == 0) rc = fft_fwd(g, F, in, w, nullptr, out, scr, nullptr, s);
+                    else if (pass == 1) rc = fft_bwd(g, F, gout, w, nullptr, gin, scr, nullptr, s);
                     else rc = fft_wgrad(g, in, gout, gw, scr, s);
                 }
             }
@@ -484,18 +533,19 @@ struct RoundNeeds {
 static RoundNeeds round_needs(const Geom& g, bool fft_ok)
 {
     RoundNeeds r = {};
+    const Fold F = fold_default(g);
     size_t d = 0, f = 0, fm = 0;
     for (int pass = 0; pass < 3; ++pass) {
         d = std::max(d, direct_workspace_bytes(g, pass));
         if (fft_ok) {
-            f = std::max(f, fft_workspace(g, pass, false).total);
-            fm = std::max(fm, fft_workspace(g, pass, true).total);
+            f = std::max(f, fft_workspace(g, F, pass, false).total);
+            fm = std::max(fm, fft_workspace(g, F, pass, true).total);
         }
     }
     r.total[ZNN_STRATEGY_DIRECT] = d;
     r.total[ZNN_STRATEGY_FFT] = f;
     r.total[ZNN_STRATEGY_FFT_MEMO] = fft_ok
-        ? fm + fft_spectra_bytes(g) + align256(sizeof(float2) * (size_t)(g.f + g.fo) * g.svol()) : 0;
+        ? fm + fft_spectra_bytes(g, F) + align256(sizeof(float2) * (size_t)(g.f + g.fo) * g.svol()) : 0;
     return r;
 }
 
@@ -553,11 +603,12 @@ int znn_autotune_round(const znn_conv_desc* desc, uint64_t memory_budget, void* 
     if ((rc = fill_pattern(w, (long)g.fo * g.f * g.kvol(), 1.0f / std::sqrt((float)(g.f * g.kvol())), s)) != ZNN_OK) return rc;
     if ((rc = fill_pattern(gout, (long)g.fo * g.ovol(), 1.0f, s)) != ZNN_OK) return rc;
     // memoized strategy: [pass workspace | kernel spectra | node spectra]
+    const Fold F = fold_default(g);
     size_t memo_ws = 0;
     if (fft_ok)
-        for (int pass = 0; pass < 3; ++pass) memo_ws = std::max(memo_ws, fft_workspace(g, pass, true).total);
+        for (int pass = 0; pass < 3; ++pass) memo_ws = std::max(memo_ws, fft_workspace(g, F, pass, true).total);
     float2* What = (float2*)(scr + memo_ws);
-    float2* Ihat = (float2*)(scr + memo_ws + fft_spectra_bytes(g));
+    float2* Ihat = (float2*)(scr + memo_ws + fft_spectra_bytes(g, F));
     float2* Ghat = Ihat + (size_t)g.f * g.svol();
 
     hipEvent_t e0, e1;
@@ -573,13 +624,13 @@ int znn_autotune_round(const znn_conv_desc* desc, uint64_t memory_budget, void* 
                 if (rc == ZNN_OK) rc = direct_bwd(g, gout, w, gin, scr, s);
                 if (rc == ZNN_OK) rc = direct_wgrad(g, in, gout, gw, scr, s);
             } else if (t == ZNN_STRATEGY_FFT) {
-                rc = fft_fwd(g, in, w, nullptr, out, scr, nullptr, s);
-                if (rc == ZNN_OK) rc = fft_bwd(g, gout, w, nullptr, gin, scr, nullptr, s);
+                rc = fft_fwd(g, F, in, w, nullptr, out, scr, nullptr, s);
+                if (rc == ZNN_OK) rc = fft_bwd(g, F, gout, w, nullptr, gin, scr, nullptr, s);
                 if (rc == ZNN_OK) rc = fft_wgrad(g, in, gout, gw, scr, s);
             } else {
-                rc = fft_kernel_spectra(g, w, What, s);
-                if (rc == ZNN_OK) rc = fft_fwd(g, in, nullptr, What, out, scr, Ihat, s);
-                if (rc == ZNN_OK) rc = fft_bwd(g, gout, nullptr, What, gin, scr, Ghat, s);
+                rc = fft_kernel_spectra(g, F, w, What, s);
+                if (rc == ZNN_OK) rc = fft_fwd(g, F, in, nullptr, What, out, scr, Ihat, s);
+                if (rc == ZNN_OK) rc = fft_bwd(g, F, gout, nullptr, What, gin, scr, Ghat, s);
                 if (rc == ZNN_OK) rc = fft_wgrad_from_spectra(g, Ihat, Ghat, gw, scr, s);
             }
         }

@@ -78,8 +78,7 @@ bool have_kernel(int nj, int nv)
 // kernel width that has an instance; 1 for sparse taps.
 int group_width(int kx, int spx)
 {
-    static const bool off = getenv("ZNN_CONV_U1") != nullptr;
-    if (off || spx != 1) return 1;
+    if (tuning().conv_u1 || spx != 1) return 1;
     const int widths[6] = {11, 7, 5, 4, 3, 2};
     for (int i = 0; i < 6; ++i)
         if (kx % widths[i] == 0) return widths[i];
@@ -103,8 +102,7 @@ ConvFn pick_kernel(int U, int nj, int nv, bool wl)
 // Weights of one chunk in LDS: when they take at most 32 KiB.
 bool weights_in_lds(int taps, int NJ)
 {
-    static const bool off = getenv("ZNN_CONV_NO_WL") != nullptr;
-    return !off && (size_t)taps * NJ * 256 <= 32 * 1024;
+    return !tuning().conv_no_wl && (size_t)taps * NJ * 256 <= 32 * 1024;
 }
 
 struct TileChoice {
@@ -126,8 +124,7 @@ constexpr size_t kConvLdsMax = 64 * 1024;
 // order afterwards.
 void split_chunks(long blocks, int nchunk, int& cps, int& splits)
 {
-    static const bool nosplit = getenv("ZNN_CONV_NO_SPLIT") != nullptr;
-    long want = nosplit || blocks >= kCUs ? 1 : (3 * kCUs + blocks - 1) / blocks;
+    long want = tuning().conv_no_split || blocks >= kCUs ? 1 : (3 * kCUs + blocks - 1) / blocks;
     if (want > nchunk) want = nchunk;
     cps = (int)(nchunk / want);        // rounded down: shares of equal length, a few more of them
     splits = (nchunk + cps - 1) / cps;
@@ -147,8 +144,7 @@ TileChoice search_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, i
     double best_cost = 1e300;
     const int nchunk = (fK + 3) / 4;
     // tuning aid: ZNN_CONV_TILE="NV,Tz,Ty,Tx" pins the configuration
-    int pin[4] = {0, 0, 0, 0};
-    if (const char* e = getenv("ZNN_CONV_TILE")) sscanf(e, "%d,%d,%d,%d", &pin[0], &pin[1], &pin[2], &pin[3]);
+    const int (&pin)[4] = tuning().conv_tile;
     const int nvs[6] = {2, 4, 5, 6, 7, 8};
     for (int ni = 0; ni < 6; ++ni) {
         const int NV = nvs[ni];
@@ -221,7 +217,6 @@ TileChoice choose_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, i
     static std::mutex lock;
     static std::vector<Entry> memo;
     const int key[11] = {fM, fK, dz, dy, dx, kz, ky, kx, spz, spy, spx};
-    if (getenv("ZNN_CONV_TILE")) return search_tile(fM, fK, dz, dy, dx, kz, ky, kx, spz, spy, spx);   // tuning aid: not remembered
     {
         std::lock_guard<std::mutex> hold(lock);
         for (const Entry& e : memo)

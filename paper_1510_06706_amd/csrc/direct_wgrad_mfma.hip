@@ -19,6 +19,9 @@
 // ascending split order, so the result is bit-reproducible (no atomics).
 #include <cstdio>
 #include <cstdlib>
+#include <cstring>
+#include <mutex>
+#include <vector>
 
 #include "direct_wgrad_impl.h"
 
@@ -74,19 +77,19 @@ struct WgradChoice {
 // whose residue modulo 32 spreads the 16 maps of an MFMA operand over the banks.
 int pad_stride(int n)
 {
-    static const int res = [] { const char* e = getenv("ZNN_WGRAD_STRIDE_MOD"); return e ? atoi(e) : 4; }();
+    const int res = tuning().wgrad_stride_mod;
     while (n % 32 != res) ++n;
     return n;
 }
 
-WgradChoice choose_wgrad(const Geom& g)
+WgradChoice search_wgrad(const Geom& g)
 {
     WgradChoice c = {};
     c.ok = false;
     const int mt = (g.fo + 15) / 16;
     // at most six 16-map tiles per workgroup: with seven or eight the gout half of the LDS tile leaves
     // too few voxels per tile (config 5: 187 -> 160 ms with two groups of four)
-    static const int maxnj = [] { const char* e = getenv("ZNN_WGRAD_MAXNJ"); const int v = e ? atoi(e) : 6; return v >= 1 && v <= 8 ? v : 6; }();
+    const int maxnj = tuning().wgrad_maxnj;
     c.JG = (mt + maxnj - 1) / maxnj;
     c.NJ = (mt + c.JG - 1) / c.JG;
     const int ncols = g.f * g.kx;
@@ -102,7 +105,7 @@ WgradChoice choose_wgrad(const Geom& g)
         if (allowed[k] >= want && c.NJ * allowed[k] <= kMaxTiles) c.NT = allowed[k];
     c.G = (nt_tot + c.NT - 1) / c.NT;
     // eight waves: the column tiles of a group are dealt to two halves of four waves each
-    static const int halves = [] { const char* e = getenv("ZNN_WGRAD_HALVES"); return e ? atoi(e) : 2; }();
+    const int halves = tuning().wgrad_halves;
     c.NH = 1;
     for (int nh = halves; nh >= 2; nh /= 2) {
         const int nt = (c.NT + nh - 1) / nh;
@@ -184,12 +187,34 @@ WgradChoice choose_wgrad(const Geom& g)
         const long span_g = ((long)c.NJ * 16 * c.GS + 255) / 256, span_i = ((long)nmaps * c.IS + 255) / 256;
         c.fast = (c.vec4 && c.XT == 1 && g.oy % c.R == 0 && (span_g + nw - 1) / nw <= 5 && (span_i + nw - 1) / nw <= 5 &&
                   (double)g.fo * g.ovol() * 4.0 < 2147483648.0 && (double)g.f * g.nvol() * 4.0 < 2147483648.0 &&
-                  !getenv("ZNN_WGRAD_SLOW_LOADER")) ? 1 : 0;
+                  !tuning().wgrad_slow_loader) ? 1 : 0;
     }
     if ((long)g.kz * g.ky > 65535 || (long)c.G * c.JG > 65535) c.ok = false;
     // the tile loader addresses a map with a 32-bit byte offset
     if (g.nvol() >= (1L << 30) || g.ovol() >= (1L << 30)) c.ok = false;
     return c;
+}
+
+// Every call of the pass asks for the same answer three times (supported?, workspace, launch):
+// remembered per shape.
+WgradChoice choose_wgrad(const Geom& g)
+{
+    struct Entry { int key[14]; WgradChoice choice; };
+    static std::mutex lock;
+    static std::vector<Entry> memo;
+    const int key[14] = {g.f, g.fo, g.nz, g.ny, g.nx, g.kz, g.ky, g.kx, g.spz, g.spy, g.spx, g.oz, g.oy, g.ox};
+    {
+        std::lock_guard<std::mutex> hold(lock);
+        for (const Entry& e : memo)
+            if (memcmp(e.key, key, sizeof(key)) == 0) return e.choice;
+    }
+    Entry e;
+    memcpy(e.key, key, sizeof(key));
+    e.choice = search_wgrad(g);
+    std::lock_guard<std::mutex> hold(lock);
+    if (memo.size() >= 256) memo.erase(memo.begin());
+    memo.push_back(e);
+    return e.choice;
 }
 
 }  // namespace

@@ -1,16 +1,18 @@
-// FFT method (Section 4): batched 3D real-to-complex and inverse transforms
-// whose 1D passes run entirely in LDS, the per-frequency complex
-// multiply-accumulate that fuses the sum over convergent edges, and the pruned
-// inverse transforms of the kernel gradient.
+// FFT method (Section 4): batched 3D real-to-complex and inverse transforms,
+// the per-frequency complex multiply-accumulate that fuses the sum over
+// convergent edges, and the pruned inverse transforms of the kernel gradient.
 //
-// A 3D transform is three launches, one per axis.  Every launch stages a batch
-// of W pencils in LDS as data[element][pencil] (pencil fastest, row length Wp
-// odd so that the transposing loads and stores spread over the banks), runs a
-// Stockham autosort FFT with radices 4/2/3/5 between two LDS buffers, and
-// writes the result back.  Input rows known to be zero (padding) are never
-// read and output rows nobody needs (outside the crop) are never written, so
-// the transforms of the small kernels and the cropped inverses are pruned for
-// free.
+// A 3D transform is three launches, one per axis.  The x pass (contiguous
+// pencils, two real rows packed into one complex transform) and every pass of
+// an extent above 96 stage a batch of W pencils in LDS as data[element][pencil]
+// (pencil fastest, row length Wp odd so that the transposing loads and stores
+// spread over the banks) and run a Stockham autosort FFT with radices 4/2/3/5
+// between two LDS buffers.  The y and z passes of 5-smooth extents up to 96 keep
+// one whole pencil per thread in registers instead (fft_reg_impl.h): their
+// neighbouring pencils are contiguous in memory, so no transpose is needed.
+// Input rows known to be zero (padding) are never read and output rows nobody
+// needs (outside the crop) are never written, so the transforms of the small
+// kernels and the cropped inverses are pruned for free.
 //
 // Spectra are stored as [map][N_z][N_y][N_x/2+1] complex fp32.
 //
@@ -751,8 +753,7 @@ int launch_wgrad_dft_k(int f, int fo, int N, int tz, long plane, long vol, const
     if ((long)jblocks * iblocks >= 2147483647L || pchunks > 65535)
         return fail(ZNN_EUNSUPPORTED, "too many edges or pencils for one launch");
     const dim3 grid((unsigned)(jblocks * iblocks), (unsigned)pchunks);
-    static const bool plain = getenv("ZNN_FFT_WGRAD_PLAIN") != nullptr;
-    if (N % 4 == 0 && tz == 1 && !plain)
+    if (N % 4 == 0 && tz == 1 && !tuning().fft_wgrad_plain)
         ZNN_LAUNCH("pruned DFT of spectral products", s, (k_wgrad_zdft4<KZ, JB, IB>), grid, dim3(kThreads), 0,
                    G, I, T, f, fo, N, plane, vol, iblocks);
     else
@@ -839,8 +840,7 @@ int launch_axis(AxisParams P, int dir, hipStream_t s)
         P.in_sa == P.out_sa && P.in_sb == P.out_sb && P.in_sc == P.out_sc)
         return ZNN_OK;   // length-1 transform in place: nothing to do
     // extents that fit the register file: one pencil per thread, no LDS
-    static const bool lds_only = getenv("ZNN_FFT_LDS_PASSES") != nullptr;
-    if (!lds_only && !P.in2 && P.istep == 1 && P.ostep == 1 && P.Oc == 1 && P.in_stride == P.L &&
+    if (!tuning().fft_lds_passes && !P.in2 && P.istep == 1 && P.ostep == 1 && P.Oc == 1 && P.in_stride == P.L &&
         P.out_stride == P.L && fft_axis_reg_supported(P.N)) {
         RegAxis R = {};
         R.in = P.in; R.out = P.out;
@@ -947,15 +947,13 @@ int inverse3d(const Geom& g, float2* spec, float* dst, long maps, int cz, int cy
     return launch_c2r(spec, dst, maps, g.Nz, g.Ny, g.Nx, cz, cy, cx, dz, dy, dx, 1, scale, s);
 }
 
-// Layers whose kernel spectra are kept as half spectra (transformed along the fast axes
-// only) and expanded inside the multiply-accumulate: the slowest non-trivial axis must
-// have a length divisible by 4, few taps, and taps one voxel apart.
-struct Fold { bool on; int N, taps, P, z0; };
-
-Fold fold_of(const Geom& g)
+// Layers whose kernel spectra can be kept as half spectra (transformed along the fast axes
+// only) and expanded inside the multiply-accumulate: the slowest non-trivial axis must have a
+// length divisible by 4, few taps, and taps one voxel apart.  `min_blocks`: fewest workgroups
+// per group of result nodes for which the folded kernel is worth launching.
+Fold fold_search(const Geom& g, long min_blocks)
 {
     Fold F = {false, 0, 0, 0, 0};
-    if (getenv("ZNN_FFT_FULL_SPECTRA")) return F;
     if (g.Nz > 1) { F.N = g.Nz; F.taps = g.kz; F.P = g.Ny * g.Nxh; F.on = g.spz == 1; }
     else if (g.Ny > 1) { F.N = g.Ny; F.taps = g.ky; F.P = g.Nxh; F.on = g.spy == 1; }
     F.on = F.on && F.N % 4 == 0 && F.taps <= kMaxFoldedTaps && F.taps < F.N;
@@ -966,8 +964,8 @@ Fold fold_of(const Geom& g)
     // Four base frequencies per thread reuse every loaded value most but leave the fewest
     // threads: they win on layers with thousands of workgroups (config 5: 30.0 ms against
     // 31.2 ms), two win below that (config 2: 1.26 against 1.33 ms; config 4: 1.54 against
-    // 1.76 ms), one is the fallback for extents not divisible by 8.  ZNN_FFT_MAC_Z0 pins it.
-    static const int pin = [] { const char* e = getenv("ZNN_FFT_MAC_Z0"); return e ? atoi(e) : 0; }();
+    // 1.76 ms), one is the fallback for extents not divisible by 8.
+    const int pin = tuning().fft_mac_z0;
     auto blocks_of = [&](int z0) {
         const int G = fft_mac_group(z0);
         return (long)((F.P + 63) / 64) * ((F.N / 4 / z0 + 3) / 4) * ((nmin + G - 1) / G);
@@ -978,15 +976,14 @@ Fold fold_of(const Geom& g)
     for (int k = 0; k < 3 && !F.z0; ++k) {
         const int z0 = order[k];
         if ((pin && z0 != pin) || (F.N / 4) % z0) continue;
-        if (blocks_of(z0) >= 128) F.z0 = z0;
+        if (blocks_of(z0) >= min_blocks) F.z0 = z0;
     }
     F.on = F.z0 != 0;
     return F;
 }
 
-int launch_mac(bool backward, const Geom& g, const float2* What, const float2* a, float2* b, hipStream_t s)
+int launch_mac(bool backward, const Geom& g, const Fold& F, const float2* What, const float2* a, float2* b, hipStream_t s)
 {
-    const Fold F = fold_of(g);
     if (F.on) return fft_mac_fused(backward, F.taps, F.z0, g.f, g.fo, F.N, F.P, What, a, b, s);
     const long svol = g.svol();
     const int outs = backward ? g.f : g.fo;
@@ -1006,14 +1003,17 @@ int launch_mac(bool backward, const Geom& g, const float2* What, const float2* a
 }  // namespace
 
 // ---------------------------------------------------------------- public (library-internal) entry points
-size_t fft_spectra_bytes(const Geom& g)
+Fold fold_full() { return Fold{false, 0, 0, 0, 0}; }
+Fold fold_default(const Geom& g) { return fold_search(g, 128); }
+Fold fold_forced(const Geom& g) { return fold_search(g, 1); }
+
+size_t fft_spectra_bytes(const Geom& g, const Fold& F)
 {
-    const Fold F = fold_of(g);
     if (F.on) return align256(sizeof(float2) * (size_t)g.f * g.fo * F.taps * F.P);
     return align256(sizeof(float2) * (size_t)g.f * g.fo * g.svol());
 }
 
-FftWorkspace fft_workspace(const Geom& g, int pass, bool resident)
+FftWorkspace fft_workspace(const Geom& g, const Fold& F, int pass, bool resident)
 {
     FftWorkspace w = {};
     size_t o = 0;
@@ -1024,7 +1024,7 @@ FftWorkspace fft_workspace(const Geom& g, int pass, bool resident)
         w.off_a = o; o += align256(spec * na);
         w.off_b = o; o += align256(spec * nb);
         w.off_w = o;
-        if (!resident) o += fft_spectra_bytes(g);
+        if (!resident) o += fft_spectra_bytes(g, F);
     } else {
         const size_t pairs = (size_t)g.f * g.fo;
         w.off_a = o; o += align256(spec * g.f);
@@ -1036,9 +1036,8 @@ FftWorkspace fft_workspace(const Geom& g, int pass, bool resident)
     return w;
 }
 
-int fft_kernel_spectra(const Geom& g, const float* w, float2* What, hipStream_t s)
+int fft_kernel_spectra(const Geom& g, const Fold& F, const float* w, float2* What, hipStream_t s)
 {
-    const Fold F = fold_of(g);
     if (F.on) {
         // half spectra [pair][tap][P]: x (and, in 3D, y) transforms of the planes that hold taps
         const long pairs = (long)g.f * g.fo;
@@ -1061,10 +1060,10 @@ int fft_kernel_spectra(const Geom& g, const float* w, float2* What, hipStream_t 
     return forward3d(g, w, What, (long)g.f * g.fo, g.kz, g.ky, g.kx, 0, 0, 0, g.spz, g.spy, g.spx, s);
 }
 
-int fft_fwd(const Geom& g, const float* in, const float* w, const float2* resident, float* out,
+int fft_fwd(const Geom& g, const Fold& F, const float* in, const float* w, const float2* resident, float* out,
             void* ws, float2* memo_in, hipStream_t s)
 {
-    const FftWorkspace L = fft_workspace(g, ZNN_PASS_FWD, resident != nullptr);
+    const FftWorkspace L = fft_workspace(g, F, ZNN_PASS_FWD, resident != nullptr);
     float2* Ihat = memo_in ? memo_in : (float2*)((char*)ws + L.off_a);
     float2* Ohat = (float2*)((char*)ws + L.off_b);
     const float2* What = resident;
@@ -1072,20 +1071,20 @@ int fft_fwd(const Geom& g, const float* in, const float* w, const float2* reside
     if (rc != ZNN_OK) return rc;
     if (!What) {
         float2* wbuf = (float2*)((char*)ws + L.off_w);
-        rc = fft_kernel_spectra(g, w, wbuf, s);
+        rc = fft_kernel_spectra(g, F, w, wbuf, s);
         if (rc != ZNN_OK) return rc;
         What = wbuf;
     }
-    rc = launch_mac(false, g, What, Ihat, Ohat, s);
+    rc = launch_mac(false, g, F, What, Ihat, Ohat, s);
     if (rc != ZNN_OK) return rc;
     return inverse3d(g, Ohat, out, g.fo, g.spz * (g.kz - 1), g.spy * (g.ky - 1), g.spx * (g.kx - 1),
                      g.oz, g.oy, g.ox, s);
 }
 
-int fft_bwd(const Geom& g, const float* gout, const float* w, const float2* resident, float* gin,
+int fft_bwd(const Geom& g, const Fold& F, const float* gout, const float* w, const float2* resident, float* gin,
             void* ws, float2* memo_gout, hipStream_t s)
 {
-    const FftWorkspace L = fft_workspace(g, ZNN_PASS_BWD, resident != nullptr);
+    const FftWorkspace L = fft_workspace(g, F, ZNN_PASS_BWD, resident != nullptr);
     float2* Ghat = memo_gout ? memo_gout : (float2*)((char*)ws + L.off_a);
     float2* Ginhat = (float2*)((char*)ws + L.off_b);
     const float2* What = resident;
@@ -1094,18 +1093,18 @@ int fft_bwd(const Geom& g, const float* gout, const float* w, const float2* resi
     if (rc != ZNN_OK) return rc;
     if (!What) {
         float2* wbuf = (float2*)((char*)ws + L.off_w);
-        rc = fft_kernel_spectra(g, w, wbuf, s);
+        rc = fft_kernel_spectra(g, F, w, wbuf, s);
         if (rc != ZNN_OK) return rc;
         What = wbuf;
     }
-    rc = launch_mac(true, g, What, Ghat, Ginhat, s);
+    rc = launch_mac(true, g, F, What, Ghat, Ginhat, s);
     if (rc != ZNN_OK) return rc;
     return inverse3d(g, Ginhat, gin, g.f, 0, 0, 0, g.nz, g.ny, g.nx, s);
 }
 
 int fft_wgrad(const Geom& g, const float* in, const float* gout, float* gw, void* ws, hipStream_t s)
 {
-    const FftWorkspace L = fft_workspace(g, ZNN_PASS_WGRAD, false);
+    const FftWorkspace L = fft_workspace(g, fold_full(), ZNN_PASS_WGRAD, false);
     float2* Ihat = (float2*)((char*)ws + L.off_a);
     float2* Ghat = (float2*)((char*)ws + L.off_b);
     int rc = forward3d(g, in, Ihat, g.f, g.nz, g.ny, g.nx, 0, 0, 0, 1, 1, 1, s);
@@ -1121,7 +1120,7 @@ int fft_wgrad(const Geom& g, const float* in, const float* gout, float* gw, void
 int fft_wgrad_from_spectra(const Geom& g, const float2* Ihat, const float2* Ghat, float* gw, void* ws,
                            hipStream_t s)
 {
-    const FftWorkspace L = fft_workspace(g, ZNN_PASS_WGRAD, false);
+    const FftWorkspace L = fft_workspace(g, fold_full(), ZNN_PASS_WGRAD, false);
     float2* T1 = (float2*)((char*)ws + L.off_t1);
     float2* T2 = (float2*)((char*)ws + L.off_t2);
     int rc = ZNN_OK;
@@ -1155,7 +1154,7 @@ int fft_wgrad_from_spectra(const Geom& g, const float2* Ihat, const float2* Ghat
         P.Oa = g.fo * g.f; P.Ob = g.kz; P.Oc = 1;
         P.in_sa = (long)g.kz * plane; P.in_sb = plane;
         P.out_sa = (long)g.kz * g.ky * g.Nxh; P.out_sb = (long)g.ky * g.Nxh;
-        if (g.ky <= kMaxPruned && !getenv("ZNN_FFT_WGRAD_PLAIN"))
+        if (g.ky <= kMaxPruned && !tuning().fft_wgrad_plain)
             rc = launch_prune(g.ky, T1, T2, (long)g.fo * g.f * g.kz, g.Ny, g.Nxh, g.spy, s);
         else
             rc = launch_axis(P, +1, s);

@@ -68,8 +68,24 @@ __device__ __forceinline__ unsigned fdiv(unsigned n, FastDiv f)
     return f.d <= 1 ? n : __umulhi(n, f.M);
 }
 
-// True when ZNN_LOG is set in the environment: launch configurations are printed to stderr.
-bool log_enabled();
+// Tuning aids.  The environment is read exactly once, the first time anything asks (plan
+// creation at the latest), and never on a launch path; none of them changes a data layout.
+struct Tuning {
+    bool log;                   // ZNN_LOG: print launch configurations to stderr
+    bool conv_u1;               // ZNN_CONV_U1: walk the taps of the direct convolution one at a time
+    bool conv_no_wl;            // ZNN_CONV_NO_WL: never stage a chunk's weights in LDS
+    bool conv_no_split;         // ZNN_CONV_NO_SPLIT: never split the input maps over workgroups
+    int  conv_tile[4];          // ZNN_CONV_TILE="NV,Tz,Ty,Tx": pin the output box (0 = not pinned)
+    int  wgrad_halves;          // ZNN_WGRAD_HALVES: 1 = four waves, 2 = eight waves per workgroup
+    int  wgrad_maxnj;           // ZNN_WGRAD_MAXNJ: most 16-map tiles per workgroup
+    int  wgrad_stride_mod;      // ZNN_WGRAD_STRIDE_MOD: residue modulo 32 of the LDS map stride
+    bool wgrad_slow_loader;     // ZNN_WGRAD_SLOW_LOADER: general tile loader everywhere
+    int  fft_mac_z0;            // ZNN_FFT_MAC_Z0: frequencies per thread of the folded multiply-accumulate / 4
+    bool fft_wgrad_plain;       // ZNN_FFT_WGRAD_PLAIN: per-z pruned DFT instead of the radix-4 grouped one
+    bool fft_lds_passes;        // ZNN_FFT_LDS_PASSES: LDS passes instead of register passes
+};
+const Tuning& tuning();
+inline bool log_enabled() { return tuning().log; }
 
 // ---------------------------------------------------------------- direct method
 int direct_fwd(const Geom& g, const float* in, const float* w, float* out, void* ws, hipStream_t s);
@@ -78,18 +94,33 @@ int direct_wgrad(const Geom& g, const float* in, const float* gout, float* gw, v
 size_t direct_workspace_bytes(const Geom& g, int pass);
 
 // ---------------------------------------------------------------- FFT method
+// Layout of a layer's kernel spectra, fixed when its plan is created (or by
+// znn_plan_set_spectra_layout) and carried by the plan from then on, so that the size query,
+// the kernel transform and every multiply-accumulate read the same decision.
+//   on = false : full spectra [f'][f][N_z][N_y][N_x/2+1] (Section 4, memoized kernel transforms)
+//   on = true  : half spectra [f'][f][taps][P], transformed along the fast axes only; the sum
+//                over the `taps` planes of the slowest axis (extent N) is taken inside the
+//                multiply-accumulate, 4*z0 frequencies per thread
+struct Fold { bool on; int N, taps, P, z0; };
+Fold fold_full();
+// The library's own choice: half spectra where the folded multiply-accumulate applies and the
+// layer has enough frequencies to fill the chip, else full spectra.
+Fold fold_default(const Geom& g);
+// Half spectra whenever the folded multiply-accumulate can take the layer at all (on = false if not).
+Fold fold_forced(const Geom& g);
+
 struct FftWorkspace {
     size_t total;
     size_t off_a, off_b;        // spectra of the two node sets of the pass
     size_t off_w;               // kernel spectra (when not resident)
     size_t off_t1, off_t2;      // partially inverted pair volumes (kernel gradient)
 };
-FftWorkspace fft_workspace(const Geom& g, int pass, bool resident);
-size_t fft_spectra_bytes(const Geom& g);
-int fft_kernel_spectra(const Geom& g, const float* w, float2* What, hipStream_t s);
-int fft_fwd(const Geom& g, const float* in, const float* w, const float2* resident, float* out,
+FftWorkspace fft_workspace(const Geom& g, const Fold& F, int pass, bool resident);
+size_t fft_spectra_bytes(const Geom& g, const Fold& F);
+int fft_kernel_spectra(const Geom& g, const Fold& F, const float* w, float2* What, hipStream_t s);
+int fft_fwd(const Geom& g, const Fold& F, const float* in, const float* w, const float2* resident, float* out,
             void* ws, float2* memo_in, hipStream_t s);
-int fft_bwd(const Geom& g, const float* gout, const float* w, const float2* resident, float* gin,
+int fft_bwd(const Geom& g, const Fold& F, const float* gout, const float* w, const float2* resident, float* gin,
             void* ws, float2* memo_gout, hipStream_t s);
 int fft_wgrad(const Geom& g, const float* in, const float* gout, float* gw, void* ws, hipStream_t s);
 int fft_wgrad_from_spectra(const Geom& g, const float2* Ihat, const float2* Ghat, float* gw, void* ws,
@@ -127,6 +158,7 @@ struct znn_plan {
     znn_conv_desc desc;
     znn::Geom g;
     int mode;                    // ZNN_DIRECT or ZNN_FFT
+    znn::Fold fold;              // layout of this layer's kernel spectra (FFT method)
     const float2* resident;      // kernel spectra held by the caller, or nullptr
     float2* memo;                // caller's buffer for memoized node spectra, or nullptr
     bool memo_has_in, memo_has_gout;

@@ -190,3 +190,42 @@ def test_bench_refuses_more_than_one_gpu():
     assert r.returncode != 0
     assert "ONE GPU" in r.stderr
     assert r.stdout.strip() == ""
+
+
+def test_spectra_layout_is_a_property_of_the_plan():
+    """Full spectra (the paper's memoized kernel transforms, Section 4) or half spectra: chosen
+    per plan through the ABI, reported back, and reflected in every size query."""
+    p = znn.Plan(120, 120, (96, 96, 96), (7, 7, 7), "fft")
+    spec = 96 * 96 * 49 * 8
+    assert p.spectra_layout == "folded"
+    assert p.spectra_bytes() == 120 * 120 * 7 * 96 * 49 * 8
+    folded_ws = p.workspace_bytes(znn.ZNN_PASS_FWD)
+    p.set_spectra_layout("full")
+    assert p.spectra_layout == "full"
+    assert p.spectra_bytes() == 120 * 120 * spec == 52022476800           # 52.02 GB
+    assert p.workspace_bytes(znn.ZNN_PASS_FWD) == folded_ws + 120 * 120 * (96 - 7) * 96 * 49 * 8
+    p.set_spectra_layout("folded")
+    assert p.spectra_layout == "folded"
+    p.set_spectra_layout("auto")
+    assert p.spectra_layout == "folded"
+    assert znn.lib().znn_plan_set_spectra_layout(p._h, 9) == znn.ZNN_EINVAL
+    p.close()
+    # a layer too small to fill the chip keeps full spectra by default but takes half spectra on request
+    q = znn.Plan(1, 4, (16, 16, 16), (3, 3, 3), "fft")
+    assert q.spectra_layout == "full"
+    q.set_spectra_layout("folded")
+    assert q.spectra_layout == "folded" and q.spectra_bytes() == 4 * 3 * 16 * 9 * 8
+    q.close()
+    # extents not divisible by 4 and sparse taps along the slowest axis cannot be folded
+    r = znn.Plan(2, 2, (18, 16, 16), (3, 3, 3), "fft")
+    assert znn.lib().znn_plan_set_spectra_layout(r._h, 2) == znn.ZNN_EUNSUPPORTED
+    assert r.spectra_layout == "full"
+    r.close()
+    r = znn.Plan(2, 2, (16, 16, 16), (3, 3, 3), "fft", sparsity=(2, 1, 1))
+    assert znn.lib().znn_plan_set_spectra_layout(r._h, 2) == znn.ZNN_EUNSUPPORTED
+    r.close()
+    d = znn.Plan(2, 2, (16, 16, 16), (3, 3, 3), "direct")
+    assert znn.lib().znn_plan_set_spectra_layout(d._h, 1) == znn.ZNN_EINVAL
+    d.close()
+    assert znn.lib().znn_plan_set_spectra_layout(None, 1) == znn.ZNN_EINVAL
+    assert znn.lib().znn_plan_spectra_layout(None, None) == znn.ZNN_EINVAL
