@@ -165,6 +165,38 @@ def test_fft_layers_with_folded_kernel_transform_match_the_oracle(f, fo, n, k, s
     p.close()
 
 
+@pytest.mark.parametrize("f,fo,n,k", [(12, 10, (16, 20, 18), (3, 3, 3)), (9, 6, (1, 32, 30), (1, 5, 3)),
+                                      (40, 40, (32, 32, 32), (5, 5, 5))])
+def test_both_spectra_layouts_match_the_oracle_and_cannot_be_mixed(f, fo, n, k):
+    """Full kernel spectra (Section 4: the memoized kernel transforms, streamed by the
+    multiply-accumulate) and half spectra (last transform axis folded into the
+    multiply-accumulate) on the same layer, each chosen through the ABI."""
+    cfg = synth.LayerShape("t", f, fo, n, k, 1.0 / np.sqrt(f * np.prod(k)), 300 + f)
+    inp, w, gout = synth.layer_tensors(cfg)
+    d_in, d_w, d_g = dev(inp), dev(w), dev(gout)
+    r_out, r_gin = oracle.conv3d_fwd(inp, w), oracle.conv3d_bwd(gout, w, n)
+    p = znn.Plan(f, fo, n, k, "fft")
+    N = p.fft_extents
+    full = f * fo * N[0] * N[1] * (N[2] // 2 + 1) * 8
+    sizes = {}
+    for layout in ("full", "folded"):
+        p.set_spectra_layout(layout)
+        assert p.spectra_layout == layout
+        sizes[layout] = p.spectra_bytes()
+        assert rel_err(host(p.fwd(d_in, d_w)), r_out) <= TOL["fft"], layout
+        assert rel_err(host(p.bwd(d_g, d_w)), r_gin) <= TOL["fft"], layout
+        p.prepare_kernels(d_w)
+        # the layout of attached spectra cannot be changed under them
+        with pytest.raises(znn.ZnnError) as e:
+            p.set_spectra_layout("full" if layout == "folded" else "folded")
+        assert e.value.code == znn.ZNN_EINVAL and p.spectra_layout == layout
+        assert rel_err(host(p.fwd(d_in, None)), r_out) <= TOL["fft"], layout
+        assert rel_err(host(p.bwd(d_g, None)), r_gin) <= TOL["fft"], layout
+        p.release_kernels()
+    assert sizes["full"] == (full + 255) // 256 * 256 and sizes["folded"] < full
+    p.close()
+
+
 REG_EXTENTS = [8, 9, 10, 12, 15, 16, 18, 20, 24, 25, 27, 30, 32, 36, 40, 45, 48, 50, 54, 60, 64, 72, 75, 80, 81,
                90, 96]
 
