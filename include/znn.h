@@ -144,6 +144,22 @@ int  znn_conv3d_fwd(znn_plan* plan, const float* in, const float* w, float* out,
                     void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * znn_conv3d_fwd for callers that cannot allocate device memory and therefore have no
+ * workspace to hand over: code running under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, results and error codes as
+ * znn_conv3d_fwd (either method; `w` may be NULL with resident spectra), bit for bit the same
+ * output, but the scratch comes from a device array of ZNN_STATIC_SCRATCH_BYTES built into the
+ * library, of which every GPU the library runs on holds its own copy until the process ends.
+ * The call allocates and frees nothing.  A layer whose forward pass needs more scratch than
+ * that (znn_plan_workspace_bytes) is refused with ZNN_EWORKSPACE before anything is launched.
+ * All calls on one GPU share the one array: calls that may overlap in time on the same GPU (two
+ * streams, two threads) race and must be serialised by the caller; calls on one stream are safe.
+ * The array's device address is looked up on the first call per device, with that device current.
+ */
+#define ZNN_STATIC_SCRATCH_BYTES (32u * 1024u * 1024u)
+int  znn_conv3d_fwd_static(znn_plan* plan, const float* in, const float* w, float* out, void* stream);
+
+/*
  * Backward pass (Section 3.1, "Convolution Jacobian"): full convolution of the
  * output gradients with the kernel reflected along all three axes, summed over
  * the outgoing edges of each input node.

@@ -29,8 +29,9 @@ EXPORTS = [
     "znn_maxfilter3d_sparse_fwd", "znn_maxfilter3d_sparse_bwd", "znn_maxpool3d_fwd", "znn_maxpool3d_bwd",
     "znn_transfer_fn_fwd", "znn_transfer_fn_bwd", "znn_cross_entropy_loss_grad",
     "znn_autotune_round_workspace_bytes", "znn_autotune_round", "znn_accumulate",
-    "znn_plan_set_spectra_layout", "znn_plan_spectra_layout",
+    "znn_plan_set_spectra_layout", "znn_plan_spectra_layout", "znn_conv3d_fwd_static",
 ]
+STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
 SPECTRA_LAYOUTS = {"auto": 0, "full": 1, "folded": 2}
 STRATEGIES = ("direct", "fft", "fft_memo")
 TRANSFER_FNS = {"rectify": 0, "logistic": 1, "tanh": 2}
@@ -88,6 +89,7 @@ def lib():
         L.znn_conv_release_kernels.argtypes = [vp]
         for name in ("znn_conv3d_fwd", "znn_conv3d_bwd", "znn_conv3d_wgrad"):
             getattr(L, name).argtypes = [vp, vp, vp, vp, vp, sz, vp]
+        L.znn_conv3d_fwd_static.argtypes = [vp, vp, vp, vp, vp]
         L.znn_maxfilter3d_fwd.argtypes = [i32, Vec3, Vec3, vp, vp, vp, vp]
         L.znn_maxfilter3d_bwd.argtypes = [i32, Vec3, Vec3, vp, vp, vp, vp]
         L.znn_maxfilter3d_sparse_fwd.argtypes = [i32, Vec3, Vec3, Vec3, vp, vp, vp, vp]
@@ -284,6 +286,16 @@ class Plan:
         ws, wsb = self._workspace(ZNN_PASS_FWD, inp.device)
         _check(lib().znn_conv3d_fwd(self._h, _ptr(inp, torch.float32), _ptr(w, torch.float32),
                                     _ptr(out, torch.float32), ws, wsb, _stream_ptr(stream)))
+        return out
+
+    def fwd_static(self, inp, w, out, stream=None):
+        """znn_conv3d_fwd_static: the forward pass with the library's built-in scratch array; this
+        wrapper allocates nothing either (the caller passes `out`)."""
+        import torch
+        assert tuple(inp.shape) == (self.f,) + self.n, inp.shape
+        assert tuple(out.shape) == (self.fo,) + self.o
+        _check(lib().znn_conv3d_fwd_static(self._h, _ptr(inp, torch.float32), _ptr(w, torch.float32),
+                                           _ptr(out, torch.float32), _stream_ptr(stream)))
         return out
 
     def bwd(self, gout, w, gin=None, stream=None):

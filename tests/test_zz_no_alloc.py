@@ -1,0 +1,58 @@
+"""The forward entry point that allocates nothing (built-in scratch array) against the ordinary
+one with a caller workspace: same kernels, so outputs must agree bit for bit; and against the
+oracle, to the tolerance of the method."""
+import ctypes
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1510_06706_amd import binding as znn
+from paper_1510_06706_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"direct": 1e-4, "fft": 1e-3}
+
+# two calls in a row on the same GPU, the second with a smaller input; the first direct-method
+# shape splits its input maps over workgroups, so partial sums go through the scratch as well
+CALLS = [(12, 24, (20, 21, 22), (3, 3, 3)), (5, 7, (12, 13, 14), (2, 3, 2))]
+
+
+@pytest.mark.parametrize("mode", ["direct", "fft"])
+def test_forward_without_allocation_matches_forward_with_workspace(mode):
+    import torch
+    dev = torch.device("cuda:0")
+    for call, (f, fo, n, k) in enumerate(CALLS):
+        cfg = synth.LayerShape("noalloc", f, fo, n, k, 1.0 / np.sqrt(f * np.prod(k)), 700 + call)
+        inp, w, _ = synth.layer_tensors(cfg)
+        d_in, d_w = torch.from_numpy(inp).to(dev), torch.from_numpy(w).to(dev)
+        p = znn.Plan(f, fo, n, k, mode)
+        assert 0 < p.workspace_bytes(znn.ZNN_PASS_FWD) <= znn.STATIC_SCRATCH_BYTES
+        want = p.fwd(d_in, d_w)
+        got = torch.full_like(want, float("nan"))
+        torch.cuda.synchronize()
+        before = torch.cuda.memory_allocated(dev)
+        p.fwd_static(d_in, d_w, got)
+        torch.cuda.synchronize()
+        assert torch.cuda.memory_allocated(dev) == before
+        assert torch.equal(got, want), (mode, call)
+        ref = oracle.conv3d_fwd(inp, w)
+        err = float(np.max(np.abs(got.cpu().numpy().astype(np.float64) - ref)) / np.max(np.abs(ref)))
+        print("no-alloc forward %s call %d: rel-err %.2e" % (mode, call, err), flush=True)
+        assert err <= TOL[mode]
+        p.close()
+
+
+def test_forward_without_allocation_refuses_layers_beyond_the_array():
+    import torch
+    cfg = synth.CONFIG2
+    p = znn.Plan(cfg.fan_in, cfg.fan_out, cfg.image, cfg.kernel, "fft")
+    assert p.workspace_bytes(znn.ZNN_PASS_FWD) > znn.STATIC_SCRATCH_BYTES
+    x = torch.zeros((cfg.fan_in,) + cfg.image, dtype=torch.float32, device="cuda:0")
+    w = torch.zeros((cfg.fan_out, cfg.fan_in) + cfg.kernel, dtype=torch.float32, device="cuda:0")
+    out = torch.zeros((cfg.fan_out,) + cfg.out, dtype=torch.float32, device="cuda:0")
+    rc = znn.lib().znn_conv3d_fwd_static(p._h, ctypes.c_void_p(x.data_ptr()), ctypes.c_void_p(w.data_ptr()),
+                                         ctypes.c_void_p(out.data_ptr()), ctypes.c_void_p(0))
+    assert rc == znn.ZNN_EWORKSPACE and "built-in array" in znn.last_error()
+    p.close()
