@@ -3,18 +3,14 @@
 This module only sequences library calls (Section 3 of the paper: forward pass,
 loss gradient, backward pass, gradients, update); every arithmetic step runs in
 libznn's kernels.  The layer lists of the benchmark networks and their seeded
-synthetic tensors live in ``synth`` and are re-exported here.
+synthetic tensors live in ``synth``.
 """
 from __future__ import annotations
 
 import numpy as np
 
 from . import binding as znn
-from .synth import (CONFIG3_ETA, CONFIG3_INPUT, CONFIG3_LAYERS, CONFIG3_SEED, CONFIG3_SPARSE_INPUT,  # noqa: F401
-                    CONFIG3_SPARSE_LAYERS, CONFIG2D_INPUT, CONFIG2D_LAYERS, CONFIG2D_SEED, ONES, WIDTH,
-                    config2d_tensors, config3_sparse_tensors, config3_tensors, net_tensors, shapes,
-                    synthetic_params)
-from .synth import _opt
+from .synth import ONES, _opt, shapes
 
 
 class Net:

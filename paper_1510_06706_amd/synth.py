@@ -1,10 +1,15 @@
 """Seeded synthetic inputs shared by the tests, the smoke check and the benchmark.
 
-This module holds no arithmetic of the method itself: it only fills arrays
-with reproducible pseudo-random fp32 values and names the layer shapes of the
-benchmark configurations.  The values come from a counter-based generator
-(SplitMix64 finaliser applied to ``seed, stream, index``), so they do not
-depend on the numpy or torch version and can be produced in any order.
+This module computes nothing of the method on values: it fills arrays with
+reproducible pseudo-random fp32 values and names the workloads (layer shapes of
+the benchmark configurations, layer lists of the networks, graph descriptions)
+together with the node extents that follow from them (``shapes``,
+``graph_shapes``: bookkeeping for the product's harness, the GPU tests and the
+benchmark).  The oracle works out its own extents, and its pin tests take their
+shapes from ``tests/workloads.py``, not from here.  The values come from a
+counter-based generator (SplitMix64 finaliser applied to ``seed, stream,
+index``), so they do not depend on the numpy or torch version and can be
+produced in any order.
 """
 from __future__ import annotations
 

@@ -1,5 +1,7 @@
-"""Parity at the benchmark's full sizes: configs 2, 4, 5 on outputs sampled one by one
-from the oracle, config 3 (a whole training round) layer by layer and end to end."""
+"""Parity at the benchmark's full sizes: configs 2 and 4 on every element of all three passes,
+config 5 on outputs the oracle computes one by one (a random sample plus positions chosen from the
+shape: corners, both sides of block boundaries, every pair of nodes in the kernel gradient),
+config 3 (a whole training round) layer by layer and end to end."""
 import numpy as np
 import pytest
 
@@ -29,54 +31,155 @@ def rel_err(got, ref):
     return float(np.max(np.abs(np.asarray(got, dtype=np.float64) - ref)) / max(np.max(np.abs(ref)), 1e-300))
 
 
-def sampled_layer_check(cfg, mode, resident, n_fwd, n_bwd, n_gw):
+def structured_positions(maps, ext):
+    """Flat offsets into a [maps][z][y][x] tensor chosen from its shape alone: in every map the eight
+    corners and, for a ladder of coordinates t (both ends of every axis and both sides of every multiple
+    of 8 and of 6, where output boxes, voxel tiles and row groups of any blocked kernel begin and end),
+    the points (t,t,t), (t, last-t, ...) and three axis-aligned edge points; the last map gets a finer set."""
+    ez, ey, ex = ext
+    vol = ez * ey * ex
+
+    def ladder(n):
+        s = {0, 1, n - 2, n - 1}
+        for step in (6, 8):
+            for m in range(step, n, step):
+                s.update((m - 1, m))
+        return sorted(v for v in s if 0 <= v < n)
+
+    pts = set()
+    for z in (0, ez - 1):
+        for y in (0, ey - 1):
+            for x in (0, ex - 1):
+                pts.add((z, y, x))
+    lz, ly, lx = ladder(ez), ladder(ey), ladder(ex)
+    for q in range(max(len(lz), len(ly), len(lx))):
+        z, y, x = lz[q % len(lz)], ly[q % len(ly)], lx[q % len(lx)]
+        pts.update([(z, y, x), (z, ey - 1 - y, x), (ez - 1 - z, y, ex - 1 - x), (z, 0, ex - 1), (0, y, 0), (ez - 1, ey - 1, x)])
+    pts = np.array(sorted(pts), dtype=np.int64)
+    flat = (pts[:, 0] * ey + pts[:, 1]) * ex + pts[:, 2]
+    out = [m * vol + flat for m in range(maps)]
+    # the last map: every ladder point on the last row and the last column of the last plane as well
+    extra = [((ez - 1) * ey + (ey - 1)) * ex + x for x in range(ex)] + [((ez - 1) * ey + y) * ex + ex - 1 for y in range(ey)]
+    out.append((maps - 1) * vol + np.array(extra, dtype=np.int64))
+    return np.unique(np.concatenate(out))
+
+
+def kernel_gradient_positions(f, fo, k):
+    """One tap of every (j, i) pair, the tap moving with the pair so that all taps occur, plus every tap of
+    the first and the last pair."""
+    taps = int(np.prod(k))
+    j, i = np.meshgrid(np.arange(fo), np.arange(f), indexing="ij")
+    pair = (j * f + i).ravel()
+    pos = pair * taps + (pair * 5 + j.ravel()) % taps
+    ends = np.concatenate([np.arange(taps), (f * fo - 1) * taps + np.arange(taps)])
+    return np.unique(np.concatenate([pos, ends]))
+
+
+def sampled_layer_check(cfg, mode, resident, n_fwd, n_bwd, n_gw, layout=None, structured=False, passes=("fwd", "bwd", "wgrad")):
     inp, w, gout = synth.layer_tensors(cfg)
     p = znn.Plan(cfg.fan_in, cfg.fan_out, cfg.image, cfg.kernel, mode)
+    if layout is not None:
+        p.set_spectra_layout(layout)
+        assert p.spectra_layout == layout
     d_in, d_w, d_g = dev(inp), dev(w), dev(gout)
     if resident:
         p.prepare_kernels(d_w)
     wk = None if resident else d_w
     rs = np.random.RandomState(cfg.seed)
-    out = host(p.fwd(d_in, wk)).ravel()
-    pos = rs.randint(0, out.size, size=n_fwd)
-    pos[:2] = (0, out.size - 1)
-    e_fwd = rel_err(out[pos], oracle.conv3d_fwd_at(inp, w, pos))
-    del out
-    gin = host(p.bwd(d_g, wk)).ravel()
-    pos = rs.randint(0, gin.size, size=n_bwd)
-    pos[:2] = (0, gin.size - 1)
-    e_bwd = rel_err(gin[pos], oracle.conv3d_bwd_at(gout, w, cfg.image, pos))
-    del gin
-    gw = host(p.wgrad(d_in, d_g)).ravel()
-    pos = rs.randint(0, gw.size, size=n_gw)
-    pos[:2] = (0, gw.size - 1)
-    e_gw = rel_err(gw[pos], oracle.conv3d_wgrad_at(inp, gout, pos))
-    print("%s %s: rel-err fwd %.2e bwd %.2e wgrad %.2e" % (cfg.name, mode, e_fwd, e_bwd, e_gw), flush=True)
+
+    def positions(total, n, extra):
+        pos = rs.randint(0, total, size=n)
+        pos[:2] = (0, total - 1)
+        return np.unique(np.concatenate([pos, extra])) if structured else pos
+
+    none = np.zeros(0, dtype=np.int64)
+    errs = {}
+    if "fwd" in passes:
+        out = host(p.fwd(d_in, wk)).ravel()
+        pos = positions(out.size, n_fwd, structured_positions(cfg.fan_out, cfg.out) if structured else none)
+        errs["fwd"] = (rel_err(out[pos], oracle.conv3d_fwd_at(inp, w, pos)), pos.size)
+        del out
+    if "bwd" in passes:
+        gin = host(p.bwd(d_g, wk)).ravel()
+        pos = positions(gin.size, n_bwd, structured_positions(cfg.fan_in, cfg.image) if structured else none)
+        errs["bwd"] = (rel_err(gin[pos], oracle.conv3d_bwd_at(gout, w, cfg.image, pos)), pos.size)
+        del gin
+    if "wgrad" in passes:
+        gw = host(p.wgrad(d_in, d_g)).ravel()
+        pos = positions(gw.size, n_gw, kernel_gradient_positions(cfg.fan_in, cfg.fan_out, cfg.kernel) if structured else none)
+        errs["wgrad"] = (rel_err(gw[pos], oracle.conv3d_wgrad_at(inp, gout, pos)), pos.size)
+    print("%s %s%s: %s" % (cfg.name, mode, "" if layout is None else " " + layout,
+                           "  ".join("%s rel-err %.2e on %d positions" % (k, e, n) for k, (e, n) in errs.items())), flush=True)
     p.close()
-    tol = TOL[mode]
-    assert e_fwd <= tol and e_bwd <= tol and e_gw <= tol
+    for k, (e, n) in errs.items():
+        assert e <= TOL[mode], (k, e)
 
 
+_FULL = {}
+
+
+def full_oracle(cfg):
+    """(inputs, complete fp64 results of the three passes) of a layer, computed once per session."""
+    if cfg.name not in _FULL:
+        inp, w, gout = synth.layer_tensors(cfg)
+        print("full oracle of %s ..." % cfg.name, flush=True)
+        _FULL[cfg.name] = (inp, w, gout, oracle.conv3d_fwd(inp, w), oracle.conv3d_bwd(gout, w, cfg.image),
+                           oracle.conv3d_wgrad(inp, gout))
+    return _FULL[cfg.name]
+
+
+def full_layer_check(cfg, mode):
+    """Every element of all three passes against the complete oracle."""
+    inp, w, gout, r_out, r_gin, r_gw = full_oracle(cfg)
+    p = znn.Plan(cfg.fan_in, cfg.fan_out, cfg.image, cfg.kernel, mode)
+    d_in, d_w, d_g = dev(inp), dev(w), dev(gout)
+    e_fwd = rel_err(host(p.fwd(d_in, d_w)), r_out)
+    e_bwd = rel_err(host(p.bwd(d_g, d_w)), r_gin)
+    e_gw = rel_err(host(p.wgrad(d_in, d_g)), r_gw)
+    print("%s %s, every element: rel-err fwd %.2e bwd %.2e wgrad %.2e" % (cfg.name, mode, e_fwd, e_bwd, e_gw), flush=True)
+    errs = [e_fwd, e_bwd, e_gw]
+    if mode == "fft":       # the memoized schedule must give the same three tensors
+        p.enable_memo()
+        p.prepare_kernels(d_w)
+        errs += [rel_err(host(p.fwd(d_in, None)), r_out), rel_err(host(p.bwd(d_g, None)), r_gin),
+                 rel_err(host(p.wgrad_memo()), r_gw)]
+    p.close()
+    assert max(errs) <= TOL[mode], errs
+
+
+@pytest.mark.timeout(900)
 @pytest.mark.parametrize("mode", ["direct", "fft"])
 def test_config2_wide_3d_layer(mode):
-    sampled_layer_check(synth.CONFIG2, mode, False, 4096, 4096, 1024)
+    full_layer_check(synth.CONFIG2, mode)
 
 
+@pytest.mark.timeout(900)
 @pytest.mark.parametrize("mode", ["direct", "fft"])
 def test_config4_two_dimensional_large_kernel(mode):
-    sampled_layer_check(synth.CONFIG4, mode, False, 4096, 4096, 1024)
+    full_layer_check(synth.CONFIG4, mode)
 
 
 @pytest.mark.timeout(600)
 def test_config5_large_layer_with_resident_kernel_spectra():
-    sampled_layer_check(synth.CONFIG5, "fft", True, 4096, 4096, 1024)
+    sampled_layer_check(synth.CONFIG5, "fft", True, 4096, 4096, 1024, structured=True)
+
+
+@pytest.mark.timeout(600)
+def test_config5_with_the_full_kernel_spectra_resident_in_hbm():
+    """Config 5 as the paper's memoization has it (Section 4; Table 2, memoized column): the transforms of
+    all 14 400 kernels, 52 GB, held in HBM and streamed by the multiply-accumulate of both passes."""
+    import torch
+    free, _ = torch.cuda.mem_get_info()
+    if free < 70e9:
+        pytest.skip("needs 52 GB of kernel spectra in device memory, %.0f GB free" % (free / 1e9))
+    sampled_layer_check(synth.CONFIG5, "fft", True, 4096, 4096, 0, layout="full", structured=True, passes=("fwd", "bwd"))
 
 
 @pytest.mark.timeout(600)
 def test_config5_by_the_direct_method():
     """The paper runs its largest layer by the FFT method only; the direct kernels take it too
     (single halo buffer, seven-tap groups, eight map tiles per wave)."""
-    sampled_layer_check(synth.CONFIG5, "direct", False, 2048, 2048, 512)
+    sampled_layer_check(synth.CONFIG5, "direct", False, 2048, 2048, 512, structured=True)
 
 
 @pytest.mark.parametrize("f,fo,n,k", [(37, 50, (40, 41, 42), (4, 3, 4)), (22, 40, (36, 36, 36), (3, 3, 3))])
@@ -96,7 +199,7 @@ def opt(spec, i, default):
 
 @pytest.mark.parametrize("mode", ["direct", "fft", "auto"])
 def test_config3_training_round(mode):
-    check_training_round("config 3", znet.CONFIG3_LAYERS, znet.CONFIG3_INPUT, znet.config3_tensors(), mode)
+    check_training_round("config 3", synth.CONFIG3_LAYERS, synth.CONFIG3_INPUT, synth.config3_tensors(), mode)
 
 
 @pytest.mark.timeout(900)
@@ -104,15 +207,15 @@ def test_config3_training_round(mode):
 def test_config3_as_a_max_filtering_net_with_sparse_layers(mode):
     """The same network with the sparsity doubling after every max-filter (Section 2, last
     paragraphs): sparse convolutions and a sparse filter inside one training round."""
-    check_training_round("config 3 sparse", znet.CONFIG3_SPARSE_LAYERS, znet.CONFIG3_SPARSE_INPUT,
-                         znet.config3_sparse_tensors(), mode)
+    check_training_round("config 3 sparse", synth.CONFIG3_SPARSE_LAYERS, synth.CONFIG3_SPARSE_INPUT,
+                         synth.config3_sparse_tensors(), mode)
 
 
 def check_training_round(name, layers, in_shape, tensors, mode):
     import torch
     x, target, params = tensors
     if mode == "auto":      # let the autotuner measure every convolutional layer first
-        sh = znet.shapes(layers, in_shape)
+        sh = synth.shapes(layers, in_shape)
         for l, spec in enumerate(layers):
             if spec[0] == "conv":
                 chosen, ms = znn.autotune(spec[1], spec[2], sh[l][1:], spec[3])
@@ -120,7 +223,7 @@ def check_training_round(name, layers, in_shape, tensors, mode):
                       % (l, "fft" if chosen == znn.ZNN_FFT else "direct", sum(ms[0]), sum(ms[1])), flush=True)
     net = znet.Net(layers, in_shape, params, mode)
     record = []
-    acts, aux, gout, grads = net.train_round(dev(x), dev(target), znet.CONFIG3_ETA, record)
+    acts, aux, gout, grads = net.train_round(dev(x), dev(target), synth.CONFIG3_ETA, record)
     torch.cuda.synchronize()
     plan_modes = net.modes()
     arriving = dict(record)
@@ -163,7 +266,7 @@ def check_training_round(name, layers, in_shape, tensors, mode):
 
     # end to end against the float64 round started from the same fp32 inputs
     p64 = [None if p is None else {k: v.astype(np.float64) for k, v in p.items()} for p in params]
-    loss, r_acts, r_aux, r_grads, r_new = onet.train_round(layers, p64, x, target, znet.CONFIG3_ETA)
+    loss, r_acts, r_aux, r_grads, r_new = onet.train_round(layers, p64, x, target, synth.CONFIG3_ETA)
     e2e = max(TOL["fft" if m == znn.ZNN_FFT else "direct"] for m in plan_modes if m is not None)
     out = host(acts[-1])
     assert rel_err(out, r_acts[-1]) <= e2e
@@ -203,7 +306,7 @@ def check_training_round(name, layers, in_shape, tensors, mode):
             fixed[bad] = g_y[bad]
             r_acts_sel[l + 1] = fixed
     r_grads = onet.backward(layers, p64, r_acts_sel, r_aux_sel, r_acts[-1] - target.astype(np.float64))
-    r_new = [None if p is None else {k: v - znet.CONFIG3_ETA * r_grads[l][k] for k, v in p.items()}
+    r_new = [None if p is None else {k: v - synth.CONFIG3_ETA * r_grads[l][k] for k, v in p.items()}
              for l, p in enumerate(p64)]
     worst_g, worst_p = 0.0, 0.0
     for l, g in enumerate(r_grads):

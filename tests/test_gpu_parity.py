@@ -361,7 +361,7 @@ def test_small_net_with_every_layer_kind_matches_the_oracle_round():
               ("conv", 5, 4, (2, 2, 1), (2, 1, 2)), ("transfer",), ("maxfilter", (2, 2, 1), (2, 1, 2)),
               ("maxpool", (1, 2, 2)), ("conv", 4, 3, (1, 2, 2)), ("transfer", "logistic")]
     in_shape = (2, 10, 12, 14)
-    x, target, params = znet.net_tensors(layers, in_shape, 31)
+    x, target, params = synth.net_tensors(layers, in_shape, 31)
     for mode in ("direct", "fft"):
         net = znet.Net(layers, in_shape, params, mode)
         acts, aux, gout, grads = net.train_round(dev(x), dev(target), 1e-2, loss="cross_entropy")
@@ -439,7 +439,7 @@ def test_training_round_with_memoized_spectra_matches_the_oracle(mode):
               ("conv", 6, 5, (2, 3, 2), (2, 2, 2)), ("transfer", "tanh"),
               ("conv", 5, 3, (3, 1, 2)), ("transfer", "logistic")]
     in_shape = (2, 14, 15, 16)
-    x, target, params = znet.net_tensors(layers, in_shape, 41)
+    x, target, params = synth.net_tensors(layers, in_shape, 41)
     net = znet.Net(layers, in_shape, params, mode)
     if mode == "tuned":
         assert set(net.tuning) == {0, 3, 5}

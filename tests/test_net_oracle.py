@@ -3,8 +3,9 @@ differences of its own loss on a small net with the benchmark network's layer ty
 import numpy as np
 
 from oracle import net as onet
-from paper_1510_06706_amd import net as znet
-from paper_1510_06706_amd import synth
+from paper_1510_06706_amd import synth     # the seeded value generator only
+
+import workloads
 
 LAYERS = [("conv", 1, 3, (2, 2, 2)), ("transfer",), ("maxfilter", (2, 2, 1)),
           ("conv", 3, 2, (2, 1, 2)), ("transfer",)]
@@ -17,19 +18,22 @@ def loss_of(params, x, t):
 
 
 def test_shapes_follow_the_valid_and_filter_size_rules():
-    s = znet.shapes(znet.CONFIG3_LAYERS, znet.CONFIG3_INPUT)
+    k3, m2 = (3, 3, 3), (2, 2, 2)
+    config3 = [("conv", 1, 40, k3), ("transfer",), ("conv", 40, 40, k3), ("transfer",), ("maxfilter", m2),
+               ("conv", 40, 40, k3), ("transfer",), ("conv", 40, 40, k3), ("transfer",), ("maxfilter", m2),
+               ("conv", 40, 40, k3), ("transfer",), ("conv", 40, 3, k3), ("transfer",)]
+    s = [a.shape for a in onet.forward(config3, workloads.layer_params(config3, 1), np.zeros((1, 26, 26, 26)))[0]]
     assert s[0] == (1, 26, 26, 26) and s[-1] == (3, 12, 12, 12)
     assert s[5] == (40, 21, 21, 21) and s[10] == (40, 16, 16, 16)
 
 
 def test_analytic_gradients_match_finite_differences():
-    params = [None if p is None else {k: v.astype(np.float64) for k, v in p.items()}
-              for p in znet.synthetic_params(LAYERS, 5)]
+    params = workloads.layer_params(LAYERS, 5)
     for p in params:          # biases well away from the rectifier's kink for most voxels
         if p and "b" in p:
             p["b"] += 0.3
     x = synth.uniform_pm1(6, 0, IN_SHAPE).astype(np.float64)
-    t = synth.uniform_01(6, 3, znet.shapes(LAYERS, IN_SHAPE)[-1]).astype(np.float64)
+    t = synth.uniform_01(6, 3, workloads.layer_shapes(LAYERS, IN_SHAPE)[-1]).astype(np.float64)
     loss, acts, aux, grads, new = onet.train_round(LAYERS, params, x, t, 1e-3)
     assert abs(loss - loss_of(params, x, t)) < 1e-12
     rs = np.random.RandomState(2)

@@ -12,7 +12,8 @@ import scipy.signal
 import oracle
 from oracle import graph as ograph
 from oracle import net as onet
-from paper_1510_06706_amd import synth
+
+import workloads
 
 
 def f64(params):
@@ -20,12 +21,12 @@ def f64(params):
 
 
 def small_graph():
-    return synth.multiscale_graph(width=2, n=11)
+    return workloads.multiscale_graph(width=2, n=11)
 
 
 def test_convergent_node_is_the_sum_of_its_edges_computed_by_scipy():
     g = small_graph()
-    inputs, targets, params = synth.graph_tensors(g, 3)
+    inputs, targets, params = workloads.graph_tensors(g, 3)
     params = f64(params)
     img, aux = ograph.forward(g, params, inputs)
     a1, b1, m = img["a1"], img["b1"], img["m"]
@@ -48,7 +49,7 @@ def test_convergent_node_is_the_sum_of_its_edges_computed_by_scipy():
 
 def test_graph_gradients_match_finite_differences_on_every_edge():
     g = small_graph()
-    inputs, targets, params = synth.graph_tensors(g, 4)
+    inputs, targets, params = workloads.graph_tensors(g, 4)
     params = f64(params)
     for p in params.values():
         if "b" in p:
@@ -81,7 +82,7 @@ def test_a_chain_written_as_a_graph_equals_the_layered_reference():
               ("conv", 3, 2, (2, 2, 1), (2, 1, 2)), ("transfer",), ("maxpool", (1, 2, 2)),
               ("conv", 2, 2, (1, 2, 1)), ("transfer", "logistic")]
     in_shape = (1, 8, 8, 8)
-    x, t, lp = synth.net_tensors(layers, in_shape, 12)
+    x, t, lp = workloads.net_tensors(layers, in_shape, 12)
     lp = [None if p is None else {k: v.astype(np.float64) for k, v in p.items()} for p in lp]
     edges, params = [], {}
     for l, spec in enumerate(layers):
@@ -93,7 +94,7 @@ def test_a_chain_written_as_a_graph_equals_the_layered_reference():
         if lp[l] is not None:
             params[name] = lp[l]
     g = {"inputs": {"n0": in_shape}, "edges": edges, "outputs": ["n%d" % len(layers)]}
-    assert synth.graph_shapes(g)["n%d" % len(layers)] == synth.shapes(layers, in_shape)[-1]
+    assert workloads.graph_shapes(g)["n%d" % len(layers)] == workloads.layer_shapes(layers, in_shape)[-1]
     v1, acts, _, g1, _ = onet.train_round(layers, lp, x, t, 1e-2, "cross_entropy")
     v2, img, _, g2, _ = ograph.train_round(g, params, {"n0": x}, {"n%d" % len(layers): t}, 1e-2, "cross_entropy")
     assert v1 == v2

@@ -15,8 +15,9 @@ import pytest
 
 import oracle
 from oracle import net as onet
-from paper_1510_06706_amd import net as znet
-from paper_1510_06706_amd import synth
+from paper_1510_06706_amd import synth     # the seeded value generator only
+
+import workloads
 
 
 def rnd(seed, stream, shape):
@@ -137,10 +138,9 @@ def test_maxfilter_net_with_sparse_layers_equals_sliding_window_maxpool_net():
                 ("conv", 3, 2, k, (2, 2, 2)), ("transfer", "tanh"), ("maxfilter", two, (2, 2, 2)),
                 ("conv", 2, 2, k, (4, 4, 4)), ("transfer", "logistic")]
     fov = 11                                   # 1 <- conv 2 <- pool 4 <- conv 5 <- pool 10 <- conv 11
-    assert znet.shapes(pool_net, (1, fov, fov, fov))[-1] == (2, 1, 1, 1)
+    assert workloads.layer_shapes(pool_net, (1, fov, fov, fov))[-1] == (2, 1, 1, 1)
     n = (13, 12, 14)
-    params = [None if p is None else {a: v.astype(np.float64) for a, v in p.items()}
-              for p in znet.synthetic_params(pool_net, 77)]
+    params = workloads.layer_params(pool_net, 77)
     x = rnd(78, 0, (1,) + n)
     dense = onet.forward(filt_net, params, x)[0][-1]
     assert dense.shape == (2,) + tuple(t - fov + 1 for t in n)
@@ -198,14 +198,13 @@ def test_net_gradients_with_every_layer_kind_match_finite_differences():
               ("conv", 2, 3, (2, 2, 1), (2, 1, 2)), ("transfer",), ("maxfilter", (2, 2, 1), (2, 1, 2)),
               ("maxpool", (1, 2, 2)), ("conv", 3, 2, (1, 2, 1)), ("transfer", "logistic")]
     in_shape = (1, 8, 7, 8)
-    assert znet.shapes(layers, in_shape)[-1] == (2, 2, 1, 3)
-    params = [None if p is None else {a: v.astype(np.float64) for a, v in p.items()}
-              for p in znet.synthetic_params(layers, 9)]
+    params = workloads.layer_params(layers, 9)
+    assert onet.forward(layers, params, np.zeros(in_shape))[0][-1].shape == (2, 2, 1, 3)
     for p in params:
         if p and "b" in p:
             p["b"] += 0.3
     x = rnd(10, 0, in_shape)
-    t = synth.uniform_01(10, 3, znet.shapes(layers, in_shape)[-1]).astype(np.float64)
+    t = synth.uniform_01(10, 3, (2, 2, 1, 3)).astype(np.float64)
 
     def loss_of():
         return oracle.loss_value(onet.forward(layers, params, x)[0][-1], t, "cross_entropy")
