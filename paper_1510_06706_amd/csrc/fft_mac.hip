@@ -35,20 +35,31 @@ __device__ __forceinline__ float2 cmulf(float2 a, float2 b)
     return make_float2(fmaf(a.x, b.x, -a.y * b.y), fmaf(a.x, b.y, a.y * b.x));
 }
 
+// Grid order.  A workgroup is `wpb` waves that share 64 in-plane frequencies and differ in
+// their frequencies along the folded axis: all of them request the same half-spectrum lines,
+// which then come out of the compute unit's cache instead of `wpb` times out of L2/HBM.
+// Workgroups that differ only in their group of result nodes read the same node spectra X;
+// the hardware deals consecutive workgroups to the eight XCDs (each with its own L2) in turn,
+// so the flat workgroup index is taken apart as
+//     xcd = b % 8,  slot = b / 8,  frequency block q = (slot / ngroups) * 8 + xcd,
+//     node group = slot % ngroups:
+// the workgroups of one frequency block run on one XCD, next to each other in time, and X
+// comes out of that XCD's L2 for all but the first of them (config 5: 20 GB fetched from
+// HBM per launch before, where the algorithm reads 4.2 GB).
 template <bool BWD, int KZ, int Z0, int G>
 __global__ void __launch_bounds__(kThreads)
-k_mac_fused(int f, int fo, int N, int P, int nzi, const float2* __restrict__ Wh,
+k_mac_fused(int f, int fo, int N, int P, int nzi, int wpb, int nq, int ngroups, const float2* __restrict__ Wh,
             const float2* __restrict__ X, float2* __restrict__ Y)
 {
-    // A workgroup is four waves that share 64 in-plane frequencies and differ in their
-    // frequencies along the folded axis: all four request the same half-spectrum lines,
-    // which then come out of the compute unit's cache instead of four times out of L2/HBM.
     const int npc = (P + 63) >> 6;
-    const int pc = blockIdx.x % npc, zb = blockIdx.x / npc;
-    const int zi = zb * 4 + (threadIdx.x >> 6);
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int q = (slot / ngroups) * 8 + xcd, og = slot % ngroups;
+    if (q >= nq) return;
+    const int pc = q % npc, zb = q / npc;
+    const int zi = zb * wpb + (threadIdx.x >> 6);
     const int p = pc * 64 + (threadIdx.x & 63);
     if (zi >= nzi || p >= P) return;
-    const int o0 = blockIdx.y * G;
+    const int o0 = og * G;
     const int nred = BWD ? fo : f, nout = BWD ? f : fo;
     const int Q = N >> 2;
     const long vol = (long)N * P;
@@ -142,11 +153,15 @@ int launch_variant(int f, int fo, int N, int P, const float2* Wh, const float2* 
     constexpr int G = fft_mac_group(Z0);
     const int nout = BWD ? f : fo;
     const int nzi = N / 4 / Z0;
-    const long blocks = (long)((P + 63) / 64) * ((nzi + 3) / 4);
-    if (blocks >= 2147483647L || (nout + G - 1) / G > 65535) return fail(ZNN_EUNSUPPORTED, "too many frequencies");
+    // waves per workgroup: four, or three when that splits the frequency groups evenly (N = 96: 6 = 3 + 3)
+    const int wpb = nzi % 4 != 0 && nzi % 3 == 0 ? 3 : 4;
+    const long nq = (long)((P + 63) / 64) * ((nzi + wpb - 1) / wpb);
+    const int ngroups = (nout + G - 1) / G;
+    const long blocks = ((nq + 7) / 8) * 8 * ngroups;
+    if (blocks >= 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many frequencies");
     ZNN_LAUNCH(BWD ? "spectral mac backward (taps folded in)" : "spectral mac forward (taps folded in)", s,
-               (k_mac_fused<BWD, KZ, Z0, G>), dim3((unsigned)blocks, (unsigned)((nout + G - 1) / G)),
-               dim3(kThreads), 0, f, fo, N, P, nzi, Wh, X, Y);
+               (k_mac_fused<BWD, KZ, Z0, G>), dim3((unsigned)blocks), dim3(64 * wpb), 0, f, fo, N, P, nzi, wpb,
+               (int)nq, ngroups, Wh, X, Y);
     return check_launch("spectral multiply-accumulate");
 }
 
