@@ -88,6 +88,7 @@ const Tuning& tuning()
         if (v.wgrad_stride_mod < 0 || v.wgrad_stride_mod > 28 || v.wgrad_stride_mod % 4) v.wgrad_stride_mod = 4;
         v.wgrad_slow_loader = flag("ZNN_WGRAD_SLOW_LOADER");
         v.fft_mac_z0 = num("ZNN_FFT_MAC_Z0", 0);
+        v.fft_mac_valu = flag("ZNN_FFT_MAC_VALU");
         v.fft_wgrad_plain = flag("ZNN_FFT_WGRAD_PLAIN");
         v.fft_lds_passes = flag("ZNN_FFT_LDS_PASSES");
         return v;

@@ -1010,7 +1010,11 @@ Fold fold_search(const Geom& g, long min_blocks)
 
 int launch_mac(bool backward, const Geom& g, const Fold& F, const float2* What, const float2* a, float2* b, hipStream_t s)
 {
-    if (F.on) return fft_mac_fused(backward, F.taps, F.z0, g.f, g.fo, F.N, F.P, What, a, b, s);
+    if (F.on) {
+        if (!tuning().fft_mac_valu && fft_mac_mfma_supported(F.taps, F.N, F.P))
+            return fft_mac_mfma(backward, F.taps, g.f, g.fo, F.N, F.P, What, a, b, s);
+        return fft_mac_fused(backward, F.taps, F.z0, g.f, g.fo, F.N, F.P, What, a, b, s);
+    }
     const long svol = g.svol();
     const int outs = backward ? g.f : g.fo;
     const int V = (svol % 2 == 0) ? 2 : 1;

@@ -81,6 +81,7 @@ struct Tuning {
     int  wgrad_stride_mod;      // ZNN_WGRAD_STRIDE_MOD: residue modulo 32 of the LDS map stride
     bool wgrad_slow_loader;     // ZNN_WGRAD_SLOW_LOADER: general tile loader everywhere
     int  fft_mac_z0;            // ZNN_FFT_MAC_Z0: frequencies per thread of the folded multiply-accumulate / 4
+    bool fft_mac_valu;          // ZNN_FFT_MAC_VALU: folded multiply-accumulate on the vector ALUs only
     bool fft_wgrad_plain;       // ZNN_FFT_WGRAD_PLAIN: per-z pruned DFT instead of the radix-4 grouped one
     bool fft_lds_passes;        // ZNN_FFT_LDS_PASSES: LDS passes instead of register passes
 };
@@ -134,6 +135,12 @@ constexpr int kMaxFoldedTaps = 16;
 constexpr int fft_mac_group(int z0) { return z0 == 1 ? 8 : 4; }
 int fft_mac_fused(bool backward, int taps, int z0, int f, int fo, int N, int P, const float2* Wh,
                   const float2* X, float2* Y, hipStream_t s);
+
+// The same with the rebuild of the kernel spectrum on the matrix cores (fft_mac_mfma.hip); takes
+// extents divisible by 32.
+bool fft_mac_mfma_supported(int taps, int N, int P);
+int fft_mac_mfma(bool backward, int taps, int f, int fo, int N, int P, const float2* Wh, const float2* X,
+                 float2* Y, hipStream_t s);
 
 // Strided-axis FFT pass with one pencil per thread, whole pencil in registers (fft_reg.hip).
 // Pencil (oa, ob, l), l < L, has its element e at in + oa*in_sa + ob*in_sb + l + e*stride;
