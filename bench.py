@@ -296,7 +296,10 @@ def main():
         what = "fwd"
     elif top["kernel"].startswith("direct backward"):
         what = "bwd"
-    bound, work = rl.work_of(cfg, N, layout or "folded", what)[rl.step_of(top["kernel"], what)]
+    key = rl.step_of(top["kernel"], what)
+    if key == "F-mac" and "MFMA" in top["kernel"]:
+        key = "F-mac/mfma"
+    bound, work = rl.work_of(cfg, N, layout or "folded", what)[key]
     roof = {"kernel": top["kernel"], "ms": top["ms_per_launch"], "launches_per_step": top["launches_per_step"]}
     roof.update(rl.price(bound, work, top["ms_per_launch"]))
     roof["algorithmic_work_per_launch"] = work

@@ -138,22 +138,22 @@ __global__ void __launch_bounds__(64 * kWaves, 2) k_mac_mfma(MacTile T)
     for (int i = threadIdx.x; i < tile; i += 64 * kWaves) tileA[i] = tileB[i] = make_float2(0.f, 0.f);
     if (T.N < 0) tileA[threadIdx.x] = tileB[threadIdx.x] = T.X[threadIdx.x];    // never taken: tells the optimizer that LDS holds data
     const float* xf = reinterpret_cast<const float*>(T.X);
-    long xthread;                                       // float offset of this thread's element for k = 0
+    unsigned xthread;                                   // byte offset of this thread's element for k = 0 inside a node spectrum
     bool xvalid;
     {
         const int within = threadIdx.x & 127, h = threadIdx.x >> 7;
         const int g_ = within >> 5, nn = (within >> 1) & 15, comp = within & 1;
         xvalid = p0 + nn < T.P;
-        xthread = ((long)(h * Q + sb * T.SW * ZG * 8 + 2 * g_) * T.P + p0 + nn) * 2 + comp;
+        xthread = (unsigned)(((long)(h * Q + sb * T.SW * ZG * 8 + 2 * g_) * T.P + p0 + nn) * 8 + comp * 4);
     }
     const int nloads = T.SW * ZG * 4;
     auto fetch_tile = [&](int r, float2* buf) {
-        const float* xb = xf + (long)r * vol * 2 + xthread;
+        const char* xb = reinterpret_cast<const char*>(xf + (long)r * vol * 2);     // uniform
         float* dst = reinterpret_cast<float*>(buf) + wave * 64;
         for (int k = 0; k < nloads; ++k) {
             const int ck = 2 * (k & 1) * Q + ((k >> 1) & 1) + 8 * (k >> 2);         // uniform
             if (xvalid)
-                __builtin_amdgcn_global_load_lds((global_cptr)(xb + (long)ck * T.P * 2), (lds_ptr)(dst + k * 256), 4, 0, 0);
+                __builtin_amdgcn_global_load_lds((global_cptr)(xb + (long)ck * T.P * 8 + xthread), (lds_ptr)(dst + k * 256), 4, 0, 0);
         }
     };
 
@@ -173,7 +173,7 @@ __global__ void __launch_bounds__(64 * kWaves, 2) k_mac_mfma(MacTile T)
         const long pair = BWD ? (long)r * T.f + o : (long)o * T.f + r;
         return whf + pair * wplane;
     };
-    float bcur[G][NB > 0 ? NB : 1], bnext[G][NB > 0 ? NB : 1];
+    float b0[G][NB > 0 ? NB : 1], b1[G][NB > 0 ? NB : 1];      // two operand sets taking turns
     auto load_b = [&](int r, float (&b)[G][NB > 0 ? NB : 1]) {
 #pragma unroll
         for (int gi = 0; gi < G; ++gi) {
@@ -185,15 +185,15 @@ __global__ void __launch_bounds__(64 * kWaves, 2) k_mac_mfma(MacTile T)
 
     __syncthreads();                    // the zeros are in place
     fetch_tile(0, tileA);
-    load_b(0, bcur);
+    load_b(0, b0);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     int xo = (sl * ZG * 8) * 64 + lane;                             // this wave's slots of buffer 0, this lane's element
 
     // one reduction index: reads the tile in `cur` while the next one lands in `nxt`
-    auto reduction_step = [&](int r, const float2* cur, float2* nxt) {
-        const bool more = r + 1 < nred;
-        if (more) {
+    auto reduction_step = [&](int r, const float2* cur, float2* nxt, float (&bcur)[G][NB > 0 ? NB : 1],
+                              float (&bnext)[G][NB > 0 ? NB : 1]) {
+        if (r + 1 < nred) {
             fetch_tile(r + 1, nxt);
             load_b(r + 1, bnext);
         }
@@ -272,19 +272,13 @@ __global__ void __launch_bounds__(64 * kWaves, 2) k_mac_mfma(MacTile T)
                               "+v"(ag[1][2].x), "+v"(ag[1][2].y), "+v"(ag[1][3].x), "+v"(ag[1][3].y),
                               "+v"(xo), "+v"(bcur[(k + 2) % G][0]));
         }
-        if (more) {
-#pragma unroll
-            for (int gi = 0; gi < G; ++gi)
-#pragma unroll
-                for (int k = 0; k < NB; ++k) bcur[gi][k] = bnext[gi][k];
-        }
         __builtin_amdgcn_s_waitcnt(0);      // this wave's part of the next tile has landed
         __syncthreads();                    // everyone's has, and nobody still reads the current one
     };
     // two steps per trip, so that each copy of the code names its buffers statically
     for (int r = 0; r < nred; r += 2) {
-        reduction_step(r, tileA, tileB);
-        if (r + 1 < nred) reduction_step(r + 1, tileB, tileA);
+        reduction_step(r, tileA, tileB, b0, b1);
+        if (r + 1 < nred) reduction_step(r + 1, tileB, tileA, b1, b0);
     }
 
     if (!pvalid) return;
@@ -352,10 +346,10 @@ int launch_dir(int taps, MacTile T, int ZG, int nout, hipStream_t s)
 
 bool fft_mac_mfma_supported(int taps, int N, int P)
 {
-    // the tile loader addresses a node spectrum with N * P elements per map in 64-bit, a half
-    // spectrum row with taps * P * 2 floats in 32-bit
+    // offsets inside one node spectrum (N * P elements) and inside one pair's half spectrum
+    // (taps * P elements) are 32-bit
     return N % 32 == 0 && taps >= 1 && taps <= kMaxFoldedTaps && (long)taps * P * 2 < 2147483647L &&
-           (long)N * P < 2147483647L;
+           (long)N * P * 8 < 4294967296L;       // a thread's byte offset inside a node spectrum fits 32 bits
 }
 
 int fft_mac_mfma(bool backward, int taps, int f, int fo, int N, int P, const float2* Wh, const float2* X,

@@ -17,6 +17,14 @@ Steps (rows of the hot path) and what bounds them:
                               radix-4 butterfly of 8 complex additions       16
                               4 complex multiply-adds with the node spectrum 32
                             -> flops4 = 6 (taps-1) + 2 max(taps-4, 0) + 48 per edge and 4 frequencies.
+  F-mac, half spectra,      the same with the class sums V_c[z0] = sum_{a = c mod 4} Wh[a] exp(-2 pi i a z0 / N)
+  rebuild on matrix cores   taken by v_mfma_f32_16x16x4_f32 (per edge, 16 in-plane frequencies and 8 z0: one MFMA
+                            per class and per two taps of the class, 2048 FLOP each, padding rows included) and
+                            only the radix-4 butterfly (16) and the four complex multiply-adds (32) left on the
+                            vector ALUs: 48 FLOP per edge and 4 frequencies.  On this chip an MFMA and vector
+                            instructions of the same SIMD take turns rather than overlap (measured: busy cycles
+                            of the two add up to the elapsed time), so the row is priced on the sum of both
+                            kinds of executed FLOPs against the one 157.3 TFLOP/s that either unit peaks at.
   F-wgrad z                 fp32 vector ALU (pruned DFT of the spectral products).  Per pair of nodes and
                             four z a quarter period apart: 4 products g conj(x) (6 FLOP), a radix-4
                             butterfly (16), one complex addition (2) and taps-1 complex multiply-adds (8):
@@ -50,6 +58,11 @@ def spectrum_elems(N) -> int:
 
 def flops4_mac_folded(taps: int) -> float:
     return 6.0 * (taps - 1) + 2.0 * max(taps - 4, 0) + 48.0
+
+
+def mfma_steps(taps: int) -> int:
+    """MFMA k-steps per (edge, 16 p, 8 z0) of the class sums: ceil(2 * taps_of_class / 4) over the four classes."""
+    return sum((2 * ((taps - c + 3) // 4) + 3) // 4 for c in range(4) if c < taps)
 
 
 def flops4_wgrad_dft(taps: int) -> float:
@@ -116,6 +129,8 @@ def work_of(cfg, N, layout: str, what: str):
     if layout == "folded":
         kspec = 8.0 * pairs * taps * (sv // Nfold)
         w["F-mac"] = ("alu", pairs * sv / 4.0 * flops4_mac_folded(taps))
+        ptiles = -(-(sv // Nfold) // 16)
+        w["F-mac/mfma"] = ("alu", pairs * sv / 4.0 * 48.0 + pairs * ptiles * (Nfold // 32) * mfma_steps(taps) * 2048.0)
     else:
         kspec = 8.0 * pairs * sv
         w["F-mac"] = ("hbm", 8.0 * sv * (pairs + f + fo))
@@ -182,8 +197,11 @@ def steps_of_pass(records, reps, cfg, N, layout, what, extra_work=None):
     for st, e in agg.items():
         e["launches"] = e["launches"] / reps
         e["ms"] = e["ms"] / reps
-        if st in model:
-            e.update(price(model[st][0], model[st][1], e["ms"]))
+        key = st + "/mfma" if st == "F-mac" and any("MFMA" in k for k in e["kernels"]) else st
+        if key in model:
+            e.update(price(model[key][0], model[key][1], e["ms"]))
+            if key.endswith("/mfma"):
+                e["work"] = "FLOPs the kernel executes: vector ALU (butterfly, product) + matrix cores (class sums)"
         rows.append(e)
     return rows
 
