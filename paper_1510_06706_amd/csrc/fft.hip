@@ -815,6 +815,18 @@ int launch_wgrad_dft(int k, int f, int fo, int N, int tz, long plane, long vol, 
 int launch_r2c(const float* src, float2* dst, long maps, int sz, int sy, int sx,
                int Nz, int Ny, int Nx, int oz, int oy, int ox, int tz, int ty, int tx, hipStream_t s)
 {
+    // rows one sample apart along x whose transform length has an instance: one row per thread, in registers
+    if (tx == 1 && !tuning().fft_lds_passes && fft_x_reg_supported(Nx) && sx <= Nx - ox) {
+        XRegR2C X = {};
+        X.src = src; X.dst = dst;
+        X.rows = maps * sz * sy;
+        X.sz = sz; X.sy = sy; X.sx = sx;
+        X.Nz = Nz; X.Ny = Ny; X.Nxh = Nx / 2 + 1;
+        X.oz = oz; X.oy = oy; X.ox = ox;
+        X.tz = tz; X.ty = ty;
+        X.fsy = make_fastdiv((unsigned)sy); X.fsz = make_fastdiv((unsigned)sz);
+        return fft_x_r2c_reg(X, Nx, s);
+    }
     R2CParams P;
     P.tz = tz; P.ty = ty; P.tx = tx;
     P.src = src; P.dst = dst;
@@ -837,6 +849,17 @@ int launch_r2c(const float* src, float2* dst, long maps, int sz, int sy, int sx,
 int launch_c2r(const float2* src, float* dst, long maps, int Nz, int Ny, int Nx,
                int cz, int cy, int cx, int dz, int dy, int dx, int tx, float scale, hipStream_t s)
 {
+    if (tx == 1 && !tuning().fft_lds_passes && fft_x_reg_supported(Nx) && dx <= Nx - cx) {
+        XRegC2R X = {};
+        X.src = src; X.dst = dst;
+        X.rows = maps * dz * dy;
+        X.cz = cz; X.cy = cy; X.cx = cx;
+        X.dz = dz; X.dy = dy; X.dx = dx;
+        X.Nz = Nz; X.Ny = Ny; X.Nxh = Nx / 2 + 1;
+        X.scale = scale;
+        X.fdy = make_fastdiv((unsigned)dy); X.fdz = make_fastdiv((unsigned)dz);
+        return fft_x_c2r_reg(X, Nx, s);
+    }
     C2RParams P;
     P.tx = tx;
     P.src = src; P.dst = dst;

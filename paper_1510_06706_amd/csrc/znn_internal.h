@@ -156,6 +156,33 @@ struct RegAxis {
 bool fft_axis_reg_supported(int N);
 int  fft_axis_reg(RegAxis P, int dir, hipStream_t s);
 
+// x-axis passes with one row per thread and the row's transform in registers (fft_x_reg*.hip).
+// r2c: rows of `sx` real samples (contiguous, `rows` = maps * sz * sy of them) land zero-extended from
+// offset ox in lines of N = 2 (Nxh - 1); row (map, z, y) goes to spectrum row (map, z*tz + oz, y*ty + oy).
+struct XRegR2C {
+    const float* src; float2* dst;
+    long rows;
+    int sz, sy, sx;
+    int Nz, Ny, Nxh;
+    int oz, oy, ox;
+    int tz, ty;
+    FastDiv fsy, fsz;
+};
+// c2r: spectrum rows (map, z + cz, y + cy), z < dz, y < dy, become contiguous rows of the dx real
+// samples from offset cx, times `scale`.
+struct XRegC2R {
+    const float2* src; float* dst;
+    long rows;
+    int cz, cy, cx;
+    int dz, dy, dx;
+    int Nz, Ny, Nxh;
+    float scale;
+    FastDiv fdy, fdz;
+};
+bool fft_x_reg_supported(int N);
+int  fft_x_r2c_reg(const XRegR2C& P, int N, hipStream_t s);
+int  fft_x_c2r_reg(const XRegC2R& P, int N, hipStream_t s);
+
 // ---------------------------------------------------------------- fill (autotuner)
 int fill_pattern(float* p, long count, float scale, hipStream_t s);
 

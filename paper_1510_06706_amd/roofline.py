@@ -87,11 +87,11 @@ def step_of(name: str, what: str) -> str:
         return "F-wgrad y"
     if what == "kernel_spectra":
         return "F-ker"
-    if name == "fft c2r x":
+    if name.startswith("fft c2r x"):
         return "F-wgrad x" if what == "wgrad_memo" or what == "wgrad" else "F-inv"
     if name.startswith("fft axis inverse"):
         return "F-wgrad y" if what in ("wgrad", "wgrad_memo") else "F-inv"
-    if name in ("fft r2c x", "pruned z DFT of kernels") or name.startswith("fft axis forward"):
+    if name.startswith("fft r2c x") or name == "pruned z DFT of kernels" or name.startswith("fft axis forward"):
         return "F-img"
     if name == "max-filter forward":
         return "MF-fwd"

@@ -218,6 +218,36 @@ def test_fft_passes_with_register_resident_pencils_for_every_extent(N):
         p.close()
 
 
+@pytest.mark.parametrize("N", [2 * h for h in REG_EXTENTS])
+def test_fft_x_passes_with_register_resident_rows_for_every_extent(N):
+    """Every transform length the one-row-per-thread x passes are instantiated for (N = 2 H), once with
+    rows that fill the line and once zero-extended, with row counts that leave a ragged last wave."""
+    print("case", N, flush=True)
+
+    def next_smooth(n):
+        while True:
+            t = n
+            for q in (2, 3, 5):
+                while t % q == 0:
+                    t //= q
+            if t == 1:
+                return n
+            n += 1
+
+    shorter = [nx for nx in range(N - 1, N - 8, -1) if next_smooth(nx) == N]
+    for nx in [N] + shorter[-1:]:
+        n, k = (5, 17, nx), (2, 3, 4)
+        cfg = synth.LayerShape("t", 2, 3, n, k, 1.0, 500 + N)
+        inp, w, gout = synth.layer_tensors(cfg)
+        p = znn.Plan(2, 3, n, k, "fft")
+        assert p.fft_extents[2] == N
+        d_in, d_w, d_g = dev(inp), dev(w), dev(gout)
+        assert rel_err(host(p.fwd(d_in, d_w)), oracle.conv3d_fwd(inp, w)) <= TOL["fft"], (n, "fwd")
+        assert rel_err(host(p.bwd(d_g, d_w)), oracle.conv3d_bwd(gout, w, n)) <= TOL["fft"], (n, "bwd")
+        assert rel_err(host(p.wgrad(d_in, d_g)), oracle.conv3d_wgrad(inp, gout)) <= TOL["fft"], (n, "wgrad")
+        p.close()
+
+
 def test_resident_kernel_spectra_give_the_same_result():
     f, fo, n, k = 6, 5, (10, 12, 9), (3, 4, 2)
     cfg = synth.LayerShape("t", f, fo, n, k, 1.0, 91)
