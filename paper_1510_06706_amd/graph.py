@@ -54,7 +54,17 @@ def edge_order(graph):
 
 class GraphNet:
     """Device-side state of a computation graph: plans per convolution edge, parameters as
-    CUDA tensors, a pool of HIP streams (all at the default priority)."""
+    CUDA tensors, a pool of HIP streams (all at the default priority).
+
+    Rounds run eagerly only.  Recording a round into a HIP graph is deliberately not offered:
+    this executor waits on pooled events that were created and first recorded outside any
+    capture, and joins its side streams (among them the kernel-gradient stream) to the
+    calling stream only through the events of later edges, so a capture would contain waits on
+    uncaptured work and forked streams that are never joined back before the capture ends;
+    recording it that way crashed inside the runtime's end-of-capture call.  A capturable
+    executor needs events created inside the capture, every side stream forked from the
+    capturing stream, and a join of every side stream before the capture ends.  Layered nets
+    (``net.Net.capture_round``) run on one stream and can be recorded."""
 
     def __init__(self, graph, params, mode="auto", device="cuda:0", streams=4):
         import torch
