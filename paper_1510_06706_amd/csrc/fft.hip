@@ -937,10 +937,23 @@ int launch_axis(AxisParams P, int dir, hipStream_t s)
 int forward3d(const Geom& g, const float* src, float2* spec, long maps, int sz, int sy, int sx,
               int oz, int oy, int ox, int tz, int ty, int tx, hipStream_t s)
 {
-    int rc = launch_r2c(src, spec, maps, sz, sy, sx, g.Nz, g.Ny, g.Nx, oz, oy, ox, tz, ty, tx, s);
-    if (rc != ZNN_OK) return rc;
     const long plane = (long)g.Ny * g.Nxh, vol = g.svol();
     if (maps > 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many maps");
+    // equal x and y transform lengths with register transforms: both passes in one launch
+    const bool fused = g.Ny == g.Nx && g.Ny > 1 && tx == 1 && ty == 1 && !tuning().fft_lds_passes && !tuning().fft_no_fused_xy &&
+                       fft_xy_reg_supported(g.Nx) && oy + sy <= g.Ny && ox + sx <= g.Nx;
+    int rc;
+    if (fused) {
+        XYFwd F = {};
+        F.src = src; F.dst = spec;
+        F.planes = maps * sz;
+        F.sz = sz; F.sy = sy; F.sx = sx;
+        F.Nz = g.Nz; F.oz = oz; F.oy = oy; F.ox = ox; F.tz = tz;
+        rc = fft_xy_fwd_reg(F, g.Nx, s);
+    } else {
+        rc = launch_r2c(src, spec, maps, sz, sy, sx, g.Nz, g.Ny, g.Nx, oz, oy, ox, tz, ty, tx, s);
+    }
+    if (rc != ZNN_OK) return rc;
     AxisParams P = {};
     // y: only the sz planes that hold data; rows oy + e*ty, e < sy, are non-zero
     P.in = spec + oz * plane; P.in2 = nullptr; P.out = spec + oz * plane;
@@ -950,7 +963,7 @@ int forward3d(const Geom& g, const float* src, float2* spec, long maps, int sz, 
     P.L = g.Nxh;
     P.Oa = (int)maps; P.Ob = sz; P.Oc = 1;
     P.in_sa = P.out_sa = vol; P.in_sb = P.out_sb = plane * tz; P.in_sc = P.out_sc = 0;
-    if (g.Ny != 1) {
+    if (g.Ny != 1 && !fused) {
         // 2D volumes with few non-zero rows (kernels): the y transform is a pruned DFT
         if (g.Nz == 1 && sy <= kMaxPruned && sy < g.Ny) rc = launch_expand(sy, spec, maps, g.Ny, oy, ty, g.Nxh, vol, s);
         else rc = launch_axis(P, -1, s);
@@ -985,6 +998,17 @@ int inverse3d(const Geom& g, float2* spec, float* dst, long maps, int cz, int cy
     P.Oa = (int)maps; P.Ob = 1; P.Oc = 1;
     P.in_sa = P.out_sa = vol;
     if (g.Nz != 1) { rc = launch_axis(P, +1, s); if (rc != ZNN_OK) return rc; }
+    const float scale = (float)(1.0 / ((double)g.Nz * g.Ny * g.Nx));
+    if (g.Ny == g.Nx && g.Ny > 1 && !tuning().fft_lds_passes && !tuning().fft_no_fused_xy && fft_xy_reg_supported(g.Nx) &&
+        cy + dy <= g.Ny && cx + dx <= g.Nx) {
+        XYInv B = {};
+        B.src = spec; B.dst = dst;
+        B.planes = maps * dz;
+        B.dz = dz; B.dy = dy; B.dx = dx;
+        B.Nz = g.Nz; B.cz = cz; B.cy = cy; B.cx = cx;
+        B.scale = scale;
+        return fft_xy_inv_reg(B, g.Nx, s);
+    }
     P.in = spec + cz * plane; P.out = spec + cz * plane;
     P.N = g.Ny; P.i0 = 0; P.ni = g.Ny; P.o0 = cy; P.no = dy;
     P.in_stride = P.out_stride = g.Nxh;
@@ -992,7 +1016,6 @@ int inverse3d(const Geom& g, float2* spec, float* dst, long maps, int cz, int cy
     P.Oa = (int)maps; P.Ob = dz; P.Oc = 1;
     P.in_sb = P.out_sb = plane;
     if (g.Ny != 1) { rc = launch_axis(P, +1, s); if (rc != ZNN_OK) return rc; }
-    const float scale = (float)(1.0 / ((double)g.Nz * g.Ny * g.Nx));
     return launch_c2r(spec, dst, maps, g.Nz, g.Ny, g.Nx, cz, cy, cx, dz, dy, dx, 1, scale, s);
 }
 
@@ -1097,6 +1120,15 @@ int fft_kernel_spectra(const Geom& g, const Fold& F, const float* w, float2* Wha
         if (pairs * F.taps > 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many kernel planes");
         if (g.Nz == 1)
             return launch_r2c(w, What, pairs, 1, g.ky, g.kx, 1, g.ky, g.Nx, 0, 0, 0, 1, 1, g.spx, s);
+        if (g.Ny == g.Nx && g.Ny > 1 && g.spy == 1 && g.spx == 1 && !tuning().fft_lds_passes && !tuning().fft_no_fused_xy &&
+            fft_xy_reg_supported(g.Nx)) {
+            XYFwd F = {};
+            F.src = w; F.dst = What;
+            F.planes = pairs * g.kz;
+            F.sz = g.kz; F.sy = g.ky; F.sx = g.kx;
+            F.Nz = g.kz; F.oz = 0; F.oy = 0; F.ox = 0; F.tz = 1;
+            return fft_xy_fwd_reg(F, g.Nx, s);
+        }
         int rc = launch_r2c(w, What, pairs, g.kz, g.ky, g.kx, g.kz, g.Ny, g.Nx, 0, 0, 0, 1, g.spy, g.spx, s);
         if (rc != ZNN_OK || g.Ny == 1) return rc;
         const long plane = (long)g.Ny * g.Nxh;

@@ -83,6 +83,7 @@ struct Tuning {
     int  fft_mac_z0;            // ZNN_FFT_MAC_Z0: frequencies per thread of the folded multiply-accumulate / 4
     bool fft_mac_valu;          // ZNN_FFT_MAC_VALU: folded multiply-accumulate on the vector ALUs only
     bool fft_wgrad_plain;       // ZNN_FFT_WGRAD_PLAIN: per-z pruned DFT instead of the radix-4 grouped one
+    bool fft_no_fused_xy;       // ZNN_FFT_NO_FUSED_XY: separate x and y passes even where one launch can take both
     bool fft_lds_passes;        // ZNN_FFT_LDS_PASSES: LDS passes instead of register passes
 };
 const Tuning& tuning();
@@ -179,6 +180,26 @@ struct XRegC2R {
     float scale;
     FastDiv fdy, fdz;
 };
+// x and y passes in one launch for volumes with equal x and y transform lengths N (fft_xy_reg*.hip):
+// a (map, z) plane per workgroup.  forward: planes = maps * sz real planes of sy rows x sx samples, placed
+// at (z * tz + oz, oy, ox); inverse: planes = maps * dz spectrum planes z + cz, cropped to rows [cy, cy+dy)
+// and samples [cx, cx+dx), times `scale`.
+struct XYFwd {
+    const float* src; float2* dst;
+    long planes;
+    int sz, sy, sx;
+    int Nz, oz, oy, ox, tz;
+};
+struct XYInv {
+    const float2* src; float* dst;
+    long planes;
+    int dz, dy, dx;
+    int Nz, cz, cy, cx;
+    float scale;
+};
+bool fft_xy_reg_supported(int N);
+int  fft_xy_fwd_reg(const XYFwd& P, int N, hipStream_t s);
+int  fft_xy_inv_reg(const XYInv& P, int N, hipStream_t s);
 bool fft_x_reg_supported(int N);
 int  fft_x_r2c_reg(const XRegR2C& P, int N, hipStream_t s);
 int  fft_x_c2r_reg(const XRegC2R& P, int N, hipStream_t s);

@@ -87,7 +87,7 @@ def step_of(name: str, what: str) -> str:
         return "F-wgrad y"
     if what == "kernel_spectra":
         return "F-ker"
-    if name.startswith("fft c2r x"):
+    if name.startswith("fft c2r"):
         return "F-wgrad x" if what == "wgrad_memo" or what == "wgrad" else "F-inv"
     if name.startswith("fft axis inverse"):
         return "F-wgrad y" if what in ("wgrad", "wgrad_memo") else "F-inv"

@@ -248,6 +248,40 @@ def test_fft_x_passes_with_register_resident_rows_for_every_extent(N):
         p.close()
 
 
+@pytest.mark.parametrize("N", [16, 18, 20, 24, 30, 32, 36, 40, 48, 50, 54, 60, 64, 72, 80, 90, 96])
+def test_fft_x_and_y_passes_in_one_launch_for_every_extent(N):
+    """Equal x and y transform lengths take both passes in one launch (a plane per workgroup): every
+    length it is instantiated for, with planes that fill the transform and with zero-extended ones
+    (which also shifts the output gradient's embedding and the crops of the inverse)."""
+    print("case", N, flush=True)
+
+    def next_smooth(n):
+        while True:
+            t = n
+            for q in (2, 3, 5):
+                while t % q == 0:
+                    t //= q
+            if t == 1:
+                return n
+            n += 1
+
+    shorter = [m for m in range(N - 1, N - 8, -1) if next_smooth(m) == N]
+    cases = [(N, N)] + ([(shorter[-1], shorter[0])] if shorter else [])
+    for ny, nx in cases:
+        n, k = (8, ny, nx), (3, 2, 4)
+        cfg = synth.LayerShape("t", 3, 2, n, k, 1.0, 600 + N)
+        inp, w, gout = synth.layer_tensors(cfg)
+        p = znn.Plan(3, 2, n, k, "fft")
+        assert p.fft_extents[1:] == (N, N)
+        d_in, d_w, d_g = dev(inp), dev(w), dev(gout)
+        assert rel_err(host(p.fwd(d_in, d_w)), oracle.conv3d_fwd(inp, w)) <= TOL["fft"], (n, "fwd")
+        assert rel_err(host(p.bwd(d_g, d_w)), oracle.conv3d_bwd(gout, w, n)) <= TOL["fft"], (n, "bwd")
+        assert rel_err(host(p.wgrad(d_in, d_g)), oracle.conv3d_wgrad(inp, gout)) <= TOL["fft"], (n, "wgrad")
+        p.set_spectra_layout("folded" if p.spectra_layout == "full" else "full")    # the other kernel transform as well
+        assert rel_err(host(p.fwd(d_in, d_w)), oracle.conv3d_fwd(inp, w)) <= TOL["fft"], (n, "fwd, other layout")
+        p.close()
+
+
 def test_resident_kernel_spectra_give_the_same_result():
     f, fo, n, k = 6, 5, (10, 12, 9), (3, 4, 2)
     cfg = synth.LayerShape("t", f, fo, n, k, 1.0, 91)
