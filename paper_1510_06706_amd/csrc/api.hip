@@ -78,6 +78,7 @@ const Tuning& tuning()
         v.conv_u1 = flag("ZNN_CONV_U1");
         v.conv_no_wl = flag("ZNN_CONV_NO_WL");
         v.conv_no_split = flag("ZNN_CONV_NO_SPLIT");
+        v.conv_no_tail = flag("ZNN_CONV_NO_TAIL");
         if (const char* e = getenv("ZNN_CONV_TILE"))
             if (sscanf(e, "%d,%d,%d,%d", &v.conv_tile[0], &v.conv_tile[1], &v.conv_tile[2], &v.conv_tile[3]) != 4)
                 v.conv_tile[0] = v.conv_tile[1] = v.conv_tile[2] = v.conv_tile[3] = 0;

@@ -13,7 +13,7 @@
 #include <mutex>
 #include <vector>
 
-#include "direct_mfma_impl.h"
+#include "direct_mfma_tail_impl.h"
 
 namespace znn {
 
@@ -58,6 +58,43 @@ k_pack_weights(const float* __restrict__ w, float* __restrict__ wp, int f, int f
 }
 
 // dst = partial[0] + partial[1] + ... in ascending order (input maps split over workgroups).
+// The same for the kernel with an 8-map block behind NJ full tiles (direct_mfma_tail_impl.h): per
+// (chunk, tap) the NJ x 64 operands of the full tiles, then [8 maps][4 input maps].
+__global__ void __launch_bounds__(256)
+k_pack_weights_tail(const float* __restrict__ w, float* __restrict__ wp, int f, int fo, int kz, int ky, int kx,
+                    int backward, int NJ, int nchunk)
+{
+    const int taps = kz * ky * kx;
+    const int WT = NJ * 64 + conv::kTailPacked;
+    const long total = (long)nchunk * taps * WT;
+    const long t = (long)blockIdx.x * 256 + threadIdx.x;
+    if (t >= total) return;
+    const int e = (int)(t % WT);
+    long r = t / WT;
+    const int tap = (int)(r % taps);
+    const int ic = (int)(r / taps);
+    int m, k;
+    if (e < NJ * 64) {
+        m = (e / 64) * 16 + (e & 15);
+        k = ic * 4 + ((e & 63) >> 4);
+    } else {
+        m = NJ * 16 + (e - NJ * 64) / 4;
+        k = ic * 4 + (e & 3);
+    }
+    const int fM = backward ? f : fo, fK = backward ? fo : f;
+    float v = 0.f;
+    if (m < fM && k < fK) {
+        if (!backward) {
+            v = w[((long)m * f + k) * taps + tap];
+        } else {
+            const int c = tap % kx, b = (tap / kx) % ky, a = tap / (kx * ky);
+            const int rt = ((kz - 1 - a) * ky + (ky - 1 - b)) * kx + (kx - 1 - c);
+            v = w[((long)k * f + m) * taps + rt];
+        }
+    }
+    wp[t] = v;
+}
+
 __global__ void __launch_bounds__(256)
 k_conv_reduce(const float* __restrict__ partial, float* __restrict__ dst, long count, int splits)
 {
@@ -85,6 +122,29 @@ int group_width(int kx, int spx)
     return 1;
 }
 
+ConvFn pick_tail_kernel(int U, int nj, int nv, bool wl)
+{
+    switch (U) {
+        case 1: return conv_tail_kernel_u1(nj, nv, wl);
+        case 2: return conv_tail_kernel_u2(nj, nv, wl);
+        case 3: return conv_tail_kernel_u3(nj, nv, wl);
+        case 4: return conv_tail_kernel_u4(nj, nv, wl);
+        case 5: return conv_tail_kernel_u5(nj, nv, wl);
+        case 7: return conv_tail_kernel_u7(nj, nv, wl);
+        case 11: return conv_tail_kernel_u11(nj, nv, wl);
+    }
+    return nullptr;
+}
+
+// The last 1..8 of the output-side maps as an 8-map block instead of a padded 16-row tile: one
+// workgroup must hold all maps, and a lane's byte offset over the chunk's four source maps must fit
+// 32 bits.
+bool tail_applies(int fM, long svol)
+{
+    const int r = fM % 16;
+    return !tuning().conv_no_tail && fM > 16 && fM / 16 <= 7 && r >= 1 && r <= conv::kTailMaps && svol * 16 < (1L << 32);
+}
+
 ConvFn pick_kernel(int U, int nj, int nv, bool wl)
 {
     switch (U) {
@@ -100,9 +160,9 @@ ConvFn pick_kernel(int U, int nj, int nv, bool wl)
 }
 
 // Weights of one chunk in LDS: when they take at most 32 KiB.
-bool weights_in_lds(int taps, int NJ)
+bool weights_in_lds(int taps, int NJ, bool tail)
 {
-    return !tuning().conv_no_wl && (size_t)taps * NJ * 256 <= 32 * 1024;
+    return !tuning().conv_no_wl && (size_t)taps * (NJ * 64 + (tail ? conv::kTailPacked : 0)) * 4 <= 32 * 1024;
 }
 
 struct TileChoice {
@@ -111,6 +171,7 @@ struct TileChoice {
     int Tz, Ty, Tx, HZ, HY, HX, MS;
     int cz, cy, cx;
     bool wl, dbuf;
+    bool tail;          // NJ full tiles and an 8-map block (direct_mfma_tail_impl.h); halo maps interleaved in LDS
     int cps, splits;    // input-map chunks per workgroup and number of such shares
     size_t lds;
 };
@@ -132,15 +193,15 @@ void split_chunks(long blocks, int nchunk, int& cps, int& splits)
 
 // Picks the tile box and the per-wave tile count so that the launch fills the
 // 256 compute units in as few, as full rounds as possible.
-TileChoice search_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, int kx, int spz, int spy, int spx)
+TileChoice search_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, int kx, int spz, int spy, int spx, bool tail)
 {
     TileChoice best = {};
     best.ok = false;
     const int taps = kz * ky * kx;
     if (taps > kMaxTaps) return best;
     const int tiles = (fM + 15) / 16;
-    const int jgroups = (tiles + 7) / 8;
-    const int NJ = (tiles + jgroups - 1) / jgroups;
+    const int jgroups = tail ? 1 : (tiles + 7) / 8;
+    const int NJ = tail ? fM / 16 : (tiles + jgroups - 1) / jgroups;
     double best_cost = 1e300;
     const int nchunk = (fK + 3) / 4;
     // tuning aid: ZNN_CONV_TILE="NV,Tz,Ty,Tx" pins the configuration
@@ -148,7 +209,7 @@ TileChoice search_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, i
     const int nvs[6] = {2, 4, 5, 6, 7, 8};
     for (int ni = 0; ni < 6; ++ni) {
         const int NV = nvs[ni];
-        if (!have_kernel(NJ, NV)) continue;
+        if (tail ? !conv::tail_instance(NJ, NV) : !have_kernel(NJ, NV)) continue;
         if (pin[0] && NV != pin[0]) continue;
         const int cap = 64 * NV;
         for (int Tx = 1; Tx <= dx && Tx <= cap; ++Tx) {
@@ -163,12 +224,13 @@ TileChoice search_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, i
                 const int HZ = Tz + spz * (kz - 1), HY = Ty + spy * (ky - 1), HX = Tx + spx * (kx - 1);
                 long hvol = (long)HZ * HY * HX;
                 long MS = hvol;
-                while (MS % 32 != 16) ++MS;
-                const bool wl = weights_in_lds(taps, NJ);
+                if (tail) MS = (MS + 15) & ~15L;        // whole 64-word spans of 16 voxels x 4 maps
+                else while (MS % 32 != 16) ++MS;
+                const bool wl = weights_in_lds(taps, NJ, tail);
                 // halo buffers (two that take turns if they fit, else one), the loader's table (one
                 // map's box, padded to the workgroup size), the chunk's weights
                 const long MSP = (MS + 255) & ~255L;
-                const size_t wbytes = wl ? (size_t)taps * NJ * 256 : 0;
+                const size_t wbytes = wl ? (size_t)taps * (NJ * 64 + (tail ? conv::kTailPacked : 0)) * 4 : 0;
                 bool dbuf = true;
                 size_t lds = (size_t)(8 * MS + MSP) * 4 + wbytes;
                 if (lds > kConvLdsMax) { dbuf = false; lds = (size_t)(4 * MS + MSP) * 4 + wbytes; }
@@ -184,7 +246,8 @@ TileChoice search_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, i
                 // its waits with (measured on the 2D benchmark layer: 1.4x)
                 const long groups = blocks * splits;
                 const double rounds = (double)((groups + kCUs - 1) / kCUs) * (groups <= kCUs ? 1.4 : 1.0);
-                const double mfma = (double)taps * NJ * NV * 32.0;
+                // an 8-map block costs four short MFMAs per two voxel tiles (about 10 cycles each)
+                const double mfma = (double)taps * (NJ * NV * 32.0 + (tail ? ((NV + 1) / 2) * 40.0 : 0.0));
                 // halo fetch per chunk: hidden behind the taps with two buffers, else one exposed memory latency
                 const double stage = dbuf ? 300.0 + (double)hvol * 4.0 / 256.0 * 2.0 : 1500.0 + (double)hvol * 4.0 / 256.0 * 6.0;
                 const double fixed = 3000.0 + (double)MS / 256.0 * 300.0;      // launch, table, zero fill, epilogue
@@ -200,6 +263,7 @@ TileChoice search_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, i
                     best.cz = cz; best.cy = cy; best.cx = cx;
                     best.wl = wl;
                     best.dbuf = dbuf;
+                    best.tail = tail;
                     best.cps = cps; best.splits = splits;
                     best.lds = lds;
                 }
@@ -211,12 +275,13 @@ TileChoice search_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, i
 
 // The search walks thousands of candidate boxes (a fraction of a millisecond on the host),
 // and every call of a pass asks for the same answer up to three times: remembered per shape.
-TileChoice choose_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, int kx, int spz, int spy, int spx)
+TileChoice choose_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, int kx, int spz, int spy, int spx, long svol)
 {
-    struct Entry { int key[11]; TileChoice choice; };
+    struct Entry { int key[12]; TileChoice choice; };
     static std::mutex lock;
     static std::vector<Entry> memo;
-    const int key[11] = {fM, fK, dz, dy, dx, kz, ky, kx, spz, spy, spx};
+    const bool tail = tail_applies(fM, svol);
+    const int key[12] = {fM, fK, dz, dy, dx, kz, ky, kx, spz, spy, spx, tail ? 1 : 0};
     {
         std::lock_guard<std::mutex> hold(lock);
         for (const Entry& e : memo)
@@ -224,7 +289,8 @@ TileChoice choose_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, i
     }
     Entry e;
     memcpy(e.key, key, sizeof(key));
-    e.choice = search_tile(fM, fK, dz, dy, dx, kz, ky, kx, spz, spy, spx);
+    e.choice = search_tile(fM, fK, dz, dy, dx, kz, ky, kx, spz, spy, spx, tail);
+    if (tail && !e.choice.ok) e.choice = search_tile(fM, fK, dz, dy, dx, kz, ky, kx, spz, spy, spx, false);
     std::lock_guard<std::mutex> hold(lock);
     if (memo.size() >= 256) memo.erase(memo.begin());
     memo.push_back(e);
@@ -238,7 +304,14 @@ size_t partial_bytes(const TileChoice& c, int fM, long dvol)
 
 size_t packed_bytes(const TileChoice& c, int fK, int taps)
 {
-    return align256((size_t)c.jgroups * ((fK + 3) / 4) * taps * c.NJ * 64 * sizeof(float));
+    const size_t per_tap = (size_t)c.NJ * 64 + (c.tail ? conv::kTailPacked : 0);
+    return align256((size_t)c.jgroups * ((fK + 3) / 4) * taps * per_tap * sizeof(float));
+}
+
+TileChoice choose_for(const Geom& g, bool backward)
+{
+    return backward ? choose_tile(g.f, g.fo, g.nz, g.ny, g.nx, g.kz, g.ky, g.kx, g.spz, g.spy, g.spx, g.ovol())
+                    : choose_tile(g.fo, g.f, g.oz, g.oy, g.ox, g.kz, g.ky, g.kx, g.spz, g.spy, g.spx, g.nvol());
 }
 
 }  // namespace
@@ -246,8 +319,7 @@ size_t packed_bytes(const TileChoice& c, int fK, int taps)
 // The tiled path takes every shape whose halo box fits LDS; otherwise the caller falls back.
 bool mfma_conv_supported(const Geom& g, bool backward)
 {
-    const TileChoice c = backward ? choose_tile(g.f, g.fo, g.nz, g.ny, g.nx, g.kz, g.ky, g.kx, g.spz, g.spy, g.spx)
-                                  : choose_tile(g.fo, g.f, g.oz, g.oy, g.ox, g.kz, g.ky, g.kx, g.spz, g.spy, g.spx);
+    const TileChoice c = choose_for(g, backward);
     // the halo loader addresses a source map with a signed 32-bit byte offset
     const long svol = backward ? g.ovol() : g.nvol();
     return c.ok && svol < (1L << 29);
@@ -255,8 +327,7 @@ bool mfma_conv_supported(const Geom& g, bool backward)
 
 size_t mfma_conv_workspace(const Geom& g, bool backward)
 {
-    const TileChoice c = backward ? choose_tile(g.f, g.fo, g.nz, g.ny, g.nx, g.kz, g.ky, g.kx, g.spz, g.spy, g.spx)
-                                  : choose_tile(g.fo, g.f, g.oz, g.oy, g.ox, g.kz, g.ky, g.kx, g.spz, g.spy, g.spx);
+    const TileChoice c = choose_for(g, backward);
     if (!c.ok) return 0;
     return packed_bytes(c, backward ? g.fo : g.f, (int)g.kvol()) +
            partial_bytes(c, backward ? g.f : g.fo, backward ? g.nvol() : g.ovol());
@@ -280,7 +351,7 @@ int mfma_conv(const Geom& g, bool backward, const float* src, const float* w, fl
         P.pz = g.spz * (g.kz - 1); P.py = g.spy * (g.ky - 1); P.px = g.spx * (g.kx - 1);
         P.dz = g.nz; P.dy = g.ny; P.dx = g.nx;
     }
-    const TileChoice c = choose_tile(P.fM, P.fK, P.dz, P.dy, P.dx, g.kz, g.ky, g.kx, g.spz, g.spy, g.spx);
+    const TileChoice c = choose_for(g, backward);
     if (!c.ok) return fail(ZNN_EUNSUPPORTED, "no tile configuration fits this shape");
     P.Tz = c.Tz; P.Ty = c.Ty; P.Tx = c.Tx;
     P.HZ = c.HZ; P.HY = c.HY; P.HX = c.HX; P.MS = c.MS;
@@ -290,20 +361,26 @@ int mfma_conv(const Geom& g, bool backward, const float* src, const float* w, fl
     P.cps = c.cps;
     P.dbuf = c.dbuf ? 1 : 0;
     if (log_enabled())
-        fprintf(stderr, "[znn] conv mfma (%s): NJ=%d jgroups=%d NV=%d U=%d tile=%dx%dx%d halo=%dx%dx%d blocks=%d splits=%d lds=%zu buffers=%d\n",
-                backward ? "bwd" : "fwd", c.NJ, c.jgroups, c.NV, group_width(g.kx, g.spx), c.Tz, c.Ty, c.Tx, c.HZ, c.HY, c.HX,
+        fprintf(stderr, "[znn] conv mfma (%s): NJ=%d%s jgroups=%d NV=%d U=%d tile=%dx%dx%d halo=%dx%dx%d blocks=%d splits=%d lds=%zu buffers=%d\n",
+                backward ? "bwd" : "fwd", c.NJ, c.tail ? "+8" : "", c.jgroups, c.NV, group_width(g.kx, g.spx), c.Tz, c.Ty, c.Tx, c.HZ, c.HY, c.HX,
                 c.cz * c.cy * c.cx, c.splits, c.lds, c.dbuf ? 2 : 1);
     const int taps = (int)g.kvol();
     float* wp = (float*)ws;
     P.wp = wp;
     P.partial = (float*)((char*)ws + packed_bytes(c, P.fK, taps));
-    const long total = (long)c.jgroups * P.nchunk * taps * c.NJ * 64;
-    ZNN_LAUNCH("weight packing", s, k_pack_weights, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
-               w, wp, g.f, g.fo, g.kz, g.ky, g.kx, backward ? 1 : 0, c.NJ, c.jgroups, P.nchunk);
+    if (c.tail) {
+        const long total = (long)P.nchunk * taps * (c.NJ * 64 + conv::kTailPacked);
+        ZNN_LAUNCH("weight packing", s, k_pack_weights_tail, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
+                   w, wp, g.f, g.fo, g.kz, g.ky, g.kx, backward ? 1 : 0, c.NJ, P.nchunk);
+    } else {
+        const long total = (long)c.jgroups * P.nchunk * taps * c.NJ * 64;
+        ZNN_LAUNCH("weight packing", s, k_pack_weights, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
+                   w, wp, g.f, g.fo, g.kz, g.ky, g.kx, backward ? 1 : 0, c.NJ, c.jgroups, P.nchunk);
+    }
     int rc = check_launch("weight packing");
     if (rc != ZNN_OK) return rc;
     const int U = group_width(g.kx, g.spx);
-    ConvFn fn = pick_kernel(U, c.NJ, c.NV, c.wl);
+    ConvFn fn = c.tail ? pick_tail_kernel(U, c.NJ, c.NV, c.wl) : pick_kernel(U, c.NJ, c.NV, c.wl);
     if (!fn) return fail(ZNN_EUNSUPPORTED, "no kernel instance for tile %dx%d", c.NJ, c.NV);
     const long blocks = (long)c.cz * c.cy * c.cx;
     if (blocks >= 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many tiles for one launch");

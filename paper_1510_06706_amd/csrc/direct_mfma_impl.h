@@ -32,6 +32,10 @@ namespace conv {
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(1))) const void* global_cptr;
 typedef __attribute__((address_space(3))) void* lds_ptr;
+// Operand addresses in LDS are kept as 32-bit LDS pointers that already include the buffer's base: an
+// operand read is then one ds_read with an immediate offset, and a tap group costs one vector addition
+// per operand (an index added to the base at every use costs a second one).
+typedef __attribute__((address_space(3))) const float* lds_floatp;
 
 struct ConvTile {
     const float* src;   // K-side images [fK][sz][sy][sx]
@@ -83,14 +87,14 @@ struct GroupWalk {
 // MFMAs (the scheduler would otherwise put every load right in front of its first use).
 template <int NJ, int NV>
 __device__ __forceinline__ void tap_mfmas(floatx4 (&acc)[NJ][NV], const float (&a)[NJ], const float (&b)[NV],
-                                          float (&bn)[NV], const float* halo, const int (&vb)[NV], int imm)
+                                          float (&bn)[NV], const lds_floatp (&vb)[NV], int imm)
 {
 #pragma unroll
     for (int jt = 0; jt < NJ; ++jt) {
 #pragma unroll
         for (int nv = 0; nv < NV; ++nv) acc[jt][nv] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[jt], b[nv], acc[jt][nv], 0, 0, 0);
 #pragma unroll
-        for (int nv = jt * NV / NJ; nv < (jt + 1) * NV / NJ; ++nv) bn[nv] = halo[vb[nv] + imm];
+        for (int nv = jt * NV / NJ; nv < (jt + 1) * NV / NJ; ++nv) bn[nv] = vb[nv][imm];
         __builtin_amdgcn_sched_barrier(0);
     }
 }
@@ -98,11 +102,11 @@ __device__ __forceinline__ void tap_mfmas(floatx4 (&acc)[NJ][NV], const float (&
 // The U taps of one group.  PAR: which operand set holds the group's first tap.  On entry
 // that set is loaded (or in flight); on exit the other-parity set of the next group's first
 // tap is in flight and vb / wg point at the next group.
-//   vb[nv] : halo index of the group's lowest-address tap for voxel tile nv (VGPR)
+//   vb[nv] : LDS address of the group's lowest-address tap for voxel tile nv (VGPR)
 //   wg     : the group's packed weights (uniform pointer), wlo: the same as an LDS index when WL
 template <int NJ, int NV, bool WL, int U, int PAR>
 __device__ __forceinline__ void group_step(floatx4 (&acc)[NJ][NV], float (&a0)[NJ], float (&b0)[NV], float (&a1)[NJ],
-                                           float (&b1)[NV], int (&vb)[NV], const int (&voff)[NV], const float* halo,
+                                           float (&b1)[NV], lds_floatp (&vb)[NV], const lds_floatp (&voff)[NV],
                                            const float*& wg, const float* wl, int& wlo, int lane, int o_next,
                                            bool advance)
 {
@@ -118,7 +122,7 @@ __device__ __forceinline__ void group_step(floatx4 (&acc)[NJ][NV], float (&a0)[N
             for (int jt = 0; jt < NJ; ++jt)
                 an[jt] = WL ? wl[wlo + ((u + 1) * NJ + jt) * 64] : wg[((u + 1) * NJ + jt) * 64 + lane];
             __builtin_amdgcn_sched_barrier(0);
-            tap_mfmas<NJ, NV>(acc, ac, bc, bn, halo, vb, U - 2 - u);
+            tap_mfmas<NJ, NV>(acc, ac, bc, bn, vb, U - 2 - u);
         } else {
             // first tap of the next group: new bases (the only vector arithmetic of the group)
             if (advance) {
@@ -130,7 +134,7 @@ __device__ __forceinline__ void group_step(floatx4 (&acc)[NJ][NV], float (&a0)[N
 #pragma unroll
             for (int jt = 0; jt < NJ; ++jt) an[jt] = WL ? wl[wlo + jt * 64] : wg[jt * 64 + lane];
             __builtin_amdgcn_sched_barrier(0);
-            tap_mfmas<NJ, NV>(acc, ac, bc, bn, halo, vb, U - 1);
+            tap_mfmas<NJ, NV>(acc, ac, bc, bn, vb, U - 1);
         }
     }
 }
@@ -160,13 +164,13 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma(ConvTile P)
     const int z0 = bzi * P.Tz, y0 = byi * P.Ty, x0 = bxi * P.Tx;
     const int Ttot = P.Tz * P.Ty * P.Tx;
 
-    int voff[NV];
+    lds_floatp voff[NV];
 #pragma unroll
     for (int nv = 0; nv < NV; ++nv) {
         int t = (wave * NV + nv) * 16 + col;
         if (t >= Ttot) t = 0;
         const int tx = t % P.Tx, ty = (t / P.Tx) % P.Ty, tz = t / (P.Tx * P.Ty);
-        voff[nv] = grp * P.MS + (tz * P.HY + ty) * P.HX + tx;
+        voff[nv] = (lds_floatp)lds + (grp * P.MS + (tz * P.HY + ty) * P.HX + tx);
     }
 
     floatx4 acc[NJ][NV];
@@ -243,13 +247,11 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma(ConvTile P)
             __syncthreads();
         }
         if (P.dbuf && ic + 1 < ic1) issue_chunk(ic + 1, lds + (cur ^ 1) * 4 * P.MS);
-        const float* halo = lds;            // the buffer's offset rides in the scalar tap offset
-
         float a0[NJ], b0[NV], a1[NJ], b1[NV];
-        int vb[NV];
+        lds_floatp vb[NV];
         GroupWalk<U> walk;
         walk.start(P);
-        walk.o += cur * 4 * P.MS;
+        walk.o += cur * 4 * P.MS;           // the buffer's offset rides in the scalar tap offset
         const float* wg = wq;
         int wlo = lane;
 #pragma unroll
@@ -257,21 +259,21 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma(ConvTile P)
 #pragma unroll
         for (int jt = 0; jt < NJ; ++jt) a0[jt] = WL ? wl[wlo + jt * 64] : wg[jt * 64 + lane];
 #pragma unroll
-        for (int nv = 0; nv < NV; ++nv) b0[nv] = halo[vb[nv] + (U - 1)];
+        for (int nv = 0; nv < NV; ++nv) b0[nv] = vb[nv][U - 1];
 
         // groups are taken two at a time so that the operand-set parity at the top of the
         // loop body is a compile-time constant for odd U as well
         int g = 0;
         for (; g + 2 <= ngroups; g += 2) {
             walk.o += walk.step(P, groups_per_row);
-            group_step<NJ, NV, WL, U, 0>(acc, a0, b0, a1, b1, vb, voff, halo, wg, wl, wlo, lane, walk.o, true);
+            group_step<NJ, NV, WL, U, 0>(acc, a0, b0, a1, b1, vb, voff, wg, wl, wlo, lane, walk.o, true);
             const bool more = g + 2 < ngroups;
             walk.o += more ? walk.step(P, groups_per_row) : 0;
-            group_step<NJ, NV, WL, U, (U & 1)>(acc, a0, b0, a1, b1, vb, voff, halo, wg, wl, wlo, lane, walk.o, more);
+            group_step<NJ, NV, WL, U, (U & 1)>(acc, a0, b0, a1, b1, vb, voff, wg, wl, wlo, lane, walk.o, more);
             asm volatile("" ::: "memory");      // requests do not sink into the next iteration
         }
         if (g < ngroups)        // odd number of groups: the last one (its prefetch re-reads itself)
-            group_step<NJ, NV, WL, U, 0>(acc, a0, b0, a1, b1, vb, voff, halo, wg, wl, wlo, lane, walk.o, false);
+            group_step<NJ, NV, WL, U, 0>(acc, a0, b0, a1, b1, vb, voff, wg, wl, wlo, lane, walk.o, false);
         wq += (long)taps * NJ * 64;
     }
 

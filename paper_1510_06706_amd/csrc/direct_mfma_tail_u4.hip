@@ -1,0 +1,9 @@
+// Direct-method kernels with an 8-map block behind the full tiles that walk the taps along x in
+// groups of 4 (direct_mfma_tail_impl.h).
+#include "direct_mfma_tail_impl.h"
+
+namespace znn {
+
+conv::ConvFn conv_tail_kernel_u4(int nj, int nv, bool wl) { return conv::pick_tail_kernel<4>(nj, nv, wl); }
+
+}  // namespace znn

@@ -75,6 +75,7 @@ struct Tuning {
     bool conv_u1;               // ZNN_CONV_U1: walk the taps of the direct convolution one at a time
     bool conv_no_wl;            // ZNN_CONV_NO_WL: never stage a chunk's weights in LDS
     bool conv_no_split;         // ZNN_CONV_NO_SPLIT: never split the input maps over workgroups
+    bool conv_no_tail;          // ZNN_CONV_NO_TAIL: pad the last maps to a 16-row tile instead of an 8-map block
     int  conv_tile[4];          // ZNN_CONV_TILE="NV,Tz,Ty,Tx": pin the output box (0 = not pinned)
     int  wgrad_halves;          // ZNN_WGRAD_HALVES: 1 = four waves, 2 = eight waves per workgroup
     int  wgrad_maxnj;           // ZNN_WGRAD_MAXNJ: most 16-map tiles per workgroup

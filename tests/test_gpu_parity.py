@@ -89,6 +89,20 @@ DIRECT_TAPS = [
     (40, 3, (20, 20, 20), (3, 3, 3), (4, 4, 4)),
     (21, 24, (26, 26, 26), (3, 3, 3), (4, 4, 4)),
     (18, 40, (30, 30, 30), (5, 5, 5), (1, 1, 1)),
+    # output-side map counts of the form 16 q + r, 1 <= r <= 8, in one or both directions: the last r
+    # maps run as an 8-map block beside q full tiles (q = 1 .. 7), for every tap-group width, with a
+    # ragged last chunk of input maps, split input maps, sparse taps and a 2D layer
+    (10, 24, (9, 9, 20), (2, 2, 7), (1, 1, 1)),
+    (22, 20, (8, 9, 16), (3, 1, 6), (1, 1, 1)),
+    (19, 36, (6, 7, 22), (2, 1, 10), (1, 1, 1)),
+    (24, 17, (5, 6, 24), (1, 2, 11), (1, 1, 1)),
+    (36, 40, (7, 8, 19), (1, 3, 9), (1, 1, 1)),
+    (20, 56, (10, 10, 12), (3, 3, 2), (1, 1, 1)),
+    (88, 24, (1, 40, 44), (1, 5, 4), (1, 1, 1)),
+    (120, 72, (6, 10, 12), (3, 3, 3), (1, 1, 1)),
+    (104, 97, (5, 9, 9), (2, 2, 2), (1, 1, 1)),
+    (23, 21, (14, 14, 14), (3, 3, 3), (2, 2, 2)),
+    (33, 24, (6, 6, 10), (2, 2, 2), (1, 1, 1)),
 ]
 
 
