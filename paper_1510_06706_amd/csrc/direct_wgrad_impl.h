@@ -19,6 +19,12 @@ typedef __attribute__((address_space(3))) void* lds_ptr;
 // landing in one buffer do not alias reads of the other and lets them overlap.
 constexpr int kBufFloats = 18432;                 // 72 KiB each
 
+// Spans of 256 floats of a tile region that one wave of the fast loader may have to fetch (one offset
+// register each): either region can take nearly the whole buffer (72 spans), dealt over the workgroup's
+// waves.  Eight-wave kernels with at most three map tiles keep the five that their tiles have needed so
+// far (the longer unrolled loader costs them 3 %).
+constexpr int max_spans(int waves, int nj) { return waves >= 8 ? (nj <= 3 ? 5 : 9) : 18; }
+
 struct WgradTile {
     const float* in; const float* gout; float* partial;
     int f, fo;
@@ -41,20 +47,20 @@ struct WgradTile {
 
 // The MFMAs of this wave's share of one staged tile.  A step covers 8 consecutive voxels:
 // lane group g (= lane/16) reads the voxel pair (2g, 2g+1) of every operand with one
-// two-dword LDS read and feeds two MFMAs from it.  The wave takes steps kp, kp+4, ... < k1.
+// two-dword LDS read and feeds two MFMAs from it.  The wave takes steps kp, kp+KW, ... < k1.
 // Two register sets take turns, so the LDS reads of the next step are queued before the
 // MFMAs of the current one and only waited for after them; the code is kept free of
 // branches around loads and MFMAs (a step past the end re-reads the last one, NTA is the
 // compile-time number of column tiles that hold real columns) because the compiler can
 // only count outstanding loads exactly in straight-line code.  NTA < 0: the number of
 // live tiles is the run-time value ntw (any ragged column group; slower).
-template <int NJ, int NT, int NTA>
+template <int NJ, int NT, int NTA, int KW>
 __device__ __forceinline__ void wgrad_steps(floatx4 (&acc)[NJ][NT], const float* buf, const int (&aoff)[NJ],
                                             const int (&boff)[NT], int kp, int k1, int grp, FastDiv dTX, int TX,
                                             int TXH, int ntw)
 {
     if (kp >= k1) return;
-    const int klast = kp + ((k1 - 1 - kp) & ~3);
+    const int klast = kp + ((k1 - 1 - kp) / KW) * KW;
     auto load_step = [&](int k, float2 (&av)[NJ], float2 (&bv)[NT]) {
         const int e = 8 * k + 2 * grp;
         const int r = (int)fdiv((unsigned)e, dTX), x = e - r * TX;
@@ -86,24 +92,31 @@ __device__ __forceinline__ void wgrad_steps(floatx4 (&acc)[NJ][NT], const float*
     float2 a0[NJ], b0[NT], a1[NJ], b1[NT];
     load_step(kp, a0, b0);
     for (;;) {
-        load_step(min(kp + 4, klast), a1, b1);
+        load_step(min(kp + KW, klast), a1, b1);
         mfma_step(a0, b0);
-        if (kp + 4 >= k1) break;
-        load_step(min(kp + 8, klast), a0, b0);
+        if (kp + KW >= k1) break;
+        load_step(min(kp + 2 * KW, klast), a0, b0);
         mfma_step(a1, b1);
-        if (kp + 8 >= k1) break;
-        kp += 8;
+        if (kp + 2 * KW >= k1) break;
+        kp += 2 * KW;
     }
 }
 
-// NH = 1: four waves share every column tile and split the voxel steps four ways.
-// NH = 2: eight waves; waves 0-3 own the first NT column tiles of the group, waves 4-7 the
-// next NT, and each half splits the voxel steps four ways.  Two waves per SIMD: while one
-// waits for its global->LDS loads to be queued the other keeps the matrix cores busy.
-template <int NJ, int NT, int NH>
-__global__ void __launch_bounds__(256 * NH) k_wgrad_mfma(WgradTile P)
+// The NG * KW waves of a workgroup form NG sets of KW waves: set h owns the column tiles
+// [h * NT, (h + 1) * NT) of the workgroup's column group, and the KW waves of a set split the voxel
+// steps of every staged tile (their accumulators are added at the end).
+//   NG = 1, KW = 4   four waves share every column tile (few columns in all).
+//   NG = 2, KW = 4   eight waves, two per SIMD: while one waits for its global->LDS loads to be queued
+//                    the other keeps the matrix cores busy.
+//   NG = 4, KW = 1   four waves with their own columns each: the workgroup covers four times the
+//                    columns with the same accumulator budget per wave, so every staged gout voxel
+//                    feeds four times the MFMAs (layers with many columns, where the fetch of the
+//                    tiles would otherwise take as long as their MFMAs).
+template <int NJ, int NT, int NG, int KW>
+__global__ void __launch_bounds__(64 * NG * KW) k_wgrad_mfma(WgradTile P)
 {
-    constexpr int NW = 4 * NH;
+    constexpr int NH = NG;
+    constexpr int NW = NG * KW;
     __shared__ __attribute__((aligned(16))) float bufA[kBufFloats];
     __shared__ __attribute__((aligned(16))) float bufB[kBufFloats];
     // The tile buffers are filled by global_load_lds only, which the optimizer does not
@@ -116,7 +129,7 @@ __global__ void __launch_bounds__(256 * NH) k_wgrad_mfma(WgradTile P)
     // the wave index is the same in all 64 lanes: telling the compiler so keeps everything
     // derived from it (loop counters, tile predicates) in scalar registers and branches
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int half = wave >> 2, kw = wave & 3;
+    const int half = wave / KW, kw = wave % KW;
     const int col = lane & 15, grp = lane >> 4;
     const int s = blockIdx.x, ab = blockIdx.y;
     const int a = ab / P.ky, b = ab % P.ky;
@@ -185,8 +198,14 @@ __global__ void __launch_bounds__(256 * NH) k_wgrad_mfma(WgradTile P)
     // uniform (scalar registers), lanes outside the images are masked off the load, and only
     // tiles that have such lanes store zeros for them.  (Vector instructions issued here hold
     // up the other waves' MFMAs on the same SIMD.)
+    // Lanes of a tile that lie outside the images hold zeros: the buffers are zeroed once and such lanes are
+    // never loaded.  A lane that was inside for the tile this buffer held before and is outside now (tiles
+    // behind the last voxel row; the last, shorter x-segment of a row) has to be zeroed by hand: `zero_pass`
+    // does only that, BEFORE the tile's loads are queued, so that the LDS stores never wait for a load that
+    // is still in flight (a store queued behind a load into the same buffer would wait for it to land, one
+    // full memory latency per map).
     auto issue_part = [&](float* dst, int stride, const float* base, long mapvol, int nm, int width, int total,
-                          FastDiv dw, int rho0, int xg0, int xlim, bool is_in, auto WT) {
+                          FastDiv dw, int rho0, int xg0, int xlim, bool is_in, bool zero_pass, auto WT) __attribute__((always_inline)) {
         constexpr int W = decltype(WT)::value;
         for (int k = 0; k * 64 * W < total; ++k) {
             const int e = k * 64 * W + lane * W;
@@ -194,6 +213,18 @@ __global__ void __launch_bounds__(256 * NH) k_wgrad_mfma(WgradTile P)
             const int rho = rho0 + r, gx = xg0 + x;
             const bool inside = e < total;
             const bool ok = inside && rho < rows && gx < xlim;
+            if (zero_pass) {
+                const bool fix = inside && !ok;
+                if (__builtin_amdgcn_ballot_w64(fix) == 0) continue;       // wave-uniform
+                for (int m = wave; m < nm; m += NW) {
+                    float* row = dst + m * stride + k * 64 * W;             // uniform
+                    if (fix) {
+#pragma unroll
+                        for (int q = 0; q < W; ++q) row[lane * W + q] = 0.f;
+                    }
+                }
+                continue;
+            }
             unsigned voff;
             if (is_in) {
                 const int z = (int)fdiv((unsigned)rho, P.dOY), y = rho - z * P.oy;
@@ -201,18 +232,12 @@ __global__ void __launch_bounds__(256 * NH) k_wgrad_mfma(WgradTile P)
             } else {
                 voff = (unsigned)(rho * P.ox + gx) * 4u;
             }
-            const bool fix = inside && !ok;
-            const bool anyfix = __builtin_amdgcn_ballot_w64(fix) != 0;      // wave-uniform
             for (int m = wave; m < nm; m += NW) {
                 const char* mb = reinterpret_cast<const char*>(base + (long)m * mapvol);   // uniform
                 float* row = dst + m * stride + k * 64 * W;                                 // uniform
                 if (ok) {
                     if constexpr (W == 4) __builtin_amdgcn_global_load_lds((global_cptr)(mb + voff), (lds_ptr)row, 16, 0, 0);
                     else __builtin_amdgcn_global_load_lds((global_cptr)(mb + voff), (lds_ptr)row, 4, 0, 0);
-                }
-                if (anyfix && fix) {
-#pragma unroll
-                    for (int q = 0; q < W; ++q) row[lane * W + q] = 0.f;
                 }
             }
         }
@@ -223,9 +248,9 @@ __global__ void __launch_bounds__(256 * NH) k_wgrad_mfma(WgradTile P)
     // which voxel a lane's four floats belong to is the same for every tile, so the lane's byte offset
     // from the tile's origin and its validity are worked out once, here, and a tile costs this wave a
     // handful of loads with no vector arithmetic at all.  Spans are dealt to the waves round-robin.
-    constexpr int kMaxSpans = 5;
+    constexpr int kMaxSpans = max_spans(NW, NJ);
     unsigned fg_off[kMaxSpans], fi_off[kMaxSpans];
-    bool fg_ok[kMaxSpans], fi_ok[kMaxSpans];
+    unsigned fg_ok = 0, fi_ok = 0;          // bit q: span q of this wave holds data for this lane
     const int nspan_g = (mreal * P.GS + 255) >> 8, nspan_i = (nmaps * P.IS + 255) >> 8;
     if (P.fast) {
 #pragma unroll
@@ -234,19 +259,19 @@ __global__ void __launch_bounds__(256 * NH) k_wgrad_mfma(WgradTile P)
             {
                 const int m = (int)fdiv((unsigned)L, P.dGS), e = L - m * P.GS;
                 const int r = (int)fdiv((unsigned)e, P.dTX), x = e - r * P.TX;
-                fg_ok[q] = m < mreal && e < RT && x < P.ox;
+                fg_ok |= (m < mreal && e < RT && x < P.ox ? 1u : 0u) << q;
                 fg_off[q] = (unsigned)(m * (int)oplane + r * P.ox + x) * 4u;
             }
             {
                 const int m = (int)fdiv((unsigned)L, P.dIS), e = L - m * P.IS;
                 const int r = (int)fdiv((unsigned)e, P.dTXH), x = e - r * TXH;
                 const int ix = (P.kx - 1 - cmax) * P.spx + x;
-                fi_ok[q] = m < nmaps && e < RTH && ix < P.nx;
+                fi_ok |= (m < nmaps && e < RTH && ix < P.nx ? 1u : 0u) << q;
                 fi_off[q] = (unsigned)(m * (int)ivol + r * P.nx + ix) * 4u;
             }
         }
     }
-    auto issue_tile_fast = [&](int tile, float* buf) {
+    auto issue_tile_fast = [&](int tile, float* buf) __attribute__((always_inline)) {
         const int rho0 = tile * P.R;                                    // XT == 1
         const int z = (int)fdiv((unsigned)rho0, P.dOY), y = rho0 - z * P.oy;
         const char* gb = reinterpret_cast<const char*>(P.gout + (long)(jg * NJ * 16) * oplane + (long)rho0 * P.ox);
@@ -255,29 +280,35 @@ __global__ void __launch_bounds__(256 * NH) k_wgrad_mfma(WgradTile P)
 #pragma unroll
         for (int q = 0; q < kMaxSpans; ++q) {
             const int sp = wave + q * NW;                               // uniform
-            if (sp < nspan_g && fg_ok[q])
+            if (sp < nspan_g && (fg_ok >> q & 1u))
                 __builtin_amdgcn_global_load_lds((global_cptr)(gb + fg_off[q]), (lds_ptr)(buf + sp * 256), 16, 0, 0);
         }
 #pragma unroll
         for (int q = 0; q < kMaxSpans; ++q) {
             const int sp = wave + q * NW;
-            if (sp < nspan_i && fi_ok[q])
+            if (sp < nspan_i && (fi_ok >> q & 1u))
                 __builtin_amdgcn_global_load_lds((global_cptr)(ib + fi_off[q]), (lds_ptr)(buf + itoff + sp * 256), 16, 0, 0);
         }
     };
-    auto issue_tile = [&](int tile, float* buf) {
+    auto issue_tile = [&](int tile, float* buf) __attribute__((always_inline)) {
         if (P.fast) { issue_tile_fast(tile, buf); return; }
         const int xt = tile % P.XT, rt = tile / P.XT;
         const int rho0 = rt * P.R, xs0 = xt * P.TX;
         const int xin0 = xs0 + (P.kx - 1 - cmax) * P.spx;
         const float* gbase = P.gout + (long)(jg * NJ * 16) * oplane;
         const float* ibase = P.in + (long)imin * ivol;
-        if (P.vec4) {
-            issue_part(buf, P.GS, gbase, oplane, mreal, P.TX, RT, P.dTX, rho0, xs0, P.ox, false, std::integral_constant<int, 4>{});
-            issue_part(buf + itoff, P.IS, ibase, ivol, nmaps, TXH, RTH, P.dTXH, rho0, xin0, P.nx, true, std::integral_constant<int, 4>{});
-        } else {
-            issue_part(buf, P.GS, gbase, oplane, mreal, P.TX, RT, P.dTX, rho0, xs0, P.ox, false, std::integral_constant<int, 1>{});
-            issue_part(buf + itoff, P.IS, ibase, ivol, nmaps, TXH, RTH, P.dTXH, rho0, xin0, P.nx, true, std::integral_constant<int, 1>{});
+        // which lanes are inside the images is the same for every tile except those behind the last voxel row
+        // and the last x-segment of a row when there are several: only those tiles need the zeroing pass
+        const bool zero_first = rho0 + P.R > rows || (P.XT > 1 && xt == P.XT - 1);
+        for (int pass = zero_first ? 0 : 1; pass < 2; ++pass) {
+            const bool zp = pass == 0;
+            if (P.vec4) {
+                issue_part(buf, P.GS, gbase, oplane, mreal, P.TX, RT, P.dTX, rho0, xs0, P.ox, false, zp, std::integral_constant<int, 4>{});
+                issue_part(buf + itoff, P.IS, ibase, ivol, nmaps, TXH, RTH, P.dTXH, rho0, xin0, P.nx, true, zp, std::integral_constant<int, 4>{});
+            } else {
+                issue_part(buf, P.GS, gbase, oplane, mreal, P.TX, RT, P.dTX, rho0, xs0, P.ox, false, zp, std::integral_constant<int, 1>{});
+                issue_part(buf + itoff, P.IS, ibase, ivol, nmaps, TXH, RTH, P.dTXH, rho0, xin0, P.nx, true, zp, std::integral_constant<int, 1>{});
+            }
         }
     };
 
@@ -286,7 +317,7 @@ __global__ void __launch_bounds__(256 * NH) k_wgrad_mfma(WgradTile P)
     // choosing per tile would merge the variants' register assignments after every tile, which
     // costs a copy of every accumulator (vector moves that hold up the matrix pipeline).
     // Two tiles per trip so that each copy of the code names its buffers statically.
-    auto tile_loop = [&](auto NTA_TAG) {
+    auto tile_loop = [&](auto NTA_TAG) __attribute__((always_inline)) {
         constexpr int NTA = decltype(NTA_TAG)::value;
         int tile = s * P.tps;
         if (tile < t_end) issue_tile(tile, bufA);
@@ -294,13 +325,13 @@ __global__ void __launch_bounds__(256 * NH) k_wgrad_mfma(WgradTile P)
             __builtin_amdgcn_s_waitcnt(0);     // this wave's loads have landed
             __syncthreads();                   // everyone's have, and nobody still reads bufB
             if (tile + 1 < t_end) issue_tile(tile + 1, bufB);
-            wgrad_steps<NJ, NT, NTA>(acc, bufA, aoff, boff, kw, nkp, grp, P.dTX, P.TX, TXH, ntw);
+            wgrad_steps<NJ, NT, NTA, KW>(acc, bufA, aoff, boff, kw, nkp, grp, P.dTX, P.TX, TXH, ntw);
             ++tile;
             if (tile >= t_end) break;
             __builtin_amdgcn_s_waitcnt(0);
             __syncthreads();
             if (tile + 1 < t_end) issue_tile(tile + 1, bufA);
-            wgrad_steps<NJ, NT, NTA>(acc, bufB, aoff, boff, kw, nkp, grp, P.dTX, P.TX, TXH, ntw);
+            wgrad_steps<NJ, NT, NTA, KW>(acc, bufB, aoff, boff, kw, nkp, grp, P.dTX, P.TX, TXH, ntw);
             ++tile;
         }
     };
@@ -311,9 +342,9 @@ __global__ void __launch_bounds__(256 * NH) k_wgrad_mfma(WgradTile P)
     else
         tile_loop(std::integral_constant<int, -1>{});
 
-    // add the accumulators of the four waves of each half in the order 0 + 1 + 2 + 3
+    // add the accumulators of the KW waves of each set in the order 0 + 1 + 2 + ...
     floatx4* red = reinterpret_cast<floatx4*>(bufA) + half * (NJ * NT * 64);
-    for (int w = 1; w < 4; ++w) {
+    for (int w = 1; w < KW; ++w) {
         __syncthreads();
         if (kw == w) {
 #pragma unroll
@@ -350,46 +381,46 @@ constexpr int kMaxTiles = 40;   // accumulator tiles per wave (4 registers each)
 
 // Per-wave tile budget: 40 tiles with four waves (one per SIMD), 24 with eight (two per
 // SIMD share the register file).
-template <int NJ, int NT, int NH> WgradFn inst()
+template <int NJ, int NT, int NG, int KW> WgradFn inst()
 {
-    if constexpr (NJ * NT <= (NH == 1 ? kMaxTiles : NH == 2 ? 24 : 12)) return k_wgrad_mfma<NJ, NT, NH>;
+    if constexpr (NJ * NT <= (NG * KW == 4 ? kMaxTiles : 24)) return k_wgrad_mfma<NJ, NT, NG, KW>;
     else return nullptr;
 }
 
-template <int NJ, int NH> WgradFn pick_nt(int nt)
+template <int NJ, int NG, int KW> WgradFn pick_nt(int nt)
 {
     switch (nt) {
-        case 1: return inst<NJ, 1, NH>();
-        case 2: return inst<NJ, 2, NH>();
-        case 3: return inst<NJ, 3, NH>();
-        case 4: return inst<NJ, 4, NH>();
-        case 5: return inst<NJ, 5, NH>();
-        case 6: return inst<NJ, 6, NH>();
-        case 7: return inst<NJ, 7, NH>();
-        case 8: return inst<NJ, 8, NH>();
-        case 10: return inst<NJ, 10, NH>();
-        case 13: return inst<NJ, 13, NH>();
-        case 16: return inst<NJ, 16, NH>();
+        case 1: return inst<NJ, 1, NG, KW>();
+        case 2: return inst<NJ, 2, NG, KW>();
+        case 3: return inst<NJ, 3, NG, KW>();
+        case 4: return inst<NJ, 4, NG, KW>();
+        case 5: return inst<NJ, 5, NG, KW>();
+        case 6: return inst<NJ, 6, NG, KW>();
+        case 7: return inst<NJ, 7, NG, KW>();
+        case 8: return inst<NJ, 8, NG, KW>();
+        case 10: return inst<NJ, 10, NG, KW>();
+        case 13: return inst<NJ, 13, NG, KW>();
+        case 16: return inst<NJ, 16, NG, KW>();
     }
     return nullptr;
 }
 
-// LO: one to four map tiles per workgroup, !LO: five to eight (two translation units per wave count).
-template <int NH, bool LO> WgradFn pick_nj(int nj, int nt)
+// LO: one to four map tiles per workgroup, !LO: five to eight (two translation units per wave layout).
+template <int NG, int KW, bool LO> WgradFn pick_nj(int nj, int nt)
 {
     if constexpr (LO) {
         switch (nj) {
-            case 1: return pick_nt<1, NH>(nt);
-            case 2: return pick_nt<2, NH>(nt);
-            case 3: return pick_nt<3, NH>(nt);
-            case 4: return pick_nt<4, NH>(nt);
+            case 1: return pick_nt<1, NG, KW>(nt);
+            case 2: return pick_nt<2, NG, KW>(nt);
+            case 3: return pick_nt<3, NG, KW>(nt);
+            case 4: return pick_nt<4, NG, KW>(nt);
         }
     } else {
         switch (nj) {
-            case 5: return pick_nt<5, NH>(nt);
-            case 6: return pick_nt<6, NH>(nt);
-            case 7: return pick_nt<7, NH>(nt);
-            case 8: return pick_nt<8, NH>(nt);
+            case 5: return pick_nt<5, NG, KW>(nt);
+            case 6: return pick_nt<6, NG, KW>(nt);
+            case 7: return pick_nt<7, NG, KW>(nt);
+            case 8: return pick_nt<8, NG, KW>(nt);
         }
     }
     return nullptr;
@@ -397,10 +428,14 @@ template <int NH, bool LO> WgradFn pick_nj(int nj, int nt)
 
 }  // namespace wgrad
 
-// One definition per translation unit direct_wgrad_h<NH>{a,b}.hip.
+// One definition per translation unit direct_wgrad_{h1,h2,n4}{a,b}.hip.
 wgrad::WgradFn wgrad_kernel_h1a(int nj, int nt);
 wgrad::WgradFn wgrad_kernel_h1b(int nj, int nt);
 wgrad::WgradFn wgrad_kernel_h2a(int nj, int nt);
 wgrad::WgradFn wgrad_kernel_h2b(int nj, int nt);
+wgrad::WgradFn wgrad_kernel_n4a(int nj, int nt);
+wgrad::WgradFn wgrad_kernel_n4b(int nj, int nt);
+wgrad::WgradFn wgrad_kernel_n8a(int nj, int nt);
+wgrad::WgradFn wgrad_kernel_n8b(int nj, int nt);
 
 }  // namespace znn

@@ -12,10 +12,11 @@
 // A workgroup owns one (a, b) tap plane, a group of columns n = c*f + i and a
 // share of the voxel rows (split-K).  Tiles of R voxel rows travel from global
 // memory straight into LDS (global_load_lds, no registers in between) into one
-// of two buffers, so the next tile is in flight while the four waves run the
-// MFMAs of the current one.  The waves take alternate 4-voxel steps of a tile;
-// their accumulators are added in a fixed order through LDS and written as one
-// partial matrix per workgroup.  A second kernel adds the partial matrices in
+// of two buffers, so the next tile is in flight while the waves run the MFMAs
+// of the current one.  With few columns the waves share the column tiles and
+// take alternate voxel steps of a tile (their accumulators are added in a fixed
+// order through LDS); with many columns every wave owns columns of its own, so
+// that a staged tile feeds four times the MFMAs.  One partial matrix per workgroup.  A second kernel adds the partial matrices in
 // ascending split order, so the result is bit-reproducible (no atomics).
 #include <cstdio>
 #include <cstdlib>
@@ -54,17 +55,20 @@ k_wgrad_reduce(const float* __restrict__ partial, float* __restrict__ gw, int f,
     gw[t] = acc;
 }
 
-WgradFn pick_wgrad(int nj, int nt, int nh)
+// ng column sets of kw waves each (direct_wgrad_impl.h).  Sixteen waves (4 x 4) were measured slower than
+// eight on every benchmark shape and are not instantiated.
+WgradFn pick_wgrad(int nj, int nt, int ng, int kw)
 {
-    // sixteen waves (NH = 4) were measured slower than eight on every benchmark shape and are not instantiated
-    if (nh == 2) return nj <= 4 ? wgrad_kernel_h2a(nj, nt) : wgrad_kernel_h2b(nj, nt);
-    if (nh == 1) return nj <= 4 ? wgrad_kernel_h1a(nj, nt) : wgrad_kernel_h1b(nj, nt);
+    if (ng == 2 && kw == 4) return nj <= 4 ? wgrad_kernel_h2a(nj, nt) : wgrad_kernel_h2b(nj, nt);
+    if (ng == 1 && kw == 4) return nj <= 4 ? wgrad_kernel_h1a(nj, nt) : wgrad_kernel_h1b(nj, nt);
+    if (ng == 4 && kw == 1) return nj <= 4 ? wgrad_kernel_n4a(nj, nt) : wgrad_kernel_n4b(nj, nt);
+    if (ng == 8 && kw == 1) return nj <= 4 ? wgrad_kernel_n8a(nj, nt) : wgrad_kernel_n8b(nj, nt);
     return nullptr;
 }
 
 struct WgradChoice {
     bool ok;
-    int NJ, JG, NT, G, NH;
+    int NJ, JG, NT, G, NG, KW;
     int TX, XT, R, GS, IS, TXH;
     int Mpad, Npad;
     int tiles, tps, ksplit;
@@ -82,43 +86,67 @@ int pad_stride(int n)
     return n;
 }
 
-WgradChoice search_wgrad(const Geom& g)
+// own: every wave owns columns (layers with many columns); else the waves of a set share its column tiles.
+WgradChoice search_wgrad_layout(const Geom& g, bool own)
 {
     WgradChoice c = {};
     c.ok = false;
     const int mt = (g.fo + 15) / 16;
-    // at most six 16-map tiles per workgroup: with seven or eight the gout half of the LDS tile leaves
-    // too few voxels per tile (config 5: 187 -> 160 ms with two groups of four)
-    const int maxnj = tuning().wgrad_maxnj;
-    c.JG = (mt + maxnj - 1) / maxnj;
-    c.NJ = (mt + c.JG - 1) / c.JG;
     const int ncols = g.f * g.kx;
     const int nt_tot = (ncols + 15) / 16;
     const int allowed[11] = {1, 2, 3, 4, 5, 6, 7, 8, 10, 13, 16};
-    int nt_max = 1;
-    for (int k = 0; k < 11; ++k)
-        if (c.NJ * allowed[k] <= kMaxTiles) nt_max = allowed[k];
-    c.G = (nt_tot + nt_max - 1) / nt_max;
-    const int want = (nt_tot + c.G - 1) / c.G;
-    c.NT = nt_max;
-    for (int k = 10; k >= 0; --k)
-        if (allowed[k] >= want && c.NJ * allowed[k] <= kMaxTiles) c.NT = allowed[k];
-    c.G = (nt_tot + c.NT - 1) / c.NT;
-    // eight waves: the column tiles of a group are dealt to two halves of four waves each
-    const int halves = tuning().wgrad_halves;
-    c.NH = 1;
-    for (int nh = halves; nh >= 2; nh /= 2) {
-        const int nt = (c.NT + nh - 1) / nh;
-        if ((nh == 2 || nh == 4) && c.NT >= nh && pick_wgrad(c.NJ, nt, nh)) {
-            c.NH = nh;
-            c.NT = nt;
-            c.G = (nt_tot + c.NT * c.NH - 1) / (c.NT * c.NH);
-            break;
+    if (own) {
+        // Many columns: waves with columns of their own.  Over the ways to cut the output maps into JG
+        // groups of NJ tiles and the columns into G groups of OW * NT tiles, take the one with the least
+        // issued MFMA work, weighted by how much of a staged tile each MFMA needs (the tile of a workgroup
+        // holds NJ * 16 gout maps and OW * NT * 16 / kx input maps; the fewer MFMAs per staged map, the less
+        // of the fetch hides behind them).
+        double best = 1e300;
+        const int OW = tuning().wgrad_own_waves;
+        for (int JG = 1; JG <= mt; ++JG) {
+            const int NJ = (mt + JG - 1) / JG;
+            if (NJ > 8 || (JG > 1 && NJ * (JG - 1) >= mt)) continue;
+            for (int G = 1; G <= nt_tot; ++G) {
+                const int per_wave = ((nt_tot + G - 1) / G + OW - 1) / OW;
+                int NT = 0;
+                for (int k = 0; k < 11 && !NT; ++k)
+                    if (allowed[k] >= per_wave) NT = allowed[k];
+                if (!NT || !pick_wgrad(NJ, NT, OW, 1)) continue;
+                if ((nt_tot + OW * NT - 1) / (OW * NT) != G) continue;     // fewer groups would do for this NT
+                const double issued = (double)JG * NJ * G * OW * NT;
+                const double per_map = (double)NJ * OW * NT / (NJ + (double)OW * NT / g.kx);
+                const double cost = issued * (1.0 + 4.0 / per_map);
+                if (cost < best) { best = cost; c.JG = JG; c.NJ = NJ; c.G = G; c.NT = NT; }
+            }
+        }
+        if (best == 1e300) return c;
+        c.NG = OW; c.KW = 1;
+    } else {
+        // at most six 16-map tiles per workgroup: with seven or eight the gout half of the LDS tile leaves
+        // too few voxels per tile (config 5: 187 -> 160 ms with two groups of four)
+        const int maxnj = tuning().wgrad_maxnj;
+        c.JG = (mt + maxnj - 1) / maxnj;
+        c.NJ = (mt + c.JG - 1) / c.JG;
+        int nt_max = 1;
+        for (int k = 0; k < 11; ++k)
+            if (c.NJ * allowed[k] <= kMaxTiles) nt_max = allowed[k];
+        c.G = (nt_tot + nt_max - 1) / nt_max;
+        const int want = (nt_tot + c.G - 1) / c.G;
+        c.NT = nt_max;
+        for (int k = 10; k >= 0; --k)
+            if (allowed[k] >= want && c.NJ * allowed[k] <= kMaxTiles) c.NT = allowed[k];
+        c.G = (nt_tot + c.NT - 1) / c.NT;
+        // eight waves: the column tiles of a group are dealt to two sets of four waves each
+        c.NG = 1; c.KW = 4;
+        if (tuning().wgrad_halves >= 2 && c.NT >= 2 && pick_wgrad(c.NJ, (c.NT + 1) / 2, 2, 4)) {
+            c.NG = 2;
+            c.NT = (c.NT + 1) / 2;
+            c.G = (nt_tot + c.NT * c.NG - 1) / (c.NT * c.NG);
         }
     }
-    if (!pick_wgrad(c.NJ, c.NT, c.NH)) return c;
+    if (!pick_wgrad(c.NJ, c.NT, c.NG, c.KW)) return c;
     c.Mpad = c.JG * c.NJ * 16;
-    c.Npad = c.G * c.NT * c.NH * 16;
+    c.Npad = c.G * c.NT * c.NG * 16;
     // Column order.  With n = c*f + i (x-tap major) a column group spans all f input maps as soon as
     // it is wider than f, so the LDS tile of a layer with many input maps holds few voxels; with
     // n = i*kx + c (map major) a group holds only the maps of its own columns.  One group: the same
@@ -129,8 +157,8 @@ WgradChoice search_wgrad(const Geom& g)
     int cspan = 0, nmaps = 1;
     bool aligned_rows = true;
     for (int cg = 0; cg < c.G; ++cg) {
-        const int n0 = cg * c.NT * c.NH * 16;
-        const int n1 = n0 + c.NT * c.NH * 16 < ncols ? n0 + c.NT * c.NH * 16 : ncols;
+        const int n0 = cg * c.NT * c.NG * 16;
+        const int n1 = n0 + c.NT * c.NG * 16 < ncols ? n0 + c.NT * c.NG * 16 : ncols;
         int cmin, cmax, maps;
         if (c.mapmajor) {
             const int imin = n0 / g.kx, imax = (n1 - 1) / g.kx;
@@ -145,33 +173,60 @@ WgradChoice search_wgrad(const Geom& g)
         if (maps > nmaps) nmaps = maps;
         if (cmax != g.kx - 1) aligned_rows = false;
     }
-    if ((size_t)c.NJ * c.NT * c.NH * 64 * 4 > (size_t)kBufFloats) return c;   // cross-wave reduction needs this
+    if (c.KW > 1 && (size_t)c.NJ * c.NT * c.NG * 64 * 4 > (size_t)kBufFloats) return c;   // cross-wave reduction needs this
     const int rows = g.oz * g.oy;
-    // fewest x-segments whose tile fits a buffer, then as many rows as fit
-    for (int XT = 1; XT <= g.ox; ++XT) {
+    const int nw = c.NG * c.KW;
+    // 16-byte loads: groups of four x-neighbours must be wholly inside or outside the images and start on
+    // multiples of four in both tensors
+    const bool in16 = g.nx % 4 == 0 && aligned_rows;
+    // fast tile loader (see the kernel): tiles of whole rows that do not straddle a z-plane, spans per wave
+    // that fit its register arrays, a lane's offset from the tile origin (up to a whole group of maps) in 32 bits
+    auto fast_tiles = [&](int R, int GS, int IS) {
+        const long span_g = ((long)c.NJ * 16 * GS + 255) / 256, span_i = ((long)nmaps * IS + 255) / 256;
+        return g.oy % R == 0 && (span_g + nw - 1) / nw <= wgrad::max_spans(nw, c.NJ) && (span_i + nw - 1) / nw <= wgrad::max_spans(nw, c.NJ) &&
+               (double)g.fo * g.ovol() * 4.0 < 2147483648.0 && (double)g.f * g.nvol() * 4.0 < 2147483648.0 &&
+               !tuning().wgrad_slow_loader;
+    };
+    // Rows of gout whose length is 2 modulo 4 (90, 246, ...): staged WITHOUT padding behind each row, a tile of
+    // R whole rows (R even) is one contiguous run per map in global memory as in LDS, so 16-byte loads may
+    // straddle rows; the voxel pairs of an MFMA step still lie inside one row.  Only with the fast loader.
+    if (g.ox % 4 == 2 && in16 && g.ovol() % 4 == 0) {
+        const int TX = g.ox, TXH = (TX + cspan * g.spx + 3) & ~3;
+        for (int R = 2; R <= 32 && R <= rows; R += 2) {
+            const int GS = pad_stride((R * TX + 7) & ~7), IS = pad_stride(R * TXH);
+            if ((long)c.NJ * 16 * GS + (long)nmaps * IS + 64 > kBufFloats) break;
+            if (!fast_tiles(R, GS, IS)) continue;
+            c.XT = 1; c.TX = TX; c.TXH = TXH; c.R = R; c.GS = GS; c.IS = IS;
+            c.vec4 = 1; c.fast = 1; c.ok = true;
+        }
+    }
+    // otherwise: fewest x-segments whose tile fits a buffer, then as many rows as fit (the most that still
+    // allow the fast loader if that is at least half as many)
+    for (int XT = 1; XT <= g.ox && !c.ok; ++XT) {
         const int seg = (g.ox + XT - 1) / XT;
         int TX = (seg + 3) & ~3;
         if (TX % 8 != 0 && rows < 2) TX += 4;          // a single row must hold whole 8-voxel steps
         const int TXH = (TX + cspan * g.spx + 3) & ~3;
-        int bestR = 0;
+        const int vec4 = (g.ox % 4 == 0 && in16) ? 1 : 0;
+        int bestR = 0, fastR = 0;
         for (int R = 1; R <= 32 && R <= rows; ++R) {
             // the MFMA loop walks 8 voxels per step; a tile that ends on half a step reads its last four
             // voxels from the zero padding behind the row (gout) and from whatever follows (in)
-            const int rtp = (R * TX + 7) & ~7;
-            const long floats = (long)c.NJ * 16 * pad_stride(rtp) + (long)nmaps * pad_stride(R * TXH) + 64;
-            if (floats <= kBufFloats) bestR = R;
+            const int GS = pad_stride((R * TX + 7) & ~7), IS = pad_stride(R * TXH);
+            if ((long)c.NJ * 16 * GS + (long)nmaps * IS + 64 > kBufFloats) break;
+            bestR = R;
+            if (vec4 && XT == 1 && fast_tiles(R, GS, IS)) fastR = R;
         }
         if (bestR == 0) continue;
+        c.fast = 2 * fastR >= bestR ? 1 : 0;
+        if (c.fast) bestR = fastR;
         c.XT = XT; c.TX = TX; c.TXH = TXH; c.R = bestR;
         c.GS = pad_stride((bestR * TX + 7) & ~7); c.IS = pad_stride(bestR * TXH);
-        c.lds = 2 * (size_t)kBufFloats * 4;
-        // 16-byte loads: groups of four x-neighbours must be wholly inside or outside the
-        // images and start on multiples of four in both tensors
-        c.vec4 = (g.ox % 4 == 0 && g.nx % 4 == 0 && aligned_rows) ? 1 : 0;
+        c.vec4 = vec4;
         c.ok = true;
-        break;
     }
     if (!c.ok) return c;
+    c.lds = 2 * (size_t)kBufFloats * 4;
     c.tiles = ((rows + c.R - 1) / c.R) * c.XT;
     // one workgroup per compute unit: split the voxel range until the grid reaches 256
     const long other = (long)g.kz * g.ky * c.G * c.JG;
@@ -180,19 +235,24 @@ WgradChoice search_wgrad(const Geom& g)
     if (ks > c.tiles) ks = c.tiles;
     c.tps = (int)((c.tiles + ks - 1) / ks);
     c.ksplit = (c.tiles + c.tps - 1) / c.tps;
-    {
-        // fast tile loader: see the kernel.  Spans per wave must fit its register arrays, and a lane's
-        // offset from the tile origin (up to a whole group of maps) must fit 32 bits.
-        const int nw = 4 * c.NH;
-        const long span_g = ((long)c.NJ * 16 * c.GS + 255) / 256, span_i = ((long)nmaps * c.IS + 255) / 256;
-        c.fast = (c.vec4 && c.XT == 1 && g.oy % c.R == 0 && (span_g + nw - 1) / nw <= 5 && (span_i + nw - 1) / nw <= 5 &&
-                  (double)g.fo * g.ovol() * 4.0 < 2147483648.0 && (double)g.f * g.nvol() * 4.0 < 2147483648.0 &&
-                  !tuning().wgrad_slow_loader) ? 1 : 0;
-    }
     if ((long)g.kz * g.ky > 65535 || (long)c.G * c.JG > 65535) c.ok = false;
     // the tile loader addresses a map with a 32-bit byte offset
     if (g.nvol() >= (1L << 30) || g.ovol() >= (1L << 30)) c.ok = false;
     return c;
+}
+
+// With many columns the layout in which every wave owns columns stages fewer tiles per MFMA (config 4:
+// 1.22 -> 1.03 ms); it is passed over when only the shared layout's tiles qualify for the fast loader
+// (config 5: 82 ms shared with the fast loader, 102 ms with own columns and the general one).
+WgradChoice search_wgrad(const Geom& g)
+{
+    const WgradChoice shared = search_wgrad_layout(g, false);
+    const int nt_tot = (g.f * g.kx + 15) / 16;
+    if (nt_tot < tuning().wgrad_own_columns_from) return shared;
+    const WgradChoice own = search_wgrad_layout(g, true);
+    if (!own.ok) return shared;
+    if (!shared.ok) return own;
+    return shared.fast && !own.fast ? shared : own;
 }
 
 // Every call of the pass asks for the same answer three times (supported?, workspace, launch):
@@ -251,11 +311,11 @@ int mfma_wgrad(const Geom& g, const float* in, const float* gout, float* gw, voi
     P.dGS = make_fastdiv(c.GS); P.dIS = make_fastdiv(c.IS);
     P.dTX = make_fastdiv(c.TX); P.dTXH = make_fastdiv(c.TXH); P.dOY = make_fastdiv(g.oy);
     if (log_enabled())
-        fprintf(stderr, "[znn] wgrad mfma: NJ=%d JG=%d NT=%d NH=%d G=%d TX=%d XT=%d R=%d lds=%zu ksplit=%d tiles=%d\n",
-                c.NJ, c.JG, c.NT, c.NH, c.G, c.TX, c.XT, c.R, c.lds, c.ksplit, c.tiles);
-    WgradFn fn = pick_wgrad(c.NJ, c.NT, c.NH);
+        fprintf(stderr, "[znn] wgrad mfma: NJ=%d JG=%d NT=%d waves=%dx%d G=%d TX=%d XT=%d R=%d lds=%zu ksplit=%d tiles=%d\n",
+                c.NJ, c.JG, c.NT, c.NG, c.KW, c.G, c.TX, c.XT, c.R, c.lds, c.ksplit, c.tiles);
+    WgradFn fn = pick_wgrad(c.NJ, c.NT, c.NG, c.KW);
     if (!fn) return fail(ZNN_EUNSUPPORTED, "no kernel instance for tile %dx%d", c.NJ, c.NT);
-    ZNN_LAUNCH("direct kernel gradient (MFMA)", s, fn, dim3((unsigned)c.ksplit, (unsigned)P.AB, (unsigned)(c.G * c.JG)), dim3(256 * c.NH), 0, P);
+    ZNN_LAUNCH("direct kernel gradient (MFMA)", s, fn, dim3((unsigned)c.ksplit, (unsigned)P.AB, (unsigned)(c.G * c.JG)), dim3(64 * c.NG * c.KW), 0, P);
     int rc = check_launch("direct kernel gradient (MFMA)");
     if (rc != ZNN_OK) return rc;
     const long total = (long)g.fo * g.f * g.kvol();

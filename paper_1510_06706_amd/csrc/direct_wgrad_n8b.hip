@@ -1,0 +1,8 @@
+// Kernel-gradient kernels with 8 waves with their own columns each and five to eight map tiles (direct_wgrad_impl.h).
+#include "direct_wgrad_impl.h"
+
+namespace znn {
+
+wgrad::WgradFn wgrad_kernel_n8b(int nj, int nt) { return wgrad::pick_nj<8, 1, false>(nj, nt); }
+
+}  // namespace znn

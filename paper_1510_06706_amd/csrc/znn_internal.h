@@ -79,6 +79,8 @@ struct Tuning {
     int  conv_tile[4];          // ZNN_CONV_TILE="NV,Tz,Ty,Tx": pin the output box (0 = not pinned)
     int  wgrad_halves;          // ZNN_WGRAD_HALVES: 1 = four waves, 2 = eight waves per workgroup
     int  wgrad_maxnj;           // ZNN_WGRAD_MAXNJ: most 16-map tiles per workgroup
+    int  wgrad_own_waves;       // ZNN_WGRAD_OWN_WAVES: 4 or 8 waves per workgroup in that layout
+    int  wgrad_own_columns_from; // ZNN_WGRAD_OWN_COLUMNS_FROM: column tiles from which every wave owns columns
     int  wgrad_stride_mod;      // ZNN_WGRAD_STRIDE_MOD: residue modulo 32 of the LDS map stride
     bool wgrad_slow_loader;     // ZNN_WGRAD_SLOW_LOADER: general tile loader everywhere
     int  fft_mac_z0;            // ZNN_FFT_MAC_Z0: frequencies per thread of the folded multiply-accumulate / 4

@@ -103,6 +103,13 @@ DIRECT_TAPS = [
     (104, 97, (5, 9, 9), (2, 2, 2), (1, 1, 1)),
     (23, 21, (14, 14, 14), (3, 3, 3), (2, 2, 2)),
     (33, 24, (6, 6, 10), (2, 2, 2), (1, 1, 1)),
+    # kernel gradient: many columns (every wave owns columns of its own; ragged last column group and
+    # waves without columns), rows of gout of length 2 modulo 4 staged without padding, both together
+    (12, 20, (8, 10, 16), (3, 3, 3), (1, 1, 1)),
+    (9, 7, (6, 12, 24), (2, 3, 7), (1, 1, 1)),
+    (100, 18, (4, 6, 12), (1, 2, 3), (1, 1, 1)),
+    (70, 33, (3, 9, 16), (2, 2, 7), (1, 1, 1)),
+    (45, 50, (1, 12, 36), (1, 3, 11), (1, 1, 1)),
 ]
 
 
