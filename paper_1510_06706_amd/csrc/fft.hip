@@ -31,7 +31,6 @@ namespace znn {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kLdsBudget = 64 * 1024;
 
 // Radix sequence of a transform; fs[i] divides by the stride s of pass i (the product of
 // the radices before it) and fw by the number of pencils per batch, so that the
@@ -41,6 +40,12 @@ struct Radices { int n; int r[12]; FastDiv fs[12]; FastDiv fw; };
 Radices factorize(int N, int W)
 {
     Radices R; R.n = 0;
+    // long pencils: radix-16 and radix-8 passes (a 16- or 8-point transform in registers per thread) halve
+    // the number of trips through LDS and of barriers
+    if (N > 96) {
+        while (N % 16 == 0) { R.r[R.n++] = 16; N /= 16; }
+        if (N % 8 == 0) { R.r[R.n++] = 8; N /= 8; }
+    }
     while (N % 4 == 0) { R.r[R.n++] = 4; N /= 4; }
     while (N % 2 == 0) { R.r[R.n++] = 2; N /= 2; }
     while (N % 3 == 0) { R.r[R.n++] = 3; N /= 3; }
@@ -51,10 +56,11 @@ Radices factorize(int N, int W)
     return R;
 }
 
-// Largest odd pencil-row length such that two N x Wp buffers plus N twiddles fit.
+// Largest odd pencil-row length such that two N x Wp buffers plus N twiddles fit a workgroup's share of LDS
+// (48 KiB unless tuned: three workgroups per compute unit; 64 KiB measured 3 % slower on 256-point passes).
 int max_row_len(int N)
 {
-    int lim = (kLdsBudget / 8 - N) / (2 * N);
+    int lim = (tuning().fft_lds_kb * 1024 / 8 - N) / (2 * N);
     if (lim < 1) lim = 1;
     if ((lim & 1) == 0) --lim;
     return lim;
@@ -83,6 +89,76 @@ __device__ __forceinline__ void make_twiddles(float2* tw, int N, int dir)
     }
 }
 
+// 4-point transform in place: b_k = sum_n a_n exp(DIR 2 pi i n k / 4).
+template <int DIR>
+__device__ __forceinline__ void dft4(float2& a0, float2& a1, float2& a2, float2& a3)
+{
+    const float2 s02 = cadd(a0, a2), d02 = csub(a0, a2);
+    const float2 s13 = cadd(a1, a3), d13 = mul_di<DIR>(csub(a1, a3));
+    a0 = cadd(s02, s13);
+    a1 = cadd(d02, d13);
+    a2 = csub(s02, s13);
+    a3 = csub(d02, d13);
+}
+
+// a * (c + DIR i s)
+template <int DIR> __device__ __forceinline__ float2 cmul_const(float2 a, float c, float s)
+{
+    return DIR > 0 ? make_float2(a.x * c - a.y * s, a.x * s + a.y * c) : make_float2(a.x * c + a.y * s, a.y * c - a.x * s);
+}
+
+// 16-point transform, v[n] -> v[k], as 4 x 4: with n = 4 n1 + n2 and k = k1 + 4 k2,
+// exp(2 pi i n k / 16) = w4^(n1 k1) w16^(n2 k1) w4^(n2 k2).
+template <int DIR>
+__device__ __forceinline__ void dft16(float2 (&v)[16])
+{
+    constexpr float c1 = 0.9238795325112867f, s1 = 0.3826834323650898f, h = 0.7071067811865476f;
+#pragma unroll
+    for (int n2 = 0; n2 < 4; ++n2) dft4<DIR>(v[n2], v[n2 + 4], v[n2 + 8], v[n2 + 12]);    // v[n2 + 4 k1]
+    // twiddles w16^(n2 k1)
+    v[1 + 4] = cmul_const<DIR>(v[1 + 4], c1, s1);
+    v[1 + 8] = cmul_const<DIR>(v[1 + 8], h, h);
+    v[1 + 12] = cmul_const<DIR>(v[1 + 12], s1, c1);
+    v[2 + 4] = cmul_const<DIR>(v[2 + 4], h, h);
+    v[2 + 8] = mul_di<DIR>(v[2 + 8]);
+    v[2 + 12] = cmul_const<DIR>(v[2 + 12], -h, h);
+    v[3 + 4] = cmul_const<DIR>(v[3 + 4], s1, c1);
+    v[3 + 8] = cmul_const<DIR>(v[3 + 8], -h, h);
+    v[3 + 12] = cmul_const<DIR>(v[3 + 12], -c1, -s1);
+#pragma unroll
+    for (int k1 = 0; k1 < 4; ++k1) dft4<DIR>(v[4 * k1], v[4 * k1 + 1], v[4 * k1 + 2], v[4 * k1 + 3]);   // v[4 k1 + k2]
+    // to natural order k = k1 + 4 k2: transpose the 4 x 4 array
+#pragma unroll
+    for (int k1 = 0; k1 < 4; ++k1)
+#pragma unroll
+        for (int k2 = k1 + 1; k2 < 4; ++k2) {
+            const float2 t = v[4 * k1 + k2];
+            v[4 * k1 + k2] = v[4 * k2 + k1];
+            v[4 * k2 + k1] = t;
+        }
+}
+
+// 8-point transform, v[n] -> v[k], as 4 x 2: with n = 2 n1 + n2 and k = k1 + 4 k2,
+// exp(2 pi i n k / 8) = w4^(n1 k1) w8^(n2 k1) (-1)^(n2 k2).
+template <int DIR>
+__device__ __forceinline__ void dft8(float2 (&v)[8])
+{
+    constexpr float h = 0.7071067811865476f;
+    dft4<DIR>(v[0], v[2], v[4], v[6]);      // n2 = 0: v[2 k1]
+    dft4<DIR>(v[1], v[3], v[5], v[7]);      // n2 = 1: v[2 k1 + 1]
+    v[3] = cmul_const<DIR>(v[3], h, h);
+    v[5] = mul_di<DIR>(v[5]);
+    v[7] = cmul_const<DIR>(v[7], -h, h);
+    float2 o[8];
+#pragma unroll
+    for (int k1 = 0; k1 < 4; ++k1) {
+        o[k1] = cadd(v[2 * k1], v[2 * k1 + 1]);
+        o[k1 + 4] = csub(v[2 * k1], v[2 * k1 + 1]);
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = o[k];
+}
+
 // Stockham autosort FFT of W pencils of length N held as src[e * Wp + p].
 // DIR = -1: forward kernel exp(-2 pi i jk/N); DIR = +1: unnormalised inverse.
 // Returns the buffer that holds the result (natural order).
@@ -106,7 +182,23 @@ __device__ float2* lds_fft(float2* src, float2* dst, const float2* tw, int N, in
             const float2* x = src + (q + s * pp) * Wp + p;
             float2* y = dst + (q + s * r * pp) * Wp + p;
             const int ti = pp * s;   // twiddle index for output 1: exp(DIR 2 pi i pp / n)
-            if (r == 4) {
+            if (r == 16) {
+                float2 v[16];
+#pragma unroll
+                for (int j = 0; j < 16; ++j) v[j] = x[j * xs];
+                dft16<DIR>(v);
+                y[0] = v[0];
+#pragma unroll
+                for (int j = 1; j < 16; ++j) y[j * ys] = cmul(v[j], tw[j * ti]);
+            } else if (r == 8) {
+                float2 v[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) v[j] = x[j * xs];
+                dft8<DIR>(v);
+                y[0] = v[0];
+#pragma unroll
+                for (int j = 1; j < 8; ++j) y[j * ys] = cmul(v[j], tw[j * ti]);
+            } else if (r == 4) {
                 const float2 a0 = x[0], a1 = x[xs], a2 = x[2 * xs], a3 = x[3 * xs];
                 const float2 s02 = cadd(a0, a2), d02 = csub(a0, a2);
                 const float2 s13 = cadd(a1, a3), d13 = mul_di<DIR>(csub(a1, a3));

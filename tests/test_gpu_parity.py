@@ -45,6 +45,9 @@ SMALL = [
     (131, 5, (5, 6, 9), (2, 1, 3)),
     (3, 4, (81, 50, 36), (3, 4, 2)),      # three different transform extents, all register-resident passes
     (2, 3, (40, 100, 30), (2, 3, 3)),     # y extent above 96: LDS pass between two register passes
+    (1, 2, (3, 128, 256), (2, 5, 3)),     # long pencils: radix-16 and radix-8 LDS passes (256 = 16 x 16, 128 = 16 x 8)
+    (2, 1, (1, 192, 160), (1, 3, 3)),     # 192 = 16 x 4 x 3, 160 = 16 x 2 x 5
+    (1, 1, (1, 120, 104), (1, 2, 2)),     # 120 = 8 x 3 x 5, 104 -> 108 = 4 x 3 x 3 x 3
 ]
 
 
