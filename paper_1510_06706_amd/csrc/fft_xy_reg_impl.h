@@ -180,11 +180,64 @@ __global__ void __launch_bounds__(kXYThreads, 2) k_fft_c2r_yx_reg(XYInv P)
     }
 }
 
+// Forward x and y passes of planes that hold a few short rows (kernels: k_y rows of k_x taps), one wave per
+// plane and NO LDS: lane k computes the coefficients X[r][k] of every source row directly from the taps
+// (s_x real multiply-adds each; the taps are the same for all lanes and come through scalar loads) and
+// then owns column k of the plane's spectrum: it runs the length-N transform along y in registers and
+// stores the column.  The general kernel above spends a length-N/2 register transform per row on seven
+// lanes and leaves its second wave idle during the y pass.
+constexpr int kTapRows = 16, kTapCols = 16;
+
+template <int N>
+__global__ void __launch_bounds__(64) k_fft_r2c_xy_taps(XYFwd P)
+{
+    constexpr int NXH = N / 2 + 1;
+    const int k = threadIdx.x;
+    if (k >= NXH) return;
+    const long plane = blockIdx.x;
+    const long map = plane / P.sz;
+    const int z = (int)(plane - map * P.sz);
+    const float* src = P.src + plane * (long)P.sy * P.sx;       // uniform
+    float2* dst = P.dst + ((map * P.Nz + (long)z * P.tz + P.oz) * N) * NXH;
+    // exp(-2 pi i (x + ox) k / N) for the row's taps
+    float2 tw[kTapCols];
+#pragma unroll
+    for (int x = 0; x < kTapCols; ++x) {
+        const int m = ((x + P.ox) * k) % N;
+        tw[x] = make_float2(TwTable<N>::t.c[m], -TwTable<N>::t.s[m]);
+    }
+    float2 v[N], w[N];
+#pragma unroll
+    for (int e = 0; e < N; ++e) v[e] = make_float2(0.f, 0.f);
+#pragma unroll
+    for (int r = 0; r < kTapRows; ++r) {
+        if (r < P.sy) {     // uniform
+            float2 a = make_float2(0.f, 0.f);
+#pragma unroll
+            for (int x = 0; x < kTapCols; ++x)
+                if (x < P.sx) {     // uniform
+                    const float t = src[r * P.sx + x];
+                    a.x = fmaf(t, tw[x].x, a.x);
+                    a.y = fmaf(t, tw[x].y, a.y);
+                }
+            v[r] = a;       // the launcher admits only planes whose rows start at y = 0
+        }
+    }
+    passes<N, -1, N, 1>(v, w);
+    constexpr bool in_w = (count_passes(N) % 2) == 1;
+#pragma unroll
+    for (int e = 0; e < N; ++e) dst[(long)e * NXH + k] = in_w ? w[e] : v[e];
+}
+
 template <int N>
 int launch_xy(const XYFwd* F, const XYInv* B, hipStream_t s)
 {
     const long planes = F ? F->planes : B->planes;
     if (planes >= 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many planes for one launch");
+    if (F && F->sy <= kTapRows && F->sx <= kTapCols && F->oy == 0 && kTapRows <= N && !tuning().fft_no_taps_pass) {
+        ZNN_LAUNCH("fft r2c x and y of taps (registers)", s, (k_fft_r2c_xy_taps<N>), dim3((unsigned)planes), dim3(64), 0, *F);
+        return check_launch("fused x/y pass of taps");
+    }
     if (F) ZNN_LAUNCH("fft r2c x and y (registers)", s, (k_fft_r2c_xy_reg<N>), dim3((unsigned)planes), dim3(kXYThreads), 0, *F);
     else   ZNN_LAUNCH("fft c2r y and x (registers)", s, (k_fft_c2r_yx_reg<N>), dim3((unsigned)planes), dim3(kXYThreads), 0, *B);
     return check_launch("fused x/y pass");

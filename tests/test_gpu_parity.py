@@ -292,18 +292,23 @@ def test_fft_x_and_y_passes_in_one_launch_for_every_extent(N):
     shorter = [m for m in range(N - 1, N - 8, -1) if next_smooth(m) == N]
     cases = [(N, N)] + ([(shorter[-1], shorter[0])] if shorter else [])
     for ny, nx in cases:
-        n, k = (8, ny, nx), (3, 2, 4)
-        cfg = synth.LayerShape("t", 3, 2, n, k, 1.0, 600 + N)
-        inp, w, gout = synth.layer_tensors(cfg)
-        p = znn.Plan(3, 2, n, k, "fft")
-        assert p.fft_extents[1:] == (N, N)
-        d_in, d_w, d_g = dev(inp), dev(w), dev(gout)
-        assert rel_err(host(p.fwd(d_in, d_w)), oracle.conv3d_fwd(inp, w)) <= TOL["fft"], (n, "fwd")
-        assert rel_err(host(p.bwd(d_g, d_w)), oracle.conv3d_bwd(gout, w, n)) <= TOL["fft"], (n, "bwd")
-        assert rel_err(host(p.wgrad(d_in, d_g)), oracle.conv3d_wgrad(inp, gout)) <= TOL["fft"], (n, "wgrad")
-        p.set_spectra_layout("folded" if p.spectra_layout == "full" else "full")    # the other kernel transform as well
-        assert rel_err(host(p.fwd(d_in, d_w)), oracle.conv3d_fwd(inp, w)) <= TOL["fft"], (n, "fwd, other layout")
-        p.close()
+        # kernels of a few short rows take a pass of their own (one wave per plane, up to 16 rows of 16 taps);
+        # a kernel with more rows goes through the general pass like an image
+        kernels = [(3, 2, 4), (2, min(16, ny - 2), min(16, nx - 3))] + ([(1, 17, 5)] if ny >= 20 else [])
+        for k in kernels:
+            n = (8, ny, nx)
+            cfg = synth.LayerShape("t", 3, 2, n, k, 1.0, 600 + N)
+            inp, w, gout = synth.layer_tensors(cfg)
+            p = znn.Plan(3, 2, n, k, "fft")
+            assert p.fft_extents[1:] == (N, N)
+            d_in, d_w, d_g = dev(inp), dev(w), dev(gout)
+            assert rel_err(host(p.fwd(d_in, d_w)), oracle.conv3d_fwd(inp, w)) <= TOL["fft"], (n, k, "fwd")
+            assert rel_err(host(p.bwd(d_g, d_w)), oracle.conv3d_bwd(gout, w, n)) <= TOL["fft"], (n, k, "bwd")
+            assert rel_err(host(p.wgrad(d_in, d_g)), oracle.conv3d_wgrad(inp, gout)) <= TOL["fft"], (n, k, "wgrad")
+            if k[0] > 1 or p.spectra_layout == "folded":
+                p.set_spectra_layout("folded" if p.spectra_layout == "full" else "full")    # the other kernel transform as well
+                assert rel_err(host(p.fwd(d_in, d_w)), oracle.conv3d_fwd(inp, w)) <= TOL["fft"], (n, k, "fwd, other layout")
+            p.close()
 
 
 def test_resident_kernel_spectra_give_the_same_result():
