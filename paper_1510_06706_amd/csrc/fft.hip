@@ -56,11 +56,14 @@ Radices factorize(int N, int W)
     return R;
 }
 
-// Largest odd pencil-row length such that two N x Wp buffers plus N twiddles fit a workgroup's share of LDS
-// (48 KiB unless tuned: three workgroups per compute unit; 64 KiB measured 3 % slower on 256-point passes).
-int max_row_len(int N)
+// Largest odd pencil-row length such that two N x Wp buffers plus N twiddles fit a workgroup's share of LDS.
+// Unless tuned: 24 KiB for the x passes (rows are contiguous, so small batches cost nothing and more
+// workgroups per compute unit hide more latency: 256-point r2c 37 -> 25 us against 64 KiB) and 40 KiB for the
+// strided passes (whose batches are runs of neighbouring pencils: shorter runs coalesce worse).
+int max_row_len(int N, bool x_pass)
 {
-    int lim = (tuning().fft_lds_kb * 1024 / 8 - N) / (2 * N);
+    const int kb = tuning().fft_lds_kb ? tuning().fft_lds_kb : x_pass ? 24 : 40;
+    int lim = (kb * 1024 / 8 - N) / (2 * N);
     if (lim < 1) lim = 1;
     if ((lim & 1) == 0) --lim;
     return lim;
@@ -926,7 +929,7 @@ int launch_r2c(const float* src, float2* dst, long maps, int sz, int sy, int sx,
     P.sz = sz; P.sy = sy; P.sx = sx;
     P.Nz = Nz; P.Ny = Ny; P.Nx = Nx; P.Nxh = Nx / 2 + 1;
     P.oz = oz; P.oy = oy; P.ox = ox;
-    int wp = max_row_len(Nx);
+    int wp = max_row_len(Nx, true);
     if (wp > 33) wp = 33;
     P.W = wp; P.Wp = wp;
     P.rad = factorize(Nx, P.W);
@@ -960,7 +963,7 @@ int launch_c2r(const float2* src, float* dst, long maps, int Nz, int Ny, int Nx,
     P.dz = dz; P.dy = dy; P.dx = dx;
     P.Nz = Nz; P.Ny = Ny; P.Nx = Nx; P.Nxh = Nx / 2 + 1;
     P.scale = scale;
-    int wp = max_row_len(Nx);
+    int wp = max_row_len(Nx, true);
     if (wp > 33) wp = 33;
     P.W = wp; P.Wp = wp;
     P.rad = factorize(Nx, P.W);
@@ -996,7 +999,7 @@ int launch_axis(AxisParams P, int dir, hipStream_t s)
     }
     // chunk width: a whole line when it fits, else a multiple of 16 pencils (128 bytes) so
     // that every chunk starts on a cache-line boundary
-    int wmax = max_row_len(P.N) > 63 ? 63 : max_row_len(P.N);
+    int wmax = max_row_len(P.N, false) > 63 ? 63 : max_row_len(P.N, false);
     if (P.L > wmax && wmax >= 16) wmax = wmax >= 48 ? 32 : (wmax / 16) * 16;
     const int chunks = (P.L + wmax - 1) / wmax;
     P.chunks = chunks;
