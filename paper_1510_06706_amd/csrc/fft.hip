@@ -867,7 +867,10 @@ template <int KZ>
 int launch_wgrad_dft_k(int f, int fo, int N, int tz, long plane, long vol, const float2* G, const float2* I, float2* T,
                        hipStream_t s)
 {
-    constexpr int JB = 2, IB = KZ <= 8 ? 4 : 2;
+    // pairs per thread: as many as the register file takes next to their 2 KZ sums each (config 5, KZ = 7:
+    // 2 x 4 pairs 3.57 ms, 3 x 3 pairs 3.18 ms: fewer loads per pair; the 2D benchmark layer, KZ = 11, whose planes
+    // give few threads, is faster with 2 x 2 than with 2 x 3: 0.29 against 0.37 ms)
+    constexpr int JB = KZ <= 3 ? 4 : KZ <= 8 ? 3 : 2, IB = KZ <= 5 ? 4 : KZ <= 8 ? 3 : 2;
     const int jblocks = (fo + JB - 1) / JB, iblocks = (f + IB - 1) / IB;
     const long pchunks = (plane + kThreads - 1) / kThreads;
     const long tiles = pchunks * ((jblocks + kTileJ - 1) / kTileJ) * ((iblocks + kTileI - 1) / kTileI);
