@@ -24,58 +24,27 @@ using conv::ConvTile;
 
 constexpr int kMaxTaps = 4096;
 
-// Packs w[f'][f][k] so that lane l of a wave finds its A element of tile jt at
-// [..][jt][l]: output map jt*16 + l%16, input map chunk*4 + l/16.  For the
-// backward pass the two map indices trade places and the tap is reflected.
-__global__ void __launch_bounds__(256)
-k_pack_weights(const float* __restrict__ w, float* __restrict__ wp, int f, int fo, int kz, int ky, int kx,
-               int backward, int NJ, int jgroups, int nchunk)
-{
-    const int taps = kz * ky * kx;
-    const long total = (long)jgroups * nchunk * taps * NJ * 64;
-    const long t = (long)blockIdx.x * 256 + threadIdx.x;
-    if (t >= total) return;
-    const int lane = (int)(t % 64);
-    long r = t / 64;
-    const int jt = (int)(r % NJ); r /= NJ;
-    const int tap = (int)(r % taps); r /= taps;
-    const int ic = (int)(r % nchunk);
-    const int jg = (int)(r / nchunk);
-    const int m = (jg * NJ + jt) * 16 + (lane & 15);   // M-side map
-    const int k = ic * 4 + (lane >> 4);                // K-side map
-    const int fM = backward ? f : fo, fK = backward ? fo : f;
-    float v = 0.f;
-    if (m < fM && k < fK) {
-        if (!backward) {
-            v = w[((long)m * f + k) * taps + tap];
-        } else {
-            const int c = tap % kx, b = (tap / kx) % ky, a = tap / (kx * ky);
-            const int rt = ((kz - 1 - a) * ky + (ky - 1 - b)) * kx + (kx - 1 - c);
-            v = w[((long)k * f + m) * taps + rt];
-        }
-    }
-    wp[t] = v;
-}
-
-// dst = partial[0] + partial[1] + ... in ascending order (input maps split over workgroups).
-// The same for the kernel with an 8-map block behind NJ full tiles (direct_mfma_tail_impl.h): per
-// (chunk, tap) the NJ x 64 operands of the full tiles, then [8 maps][4 input maps].
+// Packs w[f'][f][k] for the kernel of direct_mfma_tail_impl.h: per (map group, chunk, tap) the NJ x 64 operands of
+// the full tiles (lane l of tile jt: output-side map jt*16 + l%16, input-side map chunk*4 + l/16), then, with
+// `tail`, [8 maps][4 input maps] for the 8-map block.  For the backward pass the two map indices trade places
+// and the tap is reflected.
 __global__ void __launch_bounds__(256)
 k_pack_weights_tail(const float* __restrict__ w, float* __restrict__ wp, int f, int fo, int kz, int ky, int kx,
-                    int backward, int NJ, int nchunk)
+                    int backward, int NJ, int jgroups, int nchunk, int tail)
 {
     const int taps = kz * ky * kx;
-    const int WT = NJ * 64 + conv::kTailPacked;
-    const long total = (long)nchunk * taps * WT;
+    const int WT = NJ * 64 + (tail ? conv::kTailPacked : 0);
+    const long total = (long)jgroups * nchunk * taps * WT;
     const long t = (long)blockIdx.x * 256 + threadIdx.x;
     if (t >= total) return;
     const int e = (int)(t % WT);
     long r = t / WT;
-    const int tap = (int)(r % taps);
-    const int ic = (int)(r / taps);
+    const int tap = (int)(r % taps); r /= taps;
+    const int ic = (int)(r % nchunk);
+    const int jg = (int)(r / nchunk);
     int m, k;
     if (e < NJ * 64) {
-        m = (e / 64) * 16 + (e & 15);
+        m = (jg * NJ + e / 64) * 16 + (e & 15);
         k = ic * 4 + ((e & 63) >> 4);
     } else {
         m = NJ * 16 + (e - NJ * 64) / 4;
@@ -103,12 +72,6 @@ k_conv_reduce(const float* __restrict__ partial, float* __restrict__ dst, long c
     float acc = partial[t];
     for (int s = 1; s < splits; ++s) acc += partial[(long)s * count + t];
     dst[t] = acc;
-}
-
-// Instances exist for 1..8 map tiles and 2, 4..8 voxel tiles per wave with at most 40 accumulator tiles.
-bool have_kernel(int nj, int nv)
-{
-    return nj >= 1 && nj <= 8 && (nv == 2 || nv == 4 || (nv >= 5 && nv <= 8 && nj * nv <= 40));
 }
 
 // Taps along x are walked in groups of U (direct_mfma_impl.h): the widest divisor of the
@@ -145,16 +108,16 @@ bool tail_applies(int fM, long svol)
     return !tuning().conv_no_tail && fM > 16 && fM / 16 <= 7 && r >= 1 && r <= conv::kTailMaps && svol * 16 < (1L << 32);
 }
 
-ConvFn pick_kernel(int U, int nj, int nv, bool wl)
+ConvFn pick_plain_kernel(int U, int nj, int nv, bool wl)
 {
     switch (U) {
-        case 1: return conv_kernel_u1(nj, nv, wl);
-        case 2: return conv_kernel_u2(nj, nv, wl);
-        case 3: return conv_kernel_u3(nj, nv, wl);
-        case 4: return conv_kernel_u4(nj, nv, wl);
-        case 5: return conv_kernel_u5(nj, nv, wl);
-        case 7: return conv_kernel_u7(nj, nv, wl);
-        case 11: return conv_kernel_u11(nj, nv, wl);
+        case 1: return conv_plain_kernel_u1(nj, nv, wl);
+        case 2: return conv_plain_kernel_u2(nj, nv, wl);
+        case 3: return conv_plain_kernel_u3(nj, nv, wl);
+        case 4: return conv_plain_kernel_u4(nj, nv, wl);
+        case 5: return conv_plain_kernel_u5(nj, nv, wl);
+        case 7: return conv_plain_kernel_u7(nj, nv, wl);
+        case 11: return conv_plain_kernel_u11(nj, nv, wl);
     }
     return nullptr;
 }
@@ -171,7 +134,7 @@ struct TileChoice {
     int Tz, Ty, Tx, HZ, HY, HX, MS;
     int cz, cy, cx;
     bool wl, dbuf;
-    bool tail;          // NJ full tiles and an 8-map block (direct_mfma_tail_impl.h); halo maps interleaved in LDS
+    bool tail;          // NJ full tiles and an 8-map block (direct_mfma_tail_impl.h)
     int cps, splits;    // input-map chunks per workgroup and number of such shares
     size_t lds;
 };
@@ -209,7 +172,7 @@ TileChoice search_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, i
     const int nvs[6] = {2, 4, 5, 6, 7, 8};
     for (int ni = 0; ni < 6; ++ni) {
         const int NV = nvs[ni];
-        if (tail ? !conv::tail_instance(NJ, NV) : !have_kernel(NJ, NV)) continue;
+        if (tail ? !conv::tail_instance(NJ, NV) : !conv::plain_instance(NJ, NV)) continue;
         if (pin[0] && NV != pin[0]) continue;
         const int cap = 64 * NV;
         for (int Tx = 1; Tx <= dx && Tx <= cap; ++Tx) {
@@ -224,8 +187,7 @@ TileChoice search_tile(int fM, int fK, int dz, int dy, int dx, int kz, int ky, i
                 const int HZ = Tz + spz * (kz - 1), HY = Ty + spy * (ky - 1), HX = Tx + spx * (kx - 1);
                 long hvol = (long)HZ * HY * HX;
                 long MS = hvol;
-                if (tail) MS = (MS + 15) & ~15L;        // whole 64-word spans of 16 voxels x 4 maps
-                else while (MS % 32 != 16) ++MS;
+                MS = (MS + 15) & ~15L;      // whole 64-word spans of 16 voxels x 4 maps
                 const bool wl = weights_in_lds(taps, NJ, tail);
                 // halo buffers (two that take turns if they fit, else one), the loader's table (one
                 // map's box, padded to the workgroup size), the chunk's weights
@@ -320,9 +282,9 @@ TileChoice choose_for(const Geom& g, bool backward)
 bool mfma_conv_supported(const Geom& g, bool backward)
 {
     const TileChoice c = choose_for(g, backward);
-    // the halo loader addresses a source map with a signed 32-bit byte offset
     const long svol = backward ? g.ovol() : g.nvol();
-    return c.ok && svol < (1L << 29);
+    // the halo loader addresses the chunk's four source maps with one 32-bit byte offset
+    return c.ok && svol < (1L << 28);
 }
 
 size_t mfma_conv_workspace(const Geom& g, bool backward)
@@ -368,19 +330,15 @@ int mfma_conv(const Geom& g, bool backward, const float* src, const float* w, fl
     float* wp = (float*)ws;
     P.wp = wp;
     P.partial = (float*)((char*)ws + packed_bytes(c, P.fK, taps));
-    if (c.tail) {
-        const long total = (long)P.nchunk * taps * (c.NJ * 64 + conv::kTailPacked);
+    {
+        const long total = (long)c.jgroups * P.nchunk * taps * (c.NJ * 64 + (c.tail ? conv::kTailPacked : 0));
         ZNN_LAUNCH("weight packing", s, k_pack_weights_tail, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
-                   w, wp, g.f, g.fo, g.kz, g.ky, g.kx, backward ? 1 : 0, c.NJ, P.nchunk);
-    } else {
-        const long total = (long)c.jgroups * P.nchunk * taps * c.NJ * 64;
-        ZNN_LAUNCH("weight packing", s, k_pack_weights, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
-                   w, wp, g.f, g.fo, g.kz, g.ky, g.kx, backward ? 1 : 0, c.NJ, c.jgroups, P.nchunk);
+                   w, wp, g.f, g.fo, g.kz, g.ky, g.kx, backward ? 1 : 0, c.NJ, c.jgroups, P.nchunk, c.tail ? 1 : 0);
     }
     int rc = check_launch("weight packing");
     if (rc != ZNN_OK) return rc;
     const int U = group_width(g.kx, g.spx);
-    ConvFn fn = c.tail ? pick_tail_kernel(U, c.NJ, c.NV, c.wl) : pick_kernel(U, c.NJ, c.NV, c.wl);
+    ConvFn fn = c.tail ? pick_tail_kernel(U, c.NJ, c.NV, c.wl) : pick_plain_kernel(U, c.NJ, c.NV, c.wl);
     if (!fn) return fail(ZNN_EUNSUPPORTED, "no kernel instance for tile %dx%d", c.NJ, c.NV);
     const long blocks = (long)c.cz * c.cy * c.cx;
     if (blocks >= 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many tiles for one launch");

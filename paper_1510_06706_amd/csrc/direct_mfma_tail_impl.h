@@ -1,26 +1,22 @@
-// Direct method, forward and backward pass, for layers whose number of output-side maps is
-// 16 q + r with 1 <= r <= 8 (40, 88, 120, ...): the variant of the kernel in direct_mfma_impl.h
-// that does not pad the last r maps to a 16-row tile.
+// Kernel of the direct method's forward and backward pass (see direct_mfma_impl.h for the tile scheme and
+// the tap loop), shared by the translation units that instantiate it for one x-tap group width each.
 //
-//   maps 0 .. 16 q - 1     v_mfma_f32_16x16x4_f32       as in direct_mfma_impl.h (m: 16 maps, n: 16 voxels,
-//                                                       k: the chunk's 4 input maps)
-//   maps 16 q .. 16 q + 7  v_mfma_f32_4x4x1_16B_f32     16 independent 4x4 outer products per instruction:
-//                                                       block (mt, nt) = 4 maps x 4 voxels, mt < 2, nt < 8,
-//                                                       i.e. 8 maps x 32 voxels (two voxel tiles) and ONE
+//   full 16-map tiles      v_mfma_f32_16x16x4_f32       m: 16 maps, n: 16 voxels, k: the chunk's 4 input maps
+//   the last 1..8 maps of  v_mfma_f32_4x4x1_16B_f32     16 independent 4x4 outer products per instruction:
+//   a count 16 q + r,                                   block (mt, nt) = 4 maps x 4 voxels, mt < 2, nt < 8,
+//   r <= 8 (TAIL)                                       i.e. 8 maps x 32 voxels (two voxel tiles) and ONE
 //                                                       input map; four instructions cover the chunk
 //
 // Both forms run at the same peak rate per multiply-add, so the eight maps cost 8/16 of a padded
-// tile.  What the second form needs: its B operand holds for lane (block, v) the voxel nt*4 + v of
-// one input map, its A operand for lane (block, m) the weight of map mt*4 + m.  The halo box is
-// therefore staged with the chunk's four maps interleaved, word = 4 * voxel + map: a lane gets
-// the four maps of its voxel with one 16-byte LDS read (one register per instruction), and the
-// 16x16x4 operand (lane = map * 16 + voxel) reads 64 consecutive words for 16 consecutive voxels.
-// The packed weights carry, behind the full tiles of every tap, 8 maps x 4 input maps for the
+// tile (40, 88, 120 maps: no padding left).  What the second form needs: its B operand holds for lane
+// (block, v) the voxel nt*4 + v of one input map, its A operand for lane (block, m) the weight of map
+// mt*4 + m.  The halo box is therefore staged with the chunk's four maps interleaved, word = 4 * voxel + map:
+// a lane gets the four maps of its voxel with one 16-byte LDS read (one register per instruction), and the
+// 16x16x4 operand (lane = map * 16 + voxel) reads 64 consecutive words for 16 consecutive voxels, which
+// spreads over the LDS banks whatever the box (a map-major box needs a stride that keeps the four maps
+// apart in the banks and still collided; layers of full tiles only gained 9 % from the change of layout
+// alone).  The packed weights carry, behind the full tiles of every tap, 8 maps x 4 input maps for the
 // same kind of read.
-//
-// Everything else (tap groups of U neighbours along x, scalar tap walk, two operand sets that take
-// turns, halo fetch by global -> LDS loads with a precomputed offset table) follows
-// direct_mfma_impl.h.
 #pragma once
 
 #include "direct_mfma_impl.h"
@@ -40,12 +36,11 @@ constexpr int kTailPacked = kTailMaps * 4;      // floats behind the full tiles 
 // One tap: the MFMAs of the current operand set with the LDS reads of the next tap's 16x16x4 operands
 // dealt between them.  The 4x4x1 voxel operands `bt` of THIS tap were requested just before the call
 // and arrive while the full tiles run.
-template <int NJ, int NV>
-__device__ __forceinline__ void tap_mfmas_tail(floatx4 (&acc)[NJ][NV], floatx4 (&accT)[(NV + 1) / 2], const float (&a)[NJ],
-                                               const float (&b)[NV], const floatx4& at, const floatx4 (&bt)[(NV + 1) / 2],
+template <int NJ, int NV, int NP>
+__device__ __forceinline__ void tap_mfmas_tail(floatx4 (&acc)[NJ][NV], floatx4 (&accT)[NP ? NP : 1], const float (&a)[NJ],
+                                               const float (&b)[NV], const floatx4& at, const floatx4 (&bt)[NP ? NP : 1],
                                                float (&bn)[NV], const lds_bytes (&vb)[NV], int imm)
 {
-    constexpr int NP = (NV + 1) / 2;
 #pragma unroll
     for (int jt = 0; jt < NJ; ++jt) {
 #pragma unroll
@@ -64,16 +59,16 @@ __device__ __forceinline__ void tap_mfmas_tail(floatx4 (&acc)[NJ][NV], floatx4 (
 // The U taps of one group (see group_step in direct_mfma_impl.h).  wlo: the lane's index into the
 // group's full-tile weights, wto: into its 8-map block (LDS copy of the chunk's weights when WL; else
 // the packed weights are read from global memory at wg, the group's first tap).
-template <int NJ, int NV, bool WL, int U, int PAR>
-__device__ __forceinline__ void group_step_tail(floatx4 (&acc)[NJ][NV], floatx4 (&accT)[(NV + 1) / 2], float (&a0)[NJ],
+template <int NJ, int NV, int NP, bool WL, int U, int PAR>
+__device__ __forceinline__ void group_step_tail(floatx4 (&acc)[NJ][NV], floatx4 (&accT)[NP ? NP : 1], float (&a0)[NJ],
                                                 float (&b0)[NV], floatx4& at0, float (&a1)[NJ], float (&b1)[NV],
-                                                floatx4& at1, lds_bytes (&vb)[NV], lds_bytes (&vbT)[(NV + 1) / 2],
-                                                const lds_bytes (&voff)[NV], const lds_bytes (&voffT)[(NV + 1) / 2],
+                                                floatx4& at1, lds_bytes (&vb)[NV], lds_bytes (&vbT)[NP ? NP : 1],
+                                                const lds_bytes (&voff)[NV], const lds_bytes (&voffT)[NP ? NP : 1],
                                                 const float*& wg, const float* wl, int& wlo, int& wto, unsigned lane,
                                                 unsigned tl4, int o_next, bool advance)
 {
-    constexpr int WT = NJ * 64 + kTailPacked;
-    constexpr int NP = (NV + 1) / 2;
+    constexpr bool TAIL = NP > 0;
+    constexpr int WT = NJ * 64 + (TAIL ? kTailPacked : 0);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const bool odd = ((PAR + u) & 1) != 0;
@@ -83,17 +78,18 @@ __device__ __forceinline__ void group_step_tail(floatx4 (&acc)[NJ][NV], floatx4 
         float (&an)[NJ] = odd ? a0 : a1;
         float (&bn)[NV] = odd ? b0 : b1;
         floatx4& atn = odd ? at0 : at1;
-        floatx4 bt[NP];
+        floatx4 bt[NP ? NP : 1];
 #pragma unroll
         for (int pr = 0; pr < NP; ++pr) bt[pr] = *reinterpret_cast<lds_float4p>(vbT[pr] + (U - 1 - u) * 16);
         if (u + 1 < U) {
             const float* wtap = wg + (u + 1) * WT;      // uniform
 #pragma unroll
             for (int jt = 0; jt < NJ; ++jt) an[jt] = WL ? wl[wlo + (u + 1) * WT + jt * 64] : wtap[jt * 64 + lane];
-            atn = WL ? *reinterpret_cast<const floatx4*>(wl + wto + (u + 1) * WT)
-                     : *reinterpret_cast<const floatx4*>(wtap + NJ * 64 + tl4);
+            if constexpr (TAIL)
+                atn = WL ? *reinterpret_cast<const floatx4*>(wl + wto + (u + 1) * WT)
+                         : *reinterpret_cast<const floatx4*>(wtap + NJ * 64 + tl4);
             __builtin_amdgcn_sched_barrier(0);
-            tap_mfmas_tail<NJ, NV>(acc, accT, ac, bc, atc, bt, bn, vb, U - 2 - u);
+            tap_mfmas_tail<NJ, NV, NP>(acc, accT, ac, bc, atc, bt, bn, vb, U - 2 - u);
         } else {
             if (advance) {
                 wg += U * WT;
@@ -103,22 +99,25 @@ __device__ __forceinline__ void group_step_tail(floatx4 (&acc)[NJ][NV], floatx4 
             for (int nv = 0; nv < NV; ++nv) vb[nv] = voff[nv] + o_next * 16;
 #pragma unroll
             for (int jt = 0; jt < NJ; ++jt) an[jt] = WL ? wl[wlo + jt * 64] : wg[jt * 64 + lane];
-            atn = WL ? *reinterpret_cast<const floatx4*>(wl + wto) : *reinterpret_cast<const floatx4*>(wg + NJ * 64 + tl4);
+            if constexpr (TAIL)
+                atn = WL ? *reinterpret_cast<const floatx4*>(wl + wto) : *reinterpret_cast<const floatx4*>(wg + NJ * 64 + tl4);
             __builtin_amdgcn_sched_barrier(0);
-            tap_mfmas_tail<NJ, NV>(acc, accT, ac, bc, atc, bt, bn, vb, U - 1);
+            tap_mfmas_tail<NJ, NV, NP>(acc, accT, ac, bc, atc, bt, bn, vb, U - 1);
 #pragma unroll
             for (int pr = 0; pr < NP; ++pr) vbT[pr] = voffT[pr] + o_next * 16;
         }
     }
 }
 
-// NJ full 16-map tiles plus the 8-map block; NV voxel tiles per wave.  P.MS is the halo box
-// rounded up to 16 voxels; a halo buffer holds 4 * P.MS words.
-template <int NJ, int NV, bool WL, int U>
+// NJ full 16-map tiles, plus the 8-map block when TAIL; NV voxel tiles per wave.  P.MS is the halo box
+// rounded up to 16 voxels; a halo buffer holds 4 * P.MS words.  Without the block, gridDim.y groups of
+// NJ tiles cover more than 128 maps.
+template <int NJ, int NV, bool WL, int U, bool TAIL>
 __global__ void __launch_bounds__(256, 2) k_conv_mfma_tail(ConvTile P)
 {
-    constexpr int NP = (NV + 1) / 2;
-    constexpr int WT = NJ * 64 + kTailPacked;
+    constexpr int NP = TAIL ? (NV + 1) / 2 : 0;
+    constexpr int NPA = NP ? NP : 1;
+    constexpr int WT = NJ * 64 + (TAIL ? kTailPacked : 0);
     extern __shared__ __attribute__((aligned(16))) float lds4[];
     float* lds = lds4;
     const int taps = P.kz * P.ky * P.kx;
@@ -149,13 +148,13 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma_tail(ConvTile P)
     };
     auto pair_live = [&](int pr) { return 2 * pr + 1 < NV || tv32 < 16; };
     const lds_bytes lbase = (lds_bytes)lds;
-    lds_bytes voff[NV], voffT[NP];
+    lds_bytes voff[NV], voffT[NPA];
 #pragma unroll
     for (int nv = 0; nv < NV; ++nv) voff[nv] = lbase + (halo_byte((wave * NV + nv) * 16 + col) + grp * 4);
 #pragma unroll
     for (int pr = 0; pr < NP; ++pr) voffT[pr] = lbase + (pair_live(pr) ? halo_byte((wave * NV + 2 * pr) * 16 + tv32) : 0);
 
-    floatx4 acc[NJ][NV], accT[NP];
+    floatx4 acc[NJ][NV], accT[NPA];
 #pragma unroll
     for (int jt = 0; jt < NJ; ++jt)
 #pragma unroll
@@ -167,7 +166,8 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma_tail(ConvTile P)
     const long splane = (long)P.sy * P.sx;
     const long svol = (long)P.sz * splane;
     const int ic0 = blockIdx.z * P.cps, ic1 = min(P.nchunk, ic0 + P.cps);
-    const float* wq = P.wp + (long)ic0 * taps * WT;      // uniform
+    const int jg = blockIdx.y;
+    const float* wq = P.wp + ((long)jg * P.nchunk + ic0) * taps * WT;      // uniform
     const int groups_per_row = P.kx / U;
     const int ngroups = P.kz * P.ky * groups_per_row;
 
@@ -230,7 +230,7 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma_tail(ConvTile P)
 
         float a0[NJ], b0[NV], a1[NJ], b1[NV];
         floatx4 at0, at1;
-        lds_bytes vb[NV], vbT[NP];
+        lds_bytes vb[NV], vbT[NPA];
         GroupWalk<U> walk;
         walk.start(P);
         walk.o += cur * P.MS;               // in voxels; a voxel is four words
@@ -243,7 +243,10 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma_tail(ConvTile P)
         for (int pr = 0; pr < NP; ++pr) vbT[pr] = voffT[pr] + walk.o * 16;
 #pragma unroll
         for (int jt = 0; jt < NJ; ++jt) a0[jt] = WL ? wl[wlo + jt * 64] : wg[jt * 64 + lane];
-        at0 = WL ? *reinterpret_cast<const floatx4*>(wl + wto) : *reinterpret_cast<const floatx4*>(wg + NJ * 64 + tl4);
+        if constexpr (TAIL)
+            at0 = WL ? *reinterpret_cast<const floatx4*>(wl + wto) : *reinterpret_cast<const floatx4*>(wg + NJ * 64 + tl4);
+        else
+            at0 = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int nv = 0; nv < NV; ++nv) b0[nv] = *reinterpret_cast<lds_floatp>(vb[nv] + (U - 1) * 16);
         at1 = at0;
@@ -251,16 +254,16 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma_tail(ConvTile P)
         int g = 0;
         for (; g + 2 <= ngroups; g += 2) {
             walk.o += walk.step(P, groups_per_row);
-            group_step_tail<NJ, NV, WL, U, 0>(acc, accT, a0, b0, at0, a1, b1, at1, vb, vbT, voff, voffT, wg, wl, wlo,
+            group_step_tail<NJ, NV, NP, WL, U, 0>(acc, accT, a0, b0, at0, a1, b1, at1, vb, vbT, voff, voffT, wg, wl, wlo,
                                               wto, lane, tl4, walk.o, true);
             const bool more = g + 2 < ngroups;
             walk.o += more ? walk.step(P, groups_per_row) : 0;
-            group_step_tail<NJ, NV, WL, U, (U & 1)>(acc, accT, a0, b0, at0, a1, b1, at1, vb, vbT, voff, voffT, wg, wl,
+            group_step_tail<NJ, NV, NP, WL, U, (U & 1)>(acc, accT, a0, b0, at0, a1, b1, at1, vb, vbT, voff, voffT, wg, wl,
                                                     wlo, wto, lane, tl4, walk.o, more);
             asm volatile("" ::: "memory");
         }
         if (g < ngroups)
-            group_step_tail<NJ, NV, WL, U, 0>(acc, accT, a0, b0, at0, a1, b1, at1, vb, vbT, voff, voffT, wg, wl, wlo,
+            group_step_tail<NJ, NV, NP, WL, U, 0>(acc, accT, a0, b0, at0, a1, b1, at1, vb, vbT, voff, voffT, wg, wl, wlo,
                                               wto, lane, tl4, walk.o, false);
         wq += (long)taps * WT;
     }
@@ -283,7 +286,10 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma_tail(ConvTile P)
 #pragma unroll
         for (int jt = 0; jt < NJ; ++jt)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) out[(long)(jt * 16 + grp * 4 + r) * dvol + vox] = acc[jt][nv][r];
+            for (int r = 0; r < 4; ++r) {
+                const int j = (jg * NJ + jt) * 16 + grp * 4 + r;
+                if (TAIL || j < P.fM) out[(long)j * dvol + vox] = acc[jt][nv][r];
+            }
     }
     // 4x4x1: lane (block (mt, nt), v) holds maps mt*4 + r of voxel nt*4 + v
 #pragma unroll
@@ -298,47 +304,60 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma_tail(ConvTile P)
     }
 }
 
-// Instances: 1..7 full tiles, 4 to 8 voxel tiles per wave, within the register budget of two
-// workgroups per compute unit (more than 28 accumulator tiles spill).
+// Instances.  With the block: 1..7 full tiles, 4 to 8 voxel tiles per wave, at most 28 accumulator tiles (more
+// spill registers at two workgroups per compute unit).  Without: 1..8 tiles, 2 or 4..8 voxel tiles, at most 32.
 constexpr bool tail_instance(int nj, int nv)
 {
     return nj >= 1 && nj <= 7 && nv >= 4 && nv <= 8 && nj * nv <= 28;
 }
+constexpr bool plain_instance(int nj, int nv)
+{
+    return nj >= 1 && nj <= 8 && (nv == 2 || (nv >= 4 && nv <= 8)) && (nv <= 4 || nj * nv <= 32);
+}
 
-template <int NJ, bool WL, int U> ConvFn pick_tail_nv(int nv)
+template <int NJ, int NV, bool WL, int U, bool TAIL> ConvFn conv_instance()
+{
+    if constexpr (TAIL ? tail_instance(NJ, NV) : plain_instance(NJ, NV)) return k_conv_mfma_tail<NJ, NV, WL, U, TAIL>;
+    else return nullptr;
+}
+
+template <int NJ, bool WL, int U, bool TAIL> ConvFn pick_tail_nv(int nv)
 {
     switch (nv) {
-        case 4: if constexpr (tail_instance(NJ, 4)) return k_conv_mfma_tail<NJ, 4, WL, U>; break;
-        case 5: if constexpr (tail_instance(NJ, 5)) return k_conv_mfma_tail<NJ, 5, WL, U>; break;
-        case 6: if constexpr (tail_instance(NJ, 6)) return k_conv_mfma_tail<NJ, 6, WL, U>; break;
-        case 7: if constexpr (tail_instance(NJ, 7)) return k_conv_mfma_tail<NJ, 7, WL, U>; break;
-        case 8: if constexpr (tail_instance(NJ, 8)) return k_conv_mfma_tail<NJ, 8, WL, U>; break;
+        case 2: return conv_instance<NJ, 2, WL, U, TAIL>();
+        case 4: return conv_instance<NJ, 4, WL, U, TAIL>();
+        case 5: return conv_instance<NJ, 5, WL, U, TAIL>();
+        case 6: return conv_instance<NJ, 6, WL, U, TAIL>();
+        case 7: return conv_instance<NJ, 7, WL, U, TAIL>();
+        case 8: return conv_instance<NJ, 8, WL, U, TAIL>();
     }
     return nullptr;
 }
 
-template <bool WL, int U> ConvFn pick_tail_nj(int nj, int nv)
+template <bool WL, int U, bool TAIL> ConvFn pick_tail_nj(int nj, int nv)
 {
     switch (nj) {
-        case 1: return pick_tail_nv<1, WL, U>(nv);
-        case 2: return pick_tail_nv<2, WL, U>(nv);
-        case 3: return pick_tail_nv<3, WL, U>(nv);
-        case 4: return pick_tail_nv<4, WL, U>(nv);
-        case 5: return pick_tail_nv<5, WL, U>(nv);
-        case 6: return pick_tail_nv<6, WL, U>(nv);
-        case 7: return pick_tail_nv<7, WL, U>(nv);
+        case 1: return pick_tail_nv<1, WL, U, TAIL>(nv);
+        case 2: return pick_tail_nv<2, WL, U, TAIL>(nv);
+        case 3: return pick_tail_nv<3, WL, U, TAIL>(nv);
+        case 4: return pick_tail_nv<4, WL, U, TAIL>(nv);
+        case 5: return pick_tail_nv<5, WL, U, TAIL>(nv);
+        case 6: return pick_tail_nv<6, WL, U, TAIL>(nv);
+        case 7: return pick_tail_nv<7, WL, U, TAIL>(nv);
+        case 8: return pick_tail_nv<8, WL, U, TAIL>(nv);
     }
     return nullptr;
 }
 
-template <int U> ConvFn pick_tail_kernel(int nj, int nv, bool wl)
+template <int U, bool TAIL> ConvFn pick_tail_kernel(int nj, int nv, bool wl)
 {
-    return wl ? pick_tail_nj<true, U>(nj, nv) : pick_tail_nj<false, U>(nj, nv);
+    return wl ? pick_tail_nj<true, U, TAIL>(nj, nv) : pick_tail_nj<false, U, TAIL>(nj, nv);
 }
 
 }  // namespace conv
 
-// One definition per translation unit direct_mfma_tail_u<U>.hip.
+// One definition per translation unit direct_mfma_tail_u<U>.hip (with the 8-map block) and
+// direct_mfma_plain_u<U>.hip (without).
 conv::ConvFn conv_tail_kernel_u1(int nj, int nv, bool wl);
 conv::ConvFn conv_tail_kernel_u2(int nj, int nv, bool wl);
 conv::ConvFn conv_tail_kernel_u3(int nj, int nv, bool wl);
@@ -346,5 +365,12 @@ conv::ConvFn conv_tail_kernel_u4(int nj, int nv, bool wl);
 conv::ConvFn conv_tail_kernel_u5(int nj, int nv, bool wl);
 conv::ConvFn conv_tail_kernel_u7(int nj, int nv, bool wl);
 conv::ConvFn conv_tail_kernel_u11(int nj, int nv, bool wl);
+conv::ConvFn conv_plain_kernel_u1(int nj, int nv, bool wl);
+conv::ConvFn conv_plain_kernel_u2(int nj, int nv, bool wl);
+conv::ConvFn conv_plain_kernel_u3(int nj, int nv, bool wl);
+conv::ConvFn conv_plain_kernel_u4(int nj, int nv, bool wl);
+conv::ConvFn conv_plain_kernel_u5(int nj, int nv, bool wl);
+conv::ConvFn conv_plain_kernel_u7(int nj, int nv, bool wl);
+conv::ConvFn conv_plain_kernel_u11(int nj, int nv, bool wl);
 
 }  // namespace znn

@@ -4,6 +4,6 @@
 
 namespace znn {
 
-conv::ConvFn conv_tail_kernel_u1(int nj, int nv, bool wl) { return conv::pick_tail_kernel<1>(nj, nv, wl); }
+conv::ConvFn conv_tail_kernel_u1(int nj, int nv, bool wl) { return conv::pick_tail_kernel<1, true>(nj, nv, wl); }
 
 }  // namespace znn

@@ -4,6 +4,6 @@
 
 namespace znn {
 
-conv::ConvFn conv_tail_kernel_u2(int nj, int nv, bool wl) { return conv::pick_tail_kernel<2>(nj, nv, wl); }
+conv::ConvFn conv_tail_kernel_u2(int nj, int nv, bool wl) { return conv::pick_tail_kernel<2, true>(nj, nv, wl); }
 
 }  // namespace znn

@@ -4,6 +4,6 @@
 
 namespace znn {
 
-conv::ConvFn conv_tail_kernel_u3(int nj, int nv, bool wl) { return conv::pick_tail_kernel<3>(nj, nv, wl); }
+conv::ConvFn conv_tail_kernel_u3(int nj, int nv, bool wl) { return conv::pick_tail_kernel<3, true>(nj, nv, wl); }
 
 }  // namespace znn

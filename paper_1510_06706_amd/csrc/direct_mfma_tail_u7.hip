@@ -4,6 +4,6 @@
 
 namespace znn {
 
-conv::ConvFn conv_tail_kernel_u7(int nj, int nv, bool wl) { return conv::pick_tail_kernel<7>(nj, nv, wl); }
+conv::ConvFn conv_tail_kernel_u7(int nj, int nv, bool wl) { return conv::pick_tail_kernel<7, true>(nj, nv, wl); }
 
 }  // namespace znn
