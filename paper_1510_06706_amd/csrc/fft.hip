@@ -901,7 +901,7 @@ int launch_wgrad_dft_k(int f, int fo, int N, int tz, long plane, long vol, const
     // Planes that fill their last chunk of 256 pencils badly (the 2D benchmark layer: 129 of 256) are walked
     // with a flat (pair block, pencil) index instead of one chunk per workgroup; large planes keep the
     // chunked order, whose super-tiles keep a chunk's spectra in one XCD's L2.
-    const int flat = (double)plane < 0.9 * (double)(pchunks * kThreads) ? 1 : 0;
+    const int flat = (double)plane < 0.95 * (double)(pchunks * kThreads) ? 1 : 0;
     const long blocks = flat ? ((long)jblocks * iblocks * plane + kThreads - 1) / kThreads : ((tiles + 7) / 8) * 8 * kTileJ * kTileI;
     if (blocks >= 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many edges or pencils for one launch");
     const dim3 grid((unsigned)blocks);
