@@ -86,7 +86,7 @@ const Tuning& tuning()
         v.wgrad_maxnj = num("ZNN_WGRAD_MAXNJ", 6);
         if (v.wgrad_maxnj < 1 || v.wgrad_maxnj > 8) v.wgrad_maxnj = 6;
         v.wgrad_own_columns_from = num("ZNN_WGRAD_OWN_COLUMNS_FROM", 16);
-        v.wgrad_own_waves = num("ZNN_WGRAD_OWN_WAVES", 8) == 4 ? 4 : 8;
+        v.wgrad_own_waves = num("ZNN_WGRAD_OWN_WAVES", 4) == 8 ? 8 : 4;
         v.wgrad_stride_mod = num("ZNN_WGRAD_STRIDE_MOD", 4);
         if (v.wgrad_stride_mod < 0 || v.wgrad_stride_mod > 28 || v.wgrad_stride_mod % 4) v.wgrad_stride_mod = 4;
         v.wgrad_slow_loader = flag("ZNN_WGRAD_SLOW_LOADER");
