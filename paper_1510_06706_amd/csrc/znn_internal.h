@@ -87,6 +87,7 @@ struct Tuning {
     bool fft_mac_valu;          // ZNN_FFT_MAC_VALU: folded multiply-accumulate on the vector ALUs only
     bool fft_wgrad_plain;       // ZNN_FFT_WGRAD_PLAIN: per-z pruned DFT instead of the radix-4 grouped one
     bool fft_no_fused_xy;       // ZNN_FFT_NO_FUSED_XY: separate x and y passes even where one launch can take both
+    bool fft_no_two_level;      // ZNN_FFT_NO_TWO_LEVEL: 256-point strided passes through the LDS radix passes
     bool fft_no_taps_pass;      // ZNN_FFT_NO_TAPS_PASS: kernels take the general fused x/y pass
     int  fft_lds_kb;            // ZNN_FFT_LDS_KB: LDS per workgroup of the LDS passes (pencils per workgroup follow); 0 = per pass kind
     bool fft_lds_passes;        // ZNN_FFT_LDS_PASSES: LDS passes instead of register passes

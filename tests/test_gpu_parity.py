@@ -48,6 +48,8 @@ SMALL = [
     (1, 2, (3, 128, 256), (2, 5, 3)),     # long pencils: radix-16 and radix-8 LDS passes (256 = 16 x 16, 128 = 16 x 8)
     (2, 1, (1, 192, 160), (1, 3, 3)),     # 192 = 16 x 4 x 3, 160 = 16 x 2 x 5
     (1, 1, (1, 120, 104), (1, 2, 2)),     # 120 = 8 x 3 x 5, 104 -> 108 = 4 x 3 x 3 x 3
+    (2, 2, (1, 253, 20), (1, 4, 3)),      # y extent 256: two-level strided pass, zero-extended, ragged pencil chunk
+    (1, 2, (256, 5, 6), (3, 2, 2)),       # z extent 256
 ]
 
 
