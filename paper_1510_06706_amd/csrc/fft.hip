@@ -451,60 +451,6 @@ __global__ void __launch_bounds__(kThreads) k_fft_axis(AxisParams P)
     }
 }
 
-// ---------------------------------------------------------------- strided axis of length 256, two levels
-// 256 = 16 x 16: a thread keeps 16 samples of a pencil in registers at both levels, so the pencil makes ONE
-// trip through LDS and the workgroup meets at ONE barrier (the radix passes above: load, two passes, store,
-// four barriers, every element through LDS three times).  With n = n1 + 16 n2 and k = 16 k1 + k2,
-//   X[16 k1 + k2] = sum_n1 w16^(n1 k1) w256^(n1 k2) [ sum_n2 x[n1 + 16 n2] w16^(n2 k2) ].
-// 16 neighbouring pencils per workgroup (128 contiguous bytes per element row); thread (n1, pencil) loads its
-// samples straight from global memory, transforms over n2, multiplies by w256^(n1 k2) and parks the result in
-// LDS; thread (k2, pencil) then transforms over n1 and stores.  Same pruning of zero inputs and unwanted
-// outputs as k_fft_axis.  Plain input only (no product), consecutive elements.
-template <int DIR>
-__global__ void __launch_bounds__(kThreads) k_fft_axis256(AxisParams P)
-{
-    constexpr int W = 16, Wp = 17;
-    __shared__ float2 buf[256 * Wp];
-    __shared__ float2 tw[256];
-    make_twiddles(tw, 256, DIR);
-    const unsigned blk = blockIdx.x;
-    unsigned o = fdiv(blk, P.fchunks);
-    const int chunk = (int)(blk - o * P.chunks);
-    const unsigned o2 = fdiv(o, P.foc);
-    const int oc = (int)(o - o2 * P.Oc);
-    const int oa = (int)fdiv(o2, P.fob);
-    const int ob = (int)(o2 - (unsigned)oa * P.Ob);
-    const int p0 = chunk * W;
-    const int p = threadIdx.x & 15, hi = threadIdx.x >> 4;     // pencil of the chunk; n1 at the first level, k2 at the second
-    const bool live = p0 + p < P.L;
-    const float2* in = P.in + (oa * P.in_sa + ob * P.in_sb + oc * P.in_sc) + p0 + p;
-    float2 v[16];
-#pragma unroll
-    for (int n2 = 0; n2 < 16; ++n2) {
-        const int e = hi + 16 * n2;
-        v[n2] = (live && e >= P.i0 && e < P.i0 + P.ni) ? in[e * P.in_stride] : make_float2(0.f, 0.f);
-    }
-    dft16<DIR>(v);
-    __syncthreads();        // the twiddles are in place
-#pragma unroll
-    for (int k2 = 0; k2 < 16; ++k2) {
-        const float2 t = k2 == 0 ? v[0] : cmul(v[k2], tw[(hi * k2) & 255]);
-        buf[(hi * 16 + k2) * Wp + p] = t;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int n1 = 0; n1 < 16; ++n1) v[n1] = buf[(n1 * 16 + hi) * Wp + p];
-    dft16<DIR>(v);
-    float2* out = P.out + (oa * P.out_sa + ob * P.out_sb + oc * P.out_sc) + p0 + p;
-    if (live) {
-#pragma unroll
-        for (int k1 = 0; k1 < 16; ++k1) {
-            const int k = 16 * k1 + hi;
-            if (k >= P.o0 && k < P.o0 + P.no) out[k * P.out_stride] = v[k1];
-        }
-    }
-}
-
 // ---------------------------------------------------------------- per-frequency multiply-accumulate
 // Forward:  O^[j][w]  = sum_i W^[j][i][w] I^[i][w]
 // Backward: Gin^[i][w] = sum_j conj(W^[j][i][w]) G^[j][w]
@@ -1082,20 +1028,18 @@ int launch_axis(AxisParams P, int dir, hipStream_t s)
         }
         if (R.Oa <= 65535 && (long)R.Ob * R.L * R.L < 4294967296L) return fft_axis_reg(R, dir, s);
     }
-    if (P.N == 256 && !P.in2 && P.istep == 1 && P.ostep == 1 && !tuning().fft_no_two_level) {
-        const int chunks = (P.L + 15) / 16;
-        P.chunks = chunks;
-        P.W = 16; P.Wp = 17;
-        P.fchunks = make_fastdiv((unsigned)chunks);
-        P.foc = make_fastdiv((unsigned)P.Oc);
-        P.fob = make_fastdiv((unsigned)P.Ob);
-        const long blocks = (long)P.Oa * P.Ob * P.Oc * chunks;
-        const long dmax = std::max((long)chunks, std::max((long)P.Oc, (long)P.Ob));
-        if (blocks * dmax < 4294967296L) {
-            if (dir > 0) ZNN_LAUNCH("fft axis inverse (two levels)", s, (k_fft_axis256<+1>), dim3((unsigned)blocks), dim3(kThreads), 0, P);
-            else         ZNN_LAUNCH("fft axis forward (two levels)", s, (k_fft_axis256<-1>), dim3((unsigned)blocks), dim3(kThreads), 0, P);
-            return check_launch("strided FFT pass");
-        }
+    // longer pencils that split into two factors of at most 16: two levels, samples in registers at both
+    if (!P.in2 && P.istep == 1 && P.ostep == 1 && !tuning().fft_no_two_level && !tuning().fft_lds_passes &&
+        fft_axis_two_level_supported(P.N)) {
+        TwoLevelAxis T = {};
+        T.in = P.in; T.out = P.out;
+        T.N = P.N; T.i0 = P.i0; T.ni = P.ni; T.o0 = P.o0; T.no = P.no;
+        T.in_stride = P.in_stride; T.out_stride = P.out_stride;
+        T.L = P.L; T.Oa = P.Oa; T.Ob = P.Ob; T.Oc = P.Oc;
+        T.in_sa = P.in_sa; T.in_sb = P.in_sb; T.in_sc = P.in_sc;
+        T.out_sa = P.out_sa; T.out_sb = P.out_sb; T.out_sc = P.out_sc;
+        if ((long)P.Oa * P.Ob * P.Oc * ((P.L + 15) / 16) < 4294967296L / std::max(std::max(P.Ob, P.Oc), (P.L + 15) / 16))
+            return fft_axis_two_level(T, dir, s);
     }
     // chunk width: a whole line when it fits, else a multiple of 16 pencils (128 bytes) so
     // that every chunk starts on a cache-line boundary

@@ -163,6 +163,22 @@ struct RegAxis {
 bool fft_axis_reg_supported(int N);
 int  fft_axis_reg(RegAxis P, int dir, hipStream_t s);
 
+// Strided-axis FFT passes of lengths N = N1 * N2 above the register limit, N1, N2 <= 16, in two levels with
+// the samples in registers at both (fft_two_level.hip).  Pencil (oa, ob, oc, l), l < L, has element e at
+// in + oa*in_sa + ob*in_sb + oc*in_sc + l + e*in_stride; elements outside [i0, i0+ni) are taken as zero,
+// only [o0, o0+no) are written.
+struct TwoLevelAxis {
+    const float2* in; float2* out;
+    int N, i0, ni, o0, no;
+    long in_stride, out_stride;
+    int L, Oa, Ob, Oc;
+    long in_sa, in_sb, in_sc, out_sa, out_sb, out_sc;
+    int chunks;                     // chunks of 16 neighbouring pencils per run of L (filled by the launcher)
+    FastDiv fchunks, foc, fob;
+};
+bool fft_axis_two_level_supported(int N);
+int  fft_axis_two_level(TwoLevelAxis P, int dir, hipStream_t s);
+
 // x-axis passes with one row per thread and the row's transform in registers (fft_x_reg*.hip).
 // r2c: rows of `sx` real samples (contiguous, `rows` = maps * sz * sy of them) land zero-extended from
 // offset ox in lines of N = 2 (Nxh - 1); row (map, z, y) goes to spectrum row (map, z*tz + oz, y*ty + oy).

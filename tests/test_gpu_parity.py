@@ -313,6 +313,24 @@ def test_fft_x_and_y_passes_in_one_launch_for_every_extent(N):
             p.close()
 
 
+@pytest.mark.parametrize("N", [100, 108, 120, 128, 135, 144, 150, 160, 180, 192, 225, 240, 256])
+def test_fft_strided_passes_in_two_levels_for_every_extent(N):
+    """Strided passes of lengths above the register limit that split into two factors of at most 16 keep the
+    samples in registers at both levels: every such length, along y (2D layer, ragged chunk of pencils) and
+    along z (pencils a plane apart), zero-extended inputs and cropped outputs included."""
+    print("case", N, flush=True)
+    for f, fo, n, k in ((2, 1, (1, N, 10), (1, 4, 3)), (1, 2, (N - 1, 4, 6), (5, 2, 2))):
+        cfg = synth.LayerShape("t", f, fo, n, k, 1.0, 800 + N)
+        inp, w, gout = synth.layer_tensors(cfg)
+        p = znn.Plan(f, fo, n, k, "fft")
+        assert N in p.fft_extents
+        d_in, d_w, d_g = dev(inp), dev(w), dev(gout)
+        assert rel_err(host(p.fwd(d_in, d_w)), oracle.conv3d_fwd(inp, w)) <= TOL["fft"], (n, "fwd")
+        assert rel_err(host(p.bwd(d_g, d_w)), oracle.conv3d_bwd(gout, w, n)) <= TOL["fft"], (n, "bwd")
+        assert rel_err(host(p.wgrad(d_in, d_g)), oracle.conv3d_wgrad(inp, gout)) <= TOL["fft"], (n, "wgrad")
+        p.close()
+
+
 def test_resident_kernel_spectra_give_the_same_result():
     f, fo, n, k = 6, 5, (10, 12, 9), (3, 4, 2)
     cfg = synth.LayerShape("t", f, fo, n, k, 1.0, 91)
