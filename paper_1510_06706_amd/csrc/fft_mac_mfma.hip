@@ -39,7 +39,7 @@ typedef __attribute__((address_space(3))) void* lds_ptr;
 
 constexpr int kWaves = 4;
 constexpr int kG = 2;                   // result nodes per wave
-constexpr int kTileMax = 4 * 32 * 16;   // SW * ZG <= 4
+constexpr int kTileMax = 3 * 32 * 16;   // ZG <= 3 groups of 8 z0, four quarter-period blocks, 16 p
 
 // taps of class c (a = c, c + 4, ...) and the MFMA k-steps they take (two rows per tap, four per step)
 constexpr int class_taps(int KZ, int c) { return c < KZ ? (KZ - c + 3) / 4 : 0; }
@@ -52,10 +52,9 @@ struct MacTile {
     const float2* X;        // node spectra read   [nred][N][P]
     float2* Y;              // node spectra written [nout][N][P]
     int f, fo, N, P;
-    int nslice;             // slices of ZG z0-groups along the folded axis (N / 32 / ZG)
-    int SW;                 // slices per workgroup (1, 2 or 4); the other 4 / SW waves differ in their result nodes
-    int nq;                 // p tiles * slice blocks
-    int ngroups;            // groups of (4 / SW) * G result nodes
+    int nslice;             // slices of ZG z0-groups along the folded axis (N / 32 / ZG); a workgroup takes one
+    int nq;                 // p tiles * slices
+    int ngroups;            // groups of 4 G result nodes (G per wave)
 };
 
 template <bool BWD, int KZ, int ZG>
@@ -63,7 +62,7 @@ __global__ void __launch_bounds__(64 * kWaves, 2) k_mac_mfma(MacTile T)
 {
     constexpr int G = kG;
     constexpr int NB = total_steps(KZ);
-    // Two node-spectrum tiles (SW * ZG * 32 rows x 16 p each, in the order the lanes read them) as two
+    // Two node-spectrum tiles (ZG * 32 rows x 16 p each) as two
     // separate LDS objects: the compiler then knows that the loads landing in one do not alias the
     // reads of the other and does not wait for them before those reads.
     __shared__ float2 tileA[kTileMax], tileB[kTileMax];
@@ -81,10 +80,8 @@ __global__ void __launch_bounds__(64 * kWaves, 2) k_mac_mfma(MacTile T)
     const int pt = q_ % ptiles, sb = q_ / ptiles;
     const int p0 = pt * 16;
     const bool pvalid = p0 + n < T.P;
-    const int OS = kWaves / T.SW;                       // result-node subgroups per workgroup
-    const int sl = wave % T.SW, osub = wave / T.SW;     // this wave's slice inside the block, its subgroup
-    const int zgrp0 = (sb * T.SW + sl) * ZG;            // first z0-group of this wave
-    const int o0 = (og * OS + osub) * G;
+    const int zgrp0 = sb * ZG;                          // first z0-group of this workgroup's slice
+    const int o0 = (og * kWaves + wave) * G;            // the waves differ in their result nodes
 
     // ---- A operands: twiddles of (z0-group t, class c, k-step s); lane holds A[m = lane % 16][k = lane / 16]
     float A[ZG][NB > 0 ? NB : 1];
@@ -127,33 +124,69 @@ __global__ void __launch_bounds__(64 * kWaves, 2) k_mac_mfma(MacTile T)
     const float* whf = reinterpret_cast<const float*>(T.Wh);
     const long wplane = (long)KZ * T.P * 2;             // floats per pair
 
-    // ---- node-spectrum tile: rows of the workgroup (SW slices x ZG groups x 8 z0 x 4 q) x 16 p
-    // LDS order: ((slice, t, e, q) slot) * 64 + g * 16 + n (float2), so that a wave reads a slot
-    // with one conflict-free 8-byte read per lane.  The tile travels global -> LDS directly, one
-    // dword per lane and load (no registers, no vector arithmetic beyond one address addition):
-    // thread tid fills dword tid + 256 k of the tile, k = 0, 1, ...; which spectrum element that is
-    // splits into a per-thread part, worked out once, and a part that depends on k only (scalar).
-    // Lanes beyond the last in-plane frequency never load; their words keep the zeros written here.
-    const int tile = T.SW * ZG * 32 * 16;               // float2 per buffer
+    // ---- node-spectrum tile: the rows z = 8 (first z0-group of the workgroup) + 0 .. 8 ZG - 1, + q N/4 for
+    // q = 0..3, x 16 p.  A read takes, for one e, the rows 2 g + e of an 8-row block for the four lane groups g:
+    // so within a block the rows are stored in the order 0, 2, 4, 6, 1, 3, 5, 7 (row 2 g + e at place 4 e + g) and
+    // a read covers 512 consecutive bytes, free of bank conflicts (in natural order the four rows are 256 bytes
+    // apart and share their banks).  float2 index: ((q * ZG + block) * 8 + place) * 16 + p.
+    // The tile travels global -> LDS directly (no registers): 16 bytes per lane and load where rows start on
+    // 16-byte boundaries (P even: a wave-load fills a block), else 4 bytes (two places); which spectrum element
+    // a lane fetches splits into a per-lane part, worked out once, and a part that depends on the load only
+    // (scalar).  Lanes beyond the last in-plane frequency never load; their words keep the zeros written here.
+    constexpr int kRowsQ = 8 * ZG;                      // rows per quarter-period block
+    const int tile = 4 * kRowsQ * 16;                   // float2 per buffer
     for (int i = threadIdx.x; i < tile; i += 64 * kWaves) tileA[i] = tileB[i] = make_float2(0.f, 0.f);
     if (T.N < 0) tileA[threadIdx.x] = tileB[threadIdx.x] = T.X[threadIdx.x];    // never taken: tells the optimizer that LDS holds data
     const float* xf = reinterpret_cast<const float*>(T.X);
-    unsigned xthread;                                   // byte offset of this thread's element for k = 0 inside a node spectrum
+    const bool wide = (T.P & 1) == 0;                   // uniform
+    const int zbase = sb * kRowsQ;                      // first row of the workgroup's slice (one slice per workgroup)
+    unsigned xthread;                                   // byte offset of this lane's element of load 0 inside a node spectrum
     bool xvalid;
-    {
-        const int within = threadIdx.x & 127, h = threadIdx.x >> 7;
-        const int g_ = within >> 5, nn = (within >> 1) & 15, comp = within & 1;
-        xvalid = p0 + nn < T.P;
-        xthread = (unsigned)(((long)(h * Q + sb * T.SW * ZG * 8 + 2 * g_) * T.P + p0 + nn) * 8 + comp * 4);
+    if (wide) {
+        // lane -> place lane / 8 of the block, 16-byte segment lane % 8 of the row
+        const int place = lane >> 3, pp = p0 + 2 * (lane & 7);
+        xvalid = pp < T.P;
+        xthread = (unsigned)(((long)(zbase + 2 * (place & 3) + (place >> 2)) * T.P + pp) * 8);
+    } else {
+        // lane -> place 2 (k % 4) + lane / 32 of the block (k: the load), float lane % 32 of the row
+        const int pp = p0 + ((lane & 31) >> 1);
+        xvalid = pp < T.P;
+        xthread = (unsigned)(((long)(zbase + 2 * (lane >> 5)) * T.P + pp) * 8 + (lane & 1) * 4);
     }
-    const int nloads = T.SW * ZG * 4;
     auto fetch_tile = [&](int r, float2* buf) {
         const char* xb = reinterpret_cast<const char*>(xf + (long)r * vol * 2);     // uniform
-        float* dst = reinterpret_cast<float*>(buf) + wave * 64;
-        for (int k = 0; k < nloads; ++k) {
-            const int ck = 2 * (k & 1) * Q + ((k >> 1) & 1) + 8 * (k >> 2);         // uniform
-            if (xvalid)
-                __builtin_amdgcn_global_load_lds((global_cptr)(xb + (long)ck * T.P * 8 + xthread), (lds_ptr)(dst + k * 256), 4, 0, 0);
+        float* dst = reinterpret_cast<float*>(buf);
+        // (the empty asm makes the lane's offset a value of this reduction index: otherwise the optimizer forms
+        // every load's 64-bit address once, outside the reduction loop, and keeps them all in registers, which
+        // costs the small kernels a wave of occupancy)
+        unsigned xt = xthread;
+        asm volatile("" : "+v"(xt));
+        if (wide) {
+#pragma unroll
+            for (int j = 0; j < ZG; ++j) {
+                const int k = wave + kWaves * j;                                    // uniform: block k % ZG of quarter k / ZG
+                const unsigned ck = (unsigned)(((long)(8 * (k % ZG) + (k / ZG) * Q) * T.P) * 8);
+                if (xvalid)
+                    __builtin_amdgcn_global_load_lds((global_cptr)(xb + (ck + xt)), (lds_ptr)(dst + k * 256), 16, 0, 0);
+            }
+        } else {
+            auto load_rows = [&](int j) {
+                const int k = wave + kWaves * j;                                    // uniform: places 2 (k % 4), + 1 of block k / 4
+                const int blk = k >> 2, kk = k & 3;
+                // place 2 kk + h holds row 2 ((2 kk + h) % 4) + (2 kk + h) / 4 = 4 (kk % 2) + 2 h + kk / 2
+                const unsigned ck = (unsigned)(((long)(8 * (blk % ZG) + (blk / ZG) * Q + 4 * (kk & 1) + (kk >> 1)) * T.P) * 8);
+                if (xvalid)
+                    __builtin_amdgcn_global_load_lds((global_cptr)(xb + (ck + xt)), (lds_ptr)(dst + k * 64), 4, 0, 0);
+            };
+            // four loads per wave unrolled, more of them rolled (unrolled they cost registers: a wave of occupancy
+            // for the kernels that have three)
+            if constexpr (ZG == 1) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) load_rows(j);
+            } else {
+#pragma nounroll
+                for (int j = 0; j < 4 * ZG; ++j) load_rows(j);
+            }
         }
     };
 
@@ -188,7 +221,7 @@ __global__ void __launch_bounds__(64 * kWaves, 2) k_mac_mfma(MacTile T)
     load_b(0, b0);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
-    int xo = (sl * ZG * 8) * 64 + lane;                             // this wave's slots of buffer 0, this lane's element
+    int xo = g * 16 + n;                                            // this lane's element of place g (row 2 g) of a block
 
     // one reduction index: reads the tile in `cur` while the next one lands in `nxt`
     auto reduction_step = [&](int r, const float2* cur, float2* nxt, float (&bcur)[G][NB > 0 ? NB : 1],
@@ -220,7 +253,7 @@ __global__ void __launch_bounds__(64 * kWaves, 2) k_mac_mfma(MacTile T)
 #pragma unroll
             for (int e = 0; e < 2; ++e)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) x[e][q] = myx[((t * 2 + e) * 4 + q) * 64];
+                for (int q = 0; q < 4; ++q) x[e][q] = myx[(q * kRowsQ + 8 * t + 4 * e) * 16];
         };
         floatx4 D0[4], D1[4];
         float2 x0[2][4], x1[2][4];
@@ -300,11 +333,9 @@ __global__ void __launch_bounds__(64 * kWaves, 2) k_mac_mfma(MacTile T)
 template <bool BWD, int KZ, int ZG>
 int launch_zg(MacTile T, int nout, hipStream_t s)
 {
-    const int OS = kWaves / T.SW;
-    T.ngroups = (nout + OS * kG - 1) / (OS * kG);
+    T.ngroups = (nout + kWaves * kG - 1) / (kWaves * kG);
     const long blocks = ((long)(T.nq + 7) / 8) * 8 * T.ngroups;
     if (blocks >= 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many frequencies");
-    if (T.SW * ZG * 32 * 16 > kTileMax) return fail(ZNN_EUNSUPPORTED, "node-spectrum tile does not fit its LDS buffer");
     ZNN_LAUNCH(BWD ? "spectral mac backward (taps folded in, MFMA)" : "spectral mac forward (taps folded in, MFMA)", s,
                (k_mac_mfma<BWD, KZ, ZG>), dim3((unsigned)blocks), dim3(64 * kWaves), 0, T);
     return check_launch("spectral multiply-accumulate");
@@ -370,8 +401,7 @@ int fft_mac_mfma(bool backward, int taps, int f, int fo, int N, int P, const flo
     for (int z = 3; z >= 2; --z)
         if (groups % z == 0 && per_slice * (groups / z) >= 2048) { ZG = z; break; }
     T.nslice = groups / ZG;
-    T.SW = 1;
-    T.nq = ((P + 15) / 16) * (T.nslice / T.SW);
+    T.nq = ((P + 15) / 16) * T.nslice;
     return backward ? launch_dir<true>(taps, T, ZG, nout, s) : launch_dir<false>(taps, T, ZG, nout, s);
 }
 
