@@ -95,6 +95,7 @@ const Tuning& tuning()
         v.fft_wgrad_plain = flag("ZNN_FFT_WGRAD_PLAIN");
         v.fft_no_taps_pass = flag("ZNN_FFT_NO_TAPS_PASS");
         v.fft_no_two_level = flag("ZNN_FFT_NO_TWO_LEVEL");
+        v.fft_no_mac_inverse = flag("ZNN_FFT_NO_MAC_INVERSE");
         v.fft_lds_kb = num("ZNN_FFT_LDS_KB", 0);
         if (v.fft_lds_kb < 8 || v.fft_lds_kb > 64) v.fft_lds_kb = 0;
         v.fft_no_fused_xy = flag("ZNN_FFT_NO_FUSED_XY");

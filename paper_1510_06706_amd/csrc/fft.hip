@@ -1122,9 +1122,10 @@ int forward3d(const Geom& g, const float* src, float2* spec, long maps, int sz, 
 }
 
 // Inverse 3D transform of `maps` spectra (destroyed) to real volumes cropped to
-// [c, c+d) per axis and scaled by 1/(Nz Ny Nx).
+// [c, c+d) per axis and scaled by 1/(Nz Ny Nx).  z_done: the rows [cz, cz + dz) along z hold
+// the inverse transform along z already (the multiply-accumulate applied it).
 int inverse3d(const Geom& g, float2* spec, float* dst, long maps, int cz, int cy, int cx,
-              int dz, int dy, int dx, hipStream_t s)
+              int dz, int dy, int dx, bool z_done, hipStream_t s)
 {
     const long plane = (long)g.Ny * g.Nxh, vol = g.svol();
     if (maps > 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many maps");
@@ -1136,7 +1137,7 @@ int inverse3d(const Geom& g, float2* spec, float* dst, long maps, int cz, int cy
     P.L = (int)plane;
     P.Oa = (int)maps; P.Ob = 1; P.Oc = 1;
     P.in_sa = P.out_sa = vol;
-    if (g.Nz != 1) { rc = launch_axis(P, +1, s); if (rc != ZNN_OK) return rc; }
+    if (g.Nz != 1 && !z_done) { rc = launch_axis(P, +1, s); if (rc != ZNN_OK) return rc; }
     const float scale = (float)(1.0 / ((double)g.Nz * g.Ny * g.Nx));
     if (g.Ny == g.Nx && g.Ny > 1 && !tuning().fft_lds_passes && !tuning().fft_no_fused_xy && fft_xy_reg_supported(g.Nx) &&
         cy + dy <= g.Ny && cx + dx <= g.Nx) {
@@ -1193,11 +1194,19 @@ Fold fold_search(const Geom& g, long min_blocks)
     return F;
 }
 
-int launch_mac(bool backward, const Geom& g, const Fold& F, const float2* What, const float2* a, float2* b, hipStream_t s)
+// cz, dz: the rows along z that the inverse transform of the result has to deliver; *z_done: they hold the
+// inverse transform along z already (3D layers whose folded multiply-accumulate owns the whole axis per wave).
+int launch_mac(bool backward, const Geom& g, const Fold& F, const float2* What, const float2* a, float2* b,
+               int cz, int dz, bool* z_done, hipStream_t s)
 {
+    *z_done = false;
     if (F.on) {
-        if (!tuning().fft_mac_valu && fft_mac_mfma_supported(F.taps, F.N, F.P))
-            return fft_mac_mfma(backward, F.taps, g.f, g.fo, F.N, F.P, What, a, b, s);
+        if (!tuning().fft_mac_valu && fft_mac_mfma_supported(F.taps, F.N, F.P)) {
+            const bool inv = g.Nz > 1 && !tuning().fft_no_mac_inverse &&
+                             fft_mac_mfma_can_invert(F.taps, F.N, F.P, backward ? g.f : g.fo);
+            *z_done = inv;
+            return fft_mac_mfma(backward, F.taps, g.f, g.fo, F.N, F.P, What, a, b, cz, inv ? dz : 0, s);
+        }
         return fft_mac_fused(backward, F.taps, F.z0, g.f, g.fo, F.N, F.P, What, a, b, s);
     }
     const long svol = g.svol();
@@ -1299,10 +1308,11 @@ int fft_fwd(const Geom& g, const Fold& F, const float* in, const float* w, const
         if (rc != ZNN_OK) return rc;
         What = wbuf;
     }
-    rc = launch_mac(false, g, F, What, Ihat, Ohat, s);
+    bool z_done;
+    rc = launch_mac(false, g, F, What, Ihat, Ohat, g.spz * (g.kz - 1), g.oz, &z_done, s);
     if (rc != ZNN_OK) return rc;
     return inverse3d(g, Ohat, out, g.fo, g.spz * (g.kz - 1), g.spy * (g.ky - 1), g.spx * (g.kx - 1),
-                     g.oz, g.oy, g.ox, s);
+                     g.oz, g.oy, g.ox, z_done, s);
 }
 
 int fft_bwd(const Geom& g, const Fold& F, const float* gout, const float* w, const float2* resident, float* gin,
@@ -1321,9 +1331,10 @@ int fft_bwd(const Geom& g, const Fold& F, const float* gout, const float* w, con
         if (rc != ZNN_OK) return rc;
         What = wbuf;
     }
-    rc = launch_mac(true, g, F, What, Ghat, Ginhat, s);
+    bool z_done;
+    rc = launch_mac(true, g, F, What, Ghat, Ginhat, 0, g.nz, &z_done, s);
     if (rc != ZNN_OK) return rc;
-    return inverse3d(g, Ginhat, gin, g.f, 0, 0, 0, g.nz, g.ny, g.nx, s);
+    return inverse3d(g, Ginhat, gin, g.f, 0, 0, 0, g.nz, g.ny, g.nx, z_done, s);
 }
 
 int fft_wgrad(const Geom& g, const float* in, const float* gout, float* gw, void* ws, hipStream_t s)

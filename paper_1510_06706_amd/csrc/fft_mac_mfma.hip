@@ -26,8 +26,16 @@
 // (two buffers taking turns), so a tile is fetched once for 4 G result nodes.  Workgroups that
 // differ only in their result nodes run next to each other on one XCD (see fft_mac.hip).
 //
+// Where a wave owns the whole folded axis (N = 32 ZG) the kernel can also apply the inverse transform
+// along that axis to its sums before it stores them, which saves the separate pass over the result
+// spectra: with z = q N/4 + z0 and m = m0 + 4 m1,
+//     y[m0 + 4 m1] = sum_z0 exp(+2 pi i z0 m1 / (N/4)) * exp(+2 pi i z0 m0 / N) * sum_q Y[q N/4 + z0] i^(q m0),
+// i.e. a radix-4 butterfly over the four values a lane already holds per z0, a twiddle, and N/4-point
+// transforms over z0, for which the lanes exchange their values through a wave-private piece of LDS.
+//
 // Needs N divisible by 32 and taps one voxel apart; other layers use the vector-ALU kernel.
 #include "znn_internal.h"
+#include "fft_reg_impl.h"       // passes<>: the register FFT of the strided-axis kernels
 
 namespace znn {
 
@@ -55,10 +63,15 @@ struct MacTile {
     int nslice;             // slices of ZG z0-groups along the folded axis (N / 32 / ZG); a workgroup takes one
     int nq;                 // p tiles * slices
     int ngroups;            // groups of 4 G result nodes (G per wave)
+    int zinv_o0, zinv_no;   // zinv_no > 0: store the inverse transform along the folded axis, rows [o0, o0 + no) only
 };
 
-template <bool BWD, int KZ, int ZG>
-__global__ void __launch_bounds__(64 * kWaves, 2) k_mac_mfma(MacTile T)
+// ZINV: the sums are stored transformed back along the folded axis (rows [zinv_o0, zinv_o0 + zinv_no)); the
+// host asks for it only where a wave owns the whole axis, N = 32 ZG
+// (three waves per SIMD asked for where the loop fits them: the transform at the end would otherwise be
+// given a few registers more than the loop needs and cost the kernel a wave)
+template <bool BWD, int KZ, int ZG, bool ZINV>
+__global__ void __launch_bounds__(64 * kWaves, (ZG <= 2 && KZ <= 8) ? 3 : 2) k_mac_mfma(MacTile T)
 {
     constexpr int G = kG;
     constexpr int NB = total_steps(KZ);
@@ -66,6 +79,11 @@ __global__ void __launch_bounds__(64 * kWaves, 2) k_mac_mfma(MacTile T)
     // separate LDS objects: the compiler then knows that the loads landing in one do not alias the
     // reads of the other and does not wait for them before those reads.
     __shared__ float2 tileA[kTileMax], tileB[kTileMax];
+    // for the inverse transform of the sums: per wave two blocks of N/4 (+ 1: the blocks then start in different
+    // bank halves) rows of 16 p; and exp(+2 pi i k / N)
+    constexpr int kZRows = 8 * ZG + 1;
+    __shared__ float2 zbuf[ZINV ? kWaves * 2 * kZRows * 16 : 1];
+    __shared__ float2 ztw[ZINV ? 32 * ZG : 1];
 
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int g = lane >> 4, n = lane & 15;
@@ -137,6 +155,11 @@ __global__ void __launch_bounds__(64 * kWaves, 2) k_mac_mfma(MacTile T)
     const int tile = 4 * kRowsQ * 16;                   // float2 per buffer
     for (int i = threadIdx.x; i < tile; i += 64 * kWaves) tileA[i] = tileB[i] = make_float2(0.f, 0.f);
     if (T.N < 0) tileA[threadIdx.x] = tileB[threadIdx.x] = T.X[threadIdx.x];    // never taken: tells the optimizer that LDS holds data
+    if (ZINV && (int)threadIdx.x < 32 * ZG) {
+        float sn, cs;
+        sincospif(2.0f * (float)threadIdx.x / (float)(32 * ZG), &sn, &cs);
+        ztw[threadIdx.x] = make_float2(cs, sn);
+    }
     const float* xf = reinterpret_cast<const float*>(T.X);
     const bool wide = (T.P & 1) == 0;                   // uniform
     const int zbase = sb * kRowsQ;                      // first row of the workgroup's slice (one slice per workgroup)
@@ -314,39 +337,101 @@ __global__ void __launch_bounds__(64 * kWaves, 2) k_mac_mfma(MacTile T)
         if (r + 1 < nred) reduction_step(r + 1, tileB, tileA, b1, b0);
     }
 
-    if (!pvalid) return;
+    if constexpr (ZINV) {
+        constexpr int Q4 = 8 * ZG;
+        float2* zb = zbuf + wave * (2 * kZRows * 16);
+        const int h = (lane >> 4) & 1;
 #pragma unroll
-    for (int gi = 0; gi < G; ++gi) {
-        if (o0 + gi >= nout) break;
-        float2* yb = T.Y + (long)(o0 + gi) * vol + p0 + n;
+        for (int gi = 0; gi < G; ++gi) {
+            if (o0 + gi >= nout) break;
+            float2* yb = T.Y + (long)(o0 + gi) * vol + p0 + n;
 #pragma unroll
-        for (int t = 0; t < ZG; ++t)
+            for (int mp = 0; mp < 2; ++mp) {
+                // U[z0][m0] = exp(+2 pi i z0 m0 / N) sum_q Y[q N/4 + z0] i^(q m0) for m0 = 2 mp and 2 mp + 1 and
+                // this lane's z0 = 8 t + 2 g + e into the wave's piece of LDS (row z0 at place 8 t + 4 e + g: the
+                // lane groups g then write consecutive rows); then lane (h, n), h < 2, takes the N/4 values of
+                // m0 = 2 mp + h at its p.  The LDS operations of a wave complete in the order of issue, so a
+                // round's reads see its writes and the next round's writes come after its reads.
 #pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const int z0 = (zgrp0 + t) * 8 + 2 * g + e;
+                for (int t = 0; t < ZG; ++t)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) yb[(long)(z0 + q * Q) * T.P] = acc[gi][t][e][q];
+                    for (int e = 0; e < 2; ++e) {
+                        const float2 (&y)[4] = acc[gi][t][e];
+                        const int z0 = 8 * t + 2 * g + e;
+                        float2 u0, u1;
+                        if (mp == 0) {
+                            u0 = cadd(cadd(y[0], y[2]), cadd(y[1], y[3]));
+                            const float2 d02 = csub(y[0], y[2]), d13 = csub(y[1], y[3]);
+                            u1 = make_float2(d02.x - d13.y, d02.y + d13.x);     // d02 + i d13
+                        } else {
+                            u0 = csub(cadd(y[0], y[2]), cadd(y[1], y[3]));
+                            const float2 d02 = csub(y[0], y[2]), d13 = csub(y[1], y[3]);
+                            u1 = make_float2(d02.x + d13.y, d02.y - d13.x);     // d02 - i d13
+                            const float2 w = ztw[2 * z0];
+                            u0 = make_float2(u0.x * w.x - u0.y * w.y, u0.x * w.y + u0.y * w.x);
+                        }
+                        const float2 w = ztw[(2 * mp + 1) * z0];                // z0 m0 < 3 N / 4
+                        u1 = make_float2(u1.x * w.x - u1.y * w.y, u1.x * w.y + u1.y * w.x);
+                        zb[(8 * t + 4 * e + g) * 16 + n] = u0;
+                        zb[(kZRows + 8 * t + 4 * e + g) * 16 + n] = u1;
+                    }
+                if (lane < 32) {
+                    float2 x[Q4], y[Q4];
+#pragma unroll
+                    for (int z0 = 0; z0 < Q4; ++z0)
+                        x[z0] = zb[(h * kZRows + 8 * (z0 >> 3) + 4 * (z0 & 1) + ((z0 >> 1) & 3)) * 16 + n];
+                    passes<Q4, +1, Q4, 1>(x, y);
+                    constexpr bool in_y = (count_passes(Q4) % 2) == 1;
+                    if (pvalid) {
+#pragma unroll
+                        for (int m1 = 0; m1 < Q4; ++m1) {
+                            const int z = 2 * mp + h + 4 * m1;
+                            if (z >= T.zinv_o0 && z < T.zinv_o0 + T.zinv_no) yb[(long)z * T.P] = in_y ? y[m1] : x[m1];
+                        }
+                    }
+                }
             }
+        }
+    } else {
+        if (!pvalid) return;
+#pragma unroll
+        for (int gi = 0; gi < G; ++gi) {
+            if (o0 + gi >= nout) break;
+            float2* yb = T.Y + (long)(o0 + gi) * vol + p0 + n;
+#pragma unroll
+            for (int t = 0; t < ZG; ++t)
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const int z0 = (zgrp0 + t) * 8 + 2 * g + e;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) yb[(long)(z0 + q * Q) * T.P] = acc[gi][t][e][q];
+                }
+        }
     }
 }
 
-template <bool BWD, int KZ, int ZG>
+template <bool BWD, int KZ, int ZG, bool ZINV>
 int launch_zg(MacTile T, int nout, hipStream_t s)
 {
     T.ngroups = (nout + kWaves * kG - 1) / (kWaves * kG);
     const long blocks = ((long)(T.nq + 7) / 8) * 8 * T.ngroups;
     if (blocks >= 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many frequencies");
     ZNN_LAUNCH(BWD ? "spectral mac backward (taps folded in, MFMA)" : "spectral mac forward (taps folded in, MFMA)", s,
-               (k_mac_mfma<BWD, KZ, ZG>), dim3((unsigned)blocks), dim3(64 * kWaves), 0, T);
+               (k_mac_mfma<BWD, KZ, ZG, ZINV>), dim3((unsigned)blocks), dim3(64 * kWaves), 0, T);
     return check_launch("spectral multiply-accumulate");
 }
 
 template <bool BWD, int KZ>
 int launch_kz(MacTile T, int ZG, int nout, hipStream_t s)
 {
-    if (ZG == 3) return launch_zg<BWD, KZ, 3>(T, nout, s);
-    if (ZG == 2) return launch_zg<BWD, KZ, 2>(T, nout, s);
-    return launch_zg<BWD, KZ, 1>(T, nout, s);
+    if (T.zinv_no > 0) {
+        if (ZG == 3) return launch_zg<BWD, KZ, 3, true>(T, nout, s);
+        if (ZG == 2) return launch_zg<BWD, KZ, 2, true>(T, nout, s);
+        return launch_zg<BWD, KZ, 1, true>(T, nout, s);
+    }
+    if (ZG == 3) return launch_zg<BWD, KZ, 3, false>(T, nout, s);
+    if (ZG == 2) return launch_zg<BWD, KZ, 2, false>(T, nout, s);
+    return launch_zg<BWD, KZ, 1, false>(T, nout, s);
 }
 
 template <bool BWD>
@@ -383,8 +468,31 @@ bool fft_mac_mfma_supported(int taps, int N, int P)
            (long)N * P * 8 < 4294967296L;       // a thread's byte offset inside a node spectrum fits 32 bits
 }
 
+namespace {
+
+// z0-groups per wave
+int groups_per_wave(int N, int P, int nout)
+{
+    // z0-groups per wave: as many as divide the axis (every half-spectrum element is then loaded by fewer
+    // waves) while the launch still has two waves per SIMD; small layers take fewer groups per wave instead
+    // (the 2D benchmark layer: 1440 -> 2880 waves, 0.213 -> 0.165 ms).  One slice per workgroup: its four waves
+    // then share one node-spectrum tile for eight result nodes (two slices and four nodes measured 8 % slower).
+    const int groups = N / 32;
+    const long per_slice = (long)((P + 15) / 16) * ((nout + 1) / 2);
+    for (int z = 3; z >= 2; --z)
+        if (groups % z == 0 && per_slice * (groups / z) >= 2048) return z;
+    return 1;
+}
+
+}  // namespace
+
+bool fft_mac_mfma_can_invert(int taps, int N, int P, int nout)
+{
+    return fft_mac_mfma_supported(taps, N, P) && 32 * groups_per_wave(N, P, nout) == N;
+}
+
 int fft_mac_mfma(bool backward, int taps, int f, int fo, int N, int P, const float2* Wh, const float2* X,
-                 float2* Y, hipStream_t s)
+                 float2* Y, int zinv_o0, int zinv_no, hipStream_t s)
 {
     if (!fft_mac_mfma_supported(taps, N, P)) return fail(ZNN_EUNSUPPORTED, "layer does not fit the MFMA multiply-accumulate");
     MacTile T = {};
@@ -392,14 +500,9 @@ int fft_mac_mfma(bool backward, int taps, int f, int fo, int N, int P, const flo
     T.f = f; T.fo = fo; T.N = N; T.P = P;
     const int groups = N / 32;
     const int nout = backward ? f : fo;
-    // z0-groups per wave: as many as divide the axis (every half-spectrum element is then loaded by fewer
-    // waves) while the launch still has two waves per SIMD; small layers take fewer groups per wave instead
-    // (the 2D benchmark layer: 1440 -> 2880 waves, 0.213 -> 0.165 ms).  One slice per workgroup: its four waves
-    // then share one node-spectrum tile for eight result nodes (two slices and four nodes measured 8 % slower).
-    const long per_slice = (long)((P + 15) / 16) * ((nout + 1) / 2);
-    int ZG = 1;
-    for (int z = 3; z >= 2; --z)
-        if (groups % z == 0 && per_slice * (groups / z) >= 2048) { ZG = z; break; }
+    const int ZG = groups_per_wave(N, P, nout);
+    if (zinv_no > 0 && 32 * ZG != N) return fail(ZNN_EINVAL, "a wave does not own the whole folded axis: no inverse transform in the multiply-accumulate");
+    T.zinv_o0 = zinv_o0; T.zinv_no = zinv_no > 0 ? zinv_no : 0;
     T.nslice = groups / ZG;
     T.nq = ((P + 15) / 16) * T.nslice;
     return backward ? launch_dir<true>(taps, T, ZG, nout, s) : launch_dir<false>(taps, T, ZG, nout, s);

@@ -88,6 +88,7 @@ struct Tuning {
     bool fft_wgrad_plain;       // ZNN_FFT_WGRAD_PLAIN: per-z pruned DFT instead of the radix-4 grouped one
     bool fft_no_fused_xy;       // ZNN_FFT_NO_FUSED_XY: separate x and y passes even where one launch can take both
     bool fft_no_two_level;      // ZNN_FFT_NO_TWO_LEVEL: 256-point strided passes through the LDS radix passes
+    bool fft_no_mac_inverse;    // ZNN_FFT_NO_MAC_INVERSE: inverse transform along z as a pass of its own, never inside the multiply-accumulate
     bool fft_no_taps_pass;      // ZNN_FFT_NO_TAPS_PASS: kernels take the general fused x/y pass
     int  fft_lds_kb;            // ZNN_FFT_LDS_KB: LDS per workgroup of the LDS passes (pencils per workgroup follow); 0 = per pass kind
     bool fft_lds_passes;        // ZNN_FFT_LDS_PASSES: LDS passes instead of register passes
@@ -146,8 +147,11 @@ int fft_mac_fused(bool backward, int taps, int z0, int f, int fo, int N, int P, 
 // The same with the rebuild of the kernel spectrum on the matrix cores (fft_mac_mfma.hip); takes
 // extents divisible by 32.
 bool fft_mac_mfma_supported(int taps, int N, int P);
+bool fft_mac_mfma_can_invert(int taps, int N, int P, int nout);
 int fft_mac_mfma(bool backward, int taps, int f, int fo, int N, int P, const float2* Wh, const float2* X,
-                 float2* Y, hipStream_t s);
+                 float2* Y, int zinv_o0, int zinv_no, hipStream_t s);
+// (zinv_no > 0: the rows [zinv_o0, zinv_o0 + zinv_no) of Y receive the inverse transform of the sums along
+// the folded axis instead of the sums; only where fft_mac_mfma_can_invert says so)
 
 // Strided-axis FFT pass with one pencil per thread, whole pencil in registers (fft_reg.hip).
 // Pencil (oa, ob, l), l < L, has its element e at in + oa*in_sa + ob*in_sb + l + e*stride;

@@ -331,6 +331,41 @@ def test_fft_strided_passes_in_two_levels_for_every_extent(N):
         p.close()
 
 
+@pytest.mark.parametrize("f,fo,n,k", [
+    (2, 24, (32, 12, 21), (3, 2, 4)),       # one group of eight base frequencies per wave
+    (2, 24, (64, 70, 80), (3, 3, 3)),       # two groups per wave: forward pass
+    (24, 2, (64, 70, 80), (4, 3, 2)),       # two groups per wave: backward pass
+    (2, 24, (96, 70, 80), (5, 3, 3)),       # three groups per wave (the headline layer's shape class): forward
+    (24, 2, (96, 75, 80), (7, 2, 3)),       # three groups per wave: backward, odd number of in-plane frequencies
+])
+def test_fft_multiply_accumulate_finishes_the_inverse_transform_along_z(f, fo, n, k):
+    """3D layers whose folded multiply-accumulate owns the whole z axis per wave transform their sums back along
+    z before storing them: no separate inverse pass along z is launched for that pass, cropped rows are left
+    out, and the results still match the oracle."""
+    print("case", f, fo, n, k, flush=True)
+    cfg = synth.LayerShape("t", f, fo, n, k, 1.0, 640 + f + n[0])
+    inp, w, gout = synth.layer_tensors(cfg)
+    p = znn.Plan(f, fo, n, k, "fft")
+    p.set_spectra_layout("folded")
+    d_in, d_w, d_g = dev(inp), dev(w), dev(gout)
+    znn.trace_enable(True)
+    try:
+        znn.trace_collect()
+        out = host(p.fwd(d_in, d_w))
+        names_fwd = [name for name, _ in znn.trace_collect()]
+        gin = host(p.bwd(d_g, d_w))
+        names_bwd = [name for name, _ in znn.trace_collect()]
+    finally:
+        znn.trace_enable(False)
+    fused = names_fwd if fo >= f else names_bwd
+    assert any(name.startswith("spectral mac") and "MFMA" in name for name in fused), fused
+    # y and x extents differ in all these shapes: the one strided inverse pass left is the one along y
+    assert sum(name.startswith("fft axis inverse") for name in fused) == 1, fused
+    assert rel_err(out, oracle.conv3d_fwd(inp, w)) <= TOL["fft"]
+    assert rel_err(gin, oracle.conv3d_bwd(gout, w, n)) <= TOL["fft"]
+    p.close()
+
+
 def test_resident_kernel_spectra_give_the_same_result():
     f, fo, n, k = 6, 5, (10, 12, 9), (3, 4, 2)
     cfg = synth.LayerShape("t", f, fo, n, k, 1.0, 91)
