@@ -62,26 +62,41 @@ struct ConvTile {
 using ConvFn = void (*)(ConvTile);
 
 // Walk over the tap groups of a chunk in (a, b, c-group) order, all in scalar registers.
-// `o` is the halo offset of the group's lowest-address tap (its last one).
+// `o` is the halo offset of the group's lowest-address tap (its last one).  Packed tap (a, b, c) meets the
+// halo at tap offset (kz-1-a, ky-1-b, kx-1-c).  The walk covers `na` planes and `nb` rows of taps, the ones
+// at halo offsets alpha_hi down and beta_hi down: a workgroup whose box lies at the border of a zero-extended
+// source (backward pass) leaves out the planes and rows of taps that meet nothing but the padding.
 template <int U>
 struct GroupWalk {
-    int o, gc, gb;
-    __device__ __forceinline__ void start(const ConvTile& P)
+    int o, gc, gb, nb, wrow;
+    // wrow: packed weights (floats) of the tap rows a plane of the walk leaves out
+    __device__ __forceinline__ void start(const ConvTile& P, int alpha_hi, int beta_hi, int rows, int skipped_row_floats)
     {
-        o = ((P.kz - 1) * P.spz * P.HY + (P.ky - 1) * P.spy) * P.HX + (P.kx - U) * P.spx;
-        gc = 0; gb = 0;
+        o = (alpha_hi * P.spz * P.HY + beta_hi * P.spy) * P.HX + (P.kx - U) * P.spx;
+        gc = 0; gb = 0; nb = rows; wrow = skipped_row_floats;
     }
-    __device__ __forceinline__ int step(const ConvTile& P, int groups_per_row)
+    // step to the next group: returns the change of `o`; `wd` (floats to the next group's packed weights)
+    // grows by the rows left out when the walk enters the next plane
+    __device__ __forceinline__ int step(const ConvTile& P, int groups_per_row, int& wd)
     {
         int d = -U * P.spx;
         if (++gc == groups_per_row) {
             gc = 0;
             d += P.kx * P.spx - P.spy * P.HX;
-            if (++gb == P.ky) { gb = 0; d += (P.ky * P.spy - P.spz * P.HY) * P.HX; }
+            if (++gb == nb) { gb = 0; d += (nb * P.spy - P.spz * P.HY) * P.HX; wd += wrow; }
         }
         return d;
     }
 };
+
+// Range [lo, hi] of tap offsets t (in taps, `sp` voxels apart, t < k) along one axis for which the rows
+// origin + i + t * sp - pad, i < n, of the source meet [0, extent); hi < lo: none.
+__device__ __forceinline__ void live_taps(int origin, int n, int pad, int extent, int k, int sp, int& lo, int& hi)
+{
+    const int first = pad - origin - (n - 1), last = pad - origin + extent - 1;     // t * sp in [first, last]
+    lo = first <= 0 ? 0 : (first + sp - 1) / sp;
+    hi = last < 0 ? -1 : min(k - 1, last / sp);
+}
 
 }  // namespace conv
 

@@ -65,7 +65,7 @@ __device__ __forceinline__ void group_step_tail(floatx4 (&acc)[NJ][NV], floatx4 
                                                 floatx4& at1, lds_bytes (&vb)[NV], lds_bytes (&vbT)[NP ? NP : 1],
                                                 const lds_bytes (&voff)[NV], const lds_bytes (&voffT)[NP ? NP : 1],
                                                 const float*& wg, const float* wl, int& wlo, int& wto, unsigned lane,
-                                                unsigned tl4, int o_next, bool advance)
+                                                unsigned tl4, int o_next, int advance)
 {
     constexpr bool TAIL = NP > 0;
     constexpr int WT = NJ * 64 + (TAIL ? kTailPacked : 0);
@@ -91,9 +91,9 @@ __device__ __forceinline__ void group_step_tail(floatx4 (&acc)[NJ][NV], floatx4 
             __builtin_amdgcn_sched_barrier(0);
             tap_mfmas_tail<NJ, NV, NP>(acc, accT, ac, bc, atc, bt, bn, vb, U - 2 - u);
         } else {
-            if (advance) {
-                wg += U * WT;
-                if (WL) { wlo += U * WT; wto += U * WT; }
+            if (advance) {      // floats to the next group's packed weights, 0 after the last group
+                wg += advance;
+                if (WL) { wlo += advance; wto += advance; }
             }
 #pragma unroll
             for (int nv = 0; nv < NV; ++nv) vb[nv] = voff[nv] + o_next * 16;
@@ -169,7 +169,17 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma_tail(ConvTile P)
     const int jg = blockIdx.y;
     const float* wq = P.wp + ((long)jg * P.nchunk + ic0) * taps * WT;      // uniform
     const int groups_per_row = P.kx / U;
-    const int ngroups = P.kz * P.ky * groups_per_row;
+    // planes and rows of taps that meet the source somewhere in this workgroup's box (all of them unless the
+    // box lies in the zero-extended border of the backward pass)
+    int alo, ahi, blo, bhi;
+    live_taps(z0, min(P.Tz, P.dz - z0), P.pz, P.sz, P.kz, P.spz, alo, ahi);
+    live_taps(y0, min(P.Ty, P.dy - y0), P.py, P.sy, P.ky, P.spy, blo, bhi);
+    const bool none = ahi < alo || bhi < blo;
+    if (none) { alo = ahi = 0; blo = bhi = 0; }
+    const int na = ahi - alo + 1, nb = bhi - blo + 1;
+    const int ngroups = none ? 0 : na * nb * groups_per_row;
+    const int wstart = ((P.kz - 1 - ahi) * P.ky + (P.ky - 1 - bhi)) * P.kx * WT;    // first packed tap of the walk
+    const int wrow = (P.ky - nb) * P.kx * WT;
 
     // Halo loader: tab[r] = byte offset inside a source map of voxel r of the halo box, -1 outside the
     // image (zero padding) and behind the box.  A wave-load fills 64 consecutive words = 16 voxels x
@@ -232,10 +242,10 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma_tail(ConvTile P)
         floatx4 at0, at1;
         lds_bytes vb[NV], vbT[NPA];
         GroupWalk<U> walk;
-        walk.start(P);
+        walk.start(P, ahi, bhi, nb, wrow);
         walk.o += cur * P.MS;               // in voxels; a voxel is four words
-        const float* wg = wq;
-        int wlo = lane, wto = NJ * 64 + tl * 4;
+        const float* wg = wq + wstart;
+        int wlo = lane + wstart, wto = NJ * 64 + tl * 4 + wstart;
         const unsigned tl4 = tl * 4;
 #pragma unroll
         for (int nv = 0; nv < NV; ++nv) vb[nv] = voff[nv] + walk.o * 16;
@@ -253,18 +263,20 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma_tail(ConvTile P)
 
         int g = 0;
         for (; g + 2 <= ngroups; g += 2) {
-            walk.o += walk.step(P, groups_per_row);
+            int wd = U * WT;
+            walk.o += walk.step(P, groups_per_row, wd);
             group_step_tail<NJ, NV, NP, WL, U, 0>(acc, accT, a0, b0, at0, a1, b1, at1, vb, vbT, voff, voffT, wg, wl, wlo,
-                                              wto, lane, tl4, walk.o, true);
+                                              wto, lane, tl4, walk.o, wd);
             const bool more = g + 2 < ngroups;
-            walk.o += more ? walk.step(P, groups_per_row) : 0;
+            wd = more ? U * WT : 0;
+            if (more) walk.o += walk.step(P, groups_per_row, wd);
             group_step_tail<NJ, NV, NP, WL, U, (U & 1)>(acc, accT, a0, b0, at0, a1, b1, at1, vb, vbT, voff, voffT, wg, wl,
-                                                    wlo, wto, lane, tl4, walk.o, more);
+                                                    wlo, wto, lane, tl4, walk.o, wd);
             asm volatile("" ::: "memory");
         }
         if (g < ngroups)
             group_step_tail<NJ, NV, NP, WL, U, 0>(acc, accT, a0, b0, at0, a1, b1, at1, vb, vbT, voff, voffT, wg, wl, wlo,
-                                              wto, lane, tl4, walk.o, false);
+                                              wto, lane, tl4, walk.o, 0);
         wq += (long)taps * WT;
     }
 
@@ -305,10 +317,11 @@ __global__ void __launch_bounds__(256, 2) k_conv_mfma_tail(ConvTile P)
 }
 
 // Instances.  With the block: 1..7 full tiles, 4 to 8 voxel tiles per wave, at most 28 accumulator tiles (more
-// spill registers at two workgroups per compute unit).  Without: 1..8 tiles, 2 or 4..8 voxel tiles, at most 32.
+// spill registers at two workgroups per compute unit; so does 4 x 7, whose four partial sums of the block come
+// on top of the 28 tiles: 35 registers spilled).  Without: 1..8 tiles, 2 or 4..8 voxel tiles, at most 32.
 constexpr bool tail_instance(int nj, int nv)
 {
-    return nj >= 1 && nj <= 7 && nv >= 4 && nv <= 8 && nj * nv <= 28;
+    return nj >= 1 && nj <= 7 && nv >= 4 && nv <= 8 && nj * nv <= 28 && !(nj == 4 && nv == 7);
 }
 constexpr bool plain_instance(int nj, int nv)
 {
