@@ -55,6 +55,33 @@ k_wgrad_reduce(const float* __restrict__ partial, float* __restrict__ gw, int f,
     gw[t] = acc;
 }
 
+// The same for small layers with many splits, where one thread per element is a long chain of dependent
+// additions on few threads: wave l of a workgroup sums the splits s = l, l + 4, ... of 64 elements, then the
+// four sums are added in the order l = 0, 1, 2, 3 (fixed, so results are reproducible from run to run).
+__global__ void __launch_bounds__(256)
+k_wgrad_reduce4(const float* __restrict__ partial, float* __restrict__ gw, int f, int fo, int kz, int ky, int kx,
+                int ksplit, int Mpad, int Npad, int mapmajor)
+{
+    __shared__ float part[4][64];
+    const int taps = kz * ky * kx;
+    const long total = (long)fo * f * taps;
+    const int l = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const long t = (long)blockIdx.x * 64 + lane;
+    float acc = 0.f;
+    if (t < total) {
+        const int tap = (int)(t % taps);
+        const long e = t / taps;
+        const int i = (int)(e % f), j = (int)(e / f);
+        const int c = tap % kx, ab = tap / kx;
+        const int AB = kz * ky;
+        const int n = mapmajor ? i * kx + c : c * f + i;
+        for (int s = l; s < ksplit; s += 4) acc += partial[((long)(s * AB + ab) * Mpad + j) * Npad + n];
+    }
+    part[l][lane] = acc;
+    __syncthreads();
+    if (l == 0 && t < total) gw[t] = ((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane];
+}
+
 // ng column sets of kw waves each (direct_wgrad_impl.h).  Sixteen waves (4 x 4) were measured slower than
 // eight on every benchmark shape and are not instantiated.
 WgradFn pick_wgrad(int nj, int nt, int ng, int kw)
@@ -319,8 +346,12 @@ int mfma_wgrad(const Geom& g, const float* in, const float* gout, float* gw, voi
     int rc = check_launch("direct kernel gradient (MFMA)");
     if (rc != ZNN_OK) return rc;
     const long total = (long)g.fo * g.f * g.kvol();
-    ZNN_LAUNCH("kernel gradient reduction", s, k_wgrad_reduce, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
-                       (const float*)ws, gw, g.f, g.fo, g.kz, g.ky, g.kx, c.ksplit, c.Mpad, c.Npad, c.mapmajor);
+    if (total < 65536 && c.ksplit >= 16)
+        ZNN_LAUNCH("kernel gradient reduction", s, k_wgrad_reduce4, dim3((unsigned)((total + 63) / 64)), dim3(256), 0,
+                           (const float*)ws, gw, g.f, g.fo, g.kz, g.ky, g.kx, c.ksplit, c.Mpad, c.Npad, c.mapmajor);
+    else
+        ZNN_LAUNCH("kernel gradient reduction", s, k_wgrad_reduce, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
+                           (const float*)ws, gw, g.f, g.fo, g.kz, g.ky, g.kx, c.ksplit, c.Mpad, c.Npad, c.mapmajor);
     return check_launch("kernel gradient reduction");
 }
 
