@@ -657,23 +657,29 @@ k_wgrad_zdft(const float2* __restrict__ G, const float2* __restrict__ I, float2*
         }
 }
 
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+// fourth word of a buffer resource descriptor for untyped loads (32-bit data format, no swizzle)
+constexpr int kBufferWord3 = 0x00020000;
+
 // The same sums for N divisible by 4 and lags one voxel apart, four z a quarter period apart at
 // a time: with z = z0 + q N/4,
 //   T1[a] = sum_z0 exp(+2 pi i a z0 / N) * sum_q prod[z0 + q N/4] i^(a q),
 // so the four products are first combined by a radix-4 butterfly of additions into the four
 // classes a mod 4, and each lag then costs one complex multiply-add per FOUR z instead of one
 // per z (KZ + 1 -> KZ/4 + 2 complex operations per product).
-template <int KZ, int JB, int IB>
+// (FLAT is a template parameter because the pair block of a thread is uniform over the workgroup only
+// without it, and only then do the loads get scalar bases.)
+template <int KZ, int JB, int IB, bool FLAT>
 __global__ void __launch_bounds__(kThreads)
 k_wgrad_zdft4(const float2* __restrict__ G, const float2* __restrict__ I, float2* __restrict__ T1,
-              int f, int fo, int N, long plane, long vol, int iblocks, int flat)
+              int f, int fo, int N, long plane, long vol, int iblocks)
 {
     __shared__ float2 tw[kMaxFftExtent];
     make_twiddles(tw, N, +1);
     __syncthreads();
     int jblk, iblk;
     long p;
-    if (flat) {
+    if (FLAT) {
         // small planes: (pair block, pencil) as one flat index, so that every wave is full
         const long t = (long)blockIdx.x * kThreads + threadIdx.x;
         const long pb = t / plane;
@@ -689,12 +695,27 @@ k_wgrad_zdft4(const float2* __restrict__ G, const float2* __restrict__ I, float2
     }
     const int j0 = jblk * JB, i0 = iblk * IB;
     const int Q = N >> 2;
+    // Spectrum element (map, z, p) = base of the map + z * plane + the thread's p.  Where the maps are uniform
+    // over the workgroup (not FLAT) the loads are buffer loads: the map's base in a resource descriptor, the row
+    // z * plane * 8 as a scalar offset, p * 8 as the lane's 32-bit offset (the host checks that a map's spectrum
+    // stays below 4 GB), which costs no vector instruction; formed as 64-bit pointers per thread the addresses
+    // cost 30 vector additions per round of the loop, 6 % of its instructions.
     const float2* gp[JB];
     const float2* ip[IB];
 #pragma unroll
-    for (int jb = 0; jb < JB; ++jb) gp[jb] = G + (long)min(j0 + jb, fo - 1) * vol + p;
+    for (int jb = 0; jb < JB; ++jb) gp[jb] = G + (long)min(j0 + jb, fo - 1) * vol;
 #pragma unroll
-    for (int ib = 0; ib < IB; ++ib) ip[ib] = I + (long)min(i0 + ib, f - 1) * vol + p;
+    for (int ib = 0; ib < IB; ++ib) ip[ib] = I + (long)min(i0 + ib, f - 1) * vol;
+    __amdgpu_buffer_rsrc_t gr[JB], ir[IB];
+    if constexpr (!FLAT) {
+        const int bytes = (int)(unsigned)(vol * 8);
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb) gr[jb] = __builtin_amdgcn_make_buffer_rsrc((void*)gp[jb], 0, bytes, kBufferWord3);
+#pragma unroll
+        for (int ib = 0; ib < IB; ++ib) ir[ib] = __builtin_amdgcn_make_buffer_rsrc((void*)ip[ib], 0, bytes, kBufferWord3);
+    }
+    const int pbytes = (int)((unsigned)p * 8u);
+    const unsigned zstep = (unsigned)(plane * 8);
     float2 acc[JB][IB][KZ];
 #pragma unroll
     for (int jb = 0; jb < JB; ++jb)
@@ -706,10 +727,24 @@ k_wgrad_zdft4(const float2* __restrict__ G, const float2* __restrict__ I, float2
         float2 gv[JB][4], xv[IB][4], t[KZ];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
+            if constexpr (FLAT) {
 #pragma unroll
-            for (int jb = 0; jb < JB; ++jb) gv[jb][q] = gp[jb][(long)(z0 + q * Q) * plane];
+                for (int jb = 0; jb < JB; ++jb) gv[jb][q] = gp[jb][(long)(z0 + q * Q) * plane + p];
 #pragma unroll
-            for (int ib = 0; ib < IB; ++ib) xv[ib][q] = ip[ib][(long)(z0 + q * Q) * plane];
+                for (int ib = 0; ib < IB; ++ib) xv[ib][q] = ip[ib][(long)(z0 + q * Q) * plane + p];
+            } else {
+                const int zoff = (int)((unsigned)(z0 + q * Q) * zstep);     // uniform
+#pragma unroll
+                for (int jb = 0; jb < JB; ++jb) {
+                    const floatx2 v = __builtin_amdgcn_raw_buffer_load_b64(gr[jb], pbytes, zoff, 0);
+                    gv[jb][q] = make_float2(v.x, v.y);
+                }
+#pragma unroll
+                for (int ib = 0; ib < IB; ++ib) {
+                    const floatx2 v = __builtin_amdgcn_raw_buffer_load_b64(ir[ib], pbytes, zoff, 0);
+                    xv[ib][q] = make_float2(v.x, v.y);
+                }
+            }
         }
 #pragma unroll
         for (int a = 1; a < KZ; ++a) t[a] = tw[(a * z0) % N];       // wave-uniform LDS reads
@@ -904,11 +939,16 @@ int launch_wgrad_dft_k(int f, int fo, int N, int tz, long plane, long vol, const
     const int flat = (double)plane < 0.95 * (double)(pchunks * kThreads) ? 1 : 0;
     const long blocks = flat ? ((long)jblocks * iblocks * plane + kThreads - 1) / kThreads : ((tiles + 7) / 8) * 8 * kTileJ * kTileI;
     if (blocks >= 2147483647L) return fail(ZNN_EUNSUPPORTED, "too many edges or pencils for one launch");
+    if (vol * 8 >= 4294967296L) return fail(ZNN_EUNSUPPORTED, "a node spectrum of 4 GB or more");
     const dim3 grid((unsigned)blocks);
-    if (N % 4 == 0 && tz == 1 && !tuning().fft_wgrad_plain)
-        ZNN_LAUNCH("pruned DFT of spectral products", s, (k_wgrad_zdft4<KZ, JB, IB>), grid, dim3(kThreads), 0,
-                   G, I, T, f, fo, N, plane, vol, iblocks, flat);
-    else
+    if (N % 4 == 0 && tz == 1 && !tuning().fft_wgrad_plain) {
+        if (flat)
+            ZNN_LAUNCH("pruned DFT of spectral products", s, (k_wgrad_zdft4<KZ, JB, IB, true>), grid, dim3(kThreads), 0,
+                       G, I, T, f, fo, N, plane, vol, iblocks);
+        else
+            ZNN_LAUNCH("pruned DFT of spectral products", s, (k_wgrad_zdft4<KZ, JB, IB, false>), grid, dim3(kThreads), 0,
+                       G, I, T, f, fo, N, plane, vol, iblocks);
+    } else
         ZNN_LAUNCH("pruned DFT of spectral products", s, (k_wgrad_zdft<KZ, JB, IB>), grid, dim3(kThreads), 0,
                    G, I, T, f, fo, N, tz, plane, vol, iblocks, flat);
     return check_launch("pruned DFT of spectral products");
