@@ -25,9 +25,51 @@ constexpr int kXYThreads = 128;
 template <int N> struct XYLayout {
     static constexpr int H = N / 2, NXH = H + 1;
     static constexpr int KP = NXH | 1;              // complex row pitch (odd)
-    static constexpr int RP = N + 1;                // real row pitch (odd)
+    // real row pitch.  N divisible by 4: N + 2, so that rows stay 8-byte aligned (a thread reads its row as
+    // pairs) while RP / 2 is odd (the rows of 32 threads start in different bank pairs); N rows still fit the
+    // complex view.  Otherwise odd, read word by word.
+    static constexpr int RP = N % 4 == 0 ? N + 2 : N + 1;
     static constexpr int floats = N * KP * 2;       // the complex plane is the larger of the two views
 };
+
+// the value that the other lane of the pair (lane ^ 1) holds: a DPP move within the quad, no LDS
+__device__ __forceinline__ float from_pair_lane(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, false));
+}
+
+// z[k] *= exp(DIR 2 pi i k / N) for k < M on the lanes with `odd` set (the constants are compile-time)
+template <int N, int DIR, int M, int K = 0>
+__device__ __forceinline__ void static_for_twiddle(float2 (&z)[M], int odd)
+{
+    if constexpr (K < M) {
+        const float2 t = twmul<N, DIR, K>(z[K]);
+        if (odd) z[K] = t;
+        static_for_twiddle<N, DIR, M, K + 1>(z, odd);
+    }
+}
+
+// Length-N transform (N even) of a column by TWO neighbouring lanes: lane `half` of the pair holds the
+// samples 2 m + half in v[m], transforms them (length N/2), the odd lane multiplies its results by the
+// twiddles exp(DIR 2 pi i k / N), the lanes swap results, and the even lane ends up with the coefficients
+// k = 0 .. N/2 - 1, the odd lane with N/2 .. N - 1, in r[].  Two thirds of the instructions of the length-N
+// transform on one lane, and the column pass occupies both waves of the workgroup instead of 49 lanes of one.
+template <int N, int DIR>
+__device__ __forceinline__ void column_fft_by_lane_pair(float2 (&v)[N / 2], float2 (&r)[N / 2], int half)
+{
+    constexpr int M = N / 2;
+    float2 w[M];
+    passes<M, DIR, M, 1>(v, w);
+    constexpr bool in_w = (count_passes(M) % 2) == 1;
+    float2 (&z)[M] = in_w ? w : v;
+    static_for_twiddle<N, DIR, M>(z, half);
+#pragma unroll
+    for (int k = 0; k < M; ++k) {
+        // the partner's value of the same k
+        const float2 o = make_float2(from_pair_lane(z[k].x), from_pair_lane(z[k].y));
+        r[k] = half ? csub(o, z[k]) : cadd(z[k], o);
+    }
+}
 
 template <int N>
 __global__ void __launch_bounds__(kXYThreads) k_fft_r2c_xy_reg(XYFwd P)
@@ -67,7 +109,10 @@ __global__ void __launch_bounds__(kXYThreads) k_fft_r2c_xy_reg(XYFwd P)
     if (myrow) {
         float2 x[H], y[H];
 #pragma unroll
-        for (int m = 0; m < H; ++m) x[m] = make_float2(lds[tid * RP + 2 * m], lds[tid * RP + 2 * m + 1]);
+        for (int m = 0; m < H; ++m) {
+            if constexpr (RP % 2 == 0) x[m] = *reinterpret_cast<const float2*>(lds + tid * RP + 2 * m);
+            else x[m] = make_float2(lds[tid * RP + 2 * m], lds[tid * RP + 2 * m + 1]);
+        }
         passes<H, -1, H, 1>(x, y);
         constexpr bool in_y = (count_passes(H) % 2) == 1;
         float2 (&Z)[H] = in_y ? y : x;
@@ -89,8 +134,22 @@ __global__ void __launch_bounds__(kXYThreads) k_fft_r2c_xy_reg(XYFwd P)
     }
     __syncthreads();
 
-    // ---- y: thread k transforms column k and stores it
-    if (tid < NXH) {
+    // ---- y: two threads per column (even extents), else thread k transforms column k; and stores it
+    if constexpr (N % 2 == 0 && 2 * NXH <= kXYThreads) {
+        const int c = tid >> 1, half = tid & 1;
+        if (c < NXH) {
+            constexpr int M = N / 2;
+            float2 v[M], r[M];
+#pragma unroll
+            for (int m = 0; m < M; ++m) {
+                const int e = 2 * m + half;
+                v[m] = (e >= P.oy && e < P.oy + P.sy) ? cplane[e * KP + c] : make_float2(0.f, 0.f);
+            }
+            column_fft_by_lane_pair<N, -1>(v, r, half);
+#pragma unroll
+            for (int k = 0; k < M; ++k) dst[(long)(k + half * M) * NXH + c] = r[k];
+        }
+    } else if (tid < NXH) {
         float2 v[N], w[N];
 #pragma unroll
         for (int e = 0; e < N; ++e)
@@ -131,8 +190,19 @@ __global__ void __launch_bounds__(kXYThreads, 2) k_fft_c2r_yx_reg(XYInv P)
         __builtin_amdgcn_s_waitcnt(0);
     }
     __syncthreads();
-    // ---- y: thread k inverts column k in place
-    if (tid < NXH) {
+    // ---- y: two threads per column (even extents), else thread k, invert column k in place
+    if constexpr (N % 2 == 0 && 2 * NXH <= kXYThreads) {
+        const int c = tid >> 1, half = tid & 1;
+        if (c < NXH) {
+            constexpr int M = N / 2;
+            float2 v[M], r[M];
+#pragma unroll
+            for (int m = 0; m < M; ++m) v[m] = cplane[(2 * m + half) * KP + c];
+            column_fft_by_lane_pair<N, +1>(v, r, half);
+#pragma unroll
+            for (int k = 0; k < M; ++k) cplane[(k + half * M) * KP + c] = r[k];
+        }
+    } else if (tid < NXH) {
         float2 v[N], w[N];
 #pragma unroll
         for (int e = 0; e < N; ++e) v[e] = cplane[e * KP + tid];
