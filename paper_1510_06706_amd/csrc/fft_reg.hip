@@ -22,7 +22,8 @@ bool fft_axis_reg_supported(int N)
 int fft_axis_reg(RegAxis P, int dir, hipStream_t s)
 {
     // pencil index * L must stay below 2^32 for the multiply-high division
-    if ((long)P.Ob * P.L * P.L >= 4294967296L || P.Oa > 65535)
+    // (and twice the pencil count, the thread index of the launches with two lanes per pencil, as well)
+    if ((long)P.Ob * P.L * P.L >= 4294967296L || 2L * P.Ob * P.L >= 4294967296L || P.Oa > 65535)
         return fail(ZNN_EUNSUPPORTED, "too many pencils for one launch");
     P.fL = make_fastdiv((unsigned)P.L);
     switch (P.N) {

@@ -168,32 +168,98 @@ __device__ __forceinline__ void passes(float2 (&x)[N], float2 (&y)[N])
 
 constexpr int count_passes(int n) { int c = 0; while (n > 1) { n /= pick_radix(n); ++c; } return c; }
 
+// the value that the other lane of the pair (lane ^ 1) holds: a DPP move within the quad, no LDS
+__device__ __forceinline__ float from_pair_lane(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, false));
+}
+
+// z[k] *= exp(DIR 2 pi i k / N) for k < M on the lanes with `odd` set (the constants are compile-time)
+template <int N, int DIR, int M, int K = 0>
+__device__ __forceinline__ void static_for_twiddle(float2 (&z)[M], int odd)
+{
+    if constexpr (K < M) {
+        const float2 t = twmul<N, DIR, K>(z[K]);
+        if (odd) z[K] = t;
+        static_for_twiddle<N, DIR, M, K + 1>(z, odd);
+    }
+}
+
+// Length-N transform (N even) of a column by TWO neighbouring lanes: lane `half` of the pair holds the
+// samples 2 m + half in v[m], transforms them (length N/2), the odd lane multiplies its results by the
+// twiddles exp(DIR 2 pi i k / N), the lanes swap results, and the even lane ends up with the coefficients
+// k = 0 .. N/2 - 1, the odd lane with N/2 .. N - 1, in r[].  Two thirds of the instructions of the length-N
+// transform on one lane, and the column pass occupies both waves of the workgroup instead of 49 lanes of one.
+template <int N, int DIR>
+__device__ __forceinline__ void column_fft_by_lane_pair(float2 (&v)[N / 2], float2 (&r)[N / 2], int half)
+{
+    constexpr int M = N / 2;
+    float2 w[M];
+    passes<M, DIR, M, 1>(v, w);
+    constexpr bool in_w = (count_passes(M) % 2) == 1;
+    float2 (&z)[M] = in_w ? w : v;
+    static_for_twiddle<N, DIR, M>(z, half);
+#pragma unroll
+    for (int k = 0; k < M; ++k) {
+        // the partner's value of the same k
+        const float2 o = make_float2(from_pair_lane(z[k].x), from_pair_lane(z[k].y));
+        r[k] = half ? csub(o, z[k]) : cadd(z[k], o);
+    }
+}
+
 template <int N, int DIR>
 __global__ void __launch_bounds__(kThreads)
 k_fft_axis_reg(RegAxis P)
 {
-    const unsigned g = blockIdx.x * kThreads + threadIdx.x;
-    if (g >= (unsigned)P.Ob * (unsigned)P.L) return;
-    const unsigned ob = fdiv(g, P.fL);
-    const unsigned l = g - ob * (unsigned)P.L;
-    const long oa = blockIdx.y;
-    const float2* in = P.in + oa * P.in_sa + (long)ob * P.in_sb + l;
-    float2* out = P.out + oa * P.out_sa + (long)ob * P.out_sb + l;
-    float2 x[N], y[N];
+    if constexpr (N % 2 == 0) {
+        // two neighbouring lanes per pencil: half the registers per lane (a length-96 pencil held by one lane
+        // takes the whole register file of a SIMD for one wave) and two thirds of the instructions
+        constexpr int M = N / 2;
+        const unsigned g2 = blockIdx.x * kThreads + threadIdx.x;
+        const unsigned g = g2 >> 1;
+        const int half = (int)(g2 & 1);
+        if (g >= (unsigned)P.Ob * (unsigned)P.L) return;
+        const unsigned ob = fdiv(g, P.fL);
+        const unsigned l = g - ob * (unsigned)P.L;
+        const long oa = blockIdx.y;
+        const float2* in = P.in + oa * P.in_sa + (long)ob * P.in_sb + l;
+        float2* out = P.out + oa * P.out_sa + (long)ob * P.out_sb + l;
+        float2 v[M], r[M];
 #pragma unroll
-    for (int e = 0; e < N; ++e)
-        x[e] = (e >= P.i0 && e < P.i0 + P.ni) ? in[(long)e * P.stride] : make_float2(0.f, 0.f);
-    passes<N, DIR, N, 1>(x, y);
-    constexpr bool in_y = (count_passes(N) % 2) == 1;
+        for (int m = 0; m < M; ++m) {
+            const int e = 2 * m + half;
+            v[m] = (e >= P.i0 && e < P.i0 + P.ni) ? in[(long)e * P.stride] : make_float2(0.f, 0.f);
+        }
+        column_fft_by_lane_pair<N, DIR>(v, r, half);
 #pragma unroll
-    for (int e = 0; e < N; ++e)
-        if (e >= P.o0 && e < P.o0 + P.no) out[(long)e * P.stride] = in_y ? y[e] : x[e];
+        for (int k = 0; k < M; ++k) {
+            const int e = k + half * M;
+            if (e >= P.o0 && e < P.o0 + P.no) out[(long)e * P.stride] = r[k];
+        }
+    } else {
+        const unsigned g = blockIdx.x * kThreads + threadIdx.x;
+        if (g >= (unsigned)P.Ob * (unsigned)P.L) return;
+        const unsigned ob = fdiv(g, P.fL);
+        const unsigned l = g - ob * (unsigned)P.L;
+        const long oa = blockIdx.y;
+        const float2* in = P.in + oa * P.in_sa + (long)ob * P.in_sb + l;
+        float2* out = P.out + oa * P.out_sa + (long)ob * P.out_sb + l;
+        float2 x[N], y[N];
+#pragma unroll
+        for (int e = 0; e < N; ++e)
+            x[e] = (e >= P.i0 && e < P.i0 + P.ni) ? in[(long)e * P.stride] : make_float2(0.f, 0.f);
+        passes<N, DIR, N, 1>(x, y);
+        constexpr bool in_y = (count_passes(N) % 2) == 1;
+#pragma unroll
+        for (int e = 0; e < N; ++e)
+            if (e >= P.o0 && e < P.o0 + P.no) out[(long)e * P.stride] = in_y ? y[e] : x[e];
+    }
 }
 
 template <int N>
 int launch_n(const RegAxis& P, int dir, hipStream_t s)
 {
-    const long threads = (long)P.Ob * P.L;
+    const long threads = (long)P.Ob * P.L * (N % 2 == 0 ? 2 : 1);      // even lengths: two lanes per pencil
     const dim3 grid((unsigned)((threads + kThreads - 1) / kThreads), (unsigned)P.Oa);
     if (dir > 0) ZNN_LAUNCH("fft axis inverse (registers)", s, (k_fft_axis_reg<N, +1>), grid, dim3(kThreads), 0, P);
     else         ZNN_LAUNCH("fft axis forward (registers)", s, (k_fft_axis_reg<N, -1>), grid, dim3(kThreads), 0, P);

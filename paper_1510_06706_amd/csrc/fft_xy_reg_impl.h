@@ -32,45 +32,6 @@ template <int N> struct XYLayout {
     static constexpr int floats = N * KP * 2;       // the complex plane is the larger of the two views
 };
 
-// the value that the other lane of the pair (lane ^ 1) holds: a DPP move within the quad, no LDS
-__device__ __forceinline__ float from_pair_lane(float v)
-{
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, false));
-}
-
-// z[k] *= exp(DIR 2 pi i k / N) for k < M on the lanes with `odd` set (the constants are compile-time)
-template <int N, int DIR, int M, int K = 0>
-__device__ __forceinline__ void static_for_twiddle(float2 (&z)[M], int odd)
-{
-    if constexpr (K < M) {
-        const float2 t = twmul<N, DIR, K>(z[K]);
-        if (odd) z[K] = t;
-        static_for_twiddle<N, DIR, M, K + 1>(z, odd);
-    }
-}
-
-// Length-N transform (N even) of a column by TWO neighbouring lanes: lane `half` of the pair holds the
-// samples 2 m + half in v[m], transforms them (length N/2), the odd lane multiplies its results by the
-// twiddles exp(DIR 2 pi i k / N), the lanes swap results, and the even lane ends up with the coefficients
-// k = 0 .. N/2 - 1, the odd lane with N/2 .. N - 1, in r[].  Two thirds of the instructions of the length-N
-// transform on one lane, and the column pass occupies both waves of the workgroup instead of 49 lanes of one.
-template <int N, int DIR>
-__device__ __forceinline__ void column_fft_by_lane_pair(float2 (&v)[N / 2], float2 (&r)[N / 2], int half)
-{
-    constexpr int M = N / 2;
-    float2 w[M];
-    passes<M, DIR, M, 1>(v, w);
-    constexpr bool in_w = (count_passes(M) % 2) == 1;
-    float2 (&z)[M] = in_w ? w : v;
-    static_for_twiddle<N, DIR, M>(z, half);
-#pragma unroll
-    for (int k = 0; k < M; ++k) {
-        // the partner's value of the same k
-        const float2 o = make_float2(from_pair_lane(z[k].x), from_pair_lane(z[k].y));
-        r[k] = half ? csub(o, z[k]) : cadd(z[k], o);
-    }
-}
-
 template <int N>
 __global__ void __launch_bounds__(kXYThreads) k_fft_r2c_xy_reg(XYFwd P)
 {
